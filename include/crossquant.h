@@ -1,0 +1,123 @@
+/*
+ * crossquant.h -- C ABI of the MI355X (gfx950) CrossQuant activation-quantization library.
+ *
+ * Implements the hot path of "CrossQuant" (arxiv 2410.07505): for an activation matrix
+ * X in R^{T x I} (tokens x input channels; Background section) it computes the row-wise and
+ * column-wise absolute maxima t and c, forms each element's step
+ *     Delta~_ij = t_i^alpha * c_j^(1-alpha) / (2^(N-1) - 1)         (the CrossQuant equation)
+ * quantizes, dequantizes, counts the quantization kernel (Definition 1) and runs the
+ * integer linear layer Y = X . W (Background section) on the codes.
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer owned by the caller; the library allocates nothing,
+ *     frees nothing and never synchronises with the host.  `stream` is a hipStream_t passed as
+ *     void* (NULL = the default stream).  All work is enqueued on that stream, in order.
+ *   - X and W are IEEE binary16, row-major.  Outputs are fully overwritten; vectors that the
+ *     kernels accumulate into (t, c, zero_count) are cleared on the stream inside the call.
+ *   - Return value: CQ_OK (0) or a negative cq_status.  Argument errors are found on the host
+ *     before anything is enqueued, so an error return means nothing was launched.
+ *   - Preconditions not checked: X and W finite; buffers at least as large as stated.
+ *   - Arithmetic is fixed so results are reproducible bit for bit: scale factors use binary64
+ *     pow rounded once to binary32; every per-element result equals a single correctly rounded
+ *     binary32 multiply/divide; round() is round-half-to-even; counters and accumulators are
+ *     integers.  Order of accumulation never affects a result.
+ */
+#ifndef CROSSQUANT_H
+#define CROSSQUANT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CQ_OK = 0,
+    CQ_ERR_NULL = -1,        /* a required pointer is NULL */
+    CQ_ERR_SHAPE = -2,       /* T, I or O < 1, a leading dimension too small, or a size over the limit */
+    CQ_ERR_BITS = -3,        /* bits is neither 4 nor 8 (or INT4 packing with odd I) */
+    CQ_ERR_ALPHA = -4,       /* alpha outside [0, 1] or not a number */
+    CQ_ERR_ALIGN = -5,       /* a pointer violates the stated alignment */
+    CQ_ERR_UNSUPPORTED = -6, /* valid request this build does not implement */
+    CQ_ERR_HIP = -7          /* a kernel launch failed (hipGetLastError) */
+} cq_status;
+
+/* Upper limits on sizes (keeps every index in 32 bits inside the kernels). */
+#define CQ_MAX_DIM ((int64_t)1 << 24)        /* T, I, O, leading dimensions */
+#define CQ_MAX_ELEMS ((int64_t)1 << 40)      /* T*I, I*O, T*O */
+
+/*
+ * Row and column absolute maxima in one pass over X.
+ *   t_i = max_j |X_ij|   (Eq. 1, per-token quantization)
+ *   c_j = max_i |X_ij|   (the CrossQuant equation)
+ * X: binary16 [T][ldx], ldx >= I (elements), 2-byte aligned (16-byte alignment of X together
+ *    with ldx % 8 == 0 selects the vectorised path; any other layout takes a slower one).
+ * t: out, float[T].  c: out, float[I].  Both are exact (a maximum of binary16 values).
+ */
+int crossquant_absmax(const void *X, int64_t T, int64_t I, int64_t ldx, float *t, float *c,
+                      void *stream);
+
+/*
+ * CrossQuant quantize + dequantize + kernel count (the CrossQuant equation, Definition 1, and
+ * the dequantization of the appendix fake-quant listing).
+ *   a_i = t_i^alpha / q_max,  b_j = c_j^(1-alpha),  q_max = 2^(bits-1) - 1
+ *   D_ij = fl32(a_i * b_j);  q_ij = D_ij == 0 ? 0 : clamp(rne(fl32(X_ij / D_ij)), +-q_max)
+ *   xhat_ij = fl16(fl32(q_ij * D_ij));   zero_count = #{(i,j): q_ij == 0}
+ * t, c: in, float[T], float[I] (normally from crossquant_absmax; any non-negative finite values
+ *       are accepted, e.g. calibrated ones -- codes are clamped to +-q_max).
+ * alpha in [0,1]; bits in {8, 4}.
+ * codes: out.  bits == 8: int8 [T][I].  bits == 4: I must be even; packed two's-complement
+ *        nibbles [T][I/2], even column in the low nibble.
+ * xhat: out, nullable, binary16 [T][I].
+ * row_scale: out, float[T] (a).  col_scale: out, float[I] (b).  Required: they are also the
+ *        kernel's own inputs and what the linear layer / weight folding consume.
+ * zero_count: out, nullable, one unsigned 64-bit counter.
+ */
+int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
+                        const float *c, float alpha, int bits, void *codes, void *xhat,
+                        float *row_scale, float *col_scale, unsigned long long *zero_count,
+                        void *stream);
+
+/*
+ * Size of the quantization kernel K(CQ) = {X_ij : CQ(X_ij) = 0} (Definition 1) without writing
+ * codes; the kernel proportion of the paper is zero_count / (T*I).  alpha = 1 gives the
+ * per-token baseline K(Q) of Eq. 1.
+ * row_scale / col_scale: float[T] / float[I] work vectors, overwritten with a and b.
+ */
+int crossquant_kernel_count(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
+                            const float *c, float alpha, int bits, float *row_scale,
+                            float *col_scale, unsigned long long *zero_count, void *stream);
+
+/*
+ * Per-channel weight quantization (Eq. 2), one step per OUTPUT channel k, stored transposed.
+ *   W'_jk = fl32(fold_j * W_jk)  (fold NULL = 1);  s_k = fl32(max_j |W'_jk| / q_max)
+ *   qw_kj = s_k == 0 ? 0 : clamp(rne(fl32(W'_jk / s_k)), +-q_max)
+ * Passing fold = col_scale (b_j) carries the column factor of the element-wise CrossQuant step
+ * into the weights, so that sum_j q_ij qw_kj * a_i * s_k approximates (X W)_ik.
+ * W: binary16 [I][O] row-major (the paper's layout).  qw: out, int8 [O][I].  w_scale: out, float[O].
+ */
+int crossquant_weight_quantize(const void *W, int64_t I, int64_t O, const float *fold, int bits,
+                               int8_t *qw, float *w_scale, void *stream);
+
+/*
+ * W8A8 linear layer Y = X . W on integer codes (Background section), INT8 MFMA, int32 accumulate.
+ *   acc_ik = sum_j qx_ij * qw_kj  (exact);  Y_ik = fl16(fl32(fl32(float(acc_ik) * row_scale_i) * w_scale_k))
+ * qx: int8 [T][I].  qw: int8 [O][I] (contraction axis contiguous).  Both 16-byte aligned with
+ *     I % 16 == 0 for the fast path; other layouts take a slower loader.
+ * Y: out, binary16 [T][ldy], ldy >= O.  acc_debug: out, nullable, int32 [T][O] raw accumulators.
+ * I * 127 * 127 must fit in int32 (I <= 133,000).
+ */
+int crossquant_w8a8_linear(const int8_t *qx, const float *row_scale, const int8_t *qw,
+                           const float *w_scale, int64_t T, int64_t I, int64_t O, void *Y,
+                           int64_t ldy, int32_t *acc_debug, void *stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *crossquant_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int crossquant_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CROSSQUANT_H */

@@ -1,0 +1,186 @@
+"""ctypes binding for libcrossquant.so: same names as the C ABI, argument marshalling only.
+
+Each wrapper takes torch tensors that already live on the GPU, checks dtype / contiguity,
+passes ``data_ptr()`` and the current HIP stream handle to the C entry point, and returns
+(or fills) output tensors.  Output tensors can be passed in (``out=...``) so that a caller
+such as the benchmark allocates nothing inside its timed region.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcrossquant.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libcrossquant.so is not built (%s). Run `python -m paper_2410_07505_amd.build`; "
+        "there is no fallback path." % LIB_PATH)
+
+lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i64, _int, _f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+lib.crossquant_absmax.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp]
+lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
+lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
+lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
+for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count",
+           "crossquant_weight_quantize", "crossquant_w8a8_linear", "crossquant_version"):
+    getattr(lib, _n).restype = _int
+lib.crossquant_status_string.argtypes = [_int]
+lib.crossquant_status_string.restype = ctypes.c_char_p
+lib.crossquant_version.argtypes = []
+
+raw = lib  # the unwrapped C entry points, for callers that marshal pointers themselves
+
+
+class CrossQuantError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__("crossquant: %s (status %d)" % (crossquant_status_string(status), status))
+
+
+def crossquant_status_string(status: int) -> str:
+    return lib.crossquant_status_string(int(status)).decode()
+
+
+def crossquant_version() -> int:
+    return int(lib.crossquant_version())
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise CrossQuantError(status)
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _req(t: torch.Tensor, dtype, name: str, ndim: int) -> None:
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must have dtype %s" % (name, dtype))
+    if t.dim() != ndim:
+        raise ValueError("%s must be %d-D" % (name, ndim))
+    if ndim == 2:
+        if t.stride(1) != 1 and t.shape[1] != 1:
+            raise ValueError("%s must have unit stride along its last axis" % name)
+    elif not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+
+
+def crossquant_absmax(X: torch.Tensor, *, t: torch.Tensor = None, c: torch.Tensor = None):
+    """Row maxima t (float32 [T]) and column maxima c (float32 [I]) of |X| in one pass."""
+    _req(X, torch.float16, "X", 2)
+    T, I = X.shape
+    if t is None:
+        t = torch.empty(T, dtype=torch.float32, device=X.device)
+    if c is None:
+        c = torch.empty(I, dtype=torch.float32, device=X.device)
+    _req(t, torch.float32, "t", 1)
+    _req(c, torch.float32, "c", 1)
+    _check(lib.crossquant_absmax(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(), _stream(X)))
+    return t, c
+
+
+def crossquant_quantize(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
+                        want_xhat: bool = True, want_count: bool = True, codes: torch.Tensor = None,
+                        xhat: torch.Tensor = None, row_scale: torch.Tensor = None,
+                        col_scale: torch.Tensor = None, zero_count: torch.Tensor = None):
+    """CrossQuant codes (+ dequantized matrix, scale factors, zero count).
+
+    Returns (codes, xhat_or_None, row_scale, col_scale, zero_count_or_None); zero_count is a
+    one-element int64 tensor (the library's unsigned 64-bit counter)."""
+    _req(X, torch.float16, "X", 2)
+    T, I = X.shape
+    dev = X.device
+    if codes is None:
+        codes = (torch.empty((T, I), dtype=torch.int8, device=dev) if bits == 8
+                 else torch.empty((T, max(I // 2, 1)), dtype=torch.uint8, device=dev))
+    if xhat is None and want_xhat:
+        xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
+    if row_scale is None:
+        row_scale = torch.empty(T, dtype=torch.float32, device=dev)
+    if col_scale is None:
+        col_scale = torch.empty(I, dtype=torch.float32, device=dev)
+    if zero_count is None and want_count:
+        zero_count = torch.empty(1, dtype=torch.int64, device=dev)
+    for ten, name in ((t, "t"), (c, "c"), (row_scale, "row_scale"), (col_scale, "col_scale")):
+        _req(ten, torch.float32, name, 1)
+    if not codes.is_contiguous() or (xhat is not None and not xhat.is_contiguous()):
+        raise ValueError("codes and xhat must be contiguous")
+    _check(lib.crossquant_quantize(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(), float(alpha),
+                                   int(bits), codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(),
+                                   col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
+    return codes, xhat, row_scale, col_scale, zero_count
+
+
+def crossquant_kernel_count(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
+                            row_scale: torch.Tensor = None, col_scale: torch.Tensor = None,
+                            zero_count: torch.Tensor = None) -> torch.Tensor:
+    """Number of elements whose code is zero (one-element int64 tensor on the GPU)."""
+    _req(X, torch.float16, "X", 2)
+    T, I = X.shape
+    dev = X.device
+    if row_scale is None:
+        row_scale = torch.empty(T, dtype=torch.float32, device=dev)
+    if col_scale is None:
+        col_scale = torch.empty(I, dtype=torch.float32, device=dev)
+    if zero_count is None:
+        zero_count = torch.empty(1, dtype=torch.int64, device=dev)
+    _check(lib.crossquant_kernel_count(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(),
+                                       float(alpha), int(bits), row_scale.data_ptr(), col_scale.data_ptr(),
+                                       zero_count.data_ptr(), _stream(X)))
+    return zero_count
+
+
+def crossquant_weight_quantize(W: torch.Tensor, fold, bits: int, *, qw: torch.Tensor = None,
+                               w_scale: torch.Tensor = None):
+    """Per-output-channel weight codes qw (int8 [O][I]) and steps w_scale (float32 [O])."""
+    _req(W, torch.float16, "W", 2)
+    if not W.is_contiguous():
+        raise ValueError("W must be contiguous")
+    I, O = W.shape
+    if qw is None:
+        qw = torch.empty((O, I), dtype=torch.int8, device=W.device)
+    if w_scale is None:
+        w_scale = torch.empty(O, dtype=torch.float32, device=W.device)
+    if fold is not None:
+        _req(fold, torch.float32, "fold", 1)
+        if fold.numel() != I:
+            raise ValueError("fold needs one factor per input channel")
+    _check(lib.crossquant_weight_quantize(W.data_ptr(), I, O, _ptr(fold), int(bits), qw.data_ptr(),
+                                          w_scale.data_ptr(), _stream(W)))
+    return qw, w_scale
+
+
+def crossquant_w8a8_linear(qx: torch.Tensor, row_scale: torch.Tensor, qw: torch.Tensor, w_scale: torch.Tensor, *,
+                           Y: torch.Tensor = None, acc_debug: torch.Tensor = None, want_acc: bool = False):
+    """Y = fl16(acc * row_scale_i * w_scale_k) with acc = qx . qw^T in int32.  Returns (Y, acc_or_None)."""
+    _req(qx, torch.int8, "qx", 2)
+    _req(qw, torch.int8, "qw", 2)
+    if not qx.is_contiguous() or not qw.is_contiguous():
+        raise ValueError("qx and qw must be contiguous")
+    T, I = qx.shape
+    O, I2 = qw.shape
+    if I != I2 or row_scale.numel() != T or w_scale.numel() != O:
+        raise ValueError("shape mismatch")
+    _req(row_scale, torch.float32, "row_scale", 1)
+    _req(w_scale, torch.float32, "w_scale", 1)
+    if Y is None:
+        Y = torch.empty((T, O), dtype=torch.float16, device=qx.device)
+    if acc_debug is None and want_acc:
+        acc_debug = torch.empty((T, O), dtype=torch.int32, device=qx.device)
+    _check(lib.crossquant_w8a8_linear(qx.data_ptr(), row_scale.data_ptr(), qw.data_ptr(), w_scale.data_ptr(),
+                                      T, I, O, Y.data_ptr(), Y.stride(0), _ptr(acc_debug), _stream(qx)))
+    return Y, acc_debug

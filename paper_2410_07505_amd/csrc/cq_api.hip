@@ -1,0 +1,121 @@
+// C-ABI entry points: argument validation on the host, then kernel launches on the caller's
+// stream.  No allocation, no host synchronisation, no state.
+#include "../../include/crossquant.h"
+
+#include <cmath>
+
+#include "cq_kernels.h"
+
+namespace {
+
+inline bool dim_ok(int64_t v) { return v >= 1 && v <= CQ_MAX_DIM; }
+inline bool aligned(const void* p, uintptr_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+int check_matrix(const void* X, int64_t T, int64_t I, int64_t ldx) {
+    if (!X) return CQ_ERR_NULL;
+    if (!dim_ok(T) || !dim_ok(I) || ldx < I || ldx > CQ_MAX_DIM) return CQ_ERR_SHAPE;
+    if (T * I > CQ_MAX_ELEMS || T * ldx > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    if (!aligned(X, 2)) return CQ_ERR_ALIGN;
+    return CQ_OK;
+}
+
+int check_quant_params(float alpha, int bits, int64_t I) {
+    if (bits != 4 && bits != 8) return CQ_ERR_BITS;
+    if (bits == 4 && (I & 1)) return CQ_ERR_BITS;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;   // also rejects NaN
+    return CQ_OK;
+}
+
+inline int from_hip(hipError_t e) { return e == hipSuccess ? CQ_OK : CQ_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int crossquant_absmax(const void* X, int64_t T, int64_t I, int64_t ldx, float* t, float* c, void* stream) {
+    if (!t || !c) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (!aligned(t, 4) || !aligned(c, 4)) return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_absmax(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, t, c,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+int crossquant_quantize(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
+                        float alpha, int bits, void* codes, void* xhat, float* row_scale, float* col_scale,
+                        unsigned long long* zero_count, void* stream) {
+    if (!t || !c || !codes || !row_scale || !col_scale) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (int s = check_quant_params(alpha, bits, I)) return s;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
+        !aligned(xhat, 2) || !aligned(zero_count, 8))
+        return CQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int qmax = (1 << (bits - 1)) - 1;
+    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
+                                                   zero_count, st)))
+        return s;
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
+                                        col_scale, bits, codes, static_cast<uint16_t*>(xhat), zero_count, st));
+}
+
+int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
+                            float alpha, int bits, float* row_scale, float* col_scale,
+                            unsigned long long* zero_count, void* stream) {
+    if (!t || !c || !row_scale || !col_scale || !zero_count) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (bits != 4 && bits != 8) return CQ_ERR_BITS;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
+        !aligned(zero_count, 8))
+        return CQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int qmax = (1 << (bits - 1)) - 1;
+    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
+                                                   zero_count, st)))
+        return s;
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
+                                        col_scale, bits, nullptr, nullptr, zero_count, st));
+}
+
+int crossquant_weight_quantize(const void* W, int64_t I, int64_t O, const float* fold, int bits, int8_t* qw,
+                               float* w_scale, void* stream) {
+    if (!W || !qw || !w_scale) return CQ_ERR_NULL;
+    if (!dim_ok(I) || !dim_ok(O) || I * O > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    if (bits != 4 && bits != 8) return CQ_ERR_BITS;
+    if (!aligned(W, 2) || !aligned(w_scale, 4) || !aligned(fold, 4)) return CQ_ERR_ALIGN;
+    const int qmax = (1 << (bits - 1)) - 1;
+    return from_hip(cq::launch_weight_quantize(static_cast<const uint16_t*>(W), (int)I, (int)O, fold, qmax, qw,
+                                               w_scale, static_cast<hipStream_t>(stream)));
+}
+
+int crossquant_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_t* qw, const float* w_scale,
+                           int64_t T, int64_t I, int64_t O, void* Y, int64_t ldy, int32_t* acc_debug,
+                           void* stream) {
+    if (!qx || !row_scale || !qw || !w_scale || !Y) return CQ_ERR_NULL;
+    if (!dim_ok(T) || !dim_ok(I) || !dim_ok(O) || ldy < O || ldy > CQ_MAX_DIM) return CQ_ERR_SHAPE;
+    if (T * I > CQ_MAX_ELEMS || I * O > CQ_MAX_ELEMS || T * ldy > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    if (I > 133000) return CQ_ERR_SHAPE;     // 127 * 127 * I must fit the int32 accumulator
+    if (!aligned(row_scale, 4) || !aligned(w_scale, 4) || !aligned(Y, 2) || !aligned(acc_debug, 4))
+        return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_w8a8_linear(qx, row_scale, qw, w_scale, (int)T, (int)I, (int)O,
+                                           static_cast<uint16_t*>(Y), ldy, acc_debug,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+const char* crossquant_status_string(int status) {
+    switch (status) {
+        case CQ_OK: return "ok";
+        case CQ_ERR_NULL: return "a required pointer is NULL";
+        case CQ_ERR_SHAPE: return "invalid shape or leading dimension";
+        case CQ_ERR_BITS: return "bits must be 8, or 4 with an even number of channels";
+        case CQ_ERR_ALPHA: return "alpha must lie in [0, 1]";
+        case CQ_ERR_ALIGN: return "pointer alignment violated";
+        case CQ_ERR_UNSUPPORTED: return "unsupported request";
+        case CQ_ERR_HIP: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int crossquant_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,38 @@
+// Internal launcher interface between the C-ABI layer and the gfx950 kernels.
+// Every launcher enqueues on `stream`, allocates nothing and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cq {
+
+// binary16 bit pattern <-> binary32 (widening is exact; narrowing rounds to nearest even)
+__device__ __forceinline__ float h2f(uint32_t h) {
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+__device__ __forceinline__ uint32_t f2h(float f) {
+    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);
+}
+
+// t[0..T), c[0..I) <- 0 ; then one pass over X accumulating both maxima.
+hipError_t launch_absmax(const uint16_t* X, int T, int I, int64_t ldx, float* t, float* c,
+                         hipStream_t stream);
+
+// a_i = t_i^alpha / qmax, b_j = c_j^(1-alpha) (binary64 pow, one rounding); *zero_count <- 0.
+hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, float alpha, int qmax,
+                                 float* a, float* b, unsigned long long* zero_count,
+                                 hipStream_t stream);
+
+// Fused quantize / dequantize / zero count.  codes or xhat may be null (count only = both null).
+hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const float* a,
+                           const float* b, int bits, void* codes, uint16_t* xhat,
+                           unsigned long long* zero_count, hipStream_t stream);
+
+hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* fold, int qmax,
+                                  int8_t* qw, float* w_scale, hipStream_t stream);
+
+hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_t* qw,
+                              const float* w_scale, int T, int I, int O, uint16_t* Y, int64_t ldy,
+                              int32_t* acc_debug, hipStream_t stream);
+
+}  // namespace cq

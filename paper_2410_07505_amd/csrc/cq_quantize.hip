@@ -1,0 +1,252 @@
+// CrossQuant scale factors and the fused quantize / dequantize / kernel-count pass
+// (the CrossQuant equation, Definition 1, and the dequantization of the appendix listing).
+//
+// The element-wise step is D_ij = fl32(a_i * b_j) with a_i = t_i^alpha / q_max and
+// b_j = c_j^(1-alpha); the code is q_ij = clamp(rne(fl32(x_ij / D_ij)), +-q_max).
+//
+// HBM-bound kernel (2 B read + 1 or 0.5 B codes + optionally 2 B dequantized per element), so
+// the per-element instruction count has to stay small.  A correctly rounded binary32 division
+// costs more than the rest of the element's work together, so it is taken only where it can
+// matter: the quotient is first approximated as x * (1/a_i) * (1/b_j) (reciprocals formed once
+// per row / per lane), whose relative error is below 6 * 2^-24; the rounded integer can differ
+// from the one the exact quotient gives only if the approximation lies within that error of a
+// rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2 (a 5x margin over the bound) and
+// a wave in which any lane trips recomputes its eight elements with the exact division.  The
+// result is therefore identical, bit for bit, to dividing every element.
+//
+// Rounding to nearest-even integer and conversion to two's complement are one add of the
+// constant 1.5 * 2^23: the sum's low mantissa bits are the code.
+#include "cq_kernels.h"
+
+namespace cq {
+namespace {
+
+constexpr int kLanes = 64;
+constexpr int kColsPerWave = kLanes * 8;
+constexpr float kMagic = 12582912.0f;            // 1.5 * 2^23
+constexpr uint32_t kMagicBits = 0x4B400000u;
+constexpr float kTieTol = 1.9073486328125e-06f;  // 2^-19
+
+__global__ void scale_finalize_kernel(const float* __restrict__ t, const float* __restrict__ c, int T,
+                                      int I, float alpha, int qmax, float* __restrict__ a,
+                                      float* __restrict__ b, unsigned long long* __restrict__ zero_count) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const double al = (double)alpha;
+    if (idx == 0 && zero_count) *zero_count = 0ull;
+    if (idx < T) {
+        const double ti = (double)t[idx];
+        // pow(x, 0) = 1 for every x and pow(x, 1) = x are exact in any correct pow; written out
+        // so the two special exponents (per-column and per-token steps) never depend on it
+        const double p = (al == 0.0) ? 1.0 : (al == 1.0 ? ti : pow(ti, al));
+        a[idx] = (float)(p / (double)qmax);
+    } else if (idx - T < I) {
+        const int j = idx - T;
+        const double cj = (double)c[j];
+        const double e = 1.0 - al;
+        const double p = (e == 0.0) ? 1.0 : (e == 1.0 ? cj : pow(cj, e));
+        b[j] = (float)p;
+    }
+}
+
+template <bool VEC>
+__device__ __forceinline__ uint4 load8(const uint16_t* __restrict__ row, int j, int I) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (VEC && j + 8 <= I) {
+        v = *reinterpret_cast<const uint4*>(row + j);
+    } else if (j < I) {
+        uint32_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = (j + e < I) ? row[j + e] : 0u;
+        v.x = h[0] | (h[1] << 16);
+        v.y = h[2] | (h[3] << 16);
+        v.z = h[4] | (h[5] << 16);
+        v.w = h[6] | (h[7] << 16);
+    }
+    return v;
+}
+
+__device__ __forceinline__ float half_lo(uint32_t w) { return h2f(w & 0xFFFFu); }
+__device__ __forceinline__ float half_hi(uint32_t w) { return h2f(w >> 16); }
+
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
+    return f2h(lo) | (f2h(hi) << 16);
+}
+
+// bytes 0 of four words -> one word
+__device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_t u2, uint32_t u3) {
+    const uint32_t p01 = __builtin_amdgcn_perm(u1, u0, 0x0c0c0400u);
+    const uint32_t p23 = __builtin_amdgcn_perm(u3, u2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+}
+
+// MODE 0: count only; 1: INT8 codes; 2: packed INT4 codes.
+template <int MODE, bool XHAT, bool VEC, int RPW>
+__global__ void __launch_bounds__(256)
+quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ a_vec,
+                const float* __restrict__ b_vec, float qmax, uint8_t* __restrict__ codes,
+                uint16_t* __restrict__ xhat, unsigned long long* __restrict__ zero_count,
+                int n_col_chunks, bool out_vec) {
+    __shared__ uint32_t lds_cnt[4];
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int wave = threadIdx.x / kLanes;
+    const int col_chunk = blockIdx.x % n_col_chunks;
+    const int row_chunk = blockIdx.x / n_col_chunks;
+    const int j0 = col_chunk * kColsPerWave + lane * 8;
+    const int row0 = row_chunk * (4 * RPW) + wave * RPW;
+
+    float b[8], rb[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
+        rb[e] = (b[e] == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(b[e]);
+    }
+    int nvalid = I - j0;                       // columns of this lane that exist
+    nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
+
+    uint32_t zeros = 0;
+    constexpr int U = 4;
+    static_assert(RPW % U == 0, "rows per wave must be a multiple of the unroll");
+    for (int k0 = 0; k0 < RPW; k0 += U) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = row0 + k0 + u;
+            v[u] = (r < T) ? load8<VEC>(X + (int64_t)r * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = row0 + k0 + u;
+            if (r >= T) break;                 // wave-uniform
+            const float a = a_vec[r];
+            const float ra = (a == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(a);
+            float x[8];
+            x[0] = half_lo(v[u].x); x[1] = half_hi(v[u].x);
+            x[2] = half_lo(v[u].y); x[3] = half_hi(v[u].y);
+            x[4] = half_lo(v[u].z); x[5] = half_hi(v[u].z);
+            x[6] = half_lo(v[u].w); x[7] = half_hi(v[u].w);
+
+            float m[8];
+            bool near_tie = false;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float rt = x[e] * (ra * rb[e]);
+                rt = __builtin_fminf(__builtin_fmaxf(rt, -qmax), qmax);
+                m[e] = rt + kMagic;
+                const float f = rt - (m[e] - kMagic);
+                near_tie |= (__builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)) >= 0.5f);
+            }
+            if (__any(near_tie)) {             // rare: exact division for this wave's row piece
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float D = a * b[e];
+                    float rt = (D == 0.0f) ? 0.0f : x[e] / D;
+                    rt = __builtin_fminf(__builtin_fmaxf(rt, -qmax), qmax);
+                    m[e] = rt + kMagic;
+                }
+            }
+
+            uint32_t u32[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                u32[e] = __float_as_uint(m[e]);
+                zeros += (uint32_t)__popcll(__ballot(u32[e] == kMagicBits && e < nvalid));
+            }
+
+            if (MODE == 1) {
+                const uint32_t w0 = pack_bytes(u32[0], u32[1], u32[2], u32[3]);
+                const uint32_t w1 = pack_bytes(u32[4], u32[5], u32[6], u32[7]);
+                uint8_t* dst = codes + (int64_t)r * I + j0;
+                if (out_vec && nvalid == 8) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < nvalid) dst[e] = (uint8_t)(u32[e] & 0xFFu);
+                }
+            } else if (MODE == 2) {
+                uint32_t w0 = pack_bytes(u32[0], u32[1], u32[2], u32[3]) & 0x0F0F0F0Fu;
+                uint32_t w1 = pack_bytes(u32[4], u32[5], u32[6], u32[7]) & 0x0F0F0F0Fu;
+                w0 |= w0 >> 4;                 // bytes 0 and 2 now hold two nibbles each
+                w1 |= w1 >> 4;
+                const uint32_t w = __builtin_amdgcn_perm(w1, w0, 0x06040200u);
+                uint8_t* dst = codes + (int64_t)r * (I / 2) + j0 / 2;
+                if (out_vec && nvalid == 8) {
+                    *reinterpret_cast<uint32_t*>(dst) = w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (2 * e < nvalid) dst[e] = (uint8_t)((w >> (8 * e)) & 0xFFu);  // I is even
+                }
+            }
+            if (XHAT) {
+                float y[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y[e] = (m[e] - kMagic) * (a * b[e]);
+                uint16_t* dst = xhat + (int64_t)r * I + j0;
+                if (out_vec && nvalid == 8) {
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(pack_half2(y[0], y[1]), pack_half2(y[2], y[3]),
+                                                                pack_half2(y[4], y[5]), pack_half2(y[6], y[7]));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < nvalid) dst[e] = (uint16_t)f2h(y[e]);
+                }
+            }
+        }
+    }
+
+    if (zero_count) {
+        if (lane == 0) lds_cnt[wave] = zeros;  // the ballot counts are already wave totals
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t s = lds_cnt[0] + lds_cnt[1] + lds_cnt[2] + lds_cnt[3];
+            if (s) atomicAdd(zero_count, (unsigned long long)s);
+        }
+    }
+}
+
+template <int MODE, bool XHAT>
+hipError_t launch_mode(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
+                       float qmax, uint8_t* codes, uint16_t* xhat, unsigned long long* zc,
+                       hipStream_t stream) {
+    constexpr int RPW = 8;
+    const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
+    const int nrc = (T + 4 * RPW - 1) / (4 * RPW);
+    const dim3 grid((unsigned)(ncc * nrc)), block(256);
+    const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0);
+    // vector stores need every lane's piece aligned: I % 8 == 0 and aligned bases
+    const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 8 == 0) &&
+                         (reinterpret_cast<uintptr_t>(xhat) % 16 == 0);
+    if (vec)
+        quantize_kernel<MODE, XHAT, true, RPW><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat,
+                                                                          zc, ncc, out_vec);
+    else
+        quantize_kernel<MODE, XHAT, false, RPW><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat,
+                                                                           zc, ncc, out_vec);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, float alpha, int qmax,
+                                 float* a, float* b, unsigned long long* zero_count, hipStream_t stream) {
+    const int n = T + I;
+    scale_finalize_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(t, c, T, I, alpha, qmax, a, b,
+                                                                           zero_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
+                           int bits, void* codes, uint16_t* xhat, unsigned long long* zero_count,
+                           hipStream_t stream) {
+    const float qmax = (float)((1 << (bits - 1)) - 1);
+    uint8_t* cp = static_cast<uint8_t*>(codes);
+    if (!cp) return launch_mode<0, false>(X, T, I, ldx, a, b, qmax, nullptr, nullptr, zero_count, stream);
+    if (bits == 8)
+        return xhat ? launch_mode<1, true>(X, T, I, ldx, a, b, qmax, cp, xhat, zero_count, stream)
+                    : launch_mode<1, false>(X, T, I, ldx, a, b, qmax, cp, nullptr, zero_count, stream);
+    return xhat ? launch_mode<2, true>(X, T, I, ldx, a, b, qmax, cp, xhat, zero_count, stream)
+                : launch_mode<2, false>(X, T, I, ldx, a, b, qmax, cp, nullptr, zero_count, stream);
+}
+
+}  // namespace cq

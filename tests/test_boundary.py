@@ -1,0 +1,122 @@
+"""Host-side checks of the C-ABI library: it loads, exports what the header declares, and
+rejects bad arguments on the host before anything is launched (no GPU needed)."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "crossquant.h")
+
+
+@pytest.fixture(scope="module")
+def cq():
+    import paper_2410_07505_amd as pkg
+    return pkg
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(crossquant_\w+)\s*\(", src)))
+
+
+def test_header_declares_the_four_named_calls():
+    names = declared_functions()
+    for n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count", "crossquant_w8a8_linear"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(cq):
+    lib = ctypes.CDLL(cq.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(cq):
+    assert cq.crossquant_version() >= 100
+    seen = set()
+    for code in range(0, -8, -1):
+        s = cq.crossquant_status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert cq.crossquant_status_string(-99) == "unknown status"
+
+
+# Fake, suitably aligned, non-null "device pointers": every call below must fail validation on
+# the host, so none of them is ever dereferenced or passed to a launch.
+P = 0x10000
+
+
+def test_absmax_argument_errors(cq):
+    f = cq.raw.crossquant_absmax
+    assert f(0, 4, 8, 8, P, P, None) == -1
+    assert f(P, 4, 8, 8, 0, P, None) == -1
+    assert f(P, 4, 8, 8, P, 0, None) == -1
+    assert f(P, 0, 8, 8, P, P, None) == -2
+    assert f(P, 4, 0, 8, P, P, None) == -2
+    assert f(P, 4, 8, 7, P, P, None) == -2            # ldx < I
+    assert f(P, -1, 8, 8, P, P, None) == -2
+    assert f(P, 1 << 25, 8, 8, P, P, None) == -2
+    assert f(P + 1, 4, 8, 8, P, P, None) == -5         # binary16 needs 2-byte alignment
+    assert f(P, 4, 8, 8, P + 2, P, None) == -5
+
+
+def test_quantize_argument_errors(cq):
+    f = cq.raw.crossquant_quantize
+
+    def call(X=P, T=4, I=8, ldx=8, t=P, c=P, alpha=0.15, bits=8, codes=P, xhat=P, rs=P, cs=P, zc=P):
+        return f(X, T, I, ldx, t, c, alpha, bits, codes, xhat, rs, cs, zc, None)
+
+    assert call(X=0) == -1 and call(t=0) == -1 and call(c=0) == -1
+    assert call(codes=0) == -1 and call(rs=0) == -1 and call(cs=0) == -1
+    assert call(T=0) == -2 and call(I=0) == -2 and call(ldx=4) == -2
+    assert call(bits=3) == -3 and call(bits=16) == -3 and call(bits=0) == -3
+    assert call(bits=4, I=7, ldx=8) == -3              # INT4 packs two channels per byte
+    assert call(alpha=-0.01) == -4 and call(alpha=1.01) == -4 and call(alpha=float("nan")) == -4
+    assert call(zc=P + 4) == -5 and call(xhat=P + 1) == -5
+
+
+def test_kernel_count_argument_errors(cq):
+    f = cq.raw.crossquant_kernel_count
+
+    def call(X=P, T=4, I=8, ldx=8, t=P, c=P, alpha=1.0, bits=8, rs=P, cs=P, zc=P):
+        return f(X, T, I, ldx, t, c, alpha, bits, rs, cs, zc, None)
+
+    assert call(zc=0) == -1 and call(X=0) == -1 and call(rs=0) == -1
+    assert call(T=0) == -2
+    assert call(bits=5) == -3
+    assert call(alpha=2.0) == -4
+
+
+def test_weight_quantize_argument_errors(cq):
+    f = cq.raw.crossquant_weight_quantize
+    assert f(0, 8, 8, None, 8, P, P, None) == -1
+    assert f(P, 8, 8, None, 8, 0, P, None) == -1
+    assert f(P, 0, 8, None, 8, P, P, None) == -2
+    assert f(P, 8, 8, None, 2, P, P, None) == -3
+    assert f(P, 8, 8, P + 2, 8, P, P, None) == -5
+
+
+def test_linear_argument_errors(cq):
+    f = cq.raw.crossquant_w8a8_linear
+
+    def call(qx=P, rs=P, qw=P, ws=P, T=4, I=16, O=8, Y=P, ldy=8, acc=None):
+        return f(qx, rs, qw, ws, T, I, O, Y, ldy, acc, None)
+
+    assert call(qx=0) == -1 and call(rs=0) == -1 and call(qw=0) == -1 and call(ws=0) == -1 and call(Y=0) == -1
+    assert call(T=0) == -2 and call(O=0) == -2 and call(I=0) == -2
+    assert call(ldy=7) == -2
+    assert call(I=200000) == -2                         # accumulator could overflow int32
+    assert call(Y=P + 1) == -5 and call(acc=P + 2) == -5
+
+
+def test_python_wrappers_refuse_cpu_tensors(cq):
+    import torch
+    X = torch.zeros((4, 8), dtype=torch.float16)
+    with pytest.raises(ValueError):
+        cq.crossquant_absmax(X)

@@ -1,0 +1,403 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer, byte and index results (maxima, scale factors, codes, packed nibbles, zero
+counts, int32 accumulators) must be bit-exact; binary16 outputs are produced with the same
+operation order and are also compared bit for bit (the stated tolerance, max relative error
+1e-3, is asserted as well and is far looser)."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cq():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2410_07505_amd as pkg
+    return pkg
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def gpu(arr):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def bits16(a):
+    return np.ascontiguousarray(a).view(np.uint16)
+
+
+def bits32(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def outliers(T, I, seed, n_out=3, scale=60.0, dist="normal"):
+    return workloads.activation(T, I, dist=dist, n_outlier=min(n_out, I), scale_lo=scale, scale_hi=scale,
+                                seed=seed)
+
+
+# ----------------------------------------------------------------------------- absmax
+ABSMAX_SHAPES = [(1, 1), (1, 8), (3, 5), (37, 53), (64, 256), (130, 1000), (129, 512), (257, 1537), (1000, 24)]
+
+
+@pytest.mark.parametrize("T,I", ABSMAX_SHAPES)
+def test_absmax_small_and_ragged(cq, T, I):
+    say("absmax T=%d I=%d" % (T, I))
+    X = outliers(T, I, seed=T * 1000 + I)
+    t_ref, c_ref = oracle.absmax(X)
+    t, c = cq.crossquant_absmax(gpu(X))
+    assert np.array_equal(bits32(host(t)), bits32(t_ref))
+    assert np.array_equal(bits32(host(c)), bits32(c_ref))
+
+
+def test_absmax_strided_and_misaligned_views(cq):
+    say("absmax strided / misaligned")
+    base = outliers(70, 200, seed=5)
+    g = gpu(base)
+    for lo, hi in ((0, 96), (8, 136), (1, 130), (3, 200)):       # the last two start off 16-byte alignment
+        view = g[:, lo:hi]
+        t, c = cq.crossquant_absmax(view)
+        t_ref, c_ref = oracle.absmax(base[:, lo:hi])
+        assert np.array_equal(host(t), t_ref) and np.array_equal(host(c), c_ref), (lo, hi)
+
+
+def test_absmax_overwrites_stale_outputs_and_handles_zeros(cq):
+    import torch
+    say("absmax stale outputs")
+    X = np.zeros((40, 72), np.float16)
+    X[7, 9] = -3.0
+    t = torch.full((40,), 99.0, device="cuda")
+    c = torch.full((72,), 99.0, device="cuda")
+    cq.crossquant_absmax(gpu(X), t=t, c=c)
+    t_ref, c_ref = oracle.absmax(X)
+    assert np.array_equal(host(t), t_ref) and np.array_equal(host(c), c_ref)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_absmax_full_configs(cq, name):
+    say("absmax config %s" % name)
+    X = workloads.config_activation(name)
+    t_ref, c_ref = oracle.absmax(X)
+    t, c = cq.crossquant_absmax(gpu(X))
+    assert np.array_equal(bits32(host(t)), bits32(t_ref))
+    assert np.array_equal(bits32(host(c)), bits32(c_ref))
+
+
+# ----------------------------------------------------------------------------- scale factors
+@pytest.mark.parametrize("alpha", [0.0, 0.15, 0.45, 0.5, 0.75, 1.0])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_scale_factors_for_every_binary16_maximum(cq, alpha, bits):
+    """t and c are maxima of binary16 values, so there are only 31744 possible positive finite
+    inputs (plus zero): check the device's scale factors for all of them."""
+    import torch
+    say("scale factors alpha=%g bits=%d" % (alpha, bits))
+    vals = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float32)   # 0 .. 65504
+    n = vals.size
+    a_ref, _ = oracle.scales(vals, vals[:8], alpha, bits)
+    _, b_ref = oracle.scales(vals[:8], vals, alpha, bits)
+    # rows: T = n, I = 8
+    X = torch.zeros((n, 8), dtype=torch.float16, device="cuda")
+    t = gpu(vals)
+    c = gpu(vals[:8].copy())
+    _, _, a, _, _ = cq.crossquant_quantize(X, t, c, alpha, bits, want_xhat=False)
+    bad_a = int((bits32(host(a)) != bits32(a_ref)).sum())
+    # columns: T = 8, I = n
+    X2 = torch.zeros((8, n), dtype=torch.float16, device="cuda")
+    _, _, _, b, _ = cq.crossquant_quantize(X2, c, t, alpha, bits, want_xhat=False)
+    bad_b = int((bits32(host(b)) != bits32(b_ref)).sum())
+    assert bad_a == 0 and bad_b == 0, (bad_a, bad_b)
+
+
+# ----------------------------------------------------------------------------- quantize
+def check_quantize(cq, X, alpha, bits, Xg=None, label=""):
+    say("quantize %s shape=%s alpha=%g bits=%d" % (label, X.shape, alpha, bits))
+    Xg = gpu(X) if Xg is None else Xg
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, alpha, bits)
+    t, c = cq.crossquant_absmax(Xg)
+    codes, xhat, a, b, zc = cq.crossquant_quantize(Xg, t, c, alpha, bits)
+    # scale factors first: a mismatch here would be a pow() disagreement, not a kernel bug
+    assert np.array_equal(bits32(host(a)), bits32(ref["a"])), "row scale factors differ"
+    assert np.array_equal(bits32(host(b)), bits32(ref["b"])), "column scale factors differ"
+    got = host(codes)
+    assert got.shape == ref["codes"].shape and got.dtype == ref["codes"].dtype
+    neq = got != ref["codes"]
+    assert not neq.any(), "%d codes differ, first at %s" % (neq.sum(), np.argwhere(neq)[:4].tolist())
+    assert int(host(zc)[0]) == ref["Z"]
+    xh = host(xhat)
+    assert np.array_equal(bits16(xh), bits16(ref["xhat"]))
+    # the stated floating-point bar (implied by bit equality, kept explicit)
+    r64, g64 = ref["xhat"].astype(np.float64), xh.astype(np.float64)
+    assert np.all(np.abs(g64 - r64) <= 1e-3 * np.abs(r64))
+    assert ref["clamp_hits"] == 0
+    # codes-only and count-only variants give the same codes / count
+    codes2, none_xhat, _, _, zc2 = cq.crossquant_quantize(Xg, t, c, alpha, bits, want_xhat=False)
+    assert none_xhat is None and np.array_equal(host(codes2), ref["codes"]) and int(host(zc2)[0]) == ref["Z"]
+    zc3 = cq.crossquant_kernel_count(Xg, t, c, alpha, bits)
+    assert int(host(zc3)[0]) == ref["Z"] == oracle.kernel_count(X, t_ref, c_ref, alpha, bits)
+    return ref
+
+
+QUANT_SHAPES = [(1, 2), (3, 6), (37, 54), (64, 256), (130, 1000), (129, 520), (200, 1538)]
+
+
+@pytest.mark.parametrize("T,I", QUANT_SHAPES)
+@pytest.mark.parametrize("bits", [8, 4])
+def test_quantize_small_and_ragged(cq, T, I, bits):
+    X = outliers(T, I, seed=T + I)
+    for alpha in (0.15, 1.0):
+        check_quantize(cq, X, alpha, bits)
+
+
+def test_quantize_odd_channel_count_int8(cq):
+    X = outliers(33, 77, seed=12)
+    check_quantize(cq, X, 0.15, 8)
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.15, 0.5, 1.0])
+def test_quantize_tiny_config_all_alphas(cq, alpha):
+    X = workloads.config_activation("C1")
+    for bits in (8, 4):
+        check_quantize(cq, X, alpha, bits, label="C1")
+
+
+def test_quantize_strided_and_misaligned_input(cq):
+    base = outliers(50, 300, seed=77)
+    g = gpu(base)
+    for lo, hi in ((8, 264), (1, 257), (5, 299)):
+        view = base[:, lo:hi]
+        check_quantize(cq, view, 0.15, 8, Xg=g[:, lo:hi], label="view[%d:%d]" % (lo, hi))
+
+
+def test_quantize_zero_rows_columns_and_all_zero_matrix(cq):
+    X = outliers(40, 96, seed=3)
+    X[5, :] = 0
+    X[:, 17] = 0
+    X[9, 4] = np.float16(-0.0)
+    for alpha in (0.0, 0.15, 1.0):
+        ref = check_quantize(cq, X, alpha, 8, label="zero row/col")
+        assert np.all(ref["codes"][5] == 0) and np.all(ref["codes"][:, 17] == 0)
+    Z = np.zeros((20, 64), np.float16)
+    ref = check_quantize(cq, Z, 0.15, 8, label="all zero")
+    assert ref["Z"] == Z.size
+
+
+def test_quantize_rounding_ties(cq):
+    """Quotients that sit exactly on k + 1/2 (steps that are powers of two): the fast quotient
+    must hand these to the exact division, and half-to-even must decide them."""
+    rng = np.random.default_rng(5)
+    T, I = 96, 512
+    X = (rng.integers(-250, 251, (T, I)) / 2.0).astype(np.float16)        # multiples of 1/2
+    X[:, 0] = 127.0                                                        # t_i = 127 -> step 1 at alpha = 1
+    X[::2, 0] = -127.0
+    check_quantize(cq, X, 1.0, 8, label="ties alpha=1")
+    X4 = (rng.integers(-13, 14, (T, I)) / 2.0).astype(np.float16)
+    X4[0, :] = 7.0                                                         # c_j = 7 -> step ~1 at alpha = 0
+    check_quantize(cq, X4, 0.0, 4, label="ties alpha=0 int4")
+    check_quantize(cq, X4, 0.0, 8, label="ties alpha=0 int8")
+
+
+def test_quantize_golden_cases(cq):
+    from test_oracle_pins import read_golden
+    for case in read_golden():
+        X = case["X"]
+        Xg = gpu(X)
+        t, c = cq.crossquant_absmax(Xg)
+        codes, _, _, _, zc = cq.crossquant_quantize(Xg, t, c, case["alpha"], case["bits"])
+        got = host(codes)
+        if case["bits"] == 4:
+            assert np.array_equal(got, case["packed"])
+            got = oracle.unpack_int4(got)
+        assert np.array_equal(got, case["codes"]) and int(host(zc)[0]) == case["Z"]
+
+
+def test_quantize_with_calibrated_maxima_clamps(cq):
+    """t and c smaller than the data's maxima (e.g. calibrated elsewhere): codes saturate at
+    +-q_max exactly as in the oracle."""
+    X = outliers(48, 128, seed=9)
+    t_ref, c_ref = oracle.absmax(X)
+    t_small = (t_ref * 0.25).astype(np.float32)
+    c_small = (c_ref * 0.5).astype(np.float32)
+    for bits in (8, 4):
+        ref = oracle.quantize(X, t_small, c_small, 0.15, bits)
+        assert ref["clamp_hits"] > 0
+        codes, xhat, _, _, zc = cq.crossquant_quantize(gpu(X), gpu(t_small), gpu(c_small), 0.15, bits)
+        assert np.array_equal(host(codes), ref["codes"])
+        assert np.array_equal(bits16(host(xhat)), bits16(ref["xhat"])) and int(host(zc)[0]) == ref["Z"]
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_quantize_full_configs(cq, name):
+    cfg = workloads.CONFIGS[name]
+    X = workloads.config_activation(name)
+    Xg = gpu(X)
+    z = {}
+    for alpha in cfg.alphas + ((1.0,) if 1.0 not in cfg.alphas else ()):
+        ref = check_quantize(cq, X, alpha, cfg.bits, Xg=Xg, label=name)
+        z[alpha] = ref["Z"]
+    # direction of the paper's kernel-proportion result on outlier-channel inputs
+    assert z[0.15] < z[1.0]
+    say("%s kernel proportion: %s" % (name, {k: round(v / X.size, 4) for k, v in z.items()}))
+
+
+def test_quantize_is_deterministic(cq):
+    X = workloads.config_activation("C2")
+    Xg = gpu(X)
+    t, c = cq.crossquant_absmax(Xg)
+    r1 = cq.crossquant_quantize(Xg, t, c, 0.15, 8)
+    r2 = cq.crossquant_quantize(Xg, t, c, 0.15, 8)
+    import torch
+    assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1]) and torch.equal(r1[4], r2[4])
+
+
+# ----------------------------------------------------------------------------- weights
+WEIGHT_SHAPES = [(1, 1), (8, 8), (70, 45), (64, 64), (256, 256), (130, 1000), (1000, 130), (513, 520)]
+
+
+@pytest.mark.parametrize("I,O", WEIGHT_SHAPES)
+@pytest.mark.parametrize("bits", [8, 4])
+def test_weight_quantize_small_and_ragged(cq, I, O, bits):
+    say("weight quantize I=%d O=%d bits=%d" % (I, O, bits))
+    W = workloads.weight(I, O, seed=I + O)
+    if I > 4 and O > 4:
+        W[:, 3] = 0                                             # an all-zero output channel
+    fold = np.random.default_rng(I).uniform(0.05, 8.0, I).astype(np.float32)
+    for f in (None, fold):
+        qw_ref, s_ref = oracle.weight_quantize(W, f, bits)
+        qw, s = cq.crossquant_weight_quantize(gpu(W), None if f is None else gpu(f), bits)
+        assert np.array_equal(bits32(host(s)), bits32(s_ref))
+        assert np.array_equal(host(qw), qw_ref)
+
+
+# ----------------------------------------------------------------------------- linear
+LINEAR_SHAPES = [(1, 16, 1), (5, 32, 7), (100, 200, 300), (64, 256, 256), (256, 128, 256), (300, 208, 270),
+                 (256, 1024, 512), (513, 384, 257), (33, 100, 65)]
+
+
+@pytest.mark.parametrize("T,I,O", LINEAR_SHAPES)
+def test_linear_small_and_ragged(cq, T, I, O):
+    say("linear T=%d I=%d O=%d" % (T, I, O))
+    qx = workloads.int8_codes(T, I, seed=T)
+    qw = workloads.int8_codes(O, I, seed=O + 7)
+    rng = np.random.default_rng(T + O)
+    a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+    s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    Y, acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), want_acc=True)
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    Y2, none_acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s))
+    assert none_acc is None and np.array_equal(bits16(host(Y2)), bits16(Y_ref))
+
+
+def test_linear_extreme_accumulators(cq):
+    say("linear extremes")
+    T, I, O = 256, 8192, 256
+    qx = np.full((T, I), 127, np.int8)
+    qx[1::2] = -127
+    qw = np.full((O, I), 127, np.int8)
+    qw[::3] = -127
+    a = np.full(T, 2.0 ** -20, np.float32)
+    s = np.full(O, 2.0 ** -6, np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx[:4], a[:4], qw, s)
+    Y, acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), want_acc=True)
+    acc = host(acc)
+    assert np.array_equal(acc[:4], acc_ref) and abs(int(acc[0, 1])) == 127 * 127 * I
+    assert np.array_equal(acc[0::2], np.broadcast_to(acc[0], (T // 2, O)))
+    assert np.array_equal(acc[1::2], np.broadcast_to(acc[1], (T // 2, O)))
+    assert np.array_equal(bits16(host(Y))[:4], bits16(Y_ref))
+
+
+def test_linear_strided_output(cq):
+    import torch
+    say("linear ldy > O")
+    T, I, O = 70, 64, 40
+    qx, qw = workloads.int8_codes(T, I, seed=1), workloads.int8_codes(O, I, seed=2)
+    a = np.full(T, 0.01, np.float32)
+    s = np.full(O, 0.001, np.float32)
+    Y_ref, _ = oracle.w8a8_linear(qx, a, qw, s)
+    buf = torch.full((T, 64), 7.0, dtype=torch.float16, device="cuda")
+    cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), Y=buf[:, :O])
+    out = host(buf)
+    assert np.array_equal(bits16(out[:, :O]), bits16(Y_ref)) and np.all(out[:, O:] == 7.0)
+
+
+def test_end_to_end_tiny_config(cq):
+    """C1 through every call: absmax -> quantize -> weight quantize (folded) -> linear."""
+    say("end to end C1")
+    X, W = workloads.config_activation("C1"), workloads.config_weight("C1")
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, 0.15, 8)
+    qw_ref, s_ref = oracle.weight_quantize(W, ref["b"], 8)
+    Y_ref, acc_ref = oracle.w8a8_linear(ref["codes"], ref["a"], qw_ref, s_ref)
+    Xg, Wg = gpu(X), gpu(W)
+    t, c = cq.crossquant_absmax(Xg)
+    codes, _, a, b, _ = cq.crossquant_quantize(Xg, t, c, 0.15, 8, want_xhat=False)
+    qw, s = cq.crossquant_weight_quantize(Wg, b, 8)
+    Y, acc = cq.crossquant_w8a8_linear(codes, a, qw, s, want_acc=True)
+    assert np.array_equal(host(qw), qw_ref) and np.array_equal(bits32(host(s)), bits32(s_ref))
+    assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    full = X.astype(np.float64) @ W.astype(np.float64)
+    rel = np.linalg.norm(host(Y).astype(np.float64) - full) / np.linalg.norm(full)
+    assert rel < 0.05
+
+
+@pytest.mark.parametrize("name", ["C2", "C5"])
+def test_end_to_end_full_config_sampled(cq, name):
+    """Full-size run in the benchmark's launch configuration.  Weight codes and steps are
+    compared in full; accumulators and outputs on sampled rows and columns the oracle recomputes
+    one by one, plus exact integer checksums that cover every output in aggregate."""
+    import torch
+    say("end to end %s" % name)
+    cfg = workloads.CONFIGS[name]
+    X, W = workloads.config_activation(name), workloads.config_weight(name)
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, 0.15, 8, want_xhat=False)
+    qw_ref, s_ref = oracle.weight_quantize(W, ref["b"], 8)
+    say("oracle side ready")
+    Xg, Wg = gpu(X), gpu(W)
+    t, c = cq.crossquant_absmax(Xg)
+    codes, _, a, b, _ = cq.crossquant_quantize(Xg, t, c, 0.15, 8, want_xhat=False)
+    qw, s = cq.crossquant_weight_quantize(Wg, b, 8)
+    assert np.array_equal(host(codes), ref["codes"])
+    assert np.array_equal(bits32(host(s)), bits32(s_ref))
+    assert torch.equal(qw.cpu(), torch.from_numpy(qw_ref))
+    Y, acc = cq.crossquant_w8a8_linear(codes, a, qw, s, want_acc=True)
+    torch.cuda.synchronize()
+    say("gpu side done")
+    rng = np.random.default_rng(11)
+    rows = np.sort(rng.choice(cfg.T, 6, replace=False))
+    rows = np.unique(np.concatenate([rows, [0, cfg.T - 1, 255, 256]]))
+    cols = np.sort(rng.choice(cfg.O, 24, replace=False))
+    cols = np.unique(np.concatenate([cols, [0, cfg.O - 1, 255, 256]]))
+    Yr, accr = oracle.w8a8_linear(ref["codes"][rows], ref["a"][rows], qw_ref, s_ref)
+    assert np.array_equal(host(acc[torch.from_numpy(rows).cuda()]), accr)
+    assert np.array_equal(bits16(host(Y[torch.from_numpy(rows).cuda()])), bits16(Yr))
+    Yc, accc = oracle.w8a8_linear(ref["codes"], ref["a"], qw_ref[cols], s_ref[cols])
+    assert np.array_equal(host(acc[:, torch.from_numpy(cols).cuda()]), accc)
+    assert np.array_equal(bits16(host(Y[:, torch.from_numpy(cols).cuda()])), bits16(Yc))
+    # checksums: sum_i acc_ik = sum_j (sum_i q_ij) qw_kj ; sum_k acc_ik = sum_j q_ij (sum_k qw_kj)
+    col_sum = ref["codes"].astype(np.int64).sum(axis=0)
+    row_sum_w = qw_ref.astype(np.int64).sum(axis=0)
+    want_k = (qw_ref.astype(np.float64) @ col_sum.astype(np.float64)).astype(np.int64)   # exact: < 2^53
+    want_i = (ref["codes"].astype(np.float64) @ row_sum_w.astype(np.float64)).astype(np.int64)
+    assert np.array_equal(host(acc.sum(dim=0, dtype=torch.int64)), want_k)
+    assert np.array_equal(host(acc.sum(dim=1, dtype=torch.int64)), want_i)
+    # every output equals its own accumulator through the epilogue (checked on the GPU tensors)
+    y_from_acc = ((acc.to(torch.float32) * a[:, None]) * s[None, :]).to(torch.float16)
+    assert torch.equal(y_from_acc.view(torch.int16), Y.view(torch.int16))
