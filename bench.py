@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the CrossQuant hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input, all resident in HBM:
+  absmax (row + column maxima)  ->  quantize (codes + dequantized matrix + zero count)
+  ->  kernel count at alpha = 1 (the per-token baseline)  ->  W8A8 linear (INT8 MFMA GEMM).
+Weight quantization is weight preparation and happens once, outside the timed region.
+
+Prints one JSON line.  `value` is the quantizer's throughput (absmax + quantize stages:
+algorithmic bytes / summed stage time); the W8A8 linear's TOPS is reported beside it.  The
+`roofline` object describes the dominant kernel (the GEMM); `roofline_quantize` the fused
+quantize kernel.  Stage times come from HIP events recorded on the stream the kernels run on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published (5.0 POP/s)
+METRIC = "CrossQuant quantize GB/s (% HBM peak) + W8A8 linear TOPS (% INT8 MFMA peak)"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C5", help="workload: C2, C3 or C5 (INT8 configurations)")
+    ap.add_argument("--alpha", type=float, default=0.15)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stages", default="all",
+                    help="all, or a comma list of absmax,quantize,count,linear (for profiling one stage)")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, X, W, alpha):
+    """The CPU oracle, as it stands, timed on the host cores on a bounded sample of the same
+    workload: the full activation matrix for absmax / quantize / count, a 128-row slab of the
+    linear layer (full I x O) scaled to T rows."""
+    import numpy as np
+    import oracle
+    T, I, O = cfg.T, cfg.I, cfg.O
+    t0 = time.perf_counter()
+    t, c = oracle.absmax(X)
+    t1 = time.perf_counter()
+    ref = oracle.quantize(X, t, c, alpha, cfg.bits, want_xhat=True)
+    t2 = time.perf_counter()
+    oracle.kernel_count(X, t, c, 1.0, cfg.bits)
+    t3 = time.perf_counter()
+    slab = 128
+    Wslab_cols = O
+    qw, s = oracle.weight_quantize(W[:, :Wslab_cols], ref["b"], cfg.bits)
+    t4 = time.perf_counter()
+    oracle.w8a8_linear(ref["codes"][:slab], ref["a"][:slab], qw, s)
+    t5 = time.perf_counter()
+    n = T * I
+    q_bytes = 2 * n + (2 + 1 + 2) * n            # absmax read + quantize read/codes/xhat
+    q_time = (t1 - t0) + (t2 - t1)
+    lin_time = (t5 - t4) * (T / slab)
+    return {
+        "value": q_bytes / q_time / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "full %dx%d activation for absmax+quantize+count; linear layer on a %d-row slab "
+                  "(full %dx%d weights), time scaled by T/%d" % (T, I, slab, I, O, slab),
+        "absmax_s": t1 - t0, "quantize_s": t2 - t1, "count_s": t3 - t2,
+        "linear_s_extrapolated": lin_time, "w8a8_linear_tops": 2.0 * T * I * O / lin_time / 1e12,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (value is the one GPU's "
+              "throughput)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2410_07505_amd as cq     # raises if libcrossquant.so is missing: no fallback
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU available", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = workloads.CONFIGS[args.config]
+    if cfg.bits != 8:
+        print("bench.py: the timed step includes the W8A8 linear; pick an INT8 configuration", file=sys.stderr)
+        sys.exit(2)
+    T, I, O = cfg.T, cfg.I, cfg.O
+    alpha = args.alpha
+    stages = ("absmax", "quantize", "count", "linear") if args.stages == "all" else tuple(args.stages.split(","))
+
+    X = workloads.config_activation(args.config)
+    W = workloads.config_weight(args.config)
+    Xg = torch.from_numpy(X).to(dev)
+    Wg = torch.from_numpy(W).to(dev)
+
+    # every buffer the step touches is allocated here, once
+    t = torch.empty(T, dtype=torch.float32, device=dev)
+    c = torch.empty(I, dtype=torch.float32, device=dev)
+    a = torch.empty(T, dtype=torch.float32, device=dev)
+    b = torch.empty(I, dtype=torch.float32, device=dev)
+    a_pt = torch.empty(T, dtype=torch.float32, device=dev)
+    b_pt = torch.empty(I, dtype=torch.float32, device=dev)
+    codes = torch.empty((T, I), dtype=torch.int8, device=dev)
+    xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
+    zc = torch.zeros(1, dtype=torch.int64, device=dev)
+    zc_pt = torch.zeros(1, dtype=torch.int64, device=dev)
+    Y = torch.empty((T, O), dtype=torch.float16, device=dev)
+    qw = torch.empty((O, I), dtype=torch.int8, device=dev)
+    ws = torch.empty(O, dtype=torch.float32, device=dev)
+
+    # weight preparation (once): needs the column factors of this activation
+    cq.crossquant_absmax(Xg, t=t, c=c)
+    cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b, zero_count=zc)
+    cq.crossquant_weight_quantize(Wg, b, 8, qw=qw, w_scale=ws)
+    torch.cuda.synchronize()
+    del Wg
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record()
+        if "absmax" in stages:
+            cq.crossquant_absmax(Xg, t=t, c=c)
+        if ev is not None:
+            ev[1].record()
+        if "quantize" in stages:
+            cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
+                                   zero_count=zc)
+        if ev is not None:
+            ev[2].record()
+        if "count" in stages:
+            cq.crossquant_kernel_count(Xg, t, c, 1.0, 8, row_scale=a_pt, col_scale=b_pt, zero_count=zc_pt)
+        if ev is not None:
+            ev[3].record()
+        if "linear" in stages:
+            cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)
+        if ev is not None:
+            ev[4].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    stage_ms = np.zeros(4)
+    for ev in events:
+        for s_ in range(4):
+            stage_ms[s_] += ev[s_].elapsed_time(ev[s_ + 1])
+    stage_ms /= args.steps
+    ms_per_step = wall * 1e3 / args.steps
+
+    n = T * I
+    bytes_absmax = 2 * n + 4 * (T + I)
+    bytes_quant = (2 + 1 + 2) * n + 4 * (T + I)
+    bytes_count = 2 * n
+    ops_linear = 2.0 * T * I * O
+    quant_gbs = (bytes_absmax + bytes_quant) / ((stage_ms[0] + stage_ms[1]) * 1e-3) / 1e9 \
+        if stage_ms[0] + stage_ms[1] > 0 else 0.0
+    tops = ops_linear / (stage_ms[3] * 1e-3) / 1e12 if stage_ms[3] > 0 else 0.0
+
+    z, z_pt = int(zc.item()), int(zc_pt.item())
+    out = {
+        "metric": METRIC,
+        "value": quant_gbs, "unit": "GB/s",
+        "quantize_frac_hbm_peak": quant_gbs / HBM_PEAK_GBS,
+        "w8a8_linear_tops": tops, "w8a8_linear_frac_int8_peak": tops / INT8_PEAK_TOPS,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp16 in, fp32 scale arithmetic, int8 codes, int32 accumulate",
+        "data": "synthetic (seeded N(0,1) activations with outlier channels, N(0,0.02) weights)",
+        "config": {"workload": "%s: %s" % (cfg.name, cfg.label), "T": T, "I": I, "O": O, "bits": 8,
+                   "alpha": alpha, "stages": list(stages)},
+        "stage_ms": {"absmax": stage_ms[0], "quantize": stage_ms[1], "count_per_token": stage_ms[2],
+                     "w8a8_linear": stage_ms[3]},
+        "stage_rate": {
+            "absmax_GBs": bytes_absmax / (stage_ms[0] * 1e-3) / 1e9 if stage_ms[0] > 0 else None,
+            "quantize_GBs": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
+            "count_GBs": bytes_count / (stage_ms[2] * 1e-3) / 1e9 if stage_ms[2] > 0 else None,
+        },
+        "kernel_proportion": {"crossquant": z / n, "per_token": z_pt / n},
+        "roofline": {"kernel": "gemm_i8_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
+                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS, "traffic": None},
+        "roofline_quantize": {"kernel": "quantize_kernel (codes + xhat + zero count) incl. scale finalize",
+                              "bound": "hbm",
+                              "achieved": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": (bytes_quant / (stage_ms[1] * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                              if stage_ms[1] > 0 else None,
+                              "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, X, W, alpha)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,7 +163,7 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
                 if (GENERIC && col >= O) continue;
                 const int v = acc[mi][ni][r];
                 float y = (float)v * a;
-                y = y * w_scale[col];
+                y = rounded_f32(y * w_scale[col]);
                 Y[(int64_t)row * ldy + col] = (uint16_t)f2h(y);
                 if (acc_debug) acc_debug[(int64_t)row * O + col] = v;
             }

@@ -14,6 +14,14 @@ __device__ __forceinline__ uint32_t f2h(float f) {
     return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);
 }
 
+// A binary32 value that must be rounded on its own before it is converted to binary16: passing
+// it through an empty asm keeps the compiler from folding the multiply that produced it into a
+// mixed-precision multiply-convert, which would round once where the specification rounds twice.
+__device__ __forceinline__ float rounded_f32(float v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 // t[0..T), c[0..I) <- 0 ; then one pass over X accumulating both maxima.
 hipError_t launch_absmax(const uint16_t* X, int T, int I, int64_t ldx, float* t, float* c,
                          hipStream_t stream);

@@ -181,7 +181,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             if (XHAT) {
                 float y[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = (m[e] - kMagic) * (a * b[e]);
+                for (int e = 0; e < 8; ++e) y[e] = rounded_f32((m[e] - kMagic) * (a * b[e]));
                 uint16_t* dst = xhat + (int64_t)r * I + j0;
                 if (out_vec && nvalid == 8) {
                     *reinterpret_cast<uint4*>(dst) = make_uint4(pack_half2(y[0], y[1]), pack_half2(y[2], y[3]),
