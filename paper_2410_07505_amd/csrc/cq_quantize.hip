@@ -8,11 +8,13 @@
 // the per-element instruction count has to stay small.  A correctly rounded binary32 division
 // costs more than the rest of the element's work together, so it is taken only where it can
 // matter: the quotient is first approximated as x * (1/a_i) * (1/b_j) (reciprocals formed once
-// per row / per lane), whose relative error is below 6 * 2^-24; the rounded integer can differ
-// from the one the exact quotient gives only if the approximation lies within that error of a
-// rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2 (a 5x margin over the bound) and
-// a wave in which any lane trips recomputes its eight elements with the exact division.  The
-// result is therefore identical, bit for bit, to dividing every element.
+// per row / per lane, each within 1 ulp), which lies within 2^-21 relative of the correctly
+// rounded quotient (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own);
+// the rounded integer can differ from the one the exact quotient gives only if the approximation
+// lies within that distance of a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2
+// (a 4x margin over the bound) and a wave in which any lane trips recomputes its eight elements
+// with the exact division.  The result is therefore identical, bit for bit, to dividing every
+// element.
 //
 // Rounding to nearest-even integer and conversion to two's complement are one add of the
 // constant 1.5 * 2^23: the sum's low mantissa bits are the code.
@@ -24,7 +26,6 @@ namespace {
 constexpr int kLanes = 64;
 constexpr int kColsPerWave = kLanes * 8;
 constexpr float kMagic = 12582912.0f;            // 1.5 * 2^23
-constexpr uint32_t kMagicBits = 0x4B400000u;
 constexpr float kTieTol = 1.9073486328125e-06f;  // 2^-19
 
 __global__ void scale_finalize_kernel(const float* __restrict__ t, const float* __restrict__ c, int T,
@@ -79,20 +80,30 @@ __device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_
     return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
 }
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 8;   // waves per block
+constexpr int kU = 4;       // rows a wave has in flight
+
 // MODE 0: count only; 1: INT8 codes; 2: packed INT4 codes.
-template <int MODE, bool XHAT, bool VEC, int RPW>
-__global__ void __launch_bounds__(256)
+// Block: 8 waves sharing 512 columns; each wave streams over nb batches of 4 consecutive rows.
+// Outputs are written with non-temporal stores: they are not read again by this kernel, and
+// keeping them out of the caches leaves room for the X rows still to be read.
+template <int MODE, bool XHAT, bool VEC>
+__global__ void __launch_bounds__(kWaves * kLanes)
 quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ a_vec,
                 const float* __restrict__ b_vec, float qmax, uint8_t* __restrict__ codes,
                 uint16_t* __restrict__ xhat, unsigned long long* __restrict__ zero_count,
-                int n_col_chunks, bool out_vec) {
-    __shared__ uint32_t lds_cnt[4];
+                int n_col_chunks, int nb, bool out_vec) {
+    __shared__ uint32_t lds_cnt[kWaves];
     const int lane = threadIdx.x & (kLanes - 1);
     const int wave = threadIdx.x / kLanes;
     const int col_chunk = blockIdx.x % n_col_chunks;
     const int row_chunk = blockIdx.x / n_col_chunks;
     const int j0 = col_chunk * kColsPerWave + lane * 8;
-    const int row0 = row_chunk * (4 * RPW) + wave * RPW;
+    const int rows_per_wave = nb * kU;                      // <= 64
+    const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
 
     float b[8], rb[8];
 #pragma unroll
@@ -100,24 +111,27 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
         b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
         rb[e] = (b[e] == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(b[e]);
     }
-    int nvalid = I - j0;                       // columns of this lane that exist
+    int nvalid = I - j0;                                    // columns of this lane that exist
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
+    // the wave's row factors, one per lane, handed out with readlane as the rows come up
+    const float a_lane = (lane < rows_per_wave && row0 + lane < T) ? a_vec[row0 + lane] : 0.0f;
 
-    uint32_t zeros = 0;
-    constexpr int U = 4;
-    static_assert(RPW % U == 0, "rows per wave must be a multiple of the unroll");
-    for (int k0 = 0; k0 < RPW; k0 += U) {
-        uint4 v[U];
+    float nonzero = 0.0f;     // codes != 0 seen by this lane (exact: far below 2^24)
+    int rows_done = 0;
+    for (int bi = 0; bi < nb; ++bi) {
+        const int rbase = row0 + bi * kU;
+        if (rbase >= T) break;                              // wave-uniform
+        uint4 v[kU];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = row0 + k0 + u;
-            v[u] = (r < T) ? load8<VEC>(X + (int64_t)r * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
-        }
+        for (int u = 0; u < kU; ++u)
+            v[u] = (rbase + u < T) ? load8<VEC>(X + (int64_t)(rbase + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = row0 + k0 + u;
-            if (r >= T) break;                 // wave-uniform
-            const float a = a_vec[r];
+        for (int u = 0; u < kU; ++u) {
+            const int r = rbase + u;
+            if (r >= T) break;                              // wave-uniform
+            ++rows_done;
+            const float a = __builtin_bit_cast(
+                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), bi * kU + u));
             const float ra = (a == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(a);
             float x[8];
             x[0] = half_lo(v[u].x); x[1] = half_hi(v[u].x);
@@ -126,21 +140,21 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             x[6] = half_lo(v[u].w); x[7] = half_hi(v[u].w);
 
             float m[8];
-            bool near_tie = false;
+            float score = 0.0f;                             // max over the 8 elements of |frac| + |r| * tol
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float rt = x[e] * (ra * rb[e]);
-                rt = __builtin_fminf(__builtin_fmaxf(rt, -qmax), qmax);
+                rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
                 m[e] = rt + kMagic;
                 const float f = rt - (m[e] - kMagic);
-                near_tie |= (__builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)) >= 0.5f);
+                score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)));
             }
-            if (__any(near_tie)) {             // rare: exact division for this wave's row piece
+            if (__any(score >= 0.5f)) {                     // rare: exact division for this wave's row piece
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float D = a * b[e];
                     float rt = (D == 0.0f) ? 0.0f : x[e] / D;
-                    rt = __builtin_fminf(__builtin_fmaxf(rt, -qmax), qmax);
+                    rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
                     m[e] = rt + kMagic;
                 }
             }
@@ -149,7 +163,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 u32[e] = __float_as_uint(m[e]);
-                zeros += (uint32_t)__popcll(__ballot(u32[e] == kMagicBits && e < nvalid));
+                nonzero += __builtin_fminf(__builtin_fabsf(m[e] - kMagic), 1.0f);
             }
 
             if (MODE == 1) {
@@ -157,7 +171,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
                 const uint32_t w1 = pack_bytes(u32[4], u32[5], u32[6], u32[7]);
                 uint8_t* dst = codes + (int64_t)r * I + j0;
                 if (out_vec && nvalid == 8) {
-                    *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+                    __builtin_nontemporal_store(u32x2{w0, w1}, reinterpret_cast<u32x2*>(dst));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
@@ -171,7 +185,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
                 const uint32_t w = __builtin_amdgcn_perm(w1, w0, 0x06040200u);
                 uint8_t* dst = codes + (int64_t)r * (I / 2) + j0 / 2;
                 if (out_vec && nvalid == 8) {
-                    *reinterpret_cast<uint32_t*>(dst) = w;
+                    __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(dst));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -184,8 +198,9 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
                 for (int e = 0; e < 8; ++e) y[e] = rounded_f32((m[e] - kMagic) * (a * b[e]));
                 uint16_t* dst = xhat + (int64_t)r * I + j0;
                 if (out_vec && nvalid == 8) {
-                    *reinterpret_cast<uint4*>(dst) = make_uint4(pack_half2(y[0], y[1]), pack_half2(y[2], y[3]),
-                                                                pack_half2(y[4], y[5]), pack_half2(y[6], y[7]));
+                    __builtin_nontemporal_store(u32x4{pack_half2(y[0], y[1]), pack_half2(y[2], y[3]),
+                                                      pack_half2(y[4], y[5]), pack_half2(y[6], y[7])},
+                                                reinterpret_cast<u32x4*>(dst));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
@@ -196,10 +211,17 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     }
 
     if (zero_count) {
-        if (lane == 0) lds_cnt[wave] = zeros;  // the ballot counts are already wave totals
+        // padded columns and rows hold x = 0 and add nothing to `nonzero`
+        uint32_t zeros = (uint32_t)(rows_done * nvalid) - (uint32_t)nonzero;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) zeros += (uint32_t)__shfl_xor((int)zeros, off, kLanes);
+        if (lane == 0) lds_cnt[wave] = zeros;
         __syncthreads();
         if (threadIdx.x == 0) {
-            const uint32_t s = lds_cnt[0] + lds_cnt[1] + lds_cnt[2] + lds_cnt[3];
+            uint32_t s = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += lds_cnt[w];
+            // one atomic per block: same-address atomics serialise, so the grid is kept small
             if (s) atomicAdd(zero_count, (unsigned long long)s);
         }
     }
@@ -209,20 +231,22 @@ template <int MODE, bool XHAT>
 hipError_t launch_mode(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
                        float qmax, uint8_t* codes, uint16_t* xhat, unsigned long long* zc,
                        hipStream_t stream) {
-    constexpr int RPW = 8;
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
-    const int nrc = (T + 4 * RPW - 1) / (4 * RPW);
-    const dim3 grid((unsigned)(ncc * nrc)), block(256);
+    // rows per block = 32 * nb; keep about 512 blocks in flight
+    int nb = 16;
+    while (nb > 1 && (int64_t)ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
+    const int nrc = (T + 32 * nb - 1) / (32 * nb);
+    const dim3 grid((unsigned)(ncc * nrc)), block(kWaves * kLanes);
     const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0);
     // vector stores need every lane's piece aligned: I % 8 == 0 and aligned bases
     const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 8 == 0) &&
                          (reinterpret_cast<uintptr_t>(xhat) % 16 == 0);
     if (vec)
-        quantize_kernel<MODE, XHAT, true, RPW><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat,
-                                                                          zc, ncc, out_vec);
+        quantize_kernel<MODE, XHAT, true><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat, zc,
+                                                                     ncc, nb, out_vec);
     else
-        quantize_kernel<MODE, XHAT, false, RPW><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat,
-                                                                           zc, ncc, out_vec);
+        quantize_kernel<MODE, XHAT, false><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat, zc,
+                                                                      ncc, nb, out_vec);
     return hipGetLastError();
 }
 
