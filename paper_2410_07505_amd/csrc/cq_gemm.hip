@@ -17,6 +17,8 @@
 //     compact patch), then walked in groups of 4 tile-rows so that concurrently resident tiles
 //     share A rows and B columns.
 // Integer accumulation is exact, so tiling and order cannot change a result.
+#include <type_traits>
+
 #include "cq_kernels.h"
 
 namespace cq {
@@ -29,8 +31,17 @@ constexpr int BM = 256, BN = 256, BK = 128;
 constexpr int kThreads = 256;
 constexpr int kStageBytes = (BM + BN) * BK;       // 64 KiB
 constexpr int kLdsBytes = 2 * kStageBytes;         // 128 KiB
-constexpr int kXcds = 8;
-constexpr int kGroupM = 4;
+#ifndef CQ_GEMM_XCDS
+#define CQ_GEMM_XCDS 8
+#endif
+#ifndef CQ_GEMM_GROUP_M
+#define CQ_GEMM_GROUP_M 4
+#endif
+#ifndef CQ_GEMM_WAVES
+#define CQ_GEMM_WAVES 8
+#endif
+constexpr int kXcds = CQ_GEMM_XCDS;       // block ids are dealt round-robin to this many L2 domains
+constexpr int kGroupM = CQ_GEMM_GROUP_M;  // tile-rows walked together
 
 __device__ __forceinline__ int swz(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) * 16; }
 
@@ -171,6 +182,212 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Fast path (full tiles, 16-byte aligned operands): global -> LDS loads that bypass registers.
+// global_load_lds_dwordx4 writes the 64 lanes' 16-byte pieces to LDS at base + lane * 16, i.e. one
+// instruction fills 8 consecutive 128-byte LDS rows.  The XOR swizzle is therefore applied on
+// the global side: the lane that will land in physical chunk p of row R fetches logical chunk
+// p ^ ((R >> 1) & 7) of that row (still the same 128 contiguous bytes per 8 lanes).
+// Software pipeline per K step (4 slabs of 32 bytes, fragment registers F0/F1 alternate):
+//   read slab1 | mfma slab0 ; read slab2 | mfma slab1 ; read slab3 | mfma slab2 ;
+//   wait for the next tile, barrier ; issue the loads of the tile after next into the stage
+//   just released ; read slab0 of the next tile | mfma slab3.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// s_waitcnt immediate for gfx9-family encodings: vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no
+// wait), lgkmcnt 11:8 (15 = no wait)
+constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
+
+// a_off / b_off: byte offset of this lane's row and swizzled chunk for slab 0; slab ks flips the
+// chunk's bits 1-2, i.e. XORs the byte offset with ks * 32
+template <int NI>
+__device__ __forceinline__ void load_frags(v4i (&af)[4], v4i (&bf)[NI], const int8_t* As, const int8_t* Bs,
+                                           int a_off, int b_off, int ks) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) af[mi] = *reinterpret_cast<const v4i*>(As + mi * 32 * BK + (a_off ^ (ks * 32)));
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) bf[ni] = *reinterpret_cast<const v4i*>(Bs + ni * 32 * BK + (b_off ^ (ks * 32)));
+}
+
+template <int NI>
+__device__ __forceinline__ void mfma_slab(v16i (&acc)[4][NI], const v4i (&af)[4], const v4i (&bf)[NI]) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
+}
+
+// NWAVES = 8: waves in a 2 x 4 arrangement, each 128 x 64 (4 x 2 MFMA tiles, 128 accumulator
+// registers), two waves per SIMD.  A wave can only start a vector-memory instruction about every
+// 100 ns on this chip, so 8 waves are needed to bring in a 64 KiB tile per K step at the rate the
+// matrix pipes consume it; two resident waves per SIMD also cover each other's barrier and issue
+// stalls.  (NWAVES = 4: 2 x 2 waves of 128 x 128, kept for comparison.)
+template <int NWAVES>
+__global__ void __launch_bounds__(NWAVES * 64)
+gemm_i8_direct_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
+                      const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I, int O,
+                      uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
+                      int tiles_n) {
+    constexpr int WN = NWAVES / 2;            // waves along N
+    constexpr int WTN = BN / WN;              // wave tile width (128 or 64)
+    constexpr int NI = WTN / 32;              // MFMA tiles along N per wave
+    constexpr int LROWS = BM / NWAVES;        // LDS rows of each operand a wave fills per K step
+    constexpr int LINST = LROWS / 8;          // load instructions per operand per wave per K step
+    extern __shared__ __align__(16) int8_t lds[];
+
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    const int L = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (L >= total) return;
+    const int group_sz = kGroupM * tiles_n;
+    const int g = L / group_sz;
+    const int gm = min(kGroupM, tiles_m - g * kGroupM);
+    const int in_g = L - g * group_sz;
+    const int tile_m = g * kGroupM + in_g % gm;
+    const int tile_n = in_g / gm;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int nk = I / BK;
+
+    // ---- loader: wave w fills LDS rows [LROWS*w, LROWS*(w+1)) of A and of B; instruction ii
+    // covers rows LROWS*w + 8*ii + (lane >> 3), physical chunk lane & 7.
+    const int ld_r = lane >> 3, ld_p = lane & 7;
+    const int8_t* ga[2];
+    const int8_t* gb[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {      // rows of even / odd ii differ in (R >> 1) & 7 by 4
+        const int R = LROWS * wave + 8 * par + ld_r;
+        const int c = ld_p ^ ((R >> 1) & 7);
+        ga[par] = qx + (int64_t)(m0 + R) * I + c * 16;
+        gb[par] = qw + (int64_t)(n0 + R) * I + c * 16;
+    }
+    auto issue_tile = [&](int kt, int stage) {
+        int8_t* As = lds + stage * kStageBytes + wave * (LROWS * BK);
+        int8_t* Bs = As + BM * BK;
+        const int64_t koff = (int64_t)kt * BK;
+#pragma unroll
+        for (int ii = 0; ii < LINST; ++ii) {
+            const int64_t roff = (int64_t)(ii >> 1) * 16 * I + koff;      // rows advance by 16 per pair
+            __builtin_amdgcn_global_load_lds((gptr_t)(ga[ii & 1] + roff), (lptr_t)(As + ii * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(gb[ii & 1] + roff), (lptr_t)(Bs + ii * 1024), 16, 0, 0);
+        }
+    };
+
+    // ---- fragment addressing: lane supplies row (lane & 31), 16-byte half (lane >> 5) of each
+    // 32-byte slab; logical chunk = 2 * ks + half, physical = logical ^ ((row >> 1) & 7).
+    // (row >> 1) & 7 depends only on lane & 15 here because the row bases are multiples of 32.
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int sw = (frag_row >> 1) & 7;
+    const int a_off = (wm * 128 + frag_row) * BK + ((frag_half ^ sw) * 16);
+    const int b_off = (wn * WTN + frag_row) * BK + ((frag_half ^ sw) * 16);
+
+    v16i acc[4][NI];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0;
+
+    issue_tile(0, 0);
+    if (nk > 1) issue_tile(1, 1);
+    // tile 0 must have landed; tile 1 (2 * LINST loads per wave) may still be in flight
+    if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LINST, 15));
+    else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    __syncthreads();
+
+    v4i af0[4], bf0[NI], af1[4], bf1[NI];
+    load_frags<NI>(af0, bf0, lds, lds + BM * BK, a_off, b_off, 0);
+
+    constexpr int NMF = 4 * NI;               // MFMAs per slab
+    constexpr int NRD = 4 + NI;               // fragment reads per slab
+    // One K step.  ISSUE: refill the stage this step releases with the tile two steps ahead.
+    // PREFETCH: read slab 0 of the next tile while the last slab of this one is multiplied.
+    // The sched_group_barrier sequences ask the scheduler to alternate LDS reads (and the
+    // global -> LDS loads) with MFMAs instead of clustering them, so the matrix pipe keeps
+    // issuing while the fragments of the following slab arrive.
+    auto interleave_reads = [&]() {
+#pragma unroll
+        for (int i = 0; i < NMF - NRD; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+        }
+#pragma unroll
+        for (int i = NMF - NRD; i < NRD; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value;
+        constexpr bool PREFETCH = decltype(prefetch_c)::value;
+        const int8_t* As = lds + (kt & 1) * kStageBytes;
+        const int8_t* Bs = As + BM * BK;
+        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 1);
+        mfma_slab<NI>(acc, af0, bf0);
+        interleave_reads();
+        load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, 2);
+        mfma_slab<NI>(acc, af1, bf1);
+        interleave_reads();
+        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 3);
+        mfma_slab<NI>(acc, af0, bf0);
+        interleave_reads();
+        // every read of this stage has been issued; the next tile (other stage) must have landed
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (ISSUE) issue_tile(kt + 2, kt & 1);          // refill the stage everyone has finished with
+        if (PREFETCH) {
+            const int8_t* An = lds + ((kt + 1) & 1) * kStageBytes;
+            load_frags<NI>(af0, bf0, An, An + BM * BK, a_off, b_off, 0);
+        }
+        mfma_slab<NI>(acc, af1, bf1);
+#pragma unroll
+        for (int i = 0; i < NMF; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                              // 1 MFMA
+            if (PREFETCH && i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 DS read
+            if (ISSUE && i < 2 * LINST) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global -> LDS load
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) k_step(kt, yes{}, yes{});
+    if (kt + 1 < nk) {
+        k_step(kt, no{}, yes{});
+        ++kt;
+    }
+    k_step(kt, no{}, no{});
+
+    // ---- epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm * 128 + mi * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+            const float a = row_scale[row];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const int col = n0 + wn * WTN + ni * 32 + frag_row;
+                const int v = acc[mi][ni][r];
+                float y = (float)v * a;
+                y = rounded_f32(y * w_scale[col]);
+                Y[(int64_t)row * ldy + col] = (uint16_t)f2h(y);
+                if (acc_debug) acc_debug[(int64_t)row * O + col] = v;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_t* qw, const float* w_scale,
@@ -188,8 +405,12 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_kernel<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
-        gemm_i8_kernel<false><<<grid, block, kLdsBytes, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
-                                                                  acc_debug, tiles_m, tiles_n, vec);
+        constexpr int NW = CQ_GEMM_WAVES;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_direct_kernel<NW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        gemm_i8_direct_kernel<NW><<<grid, dim3(NW * 64), kLdsBytes, stream>>>(
+            qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
