@@ -212,13 +212,16 @@ __device__ __forceinline__ void load_frags(v4i (&af)[4], v4i (&bf)[NI], const in
     for (int ni = 0; ni < NI; ++ni) bf[ni] = *reinterpret_cast<const v4i*>(Bs + ni * 32 * BK + (b_off ^ (ks * 32)));
 }
 
+// The weight fragment is passed as the first MFMA operand, so the accumulator tile is laid out
+// transposed: lane l holds token (l & 31) and, per group of 4 registers, 4 consecutive output
+// channels 8*(r/4) + 4*(l/32) + (r%4) -- which is what lets the epilogue write 8-byte pieces.
 template <int NI>
 __device__ __forceinline__ void mfma_slab(v16i (&acc)[4][NI], const v4i (&af)[4], const v4i (&bf)[NI]) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[ni], af[mi], acc[mi][ni], 0, 0, 0);
 }
 
 // NWAVES = 8: waves in a 2 x 4 arrangement, each 128 x 64 (4 x 2 MFMA tiles, 128 accumulator
@@ -368,23 +371,56 @@ gemm_i8_direct_kernel(const int8_t* __restrict__ qx, const float* __restrict__ r
     }
     k_step(kt, no{}, no{});
 
-    // ---- epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    // ---- epilogue.  Lane l holds token t = l & 31 of each 32-token block and, for register group
+    // rg = r / 4, the 4 consecutive channels 8*rg + 4*(l >> 5) + {0..3} of each 32-channel block.
+    // Scaled binary16 results go through LDS (free now: the K loop ended on a barrier with no
+    // reads outstanding) so that every global store is a full 16 bytes per lane and a wave
+    // writes whole 128-byte row pieces; a wave can only start a vector-memory instruction every
+    // ~100 ns, so 2-byte scattered stores would cost more than the K loop of a small GEMM.
+    constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
+    int8_t* stage = lds + wave * (128 * kRowPitch);      // this wave's 128 x WTN staging area
+    const int t_lane = lane & 31;
+    float a_t[4];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[m0 + wm * 128 + mi * 32 + t_lane];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 128 + mi * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-            const float a = row_scale[row];
+    for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int col = n0 + wn * WTN + ni * 32 + frag_row;
-                const int v = acc[mi][ni][r];
-                float y = (float)v * a;
-                y = rounded_f32(y * w_scale[col]);
-                Y[(int64_t)row * ldy + col] = (uint16_t)f2h(y);
-                if (acc_debug) acc_debug[(int64_t)row * O + col] = v;
+        for (int rg = 0; rg < 4; ++rg) {
+            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
+            const float4 s4 = *reinterpret_cast<const float4*>(w_scale + n0 + wn * WTN + o_loc);
+            const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                uint32_t h[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float y = (float)acc[mi][ni][rg * 4 + j] * a_t[mi];
+                    y = rounded_f32(y * sv[j]);
+                    h[j] = f2h(y);
+                }
+                *reinterpret_cast<uint2*>(stage + (mi * 32 + t_lane) * kRowPitch + o_loc * 2) =
+                    make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                if (acc_debug) {
+                    const int row = m0 + wm * 128 + mi * 32 + t_lane;
+                    int4 v = make_int4(acc[mi][ni][rg * 4 + 0], acc[mi][ni][rg * 4 + 1], acc[mi][ni][rg * 4 + 2],
+                                       acc[mi][ni][rg * 4 + 3]);
+                    *reinterpret_cast<int4*>(acc_debug + (int64_t)row * O + n0 + wn * WTN + o_loc) = v;
+                }
             }
         }
+    }
+    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 16)
+    constexpr int kRowsPerInst = 64 / kLanesPerRow;
+    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+#pragma unroll
+    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
+        const int trow = i * kRowsPerInst + rsub;
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
+        uint16_t* dst = Y + (int64_t)(m0 + wm * 128 + trow) * ldy + n0 + wn * WTN + piece * 8;
+        *reinterpret_cast<uint4*>(dst) = v;
     }
 }
 
@@ -399,17 +435,21 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
     const dim3 grid((unsigned)(per_xcd * kXcds)), block(kThreads);
     const bool vec = (reinterpret_cast<uintptr_t>(qx) % 16 == 0) && (reinterpret_cast<uintptr_t>(qw) % 16 == 0) &&
                      (I % 16 == 0);
-    const bool full = vec && (T % BM == 0) && (O % BN == 0) && (I % BK == 0);
+    auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+    // fast path: whole tiles and everything the vector loads/stores touch aligned to 16 bytes
+    const bool full = vec && (T % BM == 0) && (O % BN == 0) && (I % BK == 0) && al16(Y) && (ldy % 8 == 0) &&
+                      al16(w_scale) && al16(acc_debug);
     hipError_t e;
     if (full) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
         constexpr int NW = CQ_GEMM_WAVES;
+        constexpr int kWtn = BN / (NW / 2);
+        // K-loop stages (128 KiB) or the epilogue's staging area, whichever is larger
+        constexpr int kDirectLds = (NW * 128 * (kWtn * 2 + 8) > kLdsBytes) ? NW * 128 * (kWtn * 2 + 8) : kLdsBytes;
+        static_assert(kDirectLds <= 160 * 1024, "LDS budget of a gfx950 CU");
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_direct_kernel<NW>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kDirectLds);
         if (e != hipSuccess) return e;
-        gemm_i8_direct_kernel<NW><<<grid, dim3(NW * 64), kLdsBytes, stream>>>(
+        gemm_i8_direct_kernel<NW><<<grid, dim3(NW * 64), kDirectLds, stream>>>(
             qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_kernel<true>),
