@@ -27,6 +27,13 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published (5.0 POP/s)
 METRIC = "CrossQuant quantize GB/s (% HBM peak) + W8A8 linear TOPS (% INT8 MFMA peak)"
 
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a plain copy of known size (profiles/bench_c5_hbm_traffic_pmc.txt).  Measured
+# once per workload; null for workloads that have not been profiled.
+MEASURED_TRAFFIC_BYTES = {
+    "C5": {"gemm": (1345.9 + 224.0) * 2 ** 20, "quantize": (64.4 + 96.1) * 2 ** 20},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -38,6 +45,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", default="all",
                     help="all, or a comma list of absmax,quantize,count,linear (for profiling one stage)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of known size (calibrates HBM byte counters under "
+                         "rocprofv3 --pmc) and exit")
     return ap.parse_args()
 
 
@@ -83,6 +93,16 @@ def main():
 
     import numpy as np
     import torch
+
+    if args.copy_calibration:
+        # 20 copies of a 256 MiB buffer: reads 256 MiB and writes 256 MiB per launch
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 20}}))
+        return
 
     import paper_2410_07505_amd as cq     # raises if libcrossquant.so is missing: no fallback
     import workloads
@@ -196,15 +216,16 @@ def main():
             "count_GBs": bytes_count / (stage_ms[2] * 1e-3) / 1e9 if stage_ms[2] > 0 else None,
         },
         "kernel_proportion": {"crossquant": z / n, "per_token": z_pt / n},
-        "roofline": {"kernel": "gemm_i8_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
-                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS, "traffic": None},
+        "roofline": {"kernel": "gemm_i8_direct_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
+                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},
         "roofline_quantize": {"kernel": "quantize_kernel (codes + xhat + zero count) incl. scale finalize",
                               "bound": "hbm",
                               "achieved": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
                               "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": (bytes_quant / (stage_ms[1] * 1e-3) / 1e9 / HBM_PEAK_GBS)
                               if stage_ms[1] > 0 else None,
-                              "traffic": None},
+                              "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("quantize")},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, X, W, alpha)
