@@ -194,6 +194,18 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
 //   wait for the next tile, barrier ; issue the loads of the tile after next into the stage
 //   just released ; read slab0 of the next tile | mfma slab3.
 // ---------------------------------------------------------------------------------------------
+#ifdef CQ_GEMM_PROFILE
+// development aid: per-phase cycle totals of wave 0 of block 0 (not compiled into the library)
+__device__ unsigned long long g_phase_cycles[8];
+__device__ unsigned long long g_trace[8][8][8];   // [wave][step - 20][stamp]
+#define CQ_STAMP(i) do { const unsigned long long now_ = __builtin_amdgcn_s_memtime(); \
+                         if (prof_on) { phase_acc[i] += now_ - last_stamp; last_stamp = now_; } \
+                         if (blockIdx.x == 0 && lane == 0 && cur_kt >= 20 && cur_kt < 28 && (i) < 8) \
+                             g_trace[wave][cur_kt - 20][i] = now_; } while (0)
+#else
+#define CQ_STAMP(i) do { } while (0)
+#endif
+
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -222,6 +234,64 @@ __device__ __forceinline__ void mfma_slab(v16i (&acc)[4][NI], const v4i (&af)[4]
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
             acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[ni], af[mi], acc[mi][ni], 0, 0, 0);
+}
+
+// Epilogue shared by the fast-path kernels.  Lane l holds token t = l & 31 of each 32-token block
+// and, for register group rg = r / 4, the 4 consecutive channels 8*rg + 4*(l >> 5) + {0..3} of
+// each 32-channel block.  Scaled binary16 results go through LDS (free once the K loop has ended
+// on a barrier with no reads outstanding) so that every global store is a full 16 bytes per lane
+// and a wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
+template <int WTN, int NI>
+__device__ __forceinline__ void epilogue_store(v16i (&acc)[4][NI], int8_t* lds, const float* __restrict__ row_scale,
+                                               const float* __restrict__ w_scale, uint16_t* __restrict__ Y,
+                                               int64_t ldy, int32_t* __restrict__ acc_debug, int O, int row0,
+                                               int col0, int lane, int wave) {
+    const int frag_half = lane >> 5;
+    constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
+    int8_t* stage = lds + wave * (128 * kRowPitch);      // this wave's 128 x WTN staging area
+    const int t_lane = lane & 31;
+    float a_t[4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[row0 + mi * 32 + t_lane];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
+            const float4 s4 = *reinterpret_cast<const float4*>(w_scale + col0 + o_loc);
+            const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                uint32_t h[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float y = (float)acc[mi][ni][rg * 4 + j] * a_t[mi];
+                    y = rounded_f32(y * sv[j]);
+                    h[j] = f2h(y);
+                }
+                *reinterpret_cast<uint2*>(stage + (mi * 32 + t_lane) * kRowPitch + o_loc * 2) =
+                    make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                if (acc_debug) {
+                    const int row = row0 + mi * 32 + t_lane;
+                    int4 v = make_int4(acc[mi][ni][rg * 4 + 0], acc[mi][ni][rg * 4 + 1], acc[mi][ni][rg * 4 + 2],
+                                       acc[mi][ni][rg * 4 + 3]);
+                    *reinterpret_cast<int4*>(acc_debug + (int64_t)row * O + col0 + o_loc) = v;
+                }
+            }
+        }
+    }
+    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 16)
+    constexpr int kRowsPerInst = 64 / kLanesPerRow;
+    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+#pragma unroll
+    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
+        const int trow = i * kRowsPerInst + rsub;
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
+        uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
+        *reinterpret_cast<uint4*>(dst) = v;
+    }
 }
 
 // NWAVES = 8: waves in a 2 x 4 arrangement, each 128 x 64 (4 x 2 MFMA tiles, 128 accumulator
@@ -317,37 +387,59 @@ gemm_i8_direct_kernel(const int8_t* __restrict__ qx, const float* __restrict__ r
     // global -> LDS loads) with MFMAs instead of clustering them, so the matrix pipe keeps
     // issuing while the fragments of the following slab arrive.
     auto interleave_reads = [&]() {
+        // reads of the following slab go out first, one per MFMA, so that the rest of this slab's
+        // MFMAs cover their latency
 #pragma unroll
-        for (int i = 0; i < NMF - NRD; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+        for (int i = 0; i < NRD; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
-        }
-#pragma unroll
-        for (int i = NMF - NRD; i < NRD; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
+#ifdef CQ_GEMM_PROFILE
+    const bool prof_on = (blockIdx.x == 0 && threadIdx.x == 0);
+    unsigned long long phase_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long last_stamp = __builtin_amdgcn_s_memtime();
+    int cur_kt = 0;
+#endif
+#ifndef CQ_GEMM_SPLIT_ISSUE
+#define CQ_GEMM_SPLIT_ISSUE 1
+#endif
+    // waves w and w + 4 share a SIMD; the upper half issues its loads later (see k_step)
+    const bool late_issuer = CQ_GEMM_SPLIT_ISSUE && NWAVES == 8 && wave >= 4;
     auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
         constexpr bool ISSUE = decltype(issue_c)::value;
         constexpr bool PREFETCH = decltype(prefetch_c)::value;
+#ifdef CQ_GEMM_PROFILE
+        cur_kt = kt;
+        CQ_STAMP(7);
+#endif
         const int8_t* As = lds + (kt & 1) * kStageBytes;
         const int8_t* Bs = As + BM * BK;
         load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 1);
         mfma_slab<NI>(acc, af0, bf0);
         interleave_reads();
+        // second wave group: its share of tile kt+1 goes out here, a quarter step after the first
+        // group's, so the two waves of a SIMD are not both stalled on load issue at the same time
+        if (late_issuer && kt >= 1 && kt + 1 < nk) issue_tile(kt + 1, (kt + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        CQ_STAMP(0);
         load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, 2);
         mfma_slab<NI>(acc, af1, bf1);
         interleave_reads();
+        CQ_STAMP(1);
         load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 3);
         mfma_slab<NI>(acc, af0, bf0);
         interleave_reads();
+        CQ_STAMP(2);
         // every read of this stage has been issued; the next tile (other stage) must have landed
         __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+        CQ_STAMP(3);
         __syncthreads();
+        CQ_STAMP(4);
         __builtin_amdgcn_sched_barrier(0);
-        if (ISSUE) issue_tile(kt + 2, kt & 1);          // refill the stage everyone has finished with
+        if (ISSUE && !late_issuer) issue_tile(kt + 2, kt & 1);   // refill the stage everyone has finished with
         if (PREFETCH) {
             const int8_t* An = lds + ((kt + 1) & 1) * kStageBytes;
             load_frags<NI>(af0, bf0, An, An + BM * BK, a_off, b_off, 0);
@@ -360,6 +452,200 @@ gemm_i8_direct_kernel(const int8_t* __restrict__ qx, const float* __restrict__ r
             if (ISSUE && i < 2 * LINST) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global -> LDS load
         }
         __builtin_amdgcn_sched_barrier(0);
+        CQ_STAMP(5);
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) k_step(kt, yes{}, yes{});
+    if (kt + 1 < nk) {
+        k_step(kt, no{}, yes{});
+        ++kt;
+    }
+    k_step(kt, no{}, no{});
+    CQ_STAMP(6);
+#ifdef CQ_GEMM_PROFILE
+    cur_kt = 1000;
+#define CQ_PROFILE_FLUSH() do { CQ_STAMP(7); if (prof_on) for (int i_ = 0; i_ < 8; ++i_) g_phase_cycles[i_] = phase_acc[i_]; } while (0)
+#else
+#define CQ_PROFILE_FLUSH() do { } while (0)
+#endif
+
+    epilogue_store<WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, O, m0 + wm * 128, n0 + wn * WTN,
+                            lane, wave);
+    CQ_PROFILE_FLUSH();
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Ring variant of the fast path (8 waves): the loads of the two wave groups are taken apart in
+// time so that one wave of every SIMD multiplies while the other is held up issuing loads.
+//
+// Measured on this chip: every vector-memory instruction holds its wave for ~96 cycles, so the 8
+// loads a wave owes per K step cost it ~770 cycles -- three quarters of its 1024 cycles of
+// MFMA work.  With all waves loading right after the barrier (the only place a 2-stage pipeline
+// allows) both waves of a SIMD stall together and the matrix pipe idles.  Here LDS is a ring of
+// five 32 KiB slots holding half tiles in load order A0 B0 A1 B1 A2 ... (half tile n lives in
+// slot n % 5).  The spare slot lets A(kt+2) be requested a whole step early, so:
+//   waves 0-3 (one per SIMD): multiply first, then request A(kt+2) (all 32 instructions of it)
+//                             just before the step's barrier;
+//   waves 4-7 (their SIMD mates): request B(kt+2) right after the barrier, then multiply.
+// Slot reuse: A(kt+2) takes the slot of B(kt-1), free since barrier kt-1; B(kt+2) takes the slot
+// of A(kt), free after barrier kt (all of tile kt's fragments are in registers by then).
+// ---------------------------------------------------------------------------------------------
+constexpr int kSlotBytes = BM * BK;               // 32 KiB: one operand's 256 x 128 tile
+constexpr int kRingSlots = 5;
+constexpr int kRingLds = kRingSlots * kSlotBytes; // 160 KiB: the whole LDS of a gfx950 CU
+
+__global__ void __launch_bounds__(512)
+gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
+                    const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I, int O,
+                    uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
+                    int tiles_n) {
+    constexpr int WN = 4, WTN = 64, NI = 2;
+    extern __shared__ __align__(16) int8_t lds[];
+
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    const int L = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (L >= total) return;
+    const int group_sz = kGroupM * tiles_n;
+    const int g = L / group_sz;
+    const int gm = min(kGroupM, tiles_m - g * kGroupM);
+    const int in_g = L - g * group_sz;
+    const int tile_m = g * kGroupM + in_g % gm;
+    const int tile_n = in_g / gm;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int nk = I / BK;
+    const bool b_loader = wave >= 4;              // waves 4-7 load B, waves 0-3 load A
+
+    // ---- loader: loader wave lw = wave & 3 fills rows [64 lw, 64 lw + 64) of its operand's half
+    // tile with 8 instructions; instruction ii covers rows 64 lw + 8 ii + (lane >> 3), physical
+    // chunk lane & 7 (the swizzle is applied to the global column).
+    const int ld_r = lane >> 3, ld_p = lane & 7;
+    const int lw = wave & 3;
+    const int8_t* gsrc[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int R = 64 * lw + 8 * par + ld_r;
+        const int c = ld_p ^ ((R >> 1) & 7);
+        gsrc[par] = (b_loader ? qw + (int64_t)(n0 + R) * I : qx + (int64_t)(m0 + R) * I) + c * 16;
+    }
+    auto issue_half = [&](int kt, int slot) {
+        int8_t* dst = lds + slot * kSlotBytes + lw * (64 * BK);
+        const int64_t koff = (int64_t)kt * BK;
+#pragma unroll
+        for (int ii = 0; ii < 8; ++ii) {
+            const int64_t roff = (int64_t)(ii >> 1) * 16 * I + koff;
+            __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii & 1] + roff), (lptr_t)(dst + ii * 1024), 16, 0, 0);
+        }
+    };
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int sw = (frag_row >> 1) & 7;
+    const int a_off = (wm * 128 + frag_row) * BK + ((frag_half ^ sw) * 16);
+    const int b_off = (wn * WTN + frag_row) * BK + ((frag_half ^ sw) * 16);
+
+    v16i acc[4][NI];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0;
+
+    // prologue: A0 A1 (waves 0-3) / B0 B1 (waves 4-7); half tile n -> slot n % 5
+    issue_half(0, b_loader ? 1 : 0);
+    if (nk > 1) issue_half(1, b_loader ? 3 : 2);
+    if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 15));
+    else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    __syncthreads();
+
+    // slots of the current tile (sa, sb) and of the next one (na, nb), advanced by 2 mod 5 per step
+    int sa = 0, sb = 1;
+    auto adv = [](int v) { v += 2; return v >= kRingSlots ? v - kRingSlots : v; };
+
+    v4i af0[4], bf0[NI], af1[4], bf1[NI];
+    load_frags<NI>(af0, bf0, lds + sa * kSlotBytes, lds + sb * kSlotBytes, a_off, b_off, 0);
+
+    constexpr int NMF = 4 * NI, NRD = 4 + NI;
+    auto interleave_reads = [&]() {
+#pragma unroll
+        for (int i = 0; i < NRD; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // reads of the next slab first
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+#ifdef CQ_GEMM_PROFILE
+    const bool prof_on = (blockIdx.x == 0 && threadIdx.x == 0);
+    unsigned long long phase_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long last_stamp = __builtin_amdgcn_s_memtime();
+    int cur_kt = 0;
+#endif
+    auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value;        // kt + 2 < nk
+        constexpr bool PREFETCH = decltype(prefetch_c)::value;  // kt + 1 < nk
+#ifdef CQ_GEMM_PROFILE
+        cur_kt = kt;
+        CQ_STAMP(7);
+#endif
+        const int8_t* As = lds + sa * kSlotBytes;
+        const int8_t* Bs = lds + sb * kSlotBytes;
+        const int na = adv(sa), nb = adv(sb);                   // slots of tile kt+1
+        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 1);
+        mfma_slab<NI>(acc, af0, bf0);
+        interleave_reads();
+        CQ_STAMP(0);
+        load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, 2);
+        mfma_slab<NI>(acc, af1, bf1);
+        interleave_reads();
+        CQ_STAMP(1);
+        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 3);
+        mfma_slab<NI>(acc, af0, bf0);
+        interleave_reads();
+        CQ_STAMP(2);
+        // A loaders: A(kt+2) = half tile 2kt+4 -> slot (2kt+4) % 5 = adv(na); its previous tenant
+        // B(kt-1) was released at the previous barrier.  Then tile kt+1's A (requested a step ago)
+        // must have landed: at most the 8 requests just made may still be in flight.
+        if (!b_loader) {
+            if (ISSUE) {
+                issue_half(kt + 2, adv(na));
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 0));
+            } else {
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+            }
+        } else {
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));      // B(kt+1), requested after the last barrier
+        }
+        CQ_STAMP(3);
+        // a bare barrier: __syncthreads() would add a release fence, i.e. a wait for *all* of this
+        // wave's outstanding loads, including the ones requested a moment ago for two steps ahead.
+        // LDS needs no fence: this wave's reads are complete (lgkmcnt(0) above) and the loads the
+        // next tile depends on are complete in the waves that issued them (their vmcnt wait above).
+        __builtin_amdgcn_s_barrier();
+        CQ_STAMP(4);
+        __builtin_amdgcn_sched_barrier(0);
+        // B loaders: B(kt+2) = half tile 2kt+5 -> slot (2kt+5) % 5 = sa, tile kt's A slot, which
+        // nobody reads any more (slab 3's fragments are in registers)
+        if (b_loader && ISSUE) issue_half(kt + 2, sa);
+        __builtin_amdgcn_sched_barrier(0);
+        if (PREFETCH) load_frags<NI>(af0, bf0, lds + na * kSlotBytes, lds + nb * kSlotBytes, a_off, b_off, 0);
+        mfma_slab<NI>(acc, af1, bf1);
+#pragma unroll
+        for (int i = 0; i < NMF; ++i) {
+            if (PREFETCH && i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        CQ_STAMP(5);
+        sa = na;
+        sb = nb;
     };
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
@@ -371,57 +657,8 @@ gemm_i8_direct_kernel(const int8_t* __restrict__ qx, const float* __restrict__ r
     }
     k_step(kt, no{}, no{});
 
-    // ---- epilogue.  Lane l holds token t = l & 31 of each 32-token block and, for register group
-    // rg = r / 4, the 4 consecutive channels 8*rg + 4*(l >> 5) + {0..3} of each 32-channel block.
-    // Scaled binary16 results go through LDS (free now: the K loop ended on a barrier with no
-    // reads outstanding) so that every global store is a full 16 bytes per lane and a wave
-    // writes whole 128-byte row pieces; a wave can only start a vector-memory instruction every
-    // ~100 ns, so 2-byte scattered stores would cost more than the K loop of a small GEMM.
-    constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
-    int8_t* stage = lds + wave * (128 * kRowPitch);      // this wave's 128 x WTN staging area
-    const int t_lane = lane & 31;
-    float a_t[4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[m0 + wm * 128 + mi * 32 + t_lane];
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
-            const float4 s4 = *reinterpret_cast<const float4*>(w_scale + n0 + wn * WTN + o_loc);
-            const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                uint32_t h[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float y = (float)acc[mi][ni][rg * 4 + j] * a_t[mi];
-                    y = rounded_f32(y * sv[j]);
-                    h[j] = f2h(y);
-                }
-                *reinterpret_cast<uint2*>(stage + (mi * 32 + t_lane) * kRowPitch + o_loc * 2) =
-                    make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                if (acc_debug) {
-                    const int row = m0 + wm * 128 + mi * 32 + t_lane;
-                    int4 v = make_int4(acc[mi][ni][rg * 4 + 0], acc[mi][ni][rg * 4 + 1], acc[mi][ni][rg * 4 + 2],
-                                       acc[mi][ni][rg * 4 + 3]);
-                    *reinterpret_cast<int4*>(acc_debug + (int64_t)row * O + n0 + wn * WTN + o_loc) = v;
-                }
-            }
-        }
-    }
-    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
-    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 16)
-    constexpr int kRowsPerInst = 64 / kLanesPerRow;
-    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
-#pragma unroll
-    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
-        const int trow = i * kRowsPerInst + rsub;
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
-        uint16_t* dst = Y + (int64_t)(m0 + wm * 128 + trow) * ldy + n0 + wn * WTN + piece * 8;
-        *reinterpret_cast<uint4*>(dst) = v;
-    }
+    epilogue_store<WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, O, m0 + wm * 128, n0 + wn * WTN,
+                            lane, wave);
 }
 
 }  // namespace
@@ -441,16 +678,28 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                       al16(w_scale) && al16(acc_debug);
     hipError_t e;
     if (full) {
-        constexpr int NW = CQ_GEMM_WAVES;
-        constexpr int kWtn = BN / (NW / 2);
-        // K-loop stages (128 KiB) or the epilogue's staging area, whichever is larger
-        constexpr int kDirectLds = (NW * 128 * (kWtn * 2 + 8) > kLdsBytes) ? NW * 128 * (kWtn * 2 + 8) : kLdsBytes;
-        static_assert(kDirectLds <= 160 * 1024, "LDS budget of a gfx950 CU");
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_direct_kernel<NW>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kDirectLds);
-        if (e != hipSuccess) return e;
-        gemm_i8_direct_kernel<NW><<<grid, dim3(NW * 64), kDirectLds, stream>>>(
-            qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n);
+#ifndef CQ_GEMM_RING
+#define CQ_GEMM_RING 1
+#endif
+        if (CQ_GEMM_RING) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_ring_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kRingLds);
+            if (e != hipSuccess) return e;
+            gemm_i8_ring_kernel<<<grid, dim3(512), kRingLds, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
+                                                                       acc_debug, tiles_m, tiles_n);
+        } else {
+            constexpr int NW = CQ_GEMM_WAVES;
+            constexpr int kWtn = BN / (NW / 2);
+            // K-loop stages (128 KiB) or the epilogue's staging area, whichever is larger
+            constexpr int kDirectLds =
+                (NW * 128 * (kWtn * 2 + 8) > kLdsBytes) ? NW * 128 * (kWtn * 2 + 8) : kLdsBytes;
+            static_assert(kDirectLds <= 160 * 1024, "LDS budget of a gfx950 CU");
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_direct_kernel<NW>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kDirectLds);
+            if (e != hipSuccess) return e;
+            gemm_i8_direct_kernel<NW><<<grid, dim3(NW * 64), kDirectLds, stream>>>(
+                qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n);
+        }
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
