@@ -89,6 +89,21 @@ int crossquant_kernel_count(const void *X, int64_t T, int64_t I, int64_t ldx, co
                             float *col_scale, unsigned long long *zero_count, void *stream);
 
 /*
+ * Quantization-kernel analysis: the "Remove Kernel" matrix (captions of the zero-shot accuracy
+ * figures: the elements of the kernel are set to zero, all others stay in FP16) and the two
+ * indicators of Table 1 / the kernel-size analysis (cases I and II).
+ *   xrk_ij = q_ij == 0 ? 0 : X_ij          (q as in crossquant_quantize for this alpha, bits)
+ *   counters[0] = #{q_ij == 0}             the kernel size Z
+ *   counters[1] = #{(i,j): c_j >= t_i}     case II
+ *   counters[2] = #{(i,j): B~_ij < B_ij}   B~ = 0.5 fl32(a_i b_j), B = 0.5 fl32(t_i / q_max) (Eq. 1's step)
+ * xrk: out, nullable, binary16 [T][I].  counters: out, three unsigned 64-bit values, 8-byte aligned.
+ * row_scale / col_scale: float[T] / float[I] work vectors, overwritten with a and b.
+ */
+int crossquant_kernel_analysis(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
+                               const float *c, float alpha, int bits, void *xrk, float *row_scale,
+                               float *col_scale, unsigned long long *counters, void *stream);
+
+/*
  * Per-channel weight quantization (Eq. 2), one step per OUTPUT channel k, stored transposed.
  *   W'_jk = fl32(fold_j * W_jk)  (fold NULL = 1);  s_k = fl32(max_j |W'_jk| / q_max)
  *   qw_kj = s_k == 0 ? 0 : clamp(rne(fl32(W'_jk / s_k)), +-q_max)

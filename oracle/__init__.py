@@ -43,7 +43,8 @@ def _load():
         lib.cq_oracle_float_to_half.argtypes = [ctypes.c_float]
         lib.cq_oracle_num_threads.restype = ctypes.c_int
         for name in ("cq_oracle_absmax", "cq_oracle_scales", "cq_oracle_quantize",
-                     "cq_oracle_kernel_count", "cq_oracle_weight_quantize", "cq_oracle_w8a8_linear"):
+                     "cq_oracle_kernel_count", "cq_oracle_weight_quantize", "cq_oracle_w8a8_linear",
+                     "cq_oracle_kernel_analysis"):
             getattr(lib, name).restype = None
         _lib = lib
     return _lib
@@ -145,6 +146,26 @@ def kernel_count(X: np.ndarray, t: np.ndarray, c: np.ndarray, alpha: float, bits
                                    ctypes.c_float(alpha), ctypes.c_int(bits), _p(a), _p(b),
                                    ctypes.byref(Z))
     return int(Z.value)
+
+
+def kernel_analysis(X: np.ndarray, t: np.ndarray, c: np.ndarray, alpha: float, bits: int,
+                    want_xrk: bool = True):
+    """"Remove Kernel" matrix and the Table 1 indicators.  Returns a dict: xrk (float16 or None),
+    Z, n_col_ge_row (#{c_j >= t_i}), n_bound_smaller (#{B~_ij < B_ij}), a, b."""
+    qmax(bits)
+    xb = _as_half_bits(X)
+    T, I = X.shape
+    t = np.ascontiguousarray(t, np.float32)
+    c = np.ascontiguousarray(c, np.float32)
+    xrk = np.empty((T, I), np.uint16) if want_xrk else None
+    a = np.empty(T, np.float32)
+    b = np.empty(I, np.float32)
+    counters = np.zeros(3, np.uint64)
+    _load().cq_oracle_kernel_analysis(_p(xb), _i64(T), _i64(I), _i64(X.strides[0] // 2), _p(t), _p(c),
+                                      ctypes.c_float(alpha), ctypes.c_int(bits), _p(xrk), _p(a), _p(b),
+                                      _p(counters))
+    return {"xrk": None if xrk is None else xrk.view(np.float16), "Z": int(counters[0]),
+            "n_col_ge_row": int(counters[1]), "n_bound_smaller": int(counters[2]), "a": a, "b": b}
 
 
 def unpack_int4(packed: np.ndarray) -> np.ndarray:

@@ -235,3 +235,39 @@ void cq_oracle_w8a8_linear(const int8_t *qx, const float *a, const int8_t *qw, c
             }
         }
 }
+
+/* ---------- quantization-kernel analysis: "Remove Kernel" and the Table 1 indicators ----------
+ * "Remove Kernel" (captions of the zero-shot accuracy figures): the elements of the quantization
+ * kernel K(Q) are set to zero and every other element is left untouched in FP16:
+ *     xrk_ij = (q_ij == 0) ? 0 : X_ij        with q_ij the code of the chosen quantizer (alpha, bits).
+ * Table 1's two indicators over all (i, j) of the matrix, for the kernel-size analysis' cases I/II:
+ *     n_col_ge_row    = #{ c_j >= t_i }                      (case II)
+ *     n_bound_smaller = #{ B~_ij < B_ij }, B~_ij = 0.5 * fl32(a_i * b_j)  (zero bound of CrossQuant),
+ *                                          B_ij  = 0.5 * fl32(t_i / q_max) (zero bound of per-token, Eq. 1)
+ * counters[0] = Z (kernel size), counters[1] = n_col_ge_row, counters[2] = n_bound_smaller.
+ * xrk (nullable): binary16 [T][I]. a, b are outputs as in cq_oracle_quantize. */
+void cq_oracle_kernel_analysis(const uint16_t *X, int64_t T, int64_t I, int64_t ldx, const float *t,
+                               const float *c, float alpha, int bits, uint16_t *xrk, float *a, float *b,
+                               uint64_t *counters)
+{
+    int qmax = qmax_of_bits(bits);
+    cq_oracle_scales(t, c, T, I, alpha, bits, a, b);
+    uint64_t zeros = 0, col_ge = 0, smaller = 0;
+#pragma omp parallel for schedule(static) reduction(+ : zeros, col_ge, smaller)
+    for (int64_t i = 0; i < T; ++i) {
+        float step_pt = (float)((double)t[i] / (double)qmax);   /* per-token step of Eq. 1 */
+        for (int64_t j = 0; j < I; ++j) {
+            uint16_t h = X[i * ldx + j];
+            float x = cq_oracle_half_to_float(h);
+            float D = a[i] * b[j];
+            int q = quantize_one(x, D, qmax);
+            if (q == 0) ++zeros;
+            if (c[j] >= t[i]) ++col_ge;
+            if (0.5f * D < 0.5f * step_pt) ++smaller;
+            if (xrk) xrk[i * I + j] = (q == 0) ? (uint16_t)0 : h;
+        }
+    }
+    counters[0] = zeros;
+    counters[1] = col_ge;
+    counters[2] = smaller;
+}

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     LIB_PATH,
     CrossQuantError,
     crossquant_absmax,
+    crossquant_kernel_analysis,
     crossquant_kernel_count,
     crossquant_quantize,
     crossquant_status_string,

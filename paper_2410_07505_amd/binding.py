@@ -26,9 +26,10 @@ _vp, _i64, _int, _f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_
 lib.crossquant_absmax.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp]
 lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
+lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
-for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count",
+for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count", "crossquant_kernel_analysis",
            "crossquant_weight_quantize", "crossquant_w8a8_linear", "crossquant_version"):
     getattr(lib, _n).restype = _int
 lib.crossquant_status_string.argtypes = [_int]
@@ -142,6 +143,30 @@ def crossquant_kernel_count(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, a
                                        float(alpha), int(bits), row_scale.data_ptr(), col_scale.data_ptr(),
                                        zero_count.data_ptr(), _stream(X)))
     return zero_count
+
+
+def crossquant_kernel_analysis(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
+                               want_xrk: bool = True, xrk: torch.Tensor = None, row_scale: torch.Tensor = None,
+                               col_scale: torch.Tensor = None, counters: torch.Tensor = None):
+    """"Remove Kernel" matrix (float16 [T][I] or None) and a three-element int64 tensor
+    {kernel size, #{c_j >= t_i}, #{B~_ij < B_ij}}."""
+    _req(X, torch.float16, "X", 2)
+    T, I = X.shape
+    dev = X.device
+    if xrk is None and want_xrk:
+        xrk = torch.empty((T, I), dtype=torch.float16, device=dev)
+    if row_scale is None:
+        row_scale = torch.empty(T, dtype=torch.float32, device=dev)
+    if col_scale is None:
+        col_scale = torch.empty(I, dtype=torch.float32, device=dev)
+    if counters is None:
+        counters = torch.empty(3, dtype=torch.int64, device=dev)
+    if xrk is not None and not xrk.is_contiguous():
+        raise ValueError("xrk must be contiguous")
+    _check(lib.crossquant_kernel_analysis(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(),
+                                          float(alpha), int(bits), _ptr(xrk), row_scale.data_ptr(),
+                                          col_scale.data_ptr(), counters.data_ptr(), _stream(X)))
+    return xrk, counters
 
 
 def crossquant_weight_quantize(W: torch.Tensor, fold, bits: int, *, qw: torch.Tensor = None,

@@ -1,0 +1,155 @@
+// Quantization-kernel analysis (Definition 1; Table 1; the "Remove Kernel" experiment of the
+// zero-shot accuracy figures): one pass over X that writes X with its kernel elements zeroed and
+// counts the kernel size and the two indicators of the kernel-size analysis,
+//   case II:  c_j >= t_i          and          B~_ij < B_ij  (zero bound of CrossQuant below per-token's).
+// Analysis tooling rather than the serving path, so it is written for clarity: the code of every
+// element comes from the correctly rounded division itself (about 25 VALU operations per
+// element, which still keeps pace with the 4 bytes per element it moves).
+#include "cq_kernels.h"
+
+namespace cq {
+namespace {
+
+constexpr int kLanes = 64;
+constexpr int kWaves = 8;
+constexpr int kU = 4;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Block: 8 waves share 512 columns; each wave takes nb batches of 4 consecutive rows.
+template <bool VEC>
+__global__ void __launch_bounds__(kWaves * kLanes)
+analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ t_vec,
+                const float* __restrict__ c_vec, const float* __restrict__ a_vec, const float* __restrict__ b_vec,
+                float qmax, uint16_t* __restrict__ xrk, unsigned long long* __restrict__ counters,
+                int n_col_chunks, int nb, bool out_vec) {
+    __shared__ uint32_t lds_cnt[kWaves][3];
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int wave = threadIdx.x / kLanes;
+    const int col_chunk = blockIdx.x % n_col_chunks;
+    const int row_chunk = blockIdx.x / n_col_chunks;
+    const int j0 = col_chunk * 512 + lane * 8;
+    const int rows_per_wave = nb * kU;
+    const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
+
+    float b[8], c[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
+        c[e] = (j0 + e < I) ? c_vec[j0 + e] : 0.0f;
+    }
+    int nvalid = I - j0;
+    nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
+    // per row: a_i, t_i and the per-token step fl32(t_i / q_max), one row per lane
+    const bool has_row = lane < rows_per_wave && row0 + lane < T;
+    const float a_lane = has_row ? a_vec[row0 + lane] : 0.0f;
+    const float t_lane = has_row ? t_vec[row0 + lane] : 0.0f;
+    const float pt_lane = (float)((double)t_lane / (double)qmax);
+
+    uint32_t zeros = 0, col_ge = 0, smaller = 0;
+    for (int bi = 0; bi < nb; ++bi) {
+        const int rbase = row0 + bi * kU;
+        if (rbase >= T) break;                              // wave-uniform
+        uint4 v[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            v[u] = make_uint4(0u, 0u, 0u, 0u);
+            const int r = rbase + u;
+            if (r < T) {
+                const uint16_t* row = X + (int64_t)r * ldx;
+                if (VEC && j0 + 8 <= I) {
+                    v[u] = *reinterpret_cast<const uint4*>(row + j0);
+                } else if (j0 < I) {
+                    uint32_t h[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) h[e] = (j0 + e < I) ? row[j0 + e] : 0u;
+                    v[u] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
+                                      h[6] | (h[7] << 16));
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int r = rbase + u;
+            if (r >= T) break;                              // wave-uniform
+            const int ri = bi * kU + u;
+            const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), ri));
+            const float ti = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t_lane), ri));
+            const float pt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pt_lane), ri));
+            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            uint32_t out[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint32_t keep = 0u;
+#pragma unroll
+                for (int hlf = 0; hlf < 2; ++hlf) {
+                    const int e = 2 * p + hlf;
+                    const uint32_t hbits = hlf ? (w[p] >> 16) : (w[p] & 0xFFFFu);
+                    const float x = h2f(hbits);
+                    const float D = a * b[e];
+                    float q = (D == 0.0f) ? 0.0f : __builtin_rintf(x / D);
+                    q = __builtin_amdgcn_fmed3f(q, -qmax, qmax);
+                    const bool valid = e < nvalid;
+                    const bool is_zero = (q == 0.0f);
+                    zeros += (valid && is_zero) ? 1u : 0u;
+                    col_ge += (valid && c[e] >= ti) ? 1u : 0u;
+                    smaller += (valid && D < pt) ? 1u : 0u;          // 0.5 * D < 0.5 * pt, exactly
+                    keep |= is_zero ? 0u : (hlf ? 0xFFFF0000u : 0x0000FFFFu);
+                }
+                out[p] = w[p] & keep;
+            }
+            if (xrk) {
+                uint16_t* dst = xrk + (int64_t)r * I + j0;
+                if (out_vec && nvalid == 8) {
+                    __builtin_nontemporal_store(u32x4{out[0], out[1], out[2], out[3]}, reinterpret_cast<u32x4*>(dst));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < nvalid) dst[e] = (uint16_t)((e & 1) ? (out[e >> 1] >> 16) : (out[e >> 1] & 0xFFFFu));
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        zeros += (uint32_t)__shfl_xor((int)zeros, off, kLanes);
+        col_ge += (uint32_t)__shfl_xor((int)col_ge, off, kLanes);
+        smaller += (uint32_t)__shfl_xor((int)smaller, off, kLanes);
+    }
+    if (lane == 0) {
+        lds_cnt[wave][0] = zeros;
+        lds_cnt[wave][1] = col_ge;
+        lds_cnt[wave][2] = smaller;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        uint32_t s = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += lds_cnt[w][threadIdx.x];
+        if (s) atomicAdd(&counters[threadIdx.x], (unsigned long long)s);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, const float* t, const float* c,
+                                  const float* a, const float* b, int qmax, uint16_t* xrk,
+                                  unsigned long long* counters, hipStream_t stream) {
+    const int ncc = (I + 511) / 512;
+    int nb = 16;
+    while (nb > 1 && (int64_t)ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
+    const int nrc = (T + 32 * nb - 1) / (32 * nb);
+    const dim3 grid((unsigned)(ncc * nrc)), block(kWaves * kLanes);
+    const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0);
+    const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(xrk) % 16 == 0);
+    if (vec)
+        analysis_kernel<true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, a, b, (float)qmax, xrk, counters, ncc,
+                                                         nb, out_vec);
+    else
+        analysis_kernel<false><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, a, b, (float)qmax, xrk, counters, ncc,
+                                                          nb, out_vec);
+    return hipGetLastError();
+}
+
+}  // namespace cq

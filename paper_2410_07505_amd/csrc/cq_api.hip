@@ -52,7 +52,7 @@ int crossquant_quantize(const void* X, int64_t T, int64_t I, int64_t ldx, const 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int qmax = (1 << (bits - 1)) - 1;
     if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
-                                                   zero_count, st)))
+                                                   zero_count, 1, st)))
         return s;
     return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
                                         col_scale, bits, codes, static_cast<uint16_t*>(xhat), zero_count, st));
@@ -71,10 +71,30 @@ int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, co
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int qmax = (1 << (bits - 1)) - 1;
     if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
-                                                   zero_count, st)))
+                                                   zero_count, 1, st)))
         return s;
     return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
                                         col_scale, bits, nullptr, nullptr, zero_count, st));
+}
+
+int crossquant_kernel_analysis(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
+                               float alpha, int bits, void* xrk, float* row_scale, float* col_scale,
+                               unsigned long long* counters, void* stream) {
+    if (!t || !c || !row_scale || !col_scale || !counters) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (bits != 4 && bits != 8) return CQ_ERR_BITS;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
+        !aligned(xrk, 2) || !aligned(counters, 8))
+        return CQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int qmax = (1 << (bits - 1)) - 1;
+    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
+                                                   counters, 3, st)))
+        return s;
+    return from_hip(cq::launch_kernel_analysis(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, t, c,
+                                               row_scale, col_scale, qmax, static_cast<uint16_t*>(xrk), counters,
+                                               st));
 }
 
 int crossquant_weight_quantize(const void* W, int64_t I, int64_t O, const float* fold, int bits, int8_t* qw,

@@ -26,10 +26,15 @@ __device__ __forceinline__ float rounded_f32(float v) {
 hipError_t launch_absmax(const uint16_t* X, int T, int I, int64_t ldx, float* t, float* c,
                          hipStream_t stream);
 
-// a_i = t_i^alpha / qmax, b_j = c_j^(1-alpha) (binary64 pow, one rounding); *zero_count <- 0.
+// a_i = t_i^alpha / qmax, b_j = c_j^(1-alpha) (binary64 pow, one rounding); counters[0..n) <- 0.
 hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, float alpha, int qmax,
-                                 float* a, float* b, unsigned long long* zero_count,
+                                 float* a, float* b, unsigned long long* counters, int n_counters,
                                  hipStream_t stream);
+
+// "Remove Kernel" matrix and the Table 1 indicators; counters = {Z, #{c_j >= t_i}, #{B~ < B}}.
+hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, const float* t,
+                                  const float* c, const float* a, const float* b, int qmax,
+                                  uint16_t* xrk, unsigned long long* counters, hipStream_t stream);
 
 // Fused quantize / dequantize / zero count.  codes or xhat may be null (count only = both null).
 hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const float* a,

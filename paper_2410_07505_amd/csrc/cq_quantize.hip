@@ -30,10 +30,10 @@ constexpr float kTieTol = 1.9073486328125e-06f;  // 2^-19
 
 __global__ void scale_finalize_kernel(const float* __restrict__ t, const float* __restrict__ c, int T,
                                       int I, float alpha, int qmax, float* __restrict__ a,
-                                      float* __restrict__ b, unsigned long long* __restrict__ zero_count) {
+                                      float* __restrict__ b, unsigned long long* __restrict__ counters, int n_counters) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const double al = (double)alpha;
-    if (idx == 0 && zero_count) *zero_count = 0ull;
+    if (idx < n_counters && counters) counters[idx] = 0ull;
     if (idx < T) {
         const double ti = (double)t[idx];
         // pow(x, 0) = 1 for every x and pow(x, 1) = x are exact in any correct pow; written out
@@ -253,10 +253,11 @@ hipError_t launch_mode(const uint16_t* X, int T, int I, int64_t ldx, const float
 }  // namespace
 
 hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, float alpha, int qmax,
-                                 float* a, float* b, unsigned long long* zero_count, hipStream_t stream) {
+                                 float* a, float* b, unsigned long long* counters, int n_counters,
+                                 hipStream_t stream) {
     const int n = T + I;
     scale_finalize_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(t, c, T, I, alpha, qmax, a, b,
-                                                                           zero_count);
+                                                                           counters, n_counters);
     return hipGetLastError();
 }
 

@@ -93,6 +93,19 @@ def test_kernel_count_argument_errors(cq):
     assert call(alpha=2.0) == -4
 
 
+def test_kernel_analysis_argument_errors(cq):
+    f = cq.raw.crossquant_kernel_analysis
+
+    def call(X=P, T=4, I=8, ldx=8, t=P, c=P, alpha=0.15, bits=8, xrk=P, rs=P, cs=P, cnt=P):
+        return f(X, T, I, ldx, t, c, alpha, bits, xrk, rs, cs, cnt, None)
+
+    assert call(cnt=0) == -1 and call(X=0) == -1 and call(cs=0) == -1
+    assert call(I=0) == -2 and call(ldx=7) == -2
+    assert call(bits=6) == -3
+    assert call(alpha=-1.0) == -4
+    assert call(cnt=P + 4) == -5 and call(xrk=P + 1) == -5
+
+
 def test_weight_quantize_argument_errors(cq):
     f = cq.raw.crossquant_weight_quantize
     assert f(0, 8, 8, None, 8, P, P, None) == -1

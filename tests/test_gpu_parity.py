@@ -265,6 +265,51 @@ def test_quantize_is_deterministic(cq):
     assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1]) and torch.equal(r1[4], r2[4])
 
 
+# ----------------------------------------------------------------------------- Remove Kernel, Table 1 indicators
+def check_analysis(cq, X, alpha, bits, Xg=None, label=""):
+    say("analysis %s shape=%s alpha=%g bits=%d" % (label, X.shape, alpha, bits))
+    Xg = gpu(X) if Xg is None else Xg
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.kernel_analysis(X, t_ref, c_ref, alpha, bits)
+    t, c = cq.crossquant_absmax(Xg)
+    xrk, counters = cq.crossquant_kernel_analysis(Xg, t, c, alpha, bits)
+    got = host(counters)
+    assert [int(v) for v in got] == [ref["Z"], ref["n_col_ge_row"], ref["n_bound_smaller"]]
+    assert np.array_equal(bits16(host(xrk)), bits16(ref["xrk"]))
+    none_xrk, counters2 = cq.crossquant_kernel_analysis(Xg, t, c, alpha, bits, want_xrk=False)
+    assert none_xrk is None and np.array_equal(host(counters2), got)
+    return ref
+
+
+@pytest.mark.parametrize("T,I", [(1, 1), (3, 6), (37, 54), (130, 1000), (129, 520), (200, 1537)])
+def test_analysis_small_and_ragged(cq, T, I):
+    X = outliers(T, I, seed=T * 7 + I)
+    if T > 2 and I > 5:
+        X[1, :] = 0
+        X[:, 4] = 0
+        X[2, 3] = np.float16(-0.0)
+    for alpha, bits in ((1.0, 8), (0.15, 8), (0.15, 4), (0.0, 8)):
+        check_analysis(cq, X, alpha, bits)
+
+
+def test_analysis_strided_input(cq):
+    base = outliers(40, 300, seed=19)
+    g = gpu(base)
+    for lo, hi in ((8, 264), (3, 259)):
+        check_analysis(cq, base[:, lo:hi], 0.15, 8, Xg=g[:, lo:hi], label="view[%d:%d]" % (lo, hi))
+
+
+@pytest.mark.parametrize("name", ["C1", "C3", "C5"])
+def test_analysis_full_configs(cq, name):
+    cfg = workloads.CONFIGS[name]
+    X = workloads.config_activation(name)
+    Xg = gpu(X)
+    for alpha in (0.15, 1.0):
+        ref = check_analysis(cq, X, alpha, cfg.bits, Xg=Xg, label=name)
+        say("%s alpha=%g: kernel %.4f, c_j>=t_i %.4f, B~<B %.4f" % (
+            name, alpha, ref["Z"] / X.size, ref["n_col_ge_row"] / X.size, ref["n_bound_smaller"] / X.size))
+
+
 # ----------------------------------------------------------------------------- weights
 WEIGHT_SHAPES = [(1, 1), (8, 8), (70, 45), (64, 64), (256, 256), (130, 1000), (1000, 130), (513, 520)]
 

@@ -465,3 +465,56 @@ def test_end_to_end_linear_tracks_the_fp_product_and_crossquant_beats_per_token(
         errs[alpha] = np.linalg.norm(Y.astype(np.float64) - ref) / np.linalg.norm(ref)
     assert errs[0.15] < 0.05 and errs[1.0] < 0.2
     assert errs[0.15] < errs[1.0]
+
+
+# ----------------------------------------------------------------------------- Remove Kernel, Table 1 indicators
+@pytest.mark.parametrize("alpha,bits", [(1.0, 8), (0.15, 8), (0.15, 4), (0.0, 8)])
+def test_remove_kernel_matrix(alpha, bits):
+    """Kernel elements become zero, all others keep their FP16 value (Fig. 1 caption)."""
+    X = outlier_matrix(48, 96, seed=61)
+    X[3, 7] = np.float16(-0.0)
+    t, c = oracle.absmax(X)
+    r = oracle.quantize(X, t, c, alpha, bits)
+    codes = r["codes"] if bits == 8 else oracle.unpack_int4(r["codes"])
+    an = oracle.kernel_analysis(X, t, c, alpha, bits)
+    want = np.where(codes == 0, np.float16(0.0), X)
+    assert np.array_equal(an["xrk"].view(np.uint16), want.view(np.uint16))
+    assert an["Z"] == r["Z"] == int((an["xrk"].view(np.uint16) == 0).sum())
+    assert np.array_equal(an["a"], r["a"]) and np.array_equal(an["b"], r["b"])
+    # removing the kernel changes nothing that quantization would have kept
+    r2 = oracle.quantize(an["xrk"], t, c, alpha, bits)
+    assert np.array_equal(r2["codes"], r["codes"])
+
+
+def test_table1_indicators_bruteforce():
+    X = outlier_matrix(40, 56, seed=67)
+    t, c = oracle.absmax(X)
+    for alpha in (0.0, 0.15, 0.45, 0.75):
+        an = oracle.kernel_analysis(X, t, c, alpha, 8, want_xrk=False)
+        # case II count by a plain double loop
+        ge = sum(1 for i in range(40) for j in range(56) if c[j] >= t[i])
+        assert an["n_col_ge_row"] == ge == int((c[None, :] >= t[:, None]).sum())
+        # zero bounds from an independent float64 evaluation; equality only possible at c_j == t_i
+        al = float(np.float32(alpha))
+        Bt = 0.5 * (t.astype(np.float64) ** al)[:, None] * (c.astype(np.float64) ** (1 - al))[None] / 127.0
+        B = 0.5 * t.astype(np.float64)[:, None] / 127.0 * np.ones((1, 56))
+        clear = np.abs(Bt - B) > 1e-6 * B
+        lo = int(((Bt < B) & clear).sum())
+        hi = lo + int((~clear).sum())
+        assert lo <= an["n_bound_smaller"] <= hi
+        # the kernel-size analysis: case I (c_j < t_i) <=> B~ < B, so the two indicators partition
+        # the matrix except where c_j == t_i within rounding
+        near_equal = int((np.abs(c[None, :] - t[:, None]) <= 1e-6 * t[:, None]).sum())
+        assert abs(an["n_col_ge_row"] + an["n_bound_smaller"] - X.size) <= near_equal
+    # alpha = 1 is per-token itself: no bound is strictly smaller (Table 1 leaves that cell empty)
+    an = oracle.kernel_analysis(X, t, c, 1.0, 8, want_xrk=False)
+    assert an["n_bound_smaller"] == 0
+
+
+def test_indicators_on_outlier_inputs_follow_the_paper():
+    """On outlier-channel inputs case II (c_j >= t_i) is rare (about 3 % in Table 1)."""
+    X = workloads.config_activation("C1")
+    t, c = oracle.absmax(X)
+    an = oracle.kernel_analysis(X, t, c, 0.15, 8, want_xrk=False)
+    assert an["n_col_ge_row"] / X.size < 0.05
+    assert an["n_bound_smaller"] / X.size > 0.95
