@@ -115,6 +115,19 @@ int crossquant_weight_quantize(const void *W, int64_t I, int64_t O, const float 
                                int8_t *qw, float *w_scale, void *stream);
 
 /*
+ * Group-wise weight quantization (Background section: W reshaped to (I*O/g) x g, one step per
+ * group).  Every output channel k is cut into groups of `group` consecutive input channels (the
+ * contraction axis, as in the weight-only code bases the paper builds on; group = 128 is the
+ * paper's W4A8-g128 setting, group = I is crossquant_weight_quantize):
+ *   s_{k,G} = fl32(max_{j in G} |W'_jk| / q_max);  qw_kj = clamp(rne(fl32(W'_jk / s_{k, j/group})), +-q_max)
+ * W: binary16 [I][O].  I % group == 0.  qw: out, int8 [O][I].  w_scale: out, float [O][I/group].
+ * w_dq: out, nullable, binary16 [I][O]: the dequantized (fake-quantized) weights fl16(fl32(q * s)).
+ */
+int crossquant_weight_quantize_grouped(const void *W, int64_t I, int64_t O, const float *fold,
+                                       int64_t group, int bits, int8_t *qw, float *w_scale, void *w_dq,
+                                       void *stream);
+
+/*
  * W8A8 linear layer Y = X . W on integer codes (Background section), INT8 MFMA, int32 accumulate.
  *   acc_ik = sum_j qx_ij * qw_kj  (exact);  Y_ik = fl16(fl32(fl32(float(acc_ik) * row_scale_i) * w_scale_k))
  * qx: int8 [T][I].  qw: int8 [O][I] (contraction axis contiguous).  Both 16-byte aligned with

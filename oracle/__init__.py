@@ -44,7 +44,7 @@ def _load():
         lib.cq_oracle_num_threads.restype = ctypes.c_int
         for name in ("cq_oracle_absmax", "cq_oracle_scales", "cq_oracle_quantize",
                      "cq_oracle_kernel_count", "cq_oracle_weight_quantize", "cq_oracle_w8a8_linear",
-                     "cq_oracle_kernel_analysis"):
+                     "cq_oracle_kernel_analysis", "cq_oracle_weight_quantize_grouped"):
             getattr(lib, name).restype = None
         _lib = lib
     return _lib
@@ -193,6 +193,23 @@ def weight_quantize(W: np.ndarray, fold, bits: int):
     s = np.empty(O, np.float32)
     _load().cq_oracle_weight_quantize(_p(wb), _i64(I), _i64(O), _p(f), ctypes.c_int(bits), _p(qw), _p(s))
     return qw, s
+
+
+def weight_quantize_grouped(W: np.ndarray, fold, group: int, bits: int, want_dq: bool = True):
+    """Group-wise weight quantization along the input-channel axis.  Returns qw int8 [O][I],
+    s float32 [O][I/group] and (optionally) the dequantized weights float16 [I][O]."""
+    qmax(bits)
+    wb = np.ascontiguousarray(_as_half_bits(W))
+    I, O = W.shape
+    if group < 1 or I % group:
+        raise ValueError("the group size must divide the number of input channels")
+    f = None if fold is None else np.ascontiguousarray(fold, np.float32)
+    qw = np.empty((O, I), np.int8)
+    s = np.empty((O, I // group), np.float32)
+    wdq = np.empty((I, O), np.uint16) if want_dq else None
+    _load().cq_oracle_weight_quantize_grouped(_p(wb), _i64(I), _i64(O), _p(f), _i64(group), ctypes.c_int(bits),
+                                              _p(qw), _p(s), _p(wdq))
+    return qw, s, (None if wdq is None else wdq.view(np.float16))
 
 
 def w8a8_linear(qx: np.ndarray, a: np.ndarray, qw: np.ndarray, s: np.ndarray,

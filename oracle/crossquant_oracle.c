@@ -271,3 +271,36 @@ void cq_oracle_kernel_analysis(const uint16_t *X, int64_t T, int64_t I, int64_t 
     counters[1] = col_ge;
     counters[2] = smaller;
 }
+
+/* ---------- group-wise weight quantization (Background section: W reshaped to (I*O/g) x g) ----------
+ * Each output channel k is cut into groups of g consecutive input channels (the contraction axis,
+ * as in the weight-only code bases the paper builds on); every group has its own step:
+ *   s_{k,G} = fl32(max_{j in G} |W'_jk| / q_max),  qw_kj = clamp(rne(fl32(W'_jk / s_{k, j/g})))
+ * with W'_jk = fl32(f_j * W_jk) as in the per-channel case (g = I reduces to it exactly).
+ * W: I x O binary16 row-major; qw: [O][I]; s: [O][I/g]; wdq (nullable): binary16 [I][O],
+ * the dequantized (fake-quantized) weights fl16(fl32(q * s)).  I must be a multiple of g. */
+void cq_oracle_weight_quantize_grouped(const uint16_t *W, int64_t I, int64_t O, const float *fold,
+                                       int64_t g, int bits, int8_t *qw, float *s, uint16_t *wdq)
+{
+    int qmax = qmax_of_bits(bits);
+    int64_t ng = I / g;
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < O; ++k)
+        for (int64_t G = 0; G < ng; ++G) {
+            float m = 0.0f;
+            for (int64_t j = G * g; j < (G + 1) * g; ++j) {
+                float w = cq_oracle_half_to_float(W[j * O + k]);
+                if (fold) w = fold[j] * w;
+                if (fabsf(w) > m) m = fabsf(w);
+            }
+            float sk = m / (float)qmax;
+            s[k * ng + G] = sk;
+            for (int64_t j = G * g; j < (G + 1) * g; ++j) {
+                float w = cq_oracle_half_to_float(W[j * O + k]);
+                if (fold) w = fold[j] * w;
+                int q = quantize_one(w, sk, qmax);
+                qw[k * I + j] = (int8_t)q;
+                if (wdq) wdq[j * O + k] = cq_oracle_float_to_half((float)q * sk);
+            }
+        }
+}

@@ -4,19 +4,20 @@ The work is done by hand-written HIP kernels for gfx950 behind the C ABI declare
 ``include/crossquant.h`` (``libcrossquant.so``, built in-tree by ``paper_2410_07505_amd.build``).
 This package is only the argument-marshalling layer: torch supplies device memory and the
 stream handle; every step of the path runs in the library's kernels.  There is no CPU or
-eager fallback: if the shared library is missing, importing :mod:`binding` raises.
+eager fallback: the first use of any entry point loads the shared library and raises if it is
+missing or stale (the binding is imported on first use so that ``python -m
+paper_2410_07505_amd.build`` can run before the library exists).
 """
-from .binding import (  # noqa: F401
-    LIB_PATH,
-    CrossQuantError,
-    crossquant_absmax,
-    crossquant_kernel_analysis,
-    crossquant_kernel_count,
-    crossquant_quantize,
-    crossquant_status_string,
-    crossquant_version,
-    crossquant_w8a8_linear,
-    crossquant_weight_quantize,
-    lib,
-    raw,
+_EXPORTS = (
+    "LIB_PATH", "CrossQuantError", "crossquant_absmax", "crossquant_kernel_analysis", "crossquant_kernel_count",
+    "crossquant_quantize", "crossquant_status_string", "crossquant_version", "crossquant_w8a8_linear",
+    "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "lib", "raw",
 )
+__all__ = list(_EXPORTS)
+
+
+def __getattr__(name):
+    if name in _EXPORTS:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError("module %r has no attribute %r" % (__name__, name))

@@ -28,9 +28,11 @@ lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int,
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
+lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
 for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count", "crossquant_kernel_analysis",
-           "crossquant_weight_quantize", "crossquant_w8a8_linear", "crossquant_version"):
+           "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "crossquant_w8a8_linear",
+           "crossquant_version"):
     getattr(lib, _n).restype = _int
 lib.crossquant_status_string.argtypes = [_int]
 lib.crossquant_status_string.restype = ctypes.c_char_p
@@ -187,6 +189,30 @@ def crossquant_weight_quantize(W: torch.Tensor, fold, bits: int, *, qw: torch.Te
     _check(lib.crossquant_weight_quantize(W.data_ptr(), I, O, _ptr(fold), int(bits), qw.data_ptr(),
                                           w_scale.data_ptr(), _stream(W)))
     return qw, w_scale
+
+
+def crossquant_weight_quantize_grouped(W: torch.Tensor, fold, group: int, bits: int, *, want_dq: bool = False,
+                                       qw: torch.Tensor = None, w_scale: torch.Tensor = None,
+                                       w_dq: torch.Tensor = None):
+    """Group-wise weight codes qw (int8 [O][I]), steps (float32 [O][I/group]) and, optionally, the
+    dequantized weights (float16 [I][O])."""
+    _req(W, torch.float16, "W", 2)
+    if not W.is_contiguous():
+        raise ValueError("W must be contiguous")
+    I, O = W.shape
+    if group < 1 or I % group:
+        raise ValueError("the group size must divide the number of input channels")
+    if qw is None:
+        qw = torch.empty((O, I), dtype=torch.int8, device=W.device)
+    if w_scale is None:
+        w_scale = torch.empty((O, I // group), dtype=torch.float32, device=W.device)
+    if w_dq is None and want_dq:
+        w_dq = torch.empty((I, O), dtype=torch.float16, device=W.device)
+    if fold is not None:
+        _req(fold, torch.float32, "fold", 1)
+    _check(lib.crossquant_weight_quantize_grouped(W.data_ptr(), I, O, _ptr(fold), int(group), int(bits),
+                                                  qw.data_ptr(), w_scale.data_ptr(), _ptr(w_dq), _stream(W)))
+    return qw, w_scale, w_dq
 
 
 def crossquant_w8a8_linear(qx: torch.Tensor, row_scale: torch.Tensor, qw: torch.Tensor, w_scale: torch.Tensor, *,

@@ -108,6 +108,19 @@ int crossquant_weight_quantize(const void* W, int64_t I, int64_t O, const float*
                                                w_scale, static_cast<hipStream_t>(stream)));
 }
 
+int crossquant_weight_quantize_grouped(const void* W, int64_t I, int64_t O, const float* fold, int64_t group,
+                                       int bits, int8_t* qw, float* w_scale, void* w_dq, void* stream) {
+    if (!W || !qw || !w_scale) return CQ_ERR_NULL;
+    if (!dim_ok(I) || !dim_ok(O) || I * O > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    if (group < 1 || group > I || I % group != 0) return CQ_ERR_SHAPE;
+    if (bits != 4 && bits != 8) return CQ_ERR_BITS;
+    if (!aligned(W, 2) || !aligned(w_scale, 4) || !aligned(fold, 4) || !aligned(w_dq, 2)) return CQ_ERR_ALIGN;
+    const int qmax = (1 << (bits - 1)) - 1;
+    return from_hip(cq::launch_weight_quantize_grouped(static_cast<const uint16_t*>(W), (int)I, (int)O, fold,
+                                                       (int)group, qmax, qw, w_scale,
+                                                       static_cast<uint16_t*>(w_dq), static_cast<hipStream_t>(stream)));
+}
+
 int crossquant_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_t* qw, const float* w_scale,
                            int64_t T, int64_t I, int64_t O, void* Y, int64_t ldy, int32_t* acc_debug,
                            void* stream) {

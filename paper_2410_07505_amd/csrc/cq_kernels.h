@@ -44,6 +44,9 @@ hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const f
 hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* fold, int qmax,
                                   int8_t* qw, float* w_scale, hipStream_t stream);
 
+hipError_t launch_weight_quantize_grouped(const uint16_t* W, int I, int O, const float* fold, int group, int qmax,
+                                          int8_t* qw, float* w_scale, uint16_t* wdq, hipStream_t stream);
+
 hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_t* qw,
                               const float* w_scale, int T, int I, int O, uint16_t* Y, int64_t ldy,
                               int32_t* acc_debug, hipStream_t stream);

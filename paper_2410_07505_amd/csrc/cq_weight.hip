@@ -129,6 +129,113 @@ weight_quant_kernel(const uint16_t* __restrict__ W, int I, int O, const float* _
     }
 }
 
+
+// Group-wise variant: every output channel is cut into groups of g consecutive input channels,
+// each with its own step (Background section's group-wise quantization).  One block handles one
+// group of one 64-channel tile: pass 1 finds the 64 group maxima, pass 2 quantizes, transposes
+// through LDS 32 input channels at a time, and optionally writes the dequantized weights.
+__global__ void __launch_bounds__(256)
+weight_group_kernel(const uint16_t* __restrict__ W, int I, int O, const float* __restrict__ fold, int g,
+                    float qmax, int8_t* __restrict__ qw, float* __restrict__ s, uint16_t* __restrict__ wdq,
+                    int n_k_tiles, bool in_vec, bool out_vec) {
+    __shared__ float lmax[32][64 + 1];
+    __shared__ float lstep[64];
+    __shared__ __align__(16) int8_t tile[64][32 + 8];          // [k][j within the 32-row pass]
+    const int kt = blockIdx.x % n_k_tiles, G = blockIdx.x / n_k_tiles;
+    const int ng = I / g;
+    const int c8 = threadIdx.x & 7, jr = threadIdx.x >> 3;
+    const int k0 = kt * 64 + c8 * 8;
+    const int j_begin = G * g, j_end = j_begin + g;
+
+    auto load_row = [&](int j, float (&w)[8]) {
+        uint32_t h[8];
+        const uint16_t* row = W + (int64_t)j * O;
+        if (in_vec && k0 + 8 <= O) {
+            const uint4 v = *reinterpret_cast<const uint4*>(row + k0);
+            h[0] = v.x & 0xFFFFu; h[1] = v.x >> 16; h[2] = v.y & 0xFFFFu; h[3] = v.y >> 16;
+            h[4] = v.z & 0xFFFFu; h[5] = v.z >> 16; h[6] = v.w & 0xFFFFu; h[7] = v.w >> 16;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = (k0 + e < O) ? row[k0 + e] : 0u;
+        }
+        const float f = fold ? fold[j] : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            w[e] = h2f(h[e]);
+            if (fold) w[e] = f * w[e];
+        }
+    };
+
+    float m[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m[e] = 0.0f;
+    for (int j = j_begin + jr; j < j_end; j += 32) {
+        float w[8];
+        load_row(j, w);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] = __builtin_fmaxf(m[e], __builtin_fabsf(w[e]));
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) lmax[jr][c8 * 8 + e] = m[e];
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        float mm = 0.0f;
+        for (int r = 0; r < 32; ++r) mm = __builtin_fmaxf(mm, lmax[r][threadIdx.x]);
+        const float step = mm / qmax;
+        lstep[threadIdx.x] = step;
+        const int k = kt * 64 + threadIdx.x;
+        if (k < O) s[(int64_t)k * ng + G] = step;
+    }
+    __syncthreads();
+    float sk[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sk[e] = lstep[c8 * 8 + e];
+
+    for (int jb = j_begin; jb < j_end; jb += 32) {
+        const int j = jb + jr;
+        if (j < j_end) {
+            float w[8];
+            load_row(j, w);
+            uint32_t hq[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float r = (sk[e] == 0.0f) ? 0.0f : w[e] / sk[e];
+                r = __builtin_rintf(r);
+                r = __builtin_amdgcn_fmed3f(r, -qmax, qmax);
+                tile[c8 * 8 + e][jr] = (int8_t)(int)r;
+                hq[e] = f2h(rounded_f32((float)(int)r * sk[e]));
+            }
+            if (wdq) {
+                uint16_t* dst = wdq + (int64_t)j * O + k0;
+                if (in_vec && k0 + 8 <= O && (reinterpret_cast<uintptr_t>(wdq) % 16 == 0)) {
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(hq[0] | (hq[1] << 16), hq[2] | (hq[3] << 16),
+                                                                hq[4] | (hq[5] << 16), hq[6] | (hq[7] << 16));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (k0 + e < O) dst[e] = (uint16_t)hq[e];
+                }
+            }
+        }
+        __syncthreads();
+        {   // 64 rows (k) of up to 32 bytes (j): thread -> (k local, 8-byte piece)
+            const int kl = threadIdx.x >> 2, piece = threadIdx.x & 3;
+            const int k = kt * 64 + kl;
+            const int jo = jb + piece * 8;
+            if (k < O && jo < j_end) {
+                int8_t* dst = qw + (int64_t)k * I + jo;
+                if (out_vec && jo + 8 <= j_end) {
+                    *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(&tile[kl][piece * 8]);
+                } else {
+                    for (int e = 0; e < 8; ++e)
+                        if (jo + e < j_end) dst[e] = tile[kl][piece * 8 + e];
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace
 
 hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* fold, int qmax, int8_t* qw,
@@ -148,6 +255,16 @@ hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* 
         weight_quant_kernel<<<dim3((unsigned)(nkt * njt)), dim3(256), 0, stream>>>(
             W, I, O, fold, w_scale, (float)qmax, qw, nkt, in_vec, out_vec);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_weight_quantize_grouped(const uint16_t* W, int I, int O, const float* fold, int group, int qmax,
+                                          int8_t* qw, float* w_scale, uint16_t* wdq, hipStream_t stream) {
+    const int nkt = (O + 63) / 64, ng = I / group;
+    const bool in_vec = (reinterpret_cast<uintptr_t>(W) % 16 == 0) && (O % 8 == 0);
+    const bool out_vec = (reinterpret_cast<uintptr_t>(qw) % 8 == 0) && (I % 8 == 0) && (group % 8 == 0);
+    weight_group_kernel<<<dim3((unsigned)(nkt * ng)), dim3(256), 0, stream>>>(W, I, O, fold, group, (float)qmax, qw,
+                                                                             w_scale, wdq, nkt, in_vec, out_vec);
     return hipGetLastError();
 }
 

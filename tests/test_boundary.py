@@ -115,6 +115,17 @@ def test_weight_quantize_argument_errors(cq):
     assert f(P, 8, 8, P + 2, 8, P, P, None) == -5
 
 
+def test_weight_quantize_grouped_argument_errors(cq):
+    f = cq.raw.crossquant_weight_quantize_grouped
+    assert f(0, 8, 8, None, 8, 8, P, P, None, None) == -1
+    assert f(P, 8, 8, None, 8, 8, P, 0, None, None) == -1
+    assert f(P, 8, 8, None, 3, 8, P, P, None, None) == -2       # group does not divide I
+    assert f(P, 8, 8, None, 0, 8, P, P, None, None) == -2
+    assert f(P, 8, 8, None, 16, 8, P, P, None, None) == -2
+    assert f(P, 8, 8, None, 8, 7, P, P, None, None) == -3
+    assert f(P, 8, 8, None, 8, 8, P, P, P + 1, None) == -5
+
+
 def test_linear_argument_errors(cq):
     f = cq.raw.crossquant_w8a8_linear
 

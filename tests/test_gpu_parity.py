@@ -329,6 +329,46 @@ def test_weight_quantize_small_and_ragged(cq, I, O, bits):
         assert np.array_equal(host(qw), qw_ref)
 
 
+@pytest.mark.parametrize("I,O,group", [(8, 8, 8), (96, 20, 32), (96, 20, 8), (256, 256, 128), (384, 130, 128),
+                                         (130, 77, 10), (1024, 520, 64), (70, 45, 70)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_weight_quantize_grouped(cq, I, O, group, bits):
+    say("grouped weight quantize I=%d O=%d g=%d bits=%d" % (I, O, group, bits))
+    W = workloads.weight(I, O, seed=I * 3 + O)
+    if I >= 2 * group and O > 3:
+        W[group:2 * group, 2] = 0                                  # an all-zero group
+    fold = np.random.default_rng(O).uniform(0.05, 8.0, I).astype(np.float32)
+    for f in (None, fold):
+        qw_ref, s_ref, dq_ref = oracle.weight_quantize_grouped(W, f, group, bits)
+        qw, s, dq = cq.crossquant_weight_quantize_grouped(gpu(W), None if f is None else gpu(f), group, bits,
+                                                          want_dq=True)
+        assert np.array_equal(bits32(host(s)), bits32(s_ref))
+        assert np.array_equal(host(qw), qw_ref)
+        assert np.array_equal(bits16(host(dq)), bits16(dq_ref))
+        qw2, s2, none_dq = cq.crossquant_weight_quantize_grouped(gpu(W), None if f is None else gpu(f), group, bits)
+        assert none_dq is None and np.array_equal(host(qw2), qw_ref) and np.array_equal(host(s2), s_ref)
+
+
+def test_weight_crossquant_through_the_activation_calls(cq):
+    """CrossQuant on weights (alpha_W): the activation calls applied to the weight stored
+    output-channel-major; alpha_W = 1 reproduces per-channel quantization (Eq. 2)."""
+    say("weight crossquant")
+    W = workloads.weight(512, 384, seed=5)
+    Wt = np.ascontiguousarray(W.T)
+    Wg = gpu(Wt)
+    t, c = cq.crossquant_absmax(Wg)
+    for alpha_w in (1.0, 0.55, 0.0):
+        t_ref, c_ref = oracle.absmax(Wt)
+        ref = oracle.quantize(Wt, t_ref, c_ref, alpha_w, 8)
+        codes, what, u, v, _ = cq.crossquant_quantize(Wg, t, c, alpha_w, 8)
+        assert np.array_equal(host(codes), ref["codes"]) and np.array_equal(bits16(host(what)), bits16(ref["xhat"]))
+        assert np.array_equal(host(u), ref["a"]) and np.array_equal(host(v), ref["b"])
+    qw_pc, s_pc = cq.crossquant_weight_quantize(gpu(W), None, 8)
+    codes, _, u, _, _ = cq.crossquant_quantize(Wg, t, c, 1.0, 8, want_xhat=False)
+    import torch
+    assert torch.equal(codes, qw_pc) and torch.equal(u, s_pc)
+
+
 # ----------------------------------------------------------------------------- linear
 LINEAR_SHAPES = [(1, 16, 1), (5, 32, 7), (100, 200, 300), (64, 256, 256), (256, 128, 256), (300, 208, 270),
                  (256, 1024, 512), (513, 384, 257), (33, 100, 65)]

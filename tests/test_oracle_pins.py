@@ -518,3 +518,48 @@ def test_indicators_on_outlier_inputs_follow_the_paper():
     an = oracle.kernel_analysis(X, t, c, 0.15, 8, want_xrk=False)
     assert an["n_col_ge_row"] / X.size < 0.05
     assert an["n_bound_smaller"] / X.size > 0.95
+
+
+# ----------------------------------------------------------------------------- group-wise weights
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("group", [8, 32, 96])
+def test_grouped_weight_quantize(bits, group):
+    qm = 2 ** (bits - 1) - 1
+    I, O = 96, 20
+    W = workloads.weight(I, O, seed=9)
+    W[8:16, 5] = 0                                       # one all-zero group
+    fold = np.random.default_rng(4).uniform(0.5, 3.0, I).astype(np.float32)
+    for f in (None, fold):
+        qw, s, wdq = oracle.weight_quantize_grouped(W, f, group, bits)
+        Wf = W.astype(np.float32) if f is None else f[:, None] * W.astype(np.float32)
+        G = Wf.reshape(I // group, group, O)             # [group index][j in group][k]
+        m = np.abs(G).max(axis=1)                        # [I/g][O]
+        want_s = (m / np.float32(qm)).T                  # [O][I/g]
+        assert np.array_equal(s, want_s)
+        step = np.repeat(want_s.T, group, axis=0)        # [I][O]
+        with np.errstate(divide="ignore", invalid="ignore"):
+            q = np.where(step == 0, 0, np.rint(Wf / step)).astype(np.int8)
+        assert np.array_equal(qw, q.T)
+        assert np.array_equal(wdq.view(np.uint16), (q.astype(np.float32) * step).astype(np.float16).view(np.uint16))
+        # every group's largest weight sits on +-q_max; the reconstruction error is at most half a step
+        nz = want_s.T > 0
+        assert np.all(np.abs(q.reshape(I // group, group, O)).max(axis=1)[nz] == qm)
+        assert np.all(np.abs(wdq.astype(np.float64) - Wf) <= 0.5 * step * (1 + 1e-6) + 1e-3 * np.abs(Wf) + 1e-9)
+    if group == 96:                                       # one group per channel = Eq. 2 per-channel
+        qw_pc, s_pc = oracle.weight_quantize(W, None, bits)
+        qw, s, _ = oracle.weight_quantize_grouped(W, None, 96, bits, want_dq=False)
+        assert np.array_equal(qw, qw_pc) and np.array_equal(s[:, 0], s_pc)
+
+
+def test_weight_crossquant_is_the_activation_routine_on_the_stored_weight():
+    """CrossQuant on weights (Appendix B.1, alpha_W): the same equation applied to the weight
+    matrix stored output-channel-major; alpha_W = 1 is per-channel quantization (Eq. 2)."""
+    W = workloads.weight(40, 24, seed=2)
+    Wt = np.ascontiguousarray(W.T)                       # [O][I], one row per output channel
+    t, c = oracle.absmax(Wt)
+    r = oracle.quantize(Wt, t, c, 1.0, 8)
+    qw_pc, s_pc = oracle.weight_quantize(W, None, 8)
+    assert np.array_equal(r["codes"], qw_pc) and np.array_equal(r["a"], s_pc)
+    r0 = oracle.quantize(Wt, t, c, 0.0, 8)               # alpha_W = 0: one step per input channel
+    im = np.abs(Wt.astype(np.float32)).argmax(axis=0)
+    assert np.array_equal(np.abs(r0["codes"][im, np.arange(40)]), np.full(40, 127))
