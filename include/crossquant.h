@@ -104,6 +104,14 @@ int crossquant_kernel_analysis(const void *X, int64_t T, int64_t I, int64_t ldx,
                                float *col_scale, unsigned long long *counters, void *stream);
 
 /*
+ * Expand packed INT4 codes (crossquant_quantize with bits == 4) to int8 codes in [-7, 7], so that
+ * A4 activations can feed crossquant_w8a8_linear (gfx950 has no INT4 matrix instruction; weight
+ * codes from crossquant_weight_quantize with bits == 4 are already stored one per byte).
+ * packed: [T][I/2], even column in the low nibble; I even.  codes: out, int8 [T][I].
+ */
+int crossquant_unpack_int4(const void *packed, int64_t T, int64_t I, int8_t *codes, void *stream);
+
+/*
  * Per-channel weight quantization (Eq. 2), one step per OUTPUT channel k, stored transposed.
  *   W'_jk = fl32(fold_j * W_jk)  (fold NULL = 1);  s_k = fl32(max_j |W'_jk| / q_max)
  *   qw_kj = s_k == 0 ? 0 : clamp(rne(fl32(W'_jk / s_k)), +-q_max)

@@ -27,10 +27,11 @@ lib.crossquant_absmax.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp]
 lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
+lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]
 lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
 lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
-for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count", "crossquant_kernel_analysis",
+for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
            "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "crossquant_w8a8_linear",
            "crossquant_version"):
     getattr(lib, _n).restype = _int
@@ -169,6 +170,18 @@ def crossquant_kernel_analysis(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor
                                           float(alpha), int(bits), _ptr(xrk), row_scale.data_ptr(),
                                           col_scale.data_ptr(), counters.data_ptr(), _stream(X)))
     return xrk, counters
+
+
+def crossquant_unpack_int4(packed: torch.Tensor, *, codes: torch.Tensor = None) -> torch.Tensor:
+    """Packed INT4 codes (uint8 [T][I/2]) -> int8 codes [T][I]."""
+    _req(packed, torch.uint8, "packed", 2)
+    if not packed.is_contiguous():
+        raise ValueError("packed must be contiguous")
+    T, half = packed.shape
+    if codes is None:
+        codes = torch.empty((T, 2 * half), dtype=torch.int8, device=packed.device)
+    _check(lib.crossquant_unpack_int4(packed.data_ptr(), T, 2 * half, codes.data_ptr(), _stream(packed)))
+    return codes
 
 
 def crossquant_weight_quantize(W: torch.Tensor, fold, bits: int, *, qw: torch.Tensor = None,

@@ -97,6 +97,13 @@ int crossquant_kernel_analysis(const void* X, int64_t T, int64_t I, int64_t ldx,
                                                st));
 }
 
+int crossquant_unpack_int4(const void* packed, int64_t T, int64_t I, int8_t* codes, void* stream) {
+    if (!packed || !codes) return CQ_ERR_NULL;
+    if (!dim_ok(T) || !dim_ok(I) || (I & 1) || T * I > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    return from_hip(cq::launch_unpack_int4(static_cast<const uint8_t*>(packed), T * (I / 2), codes,
+                                           static_cast<hipStream_t>(stream)));
+}
+
 int crossquant_weight_quantize(const void* W, int64_t I, int64_t O, const float* fold, int bits, int8_t* qw,
                                float* w_scale, void* stream) {
     if (!W || !qw || !w_scale) return CQ_ERR_NULL;

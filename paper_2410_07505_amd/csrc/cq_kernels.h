@@ -41,6 +41,9 @@ hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const f
                            const float* b, int bits, void* codes, uint16_t* xhat,
                            unsigned long long* zero_count, hipStream_t stream);
 
+// packed nibbles [n_bytes] -> int8 codes [2 * n_bytes]
+hipError_t launch_unpack_int4(const uint8_t* packed, int64_t n_bytes, int8_t* codes, hipStream_t stream);
+
 hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* fold, int qmax,
                                   int8_t* qw, float* w_scale, hipStream_t stream);
 

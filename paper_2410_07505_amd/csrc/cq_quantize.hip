@@ -250,7 +250,58 @@ hipError_t launch_mode(const uint16_t* X, int T, int I, int64_t ldx, const float
     return hipGetLastError();
 }
 
+// Packed two's-complement nibbles -> int8 codes (even column in the low nibble), so that INT4
+// activations can feed the INT8 MFMA GEMM (gfx950 has no INT4 matrix instruction).
+// One thread expands 8 packed bytes to 16 codes.
+__global__ void unpack_int4_kernel(const uint8_t* __restrict__ packed, int64_t n_bytes, int8_t* __restrict__ codes,
+                                   bool vec) {
+    const int64_t i8 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (i8 >= n_bytes) return;
+    uint32_t lo = 0u, hi = 0u;
+    const bool full = vec && i8 + 8 <= n_bytes;
+    if (full) {
+        const uint2 v = *reinterpret_cast<const uint2*>(packed + i8);
+        lo = v.x;
+        hi = v.y;
+    } else {
+        for (int e = 0; e < 8 && i8 + e < n_bytes; ++e) {
+            const uint32_t b = packed[i8 + e];
+            if (e < 4) lo |= b << (8 * e); else hi |= b << (8 * (e - 4));
+        }
+    }
+    uint32_t out[4];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        const uint32_t src = w ? hi : lo;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {                // two output words per input word
+            uint32_t o = 0u;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint32_t byte = (src >> (16 * h + 8 * e)) & 0xFFu;
+                const int n0 = (int)(byte & 0xFu), n1 = (int)(byte >> 4);
+                const int c0 = (n0 ^ 8) - 8, c1 = (n1 ^ 8) - 8;      // sign-extend 4 bits
+                o |= ((uint32_t)(c0 & 0xFF) << (16 * e)) | ((uint32_t)(c1 & 0xFF) << (16 * e + 8));
+            }
+            out[2 * w + h] = o;
+        }
+    }
+    int8_t* dst = codes + 2 * i8;
+    if (full) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
+    } else {
+        for (int e = 0; e < 16 && i8 + e / 2 < n_bytes; ++e) dst[e] = (int8_t)((out[e >> 2] >> (8 * (e & 3))) & 0xFFu);
+    }
+}
+
 }  // namespace
+
+hipError_t launch_unpack_int4(const uint8_t* packed, int64_t n_bytes, int8_t* codes, hipStream_t stream) {
+    const bool vec = (reinterpret_cast<uintptr_t>(packed) % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 16 == 0);
+    const int64_t n_threads = (n_bytes + 7) / 8;
+    unpack_int4_kernel<<<dim3((unsigned)((n_threads + 255) / 256)), dim3(256), 0, stream>>>(packed, n_bytes, codes, vec);
+    return hipGetLastError();
+}
 
 hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, float alpha, int qmax,
                                  float* a, float* b, unsigned long long* counters, int n_counters,

@@ -70,21 +70,22 @@ __global__ void weight_scale_kernel(float* __restrict__ s, int O, float qmax) {
     if (k < O) s[k] = s[k] / qmax;      // in place: max -> step
 }
 
-// 64 (input channels j) x 64 (output channels k) tile: read along k, write along j.
+// 128 (input channels j) x 64 (output channels k) tile: read along k, write along j in whole
+// 128-byte row pieces.
 __global__ void __launch_bounds__(256)
 weight_quant_kernel(const uint16_t* __restrict__ W, int I, int O, const float* __restrict__ fold,
                     const float* __restrict__ s, float qmax, int8_t* __restrict__ qw, int n_k_tiles,
                     bool in_vec, bool out_vec) {
-    __shared__ __align__(16) int8_t tile[64][64 + 16];     // [k][j], padded
+    __shared__ __align__(16) int8_t tile[64][128 + 16];    // [k][j], padded
     const int kt = blockIdx.x % n_k_tiles, jt = blockIdx.x / n_k_tiles;
-    const int k_base = kt * 64, j_base = jt * 64;
+    const int k_base = kt * 64, j_base = jt * 128;
     const int c8 = threadIdx.x & 7;          // which group of 8 output channels
     const int k0 = k_base + c8 * 8;
     float sk[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) sk[e] = (k0 + e < O) ? s[k0 + e] : 0.0f;
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < 4; ++pass) {
         const int jl = pass * 32 + (threadIdx.x >> 3);
         const int j = j_base + jl;
         uint32_t h[8];
@@ -114,21 +115,24 @@ weight_quant_kernel(const uint16_t* __restrict__ W, int I, int O, const float* _
         }
     }
     __syncthreads();
-    // 64 rows (k) of 64 bytes (j): thread -> (k local, 16-byte piece)
+    // 64 rows (k) of 128 bytes (j): thread -> (k local, 32-byte piece) = two 16-byte stores
     const int kl = threadIdx.x >> 2, piece = threadIdx.x & 3;
     const int k = k_base + kl;
     if (k < O) {
-        const int j = j_base + piece * 16;
-        int8_t* dst = qw + (int64_t)k * I + j;
-        if (out_vec && j + 16 <= I) {
-            *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(&tile[kl][piece * 16]);
-        } else {
-            for (int e = 0; e < 16; ++e)
-                if (j + e < I) dst[e] = tile[kl][piece * 16 + e];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int jo = piece * 32 + half * 16;
+            const int j = j_base + jo;
+            int8_t* dst = qw + (int64_t)k * I + j;
+            if (out_vec && j + 16 <= I) {
+                *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(&tile[kl][jo]);
+            } else {
+                for (int e = 0; e < 16; ++e)
+                    if (j + e < I) dst[e] = tile[kl][jo + e];
+            }
         }
     }
 }
-
 
 // Group-wise variant: every output channel is cut into groups of g consecutive input channels,
 // each with its own step (Background section's group-wise quantization).  One block handles one
@@ -250,7 +254,7 @@ hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* 
     }
     weight_scale_kernel<<<dim3((O + 255) / 256), dim3(256), 0, stream>>>(w_scale, O, (float)qmax);
     {
-        const int nkt = (O + 63) / 64, njt = (I + 63) / 64;
+        const int nkt = (O + 63) / 64, njt = (I + 127) / 128;
         const bool out_vec = (reinterpret_cast<uintptr_t>(qw) % 16 == 0) && (I % 16 == 0);
         weight_quant_kernel<<<dim3((unsigned)(nkt * njt)), dim3(256), 0, stream>>>(
             W, I, O, fold, w_scale, (float)qmax, qw, nkt, in_vec, out_vec);

@@ -126,6 +126,12 @@ def test_weight_quantize_grouped_argument_errors(cq):
     assert f(P, 8, 8, None, 8, 8, P, P, P + 1, None) == -5
 
 
+def test_unpack_int4_argument_errors(cq):
+    f = cq.raw.crossquant_unpack_int4
+    assert f(0, 4, 8, P, None) == -1 and f(P, 4, 8, 0, None) == -1
+    assert f(P, 0, 8, P, None) == -2 and f(P, 4, 7, P, None) == -2
+
+
 def test_linear_argument_errors(cq):
     f = cq.raw.crossquant_w8a8_linear
 

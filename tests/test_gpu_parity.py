@@ -442,6 +442,46 @@ def test_end_to_end_tiny_config(cq):
     assert rel < 0.05
 
 
+@pytest.mark.parametrize("T,I", [(1, 2), (3, 6), (37, 54), (64, 256), (129, 1030)])
+def test_unpack_int4(cq, T, I):
+    say("unpack int4 T=%d I=%d" % (T, I))
+    packed = np.random.default_rng(T + I).integers(0, 256, (T, I // 2), dtype=np.uint8)
+    got = host(cq.crossquant_unpack_int4(gpu(packed)))
+    assert np.array_equal(got, oracle.unpack_int4(packed))
+
+
+def test_end_to_end_a4w4_config(cq):
+    """C4 (4096 x 4096, A4 W4): packed INT4 activations, expanded to bytes, through the INT8 GEMM."""
+    import torch
+    say("end to end C4 (A4W4)")
+    cfg = workloads.CONFIGS["C4"]
+    X, W = workloads.config_activation("C4"), workloads.config_weight("C4")
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, 0.15, 4, want_xhat=False)
+    qx_ref = oracle.unpack_int4(ref["codes"])
+    qw_ref, s_ref = oracle.weight_quantize(W, ref["b"], 4)
+    Xg, Wg = gpu(X), gpu(W)
+    t, c = cq.crossquant_absmax(Xg)
+    packed, _, a, b, zc = cq.crossquant_quantize(Xg, t, c, 0.15, 4, want_xhat=False)
+    z_pt = cq.crossquant_kernel_count(Xg, t, c, 1.0, 4)
+    qx = cq.crossquant_unpack_int4(packed)
+    qw, s = cq.crossquant_weight_quantize(Wg, b, 4)
+    Y, acc = cq.crossquant_w8a8_linear(qx, a, qw, s, want_acc=True)
+    assert np.array_equal(host(packed), ref["codes"]) and np.array_equal(host(qx), qx_ref)
+    assert np.array_equal(host(qw), qw_ref) and np.array_equal(bits32(host(s)), bits32(s_ref))
+    assert int(np.abs(host(qx)).max()) <= 7 and int(np.abs(host(qw)).max()) <= 7
+    rows = np.array([0, 1, 255, 256, 1000, 4095])
+    Yr, accr = oracle.w8a8_linear(qx_ref[rows], ref["a"][rows], qw_ref, s_ref)
+    ridx = torch.from_numpy(rows).cuda()
+    assert np.array_equal(host(acc[ridx]), accr) and np.array_equal(bits16(host(Y[ridx])), bits16(Yr))
+    want_k = (qw_ref.astype(np.float64) @ qx_ref.astype(np.int64).sum(axis=0).astype(np.float64)).astype(np.int64)
+    assert np.array_equal(host(acc.sum(dim=0, dtype=torch.int64)), want_k)
+    # zero-count reported against the per-token baseline, as the low-bit configuration asks
+    z, zp = int(host(zc)[0]), int(host(z_pt)[0])
+    assert z == ref["Z"] and zp == oracle.kernel_count(X, t_ref, c_ref, 1.0, 4) and z < zp
+    say("C4 kernel proportion: crossquant %.4f per-token %.4f" % (z / X.size, zp / X.size))
+
+
 @pytest.mark.parametrize("name", ["C2", "C5"])
 def test_end_to_end_full_config_sampled(cq, name):
     """Full-size run in the benchmark's launch configuration.  Weight codes and steps are
