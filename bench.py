@@ -192,16 +192,21 @@ def main():
     bytes_quant = (2 + 1 + 2) * n + 4 * (T + I)
     bytes_count = 2 * n
     ops_linear = 2.0 * T * I * O
+    # a stage that was switched off (--stages) only measures the gap between two event records
+    ran = {name: (name in stages) for name in ("absmax", "quantize", "count", "linear")}
+    for idx, name in enumerate(("absmax", "quantize", "count", "linear")):
+        if not ran[name]:
+            stage_ms[idx] = 0.0
     quant_gbs = (bytes_absmax + bytes_quant) / ((stage_ms[0] + stage_ms[1]) * 1e-3) / 1e9 \
-        if stage_ms[0] + stage_ms[1] > 0 else 0.0
-    tops = ops_linear / (stage_ms[3] * 1e-3) / 1e12 if stage_ms[3] > 0 else 0.0
+        if (ran["absmax"] and ran["quantize"]) else None
+    tops = ops_linear / (stage_ms[3] * 1e-3) / 1e12 if ran["linear"] else None
 
     z, z_pt = int(zc.item()), int(zc_pt.item())
     out = {
         "metric": METRIC,
         "value": quant_gbs, "unit": "GB/s",
-        "quantize_frac_hbm_peak": quant_gbs / HBM_PEAK_GBS,
-        "w8a8_linear_tops": tops, "w8a8_linear_frac_int8_peak": tops / INT8_PEAK_TOPS,
+        "quantize_frac_hbm_peak": quant_gbs / HBM_PEAK_GBS if quant_gbs else None,
+        "w8a8_linear_tops": tops, "w8a8_linear_frac_int8_peak": tops / INT8_PEAK_TOPS if tops else None,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp16 in, fp32 scale arithmetic, int8 codes, int32 accumulate",
@@ -216,8 +221,8 @@ def main():
             "count_GBs": bytes_count / (stage_ms[2] * 1e-3) / 1e9 if stage_ms[2] > 0 else None,
         },
         "kernel_proportion": {"crossquant": z / n, "per_token": z_pt / n},
-        "roofline": {"kernel": "gemm_i8_direct_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
-                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS,
+        "roofline": {"kernel": "gemm_i8_ring_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
+                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS if tops else None,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},
         "roofline_quantize": {"kernel": "quantize_kernel (codes + xhat + zero count) incl. scale finalize",
                               "bound": "hbm",

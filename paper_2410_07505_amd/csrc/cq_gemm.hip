@@ -391,8 +391,8 @@ gemm_i8_direct_kernel(const int8_t* __restrict__ qx, const float* __restrict__ r
         // MFMAs cover their latency
 #pragma unroll
         for (int i = 0; i < NRD; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
         }
         __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -576,8 +576,10 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     auto interleave_reads = [&]() {
 #pragma unroll
         for (int i = 0; i < NRD; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // reads of the next slab first
+            // an MFMA first (its operands were read a slab ago), then one read of the next slab:
+            // the reads are all out before the slab's last MFMAs, which cover their latency
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -613,6 +615,9 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
         // A loaders: A(kt+2) = half tile 2kt+4 -> slot (2kt+4) % 5 = adv(na); its previous tenant
         // B(kt-1) was released at the previous barrier.  Then tile kt+1's A (requested a step ago)
         // must have landed: at most the 8 requests just made may still be in flight.
+#ifdef CQ_GEMM_SETPRIO
+        __builtin_amdgcn_s_setprio(0);
+#endif
         if (!b_loader) {
             if (ISSUE) {
                 issue_half(kt + 2, adv(na));
@@ -635,12 +640,15 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
         // nobody reads any more (slab 3's fragments are in registers)
         if (b_loader && ISSUE) issue_half(kt + 2, sa);
         __builtin_amdgcn_sched_barrier(0);
+#ifdef CQ_GEMM_SETPRIO
+        __builtin_amdgcn_s_setprio(1);
+#endif
         if (PREFETCH) load_frags<NI>(af0, bf0, lds + na * kSlotBytes, lds + nb * kSlotBytes, a_off, b_off, 0);
         mfma_slab<NI>(acc, af1, bf1);
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
-            if (PREFETCH && i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (PREFETCH && i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
         CQ_STAMP(5);
