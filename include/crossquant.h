@@ -79,6 +79,21 @@ int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const 
                         void *stream);
 
 /*
+ * crossquant_absmax followed by crossquant_quantize, fused: X is read from HBM once and held in
+ * the chip's registers across a grid-wide barrier (cooperative launch), which is possible when
+ * the matrix fits: ceil(T/256) * ceil(I/512) <= number of CUs (256 on MI355X, i.e. up to
+ * 4096 x 8192).  Outputs and arithmetic are exactly those of the two calls (t, c included).
+ * Returns CQ_ERR_UNSUPPORTED, with nothing enqueued, if the matrix is too large, if the device
+ * cannot launch cooperatively, or if the layout is not the vector one (X and xhat 16-byte
+ * aligned, codes 8-byte aligned, ldx % 8 == 0, I % 8 == 0): the caller then uses the two calls.
+ * Must not run concurrently with other kernels that occupy CUs of the same device for long
+ * (the grid barrier needs all blocks resident; the runtime enforces this at launch).
+ */
+int crossquant_absmax_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits,
+                               float *t, float *c, void *codes, void *xhat, float *row_scale,
+                               float *col_scale, unsigned long long *zero_count, void *stream);
+
+/*
  * Size of the quantization kernel K(CQ) = {X_ij : CQ(X_ij) = 0} (Definition 1) without writing
  * codes; the kernel proportion of the paper is zero_count / (T*I).  alpha = 1 gives the
  * per-token baseline K(Q) of Eq. 1.

@@ -25,13 +25,14 @@ lib = ctypes.CDLL(LIB_PATH)
 _vp, _i64, _int, _f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
 lib.crossquant_absmax.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp]
 lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.crossquant_absmax_quantize.argtypes = [_vp, _i64, _i64, _i64, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]
 lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
 lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
-for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
+for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_absmax_quantize", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
            "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "crossquant_w8a8_linear",
            "crossquant_version"):
     getattr(lib, _n).restype = _int
@@ -127,6 +128,44 @@ def crossquant_quantize(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha
                                    int(bits), codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(),
                                    col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
     return codes, xhat, row_scale, col_scale, zero_count
+
+
+def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want_xhat: bool = True,
+                               want_count: bool = True, t: torch.Tensor = None, c: torch.Tensor = None,
+                               codes: torch.Tensor = None, xhat: torch.Tensor = None,
+                               row_scale: torch.Tensor = None, col_scale: torch.Tensor = None,
+                               zero_count: torch.Tensor = None):
+    """crossquant_absmax + crossquant_quantize in one single-read kernel.
+
+    Returns (t, c, codes, xhat_or_None, row_scale, col_scale, zero_count_or_None).  Raises
+    CrossQuantError with status -6 when the matrix does not fit on chip or is not in the
+    vector layout; the caller then makes the two calls."""
+    _req(X, torch.float16, "X", 2)
+    T, I = X.shape
+    dev = X.device
+    if t is None:
+        t = torch.empty(T, dtype=torch.float32, device=dev)
+    if c is None:
+        c = torch.empty(I, dtype=torch.float32, device=dev)
+    if codes is None:
+        codes = (torch.empty((T, I), dtype=torch.int8, device=dev) if bits == 8
+                 else torch.empty((T, max(I // 2, 1)), dtype=torch.uint8, device=dev))
+    if xhat is None and want_xhat:
+        xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
+    if row_scale is None:
+        row_scale = torch.empty(T, dtype=torch.float32, device=dev)
+    if col_scale is None:
+        col_scale = torch.empty(I, dtype=torch.float32, device=dev)
+    if zero_count is None and want_count:
+        zero_count = torch.empty(1, dtype=torch.int64, device=dev)
+    for ten, name in ((t, "t"), (c, "c"), (row_scale, "row_scale"), (col_scale, "col_scale")):
+        _req(ten, torch.float32, name, 1)
+    if not codes.is_contiguous() or (xhat is not None and not xhat.is_contiguous()):
+        raise ValueError("codes and xhat must be contiguous")
+    _check(lib.crossquant_absmax_quantize(X.data_ptr(), T, I, X.stride(0), float(alpha), int(bits), t.data_ptr(),
+                                          c.data_ptr(), codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(),
+                                          col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
+    return t, c, codes, xhat, row_scale, col_scale, zero_count
 
 
 def crossquant_kernel_count(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,

@@ -15,63 +15,13 @@
 // 32-byte request; 64 columns = 256 bytes per instruction).
 // The atomics act on the binary32 bit pattern as an unsigned integer (values are >= 0), so the
 // result is exact and independent of the order in which blocks finish.
-#include "cq_kernels.h"
+#include "cq_device.h"
 
 namespace cq {
 namespace {
 
-typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-
-constexpr int kLanes = 64;
-constexpr int kColsPerWave = kLanes * 8;  // 512
 constexpr int kWaves = 4;
 constexpr int kBatch = 8;                 // rows per wave per batch
-
-__device__ __forceinline__ uint32_t pkmax(uint32_t a, uint32_t b) {
-    us2 r = __builtin_elementwise_max(__builtin_bit_cast(us2, a), __builtin_bit_cast(us2, b));
-    return __builtin_bit_cast(uint32_t, r);
-}
-
-__device__ __forceinline__ uint32_t half_bits_to_float_bits(uint32_t h) { return __float_as_uint(h2f(h)); }
-
-__device__ __forceinline__ uint32_t shx(uint32_t v, int off) { return (uint32_t)__shfl_xor((int)v, off, kLanes); }
-
-// 8 halfs starting at column j of a row; columns >= I read as zero (neutral for a maximum).
-template <bool VEC>
-__device__ __forceinline__ uint4 load8(const uint16_t* __restrict__ row, int j, int I) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (VEC && j + 8 <= I) {
-        v = *reinterpret_cast<const uint4*>(row + j);
-    } else if (j < I) {
-        uint32_t h[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = (j + e < I) ? row[j + e] : 0u;
-        v.x = h[0] | (h[1] << 16);
-        v.y = h[2] | (h[3] << 16);
-        v.z = h[4] | (h[5] << 16);
-        v.w = h[6] | (h[7] << 16);
-    }
-    return v;
-}
-
-// rm[g] = this lane's maximum over its 8 columns of row g (a 16-bit pattern).  Returns, in lane
-// l with (l & 7) == 0, the maximum over all 64 lanes of row (l >> 3).
-__device__ __forceinline__ uint32_t rows8_reduce(const uint32_t* rm, int lane) {
-    const uint32_t p0 = rm[0] | (rm[1] << 16), p1 = rm[2] | (rm[3] << 16);
-    const uint32_t p2 = rm[4] | (rm[5] << 16), p3 = rm[6] | (rm[7] << 16);
-    const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8;
-    // lanes with bit 5 clear keep rows 0-3 and hand rows 4-7 to their partner, and vice versa
-    const uint32_t q0 = pkmax(b5 ? p2 : p0, shx(b5 ? p0 : p2, 32));
-    const uint32_t q1 = pkmax(b5 ? p3 : p1, shx(b5 ? p1 : p3, 32));
-    const uint32_t r = pkmax(b4 ? q1 : q0, shx(b4 ? q0 : q1, 16));
-    const uint32_t keep = b3 ? (r >> 16) : (r & 0xFFFFu);
-    const uint32_t send = b3 ? (r & 0xFFFFu) : (r >> 16);
-    uint32_t m = max(keep, shx(send, 8));
-    m = max(m, shx(m, 4));
-    m = max(m, shx(m, 2));
-    m = max(m, shx(m, 1));
-    return m;
-}
 
 __global__ void zero_fill_kernel(uint32_t* __restrict__ p0, int n0, uint32_t* __restrict__ p1, int n1) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -105,16 +55,7 @@ absmax_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, uint32_
             v[k] = (rb + k < T) ? load8<VEC>(X + (int64_t)(rb + k) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
         uint32_t rm[kBatch];
 #pragma unroll
-        for (int k = 0; k < kBatch; ++k) {
-            const uint32_t x0 = v[k].x & 0x7FFF7FFFu, x1 = v[k].y & 0x7FFF7FFFu;
-            const uint32_t x2 = v[k].z & 0x7FFF7FFFu, x3 = v[k].w & 0x7FFF7FFFu;
-            c0 = pkmax(c0, x0);
-            c1 = pkmax(c1, x1);
-            c2 = pkmax(c2, x2);
-            c3 = pkmax(c3, x3);
-            const uint32_t m = pkmax(pkmax(x0, x1), pkmax(x2, x3));
-            rm[k] = max(m & 0xFFFFu, m >> 16);
-        }
+        for (int k = 0; k < kBatch; ++k) rm[k] = absmax8(v[k], c0, c1, c2, c3);
         const uint32_t m = rows8_reduce(rm, lane);
         const int r = rb + (lane >> 3);
         if ((lane & 7) == 0 && r < T && m) atomicMax(&t_bits[r], half_bits_to_float_bits(m));

@@ -1,0 +1,199 @@
+// Device-side building blocks shared by the streaming kernels (absmax, quantize, fused).
+#pragma once
+#include "cq_kernels.h"
+
+namespace cq {
+
+constexpr int kLanes = 64;
+constexpr int kColsPerWave = kLanes * 8;          // a wave owns 512 columns: 8 halfs (16 bytes) per lane
+constexpr float kMagic = 12582912.0f;             // 1.5 * 2^23: adding it rounds to nearest-even integer
+constexpr float kTieTol = 1.9073486328125e-06f;   // 2^-19
+
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// packed maximum of two pairs of 16-bit patterns (|x| of binary16 orders like an unsigned integer)
+__device__ __forceinline__ uint32_t pkmax(uint32_t a, uint32_t b) {
+    us2 r = __builtin_elementwise_max(__builtin_bit_cast(us2, a), __builtin_bit_cast(us2, b));
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ uint32_t half_bits_to_float_bits(uint32_t h) { return __float_as_uint(h2f(h)); }
+
+__device__ __forceinline__ uint32_t shx(uint32_t v, int off) { return (uint32_t)__shfl_xor((int)v, off, kLanes); }
+
+// 8 halfs starting at column j of a row; columns >= I read as zero.
+template <bool VEC>
+__device__ __forceinline__ uint4 load8(const uint16_t* __restrict__ row, int j, int I) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (VEC && j + 8 <= I) {
+        v = *reinterpret_cast<const uint4*>(row + j);
+    } else if (j < I) {
+        uint32_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = (j + e < I) ? row[j + e] : 0u;
+        v.x = h[0] | (h[1] << 16);
+        v.y = h[2] | (h[3] << 16);
+        v.z = h[4] | (h[5] << 16);
+        v.w = h[6] | (h[7] << 16);
+    }
+    return v;
+}
+
+// Per-lane maximum |x| of a 16-byte piece (a 16-bit pattern), also folded into four packed
+// running column maxima.
+__device__ __forceinline__ uint32_t absmax8(const uint4& v, uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3) {
+    const uint32_t x0 = v.x & 0x7FFF7FFFu, x1 = v.y & 0x7FFF7FFFu;
+    const uint32_t x2 = v.z & 0x7FFF7FFFu, x3 = v.w & 0x7FFF7FFFu;
+    c0 = pkmax(c0, x0);
+    c1 = pkmax(c1, x1);
+    c2 = pkmax(c2, x2);
+    c3 = pkmax(c3, x3);
+    const uint32_t m = pkmax(pkmax(x0, x1), pkmax(x2, x3));
+    return max(m & 0xFFFFu, m >> 16);
+}
+
+// rm[g] = this lane's maximum over its 8 columns of row g (a 16-bit pattern).  Returns, in lane
+// l with (l & 7) == 0, the maximum over all 64 lanes of row (l >> 3).  A transposed butterfly:
+// every exchange step halves the number of rows a lane still carries (7 shuffles for 8 rows).
+__device__ __forceinline__ uint32_t rows8_reduce(const uint32_t* rm, int lane) {
+    const uint32_t p0 = rm[0] | (rm[1] << 16), p1 = rm[2] | (rm[3] << 16);
+    const uint32_t p2 = rm[4] | (rm[5] << 16), p3 = rm[6] | (rm[7] << 16);
+    const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8;
+    // lanes with bit 5 clear keep rows 0-3 and hand rows 4-7 to their partner, and vice versa
+    const uint32_t q0 = pkmax(b5 ? p2 : p0, shx(b5 ? p0 : p2, 32));
+    const uint32_t q1 = pkmax(b5 ? p3 : p1, shx(b5 ? p1 : p3, 32));
+    const uint32_t r = pkmax(b4 ? q1 : q0, shx(b4 ? q0 : q1, 16));
+    const uint32_t keep = b3 ? (r >> 16) : (r & 0xFFFFu);
+    const uint32_t send = b3 ? (r & 0xFFFFu) : (r >> 16);
+    uint32_t m = max(keep, shx(send, 8));
+    m = max(m, shx(m, 4));
+    m = max(m, shx(m, 2));
+    m = max(m, shx(m, 1));
+    return m;
+}
+
+// ---- scale factors of the CrossQuant step (binary64 pow, one rounding to binary32).
+// pow(x, 0) = 1 for every x and pow(x, 1) = x are exact in any correct pow; they are written out
+// so that the two special exponents (per-column and per-token steps) never depend on it.
+__device__ __forceinline__ float row_factor(float t, double al, int qmax) {
+    const double ti = (double)t;
+    const double p = (al == 0.0) ? 1.0 : (al == 1.0 ? ti : pow(ti, al));
+    return (float)(p / (double)qmax);
+}
+__device__ __forceinline__ float col_factor(float c, double al) {
+    const double cj = (double)c;
+    const double e = 1.0 - al;
+    const double p = (e == 0.0) ? 1.0 : (e == 1.0 ? cj : pow(cj, e));
+    return (float)p;
+}
+
+__device__ __forceinline__ float safe_rcp(float v) { return (v == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(v); }
+
+__device__ __forceinline__ float half_lo(uint32_t w) { return h2f(w & 0xFFFFu); }
+__device__ __forceinline__ float half_hi(uint32_t w) { return h2f(w >> 16); }
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) { return f2h(lo) | (f2h(hi) << 16); }
+
+// bytes 0 of four words -> one word
+__device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_t u2, uint32_t u3) {
+    const uint32_t p01 = __builtin_amdgcn_perm(u1, u0, 0x0c0c0400u);
+    const uint32_t p23 = __builtin_amdgcn_perm(u3, u2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+}
+
+// ---- one lane's 8 elements of one row.  On return m[e] = kMagic + q_e with
+// q_e = clamp(rne(fl32(x_e / fl32(a * b[e]))), +-qmax), identical to dividing every element.
+// The quotient is first approximated as x * (1/a) * (1/b) (ra, rb: reciprocals within 1 ulp, 0
+// where the factor is 0), which lies within 2^-21 relative of the correctly rounded quotient
+// (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own); the rounded
+// integer can differ from the exact one only if the approximation lies within that distance of
+// a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2 (a 4x margin) and a wave in
+// which any lane trips recomputes its eight elements with the exact division.
+__device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, const float (&b)[8],
+                                          const float (&rb)[8], float qmax, float (&m)[8]) {
+    float x[8];
+    x[0] = half_lo(v.x); x[1] = half_hi(v.x);
+    x[2] = half_lo(v.y); x[3] = half_hi(v.y);
+    x[4] = half_lo(v.z); x[5] = half_hi(v.z);
+    x[6] = half_lo(v.w); x[7] = half_hi(v.w);
+    float score = 0.0f;                                 // max over the 8 elements of |frac| + |r| * tol
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float rt = x[e] * (ra * rb[e]);
+        rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
+        m[e] = rt + kMagic;
+        const float f = rt - (m[e] - kMagic);
+        score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)));
+    }
+    if (__any(score >= 0.5f)) {                         // rare: exact division for this wave's row piece
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float D = a * b[e];
+            float rt = (D == 0.0f) ? 0.0f : x[e] / D;
+            rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
+            m[e] = rt + kMagic;
+        }
+    }
+}
+
+// number of non-zero codes among m[0..8) (as a float: exact far below 2^24)
+__device__ __forceinline__ float count_nonzero8(const float (&m)[8]) {
+    float nz = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) nz += __builtin_fminf(__builtin_fabsf(m[e] - kMagic), 1.0f);
+    return nz;
+}
+
+// INT8 codes: 8 bytes at dst (the low mantissa byte of kMagic + q is q in two's complement)
+__device__ __forceinline__ void store_codes_i8(const float (&m)[8], uint8_t* dst, bool vec_ok, int nvalid) {
+    uint32_t u[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) u[e] = __float_as_uint(m[e]);
+    if (vec_ok && nvalid == 8) {
+        __builtin_nontemporal_store(u32x2{pack_bytes(u[0], u[1], u[2], u[3]), pack_bytes(u[4], u[5], u[6], u[7])},
+                                    reinterpret_cast<u32x2*>(dst));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < nvalid) dst[e] = (uint8_t)(u[e] & 0xFFu);
+    }
+}
+
+// INT4 codes: 4 bytes at dst, two's-complement nibbles, even column in the low nibble
+__device__ __forceinline__ void store_codes_i4(const float (&m)[8], uint8_t* dst, bool vec_ok, int nvalid) {
+    uint32_t u[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) u[e] = __float_as_uint(m[e]);
+    uint32_t w0 = pack_bytes(u[0], u[1], u[2], u[3]) & 0x0F0F0F0Fu;
+    uint32_t w1 = pack_bytes(u[4], u[5], u[6], u[7]) & 0x0F0F0F0Fu;
+    w0 |= w0 >> 4;                 // bytes 0 and 2 now hold two nibbles each
+    w1 |= w1 >> 4;
+    const uint32_t w = __builtin_amdgcn_perm(w1, w0, 0x06040200u);
+    if (vec_ok && nvalid == 8) {
+        __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(dst));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (2 * e < nvalid) dst[e] = (uint8_t)((w >> (8 * e)) & 0xFFu);  // the channel count is even
+    }
+}
+
+// dequantized values fl16(fl32(q * fl32(a * b))): 16 bytes at dst
+__device__ __forceinline__ void store_xhat(const float (&m)[8], float a, const float (&b)[8], uint16_t* dst,
+                                           bool vec_ok, int nvalid) {
+    float y[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y[e] = rounded_f32((m[e] - kMagic) * (a * b[e]));
+    if (vec_ok && nvalid == 8) {
+        __builtin_nontemporal_store(u32x4{pack_half2(y[0], y[1]), pack_half2(y[2], y[3]), pack_half2(y[4], y[5]),
+                                          pack_half2(y[6], y[7])},
+                                    reinterpret_cast<u32x4*>(dst));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < nvalid) dst[e] = (uint16_t)f2h(y[e]);
+    }
+}
+
+}  // namespace cq

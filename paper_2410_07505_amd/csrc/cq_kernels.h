@@ -44,6 +44,12 @@ hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const f
 // packed nibbles [n_bytes] -> int8 codes [2 * n_bytes]
 hipError_t launch_unpack_int4(const uint8_t* packed, int64_t n_bytes, int8_t* codes, hipStream_t stream);
 
+// Single-read fused maxima + quantize (cooperative launch).  hipErrorNotSupported, with nothing
+// enqueued, if the matrix does not fit in the chip's registers.
+hipError_t launch_absmax_quantize(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int bits, float* t,
+                                  float* c, float* a, float* b, void* codes, uint16_t* xhat,
+                                  unsigned long long* zero_count, hipStream_t stream);
+
 hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* fold, int qmax,
                                   int8_t* qw, float* w_scale, hipStream_t stream);
 

@@ -18,70 +18,21 @@
 //
 // Rounding to nearest-even integer and conversion to two's complement are one add of the
 // constant 1.5 * 2^23: the sum's low mantissa bits are the code.
-#include "cq_kernels.h"
+#include "cq_device.h"
 
 namespace cq {
 namespace {
 
-constexpr int kLanes = 64;
-constexpr int kColsPerWave = kLanes * 8;
-constexpr float kMagic = 12582912.0f;            // 1.5 * 2^23
-constexpr float kTieTol = 1.9073486328125e-06f;  // 2^-19
-
 __global__ void scale_finalize_kernel(const float* __restrict__ t, const float* __restrict__ c, int T,
                                       int I, float alpha, int qmax, float* __restrict__ a,
-                                      float* __restrict__ b, unsigned long long* __restrict__ counters, int n_counters) {
+                                      float* __restrict__ b, unsigned long long* __restrict__ counters,
+                                      int n_counters) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const double al = (double)alpha;
     if (idx < n_counters && counters) counters[idx] = 0ull;
-    if (idx < T) {
-        const double ti = (double)t[idx];
-        // pow(x, 0) = 1 for every x and pow(x, 1) = x are exact in any correct pow; written out
-        // so the two special exponents (per-column and per-token steps) never depend on it
-        const double p = (al == 0.0) ? 1.0 : (al == 1.0 ? ti : pow(ti, al));
-        a[idx] = (float)(p / (double)qmax);
-    } else if (idx - T < I) {
-        const int j = idx - T;
-        const double cj = (double)c[j];
-        const double e = 1.0 - al;
-        const double p = (e == 0.0) ? 1.0 : (e == 1.0 ? cj : pow(cj, e));
-        b[j] = (float)p;
-    }
+    if (idx < T) a[idx] = row_factor(t[idx], al, qmax);
+    else if (idx - T < I) b[idx - T] = col_factor(c[idx - T], al);
 }
-
-template <bool VEC>
-__device__ __forceinline__ uint4 load8(const uint16_t* __restrict__ row, int j, int I) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (VEC && j + 8 <= I) {
-        v = *reinterpret_cast<const uint4*>(row + j);
-    } else if (j < I) {
-        uint32_t h[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = (j + e < I) ? row[j + e] : 0u;
-        v.x = h[0] | (h[1] << 16);
-        v.y = h[2] | (h[3] << 16);
-        v.z = h[4] | (h[5] << 16);
-        v.w = h[6] | (h[7] << 16);
-    }
-    return v;
-}
-
-__device__ __forceinline__ float half_lo(uint32_t w) { return h2f(w & 0xFFFFu); }
-__device__ __forceinline__ float half_hi(uint32_t w) { return h2f(w >> 16); }
-
-__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
-    return f2h(lo) | (f2h(hi) << 16);
-}
-
-// bytes 0 of four words -> one word
-__device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_t u2, uint32_t u3) {
-    const uint32_t p01 = __builtin_amdgcn_perm(u1, u0, 0x0c0c0400u);
-    const uint32_t p23 = __builtin_amdgcn_perm(u3, u2, 0x0c0c0400u);
-    return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
-}
-
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 8;   // waves per block
 constexpr int kU = 4;       // rows a wave has in flight
@@ -109,7 +60,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
-        rb[e] = (b[e] == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(b[e]);
+        rb[e] = safe_rcp(b[e]);
     }
     int nvalid = I - j0;                                    // columns of this lane that exist
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
@@ -132,81 +83,12 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             ++rows_done;
             const float a = __builtin_bit_cast(
                 float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), bi * kU + u));
-            const float ra = (a == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(a);
-            float x[8];
-            x[0] = half_lo(v[u].x); x[1] = half_hi(v[u].x);
-            x[2] = half_lo(v[u].y); x[3] = half_hi(v[u].y);
-            x[4] = half_lo(v[u].z); x[5] = half_hi(v[u].z);
-            x[6] = half_lo(v[u].w); x[7] = half_hi(v[u].w);
-
             float m[8];
-            float score = 0.0f;                             // max over the 8 elements of |frac| + |r| * tol
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float rt = x[e] * (ra * rb[e]);
-                rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
-                m[e] = rt + kMagic;
-                const float f = rt - (m[e] - kMagic);
-                score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)));
-            }
-            if (__any(score >= 0.5f)) {                     // rare: exact division for this wave's row piece
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float D = a * b[e];
-                    float rt = (D == 0.0f) ? 0.0f : x[e] / D;
-                    rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
-                    m[e] = rt + kMagic;
-                }
-            }
-
-            uint32_t u32[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                u32[e] = __float_as_uint(m[e]);
-                nonzero += __builtin_fminf(__builtin_fabsf(m[e] - kMagic), 1.0f);
-            }
-
-            if (MODE == 1) {
-                const uint32_t w0 = pack_bytes(u32[0], u32[1], u32[2], u32[3]);
-                const uint32_t w1 = pack_bytes(u32[4], u32[5], u32[6], u32[7]);
-                uint8_t* dst = codes + (int64_t)r * I + j0;
-                if (out_vec && nvalid == 8) {
-                    __builtin_nontemporal_store(u32x2{w0, w1}, reinterpret_cast<u32x2*>(dst));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (e < nvalid) dst[e] = (uint8_t)(u32[e] & 0xFFu);
-                }
-            } else if (MODE == 2) {
-                uint32_t w0 = pack_bytes(u32[0], u32[1], u32[2], u32[3]) & 0x0F0F0F0Fu;
-                uint32_t w1 = pack_bytes(u32[4], u32[5], u32[6], u32[7]) & 0x0F0F0F0Fu;
-                w0 |= w0 >> 4;                 // bytes 0 and 2 now hold two nibbles each
-                w1 |= w1 >> 4;
-                const uint32_t w = __builtin_amdgcn_perm(w1, w0, 0x06040200u);
-                uint8_t* dst = codes + (int64_t)r * (I / 2) + j0 / 2;
-                if (out_vec && nvalid == 8) {
-                    __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(dst));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (2 * e < nvalid) dst[e] = (uint8_t)((w >> (8 * e)) & 0xFFu);  // I is even
-                }
-            }
-            if (XHAT) {
-                float y[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = rounded_f32((m[e] - kMagic) * (a * b[e]));
-                uint16_t* dst = xhat + (int64_t)r * I + j0;
-                if (out_vec && nvalid == 8) {
-                    __builtin_nontemporal_store(u32x4{pack_half2(y[0], y[1]), pack_half2(y[2], y[3]),
-                                                      pack_half2(y[4], y[5]), pack_half2(y[6], y[7])},
-                                                reinterpret_cast<u32x4*>(dst));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (e < nvalid) dst[e] = (uint16_t)f2h(y[e]);
-                }
-            }
+            quantize8(v[u], a, safe_rcp(a), b, rb, qmax, m);
+            nonzero += count_nonzero8(m);
+            if (MODE == 1) store_codes_i8(m, codes + (int64_t)r * I + j0, out_vec, nvalid);
+            if (MODE == 2) store_codes_i4(m, codes + (int64_t)r * (I / 2) + j0 / 2, out_vec, nvalid);
+            if (XHAT) store_xhat(m, a, b, xhat + (int64_t)r * I + j0, out_vec, nvalid);
         }
     }
 

@@ -81,6 +81,20 @@ def test_quantize_argument_errors(cq):
     assert call(zc=P + 4) == -5 and call(xhat=P + 1) == -5
 
 
+def test_absmax_quantize_argument_errors(cq):
+    f = cq.raw.crossquant_absmax_quantize
+
+    def call(X=P, T=4, I=8, ldx=8, alpha=0.15, bits=8, t=P, c=P, codes=P, xhat=P, rs=P, cs=P, zc=P):
+        return f(X, T, I, ldx, alpha, bits, t, c, codes, xhat, rs, cs, zc, None)
+
+    assert call(X=0) == -1 and call(t=0) == -1 and call(c=0) == -1 and call(codes=0) == -1 and call(rs=0) == -1
+    assert call(T=0) == -2 and call(ldx=4) == -2
+    assert call(bits=5) == -3 and call(alpha=1.5) == -4
+    assert call(zc=P + 4) == -5 and call(xhat=P + 1) == -5
+    # valid requests outside the vector layout are "unsupported", found on the host
+    assert call(X=P + 2) == -6 and call(I=12, ldx=12) == -6 and call(ldx=12) == -6 and call(codes=P + 4) == -6
+
+
 def test_kernel_count_argument_errors(cq):
     f = cq.raw.crossquant_kernel_count
 

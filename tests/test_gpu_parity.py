@@ -265,6 +265,99 @@ def test_quantize_is_deterministic(cq):
     assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1]) and torch.equal(r1[4], r2[4])
 
 
+# ----------------------------------------------------------------------------- single-read fused call
+def check_fused(cq, X, alpha, bits, Xg=None, label="", want_xhat=True):
+    say("absmax_quantize %s shape=%s alpha=%g bits=%d xhat=%s" % (label, X.shape, alpha, bits, want_xhat))
+    import torch
+    Xg = gpu(X) if Xg is None else Xg
+    T, I = X.shape
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, alpha, bits)
+    # stale contents everywhere: the call must overwrite all of it
+    stale = dict(t=torch.full((T,), 7.0, device="cuda"), c=torch.full((I,), 9.0, device="cuda"),
+                 zero_count=torch.full((1,), 12345, dtype=torch.int64, device="cuda"))
+    t, c, codes, xhat, a, b, zc = cq.crossquant_absmax_quantize(Xg, alpha, bits, want_xhat=want_xhat, **stale)
+    assert np.array_equal(bits32(host(t)), bits32(t_ref)) and np.array_equal(bits32(host(c)), bits32(c_ref))
+    assert np.array_equal(bits32(host(a)), bits32(ref["a"])), "row scale factors differ"
+    assert np.array_equal(bits32(host(b)), bits32(ref["b"])), "column scale factors differ"
+    got = host(codes)
+    neq = got != ref["codes"]
+    assert not neq.any(), "%d codes differ, first at %s" % (neq.sum(), np.argwhere(neq)[:4].tolist())
+    assert int(host(zc)[0]) == ref["Z"]
+    if want_xhat:
+        xh = host(xhat)
+        assert np.array_equal(bits16(xh), bits16(ref["xhat"]))
+        r64, g64 = ref["xhat"].astype(np.float64), xh.astype(np.float64)
+        assert np.all(np.abs(g64 - r64) <= 1e-3 * np.abs(r64))
+    else:
+        assert xhat is None
+    return ref
+
+
+FUSED_SHAPES = [(1, 8), (3, 16), (37, 56), (64, 256), (130, 1000), (129, 520), (257, 1544), (300, 2048), (1000, 4104)]
+
+
+@pytest.mark.parametrize("T,I", FUSED_SHAPES)
+@pytest.mark.parametrize("bits", [8, 4])
+def test_fused_small_and_ragged(cq, T, I, bits):
+    X = outliers(T, I, seed=T + I)
+    check_fused(cq, X, 0.15, bits)
+    check_fused(cq, X, 1.0, bits, want_xhat=False)
+
+
+def test_fused_zero_rows_columns_ties_and_strided(cq):
+    X = outliers(40, 96, seed=3)
+    X[5, :] = 0
+    X[:, 17] = 0
+    for alpha in (0.0, 0.15, 1.0):
+        check_fused(cq, X, alpha, 8, label="zero row/col")
+    check_fused(cq, np.zeros((20, 64), np.float16), 0.15, 8, label="all zero")
+    rng = np.random.default_rng(5)
+    Xt = (rng.integers(-250, 251, (96, 512)) / 2.0).astype(np.float16)
+    Xt[:, 0] = 127.0
+    check_fused(cq, Xt, 1.0, 8, label="ties")
+    base = outliers(50, 304, seed=77)
+    g = gpu(base)
+    check_fused(cq, base[:, 8:264], 0.15, 8, Xg=g[:, 8:264], label="view[8:264]")
+
+
+def test_fused_reports_unsupported_requests(cq):
+    """Layouts the register-resident kernel does not take, and matrices that do not fit on the
+    chip, come back as CQ_ERR_UNSUPPORTED with nothing enqueued; the two calls serve them."""
+    import torch
+    base = outliers(50, 304, seed=78)
+    g = gpu(base)
+    for view in (g[:, 1:257], g[:, 0:54]):                     # misaligned rows; I % 8 != 0
+        with pytest.raises(cq.CrossQuantError) as e:
+            cq.crossquant_absmax_quantize(view, 0.15, 8)
+        assert e.value.status == -6
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    rows = 256 * (n_cu // 16) + 1                              # one row block too many at I = 8192
+    big = torch.zeros((rows, 8192), dtype=torch.float16, device="cuda")
+    with pytest.raises(cq.CrossQuantError) as e:
+        cq.crossquant_absmax_quantize(big, 0.15, 8)
+    assert e.value.status == -6
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["C2", "C5"])
+def test_fused_full_configs(cq, name):
+    import torch
+    cfg = workloads.CONFIGS[name]
+    X = workloads.config_activation(name)
+    Xg = gpu(X)
+    T, I = X.shape
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    if ((T + 255) // 256) * ((I + 511) // 512) > n_cu:
+        pytest.skip("%s does not fit on this device's registers" % name)
+    check_fused(cq, X, 0.15, 8, Xg=Xg, label=name)
+    check_fused(cq, X, 0.15, 4, Xg=Xg, label=name, want_xhat=False)
+    # same inputs twice: identical outputs (the atomics' order must not matter)
+    r1 = cq.crossquant_absmax_quantize(Xg, 0.15, 8)
+    r2 = cq.crossquant_absmax_quantize(Xg, 0.15, 8)
+    assert all(torch.equal(x, y) for x, y in zip(r1, r2))
+
+
 # ----------------------------------------------------------------------------- Remove Kernel, Table 1 indicators
 def check_analysis(cq, X, alpha, bits, Xg=None, label=""):
     say("analysis %s shape=%s alpha=%g bits=%d" % (label, X.shape, alpha, bits))
