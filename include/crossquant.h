@@ -94,6 +94,26 @@ int crossquant_absmax_quantize(const void *X, int64_t T, int64_t I, int64_t ldx,
                                float *col_scale, unsigned long long *zero_count, void *stream);
 
 /*
+ * Batched forms for a [B][S][I] activation tensor (the shape the appendix fake-quant listing is
+ * written for: the row maximum runs over the last axis, the column maximum over the second to
+ * last, i.e. over the S tokens of ONE sequence).  Every sequence b is an independent S x I
+ * problem with its own column maxima: results equal B separate calls of the plain forms, in one
+ * launch.  Sequence b starts at X + b * batch_stride (elements; >= (S-1)*ldx + I); rows inside a
+ * sequence are ldx apart.
+ * t, row_scale: float[B*S] (token b*S + s).  c, col_scale: float[B][I].
+ * codes: [B*S][I] (or [B*S][I/2] packed); NULL = count only (then xhat must be NULL and
+ *        zero_count non-NULL).  xhat: nullable, binary16 [B*S][I].
+ * zero_count: one counter for the whole batch.
+ * Limits: B*S and B*I <= CQ_MAX_DIM.
+ */
+int crossquant_absmax_batched(const void *X, int64_t B, int64_t S, int64_t I, int64_t ldx,
+                              int64_t batch_stride, float *t, float *c, void *stream);
+int crossquant_quantize_batched(const void *X, int64_t B, int64_t S, int64_t I, int64_t ldx,
+                                int64_t batch_stride, const float *t, const float *c, float alpha,
+                                int bits, void *codes, void *xhat, float *row_scale, float *col_scale,
+                                unsigned long long *zero_count, void *stream);
+
+/*
  * Size of the quantization kernel K(CQ) = {X_ij : CQ(X_ij) = 0} (Definition 1) without writing
  * codes; the kernel proportion of the paper is zero_count / (T*I).  alpha = 1 gives the
  * per-token baseline K(Q) of Eq. 1.

@@ -132,6 +132,27 @@ def quantize(X: np.ndarray, t: np.ndarray, c: np.ndarray, alpha: float, bits: in
             "b": b, "Z": int(Z.value), "clamp_hits": int(clamps.value)}
 
 
+def absmax_batched(X3: np.ndarray):
+    """[B][S][I] tensor (the appendix listing's shape): per-token maxima t [B][S] and per-sequence
+    column maxima c [B][I].  Each sequence is an independent S x I problem."""
+    if X3.ndim != 3:
+        raise ValueError("expected a [B][S][I] array")
+    ts, cs = zip(*(absmax(X3[b]) for b in range(X3.shape[0])))
+    return np.stack(ts), np.stack(cs)
+
+
+def quantize_batched(X3: np.ndarray, t: np.ndarray, c: np.ndarray, alpha: float, bits: int):
+    """CrossQuant applied to every sequence of a [B][S][I] tensor with that sequence's own t and c.
+    Returns a dict like quantize(), arrays stacked along a leading batch axis, Z summed."""
+    if X3.ndim != 3:
+        raise ValueError("expected a [B][S][I] array")
+    outs = [quantize(X3[b], t[b], c[b], alpha, bits) for b in range(X3.shape[0])]
+    res = {k: np.stack([o[k] for o in outs]) for k in ("codes", "xhat", "a", "b")}
+    res["Z"] = sum(o["Z"] for o in outs)
+    res["clamp_hits"] = sum(o["clamp_hits"] for o in outs)
+    return res
+
+
 def kernel_count(X: np.ndarray, t: np.ndarray, c: np.ndarray, alpha: float, bits: int) -> int:
     """Size of the quantization kernel (Definition 1): number of elements with code 0."""
     qmax(bits)

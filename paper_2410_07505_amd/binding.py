@@ -26,13 +26,16 @@ _vp, _i64, _int, _f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_
 lib.crossquant_absmax.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp]
 lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_absmax_quantize.argtypes = [_vp, _i64, _i64, _i64, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.crossquant_absmax_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp]
+lib.crossquant_quantize_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]
 lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
 lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
-for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_absmax_quantize", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
+for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_absmax_quantize", "crossquant_absmax_batched",
+           "crossquant_quantize_batched", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
            "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "crossquant_w8a8_linear",
            "crossquant_version"):
     getattr(lib, _n).restype = _int
@@ -166,6 +169,53 @@ def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want
                                           c.data_ptr(), codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(),
                                           col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
     return t, c, codes, xhat, row_scale, col_scale, zero_count
+
+
+def _req3(X: torch.Tensor):
+    if not isinstance(X, torch.Tensor) or not X.is_cuda:
+        raise ValueError("X must be a CUDA/HIP tensor")
+    if X.dtype != torch.float16 or X.dim() != 3 or X.stride(2) != 1:
+        raise ValueError("X must be a float16 [B][S][I] tensor with contiguous rows")
+
+
+def crossquant_absmax_batched(X: torch.Tensor, *, t: torch.Tensor = None, c: torch.Tensor = None):
+    """Per-token maxima t (float32 [B][S]) and per-sequence column maxima c (float32 [B][I])."""
+    _req3(X)
+    B, S, I = X.shape
+    if t is None:
+        t = torch.empty((B, S), dtype=torch.float32, device=X.device)
+    if c is None:
+        c = torch.empty((B, I), dtype=torch.float32, device=X.device)
+    if not (t.is_contiguous() and c.is_contiguous()):
+        raise ValueError("t and c must be contiguous")
+    _check(lib.crossquant_absmax_batched(X.data_ptr(), B, S, I, X.stride(1), X.stride(0), t.data_ptr(), c.data_ptr(),
+                                         _stream(X)))
+    return t, c
+
+
+def crossquant_quantize_batched(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
+                                want_codes: bool = True, want_xhat: bool = True, want_count: bool = True):
+    """Batched CrossQuant with per-sequence column factors.
+
+    Returns (codes [B][S][I or I/2] or None, xhat or None, row_scale [B][S], col_scale [B][I],
+    zero_count or None)."""
+    _req3(X)
+    B, S, I = X.shape
+    dev = X.device
+    codes = None
+    if want_codes:
+        codes = (torch.empty((B, S, I), dtype=torch.int8, device=dev) if bits == 8
+                 else torch.empty((B, S, max(I // 2, 1)), dtype=torch.uint8, device=dev))
+    xhat = torch.empty((B, S, I), dtype=torch.float16, device=dev) if (want_xhat and want_codes) else None
+    row_scale = torch.empty((B, S), dtype=torch.float32, device=dev)
+    col_scale = torch.empty((B, I), dtype=torch.float32, device=dev)
+    zero_count = torch.empty(1, dtype=torch.int64, device=dev) if (want_count or not want_codes) else None
+    if not (t.is_contiguous() and c.is_contiguous()) or t.numel() != B * S or c.numel() != B * I:
+        raise ValueError("t must hold B*S and c B*I contiguous float32 values")
+    _check(lib.crossquant_quantize_batched(X.data_ptr(), B, S, I, X.stride(1), X.stride(0), t.data_ptr(), c.data_ptr(),
+                                           float(alpha), int(bits), _ptr(codes), _ptr(xhat), row_scale.data_ptr(),
+                                           col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
+    return codes, xhat, row_scale, col_scale, zero_count
 
 
 def crossquant_kernel_count(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,

@@ -15,6 +15,10 @@
 // 32-byte request; 64 columns = 256 bytes per instruction).
 // The atomics act on the binary32 bit pattern as an unsigned integer (values are >= 0), so the
 // result is exact and independent of the order in which blocks finish.
+//
+// A batch of B matrices (sequences of a [B][S][I] activation tensor, each with its own column
+// maxima) is one launch: the flat grid is B copies of the one-matrix grid, and a block first
+// steps its pointers to its own matrix.
 #include "cq_device.h"
 
 namespace cq {
@@ -33,14 +37,19 @@ __global__ void zero_fill_kernel(uint32_t* __restrict__ p0, int n0, uint32_t* __
 template <bool VEC>
 __global__ void __launch_bounds__(kWaves * kLanes)
 absmax_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, uint32_t* __restrict__ t_bits,
-              uint32_t* __restrict__ c_bits, int n_col_chunks, int nb) {
+              uint32_t* __restrict__ c_bits, int n_col_chunks, int nb, int blocks_per_matrix, int64_t matrix_stride) {
     __shared__ uint32_t lds_col[kWaves][4][kLanes];  // [wave][packed reg][lane]
 
     const int lane = threadIdx.x & (kLanes - 1);
     const int wave = threadIdx.x / kLanes;
+    const int matrix = blockIdx.x / blocks_per_matrix;
+    const int blk = blockIdx.x - matrix * blocks_per_matrix;
+    X += (int64_t)matrix * matrix_stride;
+    t_bits += (int64_t)matrix * T;
+    c_bits += (int64_t)matrix * I;
     // flat grid, column chunk fastest: neighbouring blocks read neighbouring 1 KiB pieces of a row
-    const int col_chunk = blockIdx.x % n_col_chunks;
-    const int row_chunk = blockIdx.x / n_col_chunks;
+    const int col_chunk = blk % n_col_chunks;
+    const int row_chunk = blk / n_col_chunks;
     const int j0 = col_chunk * kColsPerWave + lane * 8;
     const int rows_per_wave = nb * kBatch;
     const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
@@ -81,27 +90,27 @@ absmax_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, uint32_
 
 }  // namespace
 
-hipError_t launch_absmax(const uint16_t* X, int T, int I, int64_t ldx, float* t, float* c,
-                         hipStream_t stream) {
+hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, float* t,
+                         float* c, hipStream_t stream) {
     {
-        const int n = T + I;
+        const int n = B * (T + I);                        // t is [B*T], c is [B*I]
         zero_fill_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(
-            reinterpret_cast<uint32_t*>(t), T, reinterpret_cast<uint32_t*>(c), I);
+            reinterpret_cast<uint32_t*>(t), B * T, reinterpret_cast<uint32_t*>(c), B * I);
     }
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
     // rows per block = 32 * nb: as many as keep at least 512 blocks in flight (fewer, larger
     // blocks mean fewer atomics; too few blocks leave CUs idle)
     int nb = 8;
-    while (nb > 1 && (int64_t)ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
+    while (nb > 1 && (int64_t)B * ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
-    const dim3 grid((unsigned)(ncc * nrc)), block(kWaves * kLanes);
-    const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0);
+    const dim3 grid((unsigned)(B * ncc * nrc)), block(kWaves * kLanes);
+    const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0) && (B == 1 || matrix_stride % 8 == 0);
     if (vec)
         absmax_kernel<true><<<grid, block, 0, stream>>>(X, T, I, ldx, reinterpret_cast<uint32_t*>(t),
-                                                        reinterpret_cast<uint32_t*>(c), ncc, nb);
+                                                        reinterpret_cast<uint32_t*>(c), ncc, nb, ncc * nrc, matrix_stride);
     else
         absmax_kernel<false><<<grid, block, 0, stream>>>(X, T, I, ldx, reinterpret_cast<uint32_t*>(t),
-                                                         reinterpret_cast<uint32_t*>(c), ncc, nb);
+                                                         reinterpret_cast<uint32_t*>(c), ncc, nb, ncc * nrc, matrix_stride);
     return hipGetLastError();
 }
 

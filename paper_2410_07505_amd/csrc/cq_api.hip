@@ -19,6 +19,15 @@ int check_matrix(const void* X, int64_t T, int64_t I, int64_t ldx) {
     return CQ_OK;
 }
 
+// [B][S][I] tensor: sequence b starts batch_stride elements after sequence b-1
+int check_batch(const void* X, int64_t B, int64_t S, int64_t I, int64_t ldx, int64_t batch_stride) {
+    if (int s = check_matrix(X, S, I, ldx)) return s;
+    if (!dim_ok(B) || B * S > CQ_MAX_DIM || B * I > CQ_MAX_DIM) return CQ_ERR_SHAPE;
+    if (batch_stride < (S - 1) * ldx + I || batch_stride > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    if (B * S * I > CQ_MAX_ELEMS || (B - 1) * batch_stride > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    return CQ_OK;
+}
+
 int check_quant_params(float alpha, int bits, int64_t I) {
     if (bits != 4 && bits != 8) return CQ_ERR_BITS;
     if (bits == 4 && (I & 1)) return CQ_ERR_BITS;
@@ -36,7 +45,16 @@ int crossquant_absmax(const void* X, int64_t T, int64_t I, int64_t ldx, float* t
     if (!t || !c) return CQ_ERR_NULL;
     if (int s = check_matrix(X, T, I, ldx)) return s;
     if (!aligned(t, 4) || !aligned(c, 4)) return CQ_ERR_ALIGN;
-    return from_hip(cq::launch_absmax(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, t, c,
+    return from_hip(cq::launch_absmax(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, t, c,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+int crossquant_absmax_batched(const void* X, int64_t B, int64_t S, int64_t I, int64_t ldx, int64_t batch_stride,
+                              float* t, float* c, void* stream) {
+    if (!t || !c) return CQ_ERR_NULL;
+    if (int s = check_batch(X, B, S, I, ldx, batch_stride)) return s;
+    if (!aligned(t, 4) || !aligned(c, 4)) return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_absmax(static_cast<const uint16_t*>(X), (int)B, (int)S, (int)I, ldx, batch_stride, t, c,
                                       static_cast<hipStream_t>(stream)));
 }
 
@@ -54,8 +72,29 @@ int crossquant_quantize(const void* X, int64_t T, int64_t I, int64_t ldx, const 
     if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
                                                    zero_count, 1, st)))
         return s;
-    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, row_scale,
                                         col_scale, bits, codes, static_cast<uint16_t*>(xhat), zero_count, st));
+}
+
+int crossquant_quantize_batched(const void* X, int64_t B, int64_t S, int64_t I, int64_t ldx, int64_t batch_stride,
+                                const float* t, const float* c, float alpha, int bits, void* codes, void* xhat,
+                                float* row_scale, float* col_scale, unsigned long long* zero_count, void* stream) {
+    if (!t || !c || !row_scale || !col_scale) return CQ_ERR_NULL;
+    if (!codes && (xhat || !zero_count)) return CQ_ERR_NULL;      // codes == NULL: count only
+    if (int s = check_batch(X, B, S, I, ldx, batch_stride)) return s;
+    if (int s = check_quant_params(alpha, bits, codes ? I : 0)) return s;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
+        !aligned(xhat, 2) || !aligned(zero_count, 8))
+        return CQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int qmax = (1 << (bits - 1)) - 1;
+    // the scale factors are element-wise in t and c: the batch is just longer vectors
+    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)(B * S), (int)(B * I), alpha, qmax, row_scale, col_scale,
+                                                   zero_count, 1, st)))
+        return s;
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)B, (int)S, (int)I, ldx, batch_stride,
+                                        row_scale, col_scale, bits, codes, static_cast<uint16_t*>(xhat), zero_count,
+                                        st));
 }
 
 int crossquant_absmax_quantize(const void* X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits, float* t,
@@ -92,7 +131,7 @@ int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, co
     if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
                                                    zero_count, 1, st)))
         return s;
-    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, row_scale,
                                         col_scale, bits, nullptr, nullptr, zero_count, st));
 }
 

@@ -93,6 +93,9 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
         if (!(col_ok && row0 + k < T)) w = make_uint4(0u, 0u, 0u, 0u);
         return w;
     };
+    // the register rows' loads go out first and stay in flight while the LDS rows pass through
+#pragma unroll
+    for (int k = 0; k < kFRegRows; ++k) v[k] = load_row(k);
 #pragma unroll
     for (int g = 0; g < kFLdsRows / 8; ++g) {
         uint4 w[8];
@@ -109,8 +112,6 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
         if ((lane & 7) == 0 && r < T && m) atomicMax(&t_bits[r], half_bits_to_float_bits(m));
         __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int k = 0; k < kFRegRows; ++k) v[k] = load_row(k);
 #pragma unroll
     for (int g = 0; g < kFRegRows / 8; ++g) {
         uint32_t rm[8];

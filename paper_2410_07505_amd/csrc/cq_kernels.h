@@ -23,8 +23,9 @@ __device__ __forceinline__ float rounded_f32(float v) {
 }
 
 // t[0..T), c[0..I) <- 0 ; then one pass over X accumulating both maxima.
-hipError_t launch_absmax(const uint16_t* X, int T, int I, int64_t ldx, float* t, float* c,
-                         hipStream_t stream);
+// B matrices of T rows, matrix_stride elements apart (B = 1: a plain matrix); t is [B*T], c is [B*I].
+hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, float* t,
+                         float* c, hipStream_t stream);
 
 // a_i = t_i^alpha / qmax, b_j = c_j^(1-alpha) (binary64 pow, one rounding); counters[0..n) <- 0.
 hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, float alpha, int qmax,
@@ -37,7 +38,8 @@ hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, 
                                   uint16_t* xrk, unsigned long long* counters, hipStream_t stream);
 
 // Fused quantize / dequantize / zero count.  codes or xhat may be null (count only = both null).
-hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const float* a,
+// B matrices as in launch_absmax; a is [B*T], b is [B*I], codes / xhat are [B*T][...].
+hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* a,
                            const float* b, int bits, void* codes, uint16_t* xhat,
                            unsigned long long* zero_count, hipStream_t stream);
 

@@ -41,17 +41,27 @@ constexpr int kU = 4;       // rows a wave has in flight
 // Block: 8 waves sharing 512 columns; each wave streams over nb batches of 4 consecutive rows.
 // Outputs are written with non-temporal stores: they are not read again by this kernel, and
 // keeping them out of the caches leaves room for the X rows still to be read.
+// A batch of B matrices (each with its own column factors) is one launch: B copies of the
+// one-matrix grid; a block first steps its pointers to its own matrix.
 template <int MODE, bool XHAT, bool VEC>
 __global__ void __launch_bounds__(kWaves * kLanes)
 quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ a_vec,
                 const float* __restrict__ b_vec, float qmax, uint8_t* __restrict__ codes,
                 uint16_t* __restrict__ xhat, unsigned long long* __restrict__ zero_count,
-                int n_col_chunks, int nb, bool out_vec) {
+                int n_col_chunks, int nb, bool out_vec, int blocks_per_matrix, int64_t matrix_stride) {
     __shared__ uint32_t lds_cnt[kWaves];
     const int lane = threadIdx.x & (kLanes - 1);
     const int wave = threadIdx.x / kLanes;
-    const int col_chunk = blockIdx.x % n_col_chunks;
-    const int row_chunk = blockIdx.x / n_col_chunks;
+    const int matrix = blockIdx.x / blocks_per_matrix;
+    const int blk = blockIdx.x - matrix * blocks_per_matrix;
+    X += (int64_t)matrix * matrix_stride;
+    a_vec += (int64_t)matrix * T;
+    b_vec += (int64_t)matrix * I;
+    if (MODE == 1) codes += (int64_t)matrix * T * I;
+    if (MODE == 2) codes += (int64_t)matrix * T * (I / 2);
+    if (XHAT) xhat += (int64_t)matrix * T * I;
+    const int col_chunk = blk % n_col_chunks;
+    const int row_chunk = blk / n_col_chunks;
     const int j0 = col_chunk * kColsPerWave + lane * 8;
     const int rows_per_wave = nb * kU;                      // <= 64
     const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
@@ -110,25 +120,25 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 }
 
 template <int MODE, bool XHAT>
-hipError_t launch_mode(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
-                       float qmax, uint8_t* codes, uint16_t* xhat, unsigned long long* zc,
+hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* a,
+                       const float* b, float qmax, uint8_t* codes, uint16_t* xhat, unsigned long long* zc,
                        hipStream_t stream) {
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
     // rows per block = 32 * nb; keep about 512 blocks in flight
     int nb = 16;
-    while (nb > 1 && (int64_t)ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
+    while (nb > 1 && (int64_t)B * ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
-    const dim3 grid((unsigned)(ncc * nrc)), block(kWaves * kLanes);
-    const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0);
+    const dim3 grid((unsigned)(B * ncc * nrc)), block(kWaves * kLanes);
+    const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0) && (B == 1 || matrix_stride % 8 == 0);
     // vector stores need every lane's piece aligned: I % 8 == 0 and aligned bases
     const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 8 == 0) &&
                          (reinterpret_cast<uintptr_t>(xhat) % 16 == 0);
     if (vec)
         quantize_kernel<MODE, XHAT, true><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat, zc,
-                                                                     ncc, nb, out_vec);
+                                                                     ncc, nb, out_vec, ncc * nrc, matrix_stride);
     else
         quantize_kernel<MODE, XHAT, false><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat, zc,
-                                                                      ncc, nb, out_vec);
+                                                                      ncc, nb, out_vec, ncc * nrc, matrix_stride);
     return hipGetLastError();
 }
 
@@ -194,17 +204,17 @@ hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, f
     return hipGetLastError();
 }
 
-hipError_t launch_quantize(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
-                           int bits, void* codes, uint16_t* xhat, unsigned long long* zero_count,
+hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* a,
+                           const float* b, int bits, void* codes, uint16_t* xhat, unsigned long long* zero_count,
                            hipStream_t stream) {
     const float qmax = (float)((1 << (bits - 1)) - 1);
     uint8_t* cp = static_cast<uint8_t*>(codes);
-    if (!cp) return launch_mode<0, false>(X, T, I, ldx, a, b, qmax, nullptr, nullptr, zero_count, stream);
+    if (!cp) return launch_mode<0, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, nullptr, nullptr, zero_count, stream);
     if (bits == 8)
-        return xhat ? launch_mode<1, true>(X, T, I, ldx, a, b, qmax, cp, xhat, zero_count, stream)
-                    : launch_mode<1, false>(X, T, I, ldx, a, b, qmax, cp, nullptr, zero_count, stream);
-    return xhat ? launch_mode<2, true>(X, T, I, ldx, a, b, qmax, cp, xhat, zero_count, stream)
-                : launch_mode<2, false>(X, T, I, ldx, a, b, qmax, cp, nullptr, zero_count, stream);
+        return xhat ? launch_mode<1, true>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, xhat, zero_count, stream)
+                    : launch_mode<1, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, nullptr, zero_count, stream);
+    return xhat ? launch_mode<2, true>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, xhat, zero_count, stream)
+                : launch_mode<2, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, nullptr, zero_count, stream);
 }
 
 }  // namespace cq

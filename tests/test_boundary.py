@@ -95,6 +95,25 @@ def test_absmax_quantize_argument_errors(cq):
     assert call(X=P + 2) == -6 and call(I=12, ldx=12) == -6 and call(ldx=12) == -6 and call(codes=P + 4) == -6
 
 
+def test_batched_argument_errors(cq):
+    f = cq.raw.crossquant_absmax_batched
+    assert f(0, 2, 4, 8, 8, 32, P, P, None) == -1 and f(P, 2, 4, 8, 8, 32, 0, P, None) == -1
+    assert f(P, 0, 4, 8, 8, 32, P, P, None) == -2
+    assert f(P, 2, 4, 8, 8, 31, P, P, None) == -2          # sequences would overlap
+    assert f(P, 1 << 20, 1 << 10, 8, 8, 1 << 13, P, P, None) == -2   # B*S over the limit
+    g = cq.raw.crossquant_quantize_batched
+
+    def call(X=P, B=2, S=4, I=8, ldx=8, bs=32, t=P, c=P, alpha=0.15, bits=8, codes=P, xhat=P, rs=P, cs=P, zc=P):
+        return g(X, B, S, I, ldx, bs, t, c, alpha, bits, codes, xhat, rs, cs, zc, None)
+
+    assert call(t=0) == -1 and call(rs=0) == -1
+    assert call(codes=0) == -1                              # count only, but xhat given
+    assert call(codes=0, xhat=0, zc=0) == -1                # count only without a counter
+    assert call(B=0) == -2 and call(bs=8) == -2
+    assert call(bits=7) == -3 and call(bits=4, I=7, ldx=8) == -3 and call(alpha=-0.5) == -4
+    assert call(zc=P + 4) == -5
+
+
 def test_kernel_count_argument_errors(cq):
     f = cq.raw.crossquant_kernel_count
 

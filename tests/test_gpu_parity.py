@@ -358,6 +358,68 @@ def test_fused_full_configs(cq, name):
     assert all(torch.equal(x, y) for x, y in zip(r1, r2))
 
 
+# ----------------------------------------------------------------------------- batched [B][S][I]
+def batch_tensor(B, S, I, seed):
+    return np.stack([workloads.activation(S, I, n_outlier=min(2, I), scale_lo=20.0 * (b + 1), scale_hi=20.0 * (b + 1),
+                                          seed=seed + b) for b in range(B)])
+
+
+def check_batched(cq, X3, alpha, bits, Xg=None, label=""):
+    say("batched %s shape=%s alpha=%g bits=%d" % (label, X3.shape, alpha, bits))
+    Xg = gpu(X3) if Xg is None else Xg
+    t_ref, c_ref = oracle.absmax_batched(X3)
+    ref = oracle.quantize_batched(X3, t_ref, c_ref, alpha, bits)
+    t, c = cq.crossquant_absmax_batched(Xg)
+    assert np.array_equal(bits32(host(t)), bits32(t_ref)) and np.array_equal(bits32(host(c)), bits32(c_ref))
+    codes, xhat, a, b, zc = cq.crossquant_quantize_batched(Xg, t, c, alpha, bits)
+    assert np.array_equal(bits32(host(a)), bits32(ref["a"])) and np.array_equal(bits32(host(b)), bits32(ref["b"]))
+    assert np.array_equal(host(codes), ref["codes"])
+    assert np.array_equal(bits16(host(xhat)), bits16(ref["xhat"]))
+    assert int(host(zc)[0]) == ref["Z"]
+    none_codes, none_xhat, _, _, zc2 = cq.crossquant_quantize_batched(Xg, t, c, alpha, bits, want_codes=False)
+    assert none_codes is None and none_xhat is None and int(host(zc2)[0]) == ref["Z"]
+    return ref
+
+
+@pytest.mark.parametrize("B,S,I", [(1, 5, 16), (3, 37, 54), (4, 64, 256), (2, 130, 1000), (5, 33, 1538), (7, 1, 8),
+                                   (6, 200, 520)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_batched_small_and_ragged(cq, B, S, I, bits):
+    X3 = batch_tensor(B, S, I, seed=B * 1000 + S + I)
+    check_batched(cq, X3, 0.15, bits)
+
+
+def test_batched_views_with_padding_between_sequences(cq):
+    base = batch_tensor(3, 40, 304, seed=9)
+    g = gpu(base)
+    for (s0, s1, lo, hi) in ((0, 40, 8, 264), (3, 35, 0, 304), (2, 39, 1, 257)):
+        view = np.ascontiguousarray(base[:, s0:s1, lo:hi])
+        check_batched(cq, view, 0.15, 8, Xg=g[:, s0:s1, lo:hi], label="view[%d:%d,%d:%d]" % (s0, s1, lo, hi))
+
+
+def test_batched_equals_separate_calls_at_layer_scale(cq):
+    """32 sequences of 128 tokens x 4096 channels: one launch each for the maxima and the
+    quantizer, compared with the oracle on sampled sequences and with per-sequence GPU calls."""
+    import torch
+    B, S, I = 32, 128, 4096
+    X3 = batch_tensor(B, S, I, seed=77)
+    Xg = gpu(X3)
+    t, c = cq.crossquant_absmax_batched(Xg)
+    codes, xhat, a, b, zc = cq.crossquant_quantize_batched(Xg, t, c, 0.15, 8)
+    z = 0
+    for bi in range(B):
+        t1, c1 = cq.crossquant_absmax(Xg[bi])
+        q1, x1, a1, b1, z1 = cq.crossquant_quantize(Xg[bi], t1, c1, 0.15, 8)
+        assert torch.equal(t1, t[bi]) and torch.equal(c1, c[bi]) and torch.equal(q1, codes[bi])
+        assert torch.equal(x1, xhat[bi]) and torch.equal(a1, a[bi]) and torch.equal(b1, b[bi])
+        z += int(z1.item())
+    assert z == int(zc.item())
+    for bi in (0, 17, 31):
+        tr, cr = oracle.absmax(X3[bi])
+        ref = oracle.quantize(X3[bi], tr, cr, 0.15, 8)
+        assert np.array_equal(host(codes[bi]), ref["codes"]) and np.array_equal(bits16(host(xhat[bi])), bits16(ref["xhat"]))
+
+
 # ----------------------------------------------------------------------------- Remove Kernel, Table 1 indicators
 def check_analysis(cq, X, alpha, bits, Xg=None, label=""):
     say("analysis %s shape=%s alpha=%g bits=%d" % (label, X.shape, alpha, bits))

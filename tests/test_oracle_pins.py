@@ -563,3 +563,35 @@ def test_weight_crossquant_is_the_activation_routine_on_the_stored_weight():
     r0 = oracle.quantize(Wt, t, c, 0.0, 8)               # alpha_W = 0: one step per input channel
     im = np.abs(Wt.astype(np.float32)).argmax(axis=0)
     assert np.array_equal(np.abs(r0["codes"][im, np.arange(40)]), np.full(40, 127))
+
+
+def test_batched_tensor_has_per_sequence_column_maxima():
+    """[B][S][I] input (the appendix listing's dims: row maximum over the last axis, column
+    maximum over the second to last): every sequence is its own S x I problem."""
+    B, S, I = 3, 20, 48
+    X3 = np.stack([workloads.activation(S, I, n_outlier=2, scale_lo=30 * (b + 1), scale_hi=30 * (b + 1), seed=40 + b)
+                   for b in range(B)])
+    t, c = oracle.absmax_batched(X3)
+    A = np.abs(X3.astype(np.float32))
+    assert np.array_equal(t, A.max(axis=2)) and np.array_equal(c, A.max(axis=1))
+    r = oracle.quantize_batched(X3, t, c, 0.15, 8)
+    assert r["codes"].shape == (B, S, I) and r["a"].shape == (B, S) and r["b"].shape == (B, I)
+    # B = 1 is the plain 2-D routine
+    r1 = oracle.quantize_batched(X3[:1], t[:1], c[:1], 0.15, 8)
+    r2 = oracle.quantize(X3[0], t[0], c[0], 0.15, 8)
+    assert np.array_equal(r1["codes"][0], r2["codes"]) and r1["Z"] == r2["Z"]
+    # sequences do not influence each other ...
+    Y3 = X3.copy()
+    Y3[1] *= np.float16(0.5)
+    ty, cy = oracle.absmax_batched(Y3)
+    ry = oracle.quantize_batched(Y3, ty, cy, 0.15, 8)
+    assert np.array_equal(ry["codes"][0], r["codes"][0]) and np.array_equal(ry["codes"][2], r["codes"][2])
+    # ... (halving a sequence halves its steps: same codes) ...
+    assert np.array_equal(ry["codes"][1], r["codes"][1])
+    # ... unlike the flattened [B*S][I] reading, whose shared column maxima couple them
+    Xf = X3.reshape(B * S, I)
+    tf, cf = oracle.absmax(Xf)
+    rf = oracle.quantize(Xf, tf, cf, 0.15, 8)
+    assert np.array_equal(cf, c.max(axis=0))
+    assert not np.array_equal(rf["codes"].reshape(B, S, I)[0], r["codes"][0])
+    assert r["Z"] == sum(int((r["codes"][b] == 0).sum()) for b in range(B))
