@@ -95,6 +95,20 @@ __device__ __forceinline__ float half_lo(uint32_t w) { return h2f(w & 0xFFFFu); 
 __device__ __forceinline__ float half_hi(uint32_t w) { return h2f(w >> 16); }
 __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) { return f2h(lo) | (f2h(hi) << 16); }
 
+// Output stores.  CQ_NT_STORES selects non-temporal stores (outputs are not read again by the
+// producing kernel).
+#ifndef CQ_NT_STORES
+#define CQ_NT_STORES 1
+#endif
+template <typename V>
+__device__ __forceinline__ void store_out(V v, V* dst) {
+#if CQ_NT_STORES
+    __builtin_nontemporal_store(v, dst);
+#else
+    *dst = v;
+#endif
+}
+
 // bytes 0 of four words -> one word
 __device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_t u2, uint32_t u3) {
     const uint32_t p01 = __builtin_amdgcn_perm(u1, u0, 0x0c0c0400u);
@@ -151,8 +165,8 @@ __device__ __forceinline__ void store_codes_i8(const float (&m)[8], uint8_t* dst
 #pragma unroll
     for (int e = 0; e < 8; ++e) u[e] = __float_as_uint(m[e]);
     if (vec_ok && nvalid == 8) {
-        __builtin_nontemporal_store(u32x2{pack_bytes(u[0], u[1], u[2], u[3]), pack_bytes(u[4], u[5], u[6], u[7])},
-                                    reinterpret_cast<u32x2*>(dst));
+        store_out(u32x2{pack_bytes(u[0], u[1], u[2], u[3]), pack_bytes(u[4], u[5], u[6], u[7])},
+                  reinterpret_cast<u32x2*>(dst));
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -171,7 +185,7 @@ __device__ __forceinline__ void store_codes_i4(const float (&m)[8], uint8_t* dst
     w1 |= w1 >> 4;
     const uint32_t w = __builtin_amdgcn_perm(w1, w0, 0x06040200u);
     if (vec_ok && nvalid == 8) {
-        __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(dst));
+        store_out(w, reinterpret_cast<uint32_t*>(dst));
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -186,9 +200,8 @@ __device__ __forceinline__ void store_xhat(const float (&m)[8], float a, const f
 #pragma unroll
     for (int e = 0; e < 8; ++e) y[e] = rounded_f32((m[e] - kMagic) * (a * b[e]));
     if (vec_ok && nvalid == 8) {
-        __builtin_nontemporal_store(u32x4{pack_half2(y[0], y[1]), pack_half2(y[2], y[3]), pack_half2(y[4], y[5]),
-                                          pack_half2(y[6], y[7])},
-                                    reinterpret_cast<u32x4*>(dst));
+        store_out(u32x4{pack_half2(y[0], y[1]), pack_half2(y[2], y[3]), pack_half2(y[4], y[5]), pack_half2(y[6], y[7])},
+                  reinterpret_cast<u32x4*>(dst));
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
