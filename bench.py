@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C5", help="workload: C2, C3 or C5 (INT8 configurations)")
     ap.add_argument("--alpha", type=float, default=0.15)
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the step from a captured HIP graph and report its time per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", default="all",
                     help="all, or a comma list of absmax,quantize,count,linear (for profiling one stage)")
@@ -237,6 +239,24 @@ def main():
         except cq.CrossQuantError as e:
             fused = {"unsupported": str(e)}
 
+    graph_ms = None
+    if args.graph and args.stages == "all":
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg) * 1e3 / args.steps
+
     out = {
         "metric": METRIC,
         "value": quant_gbs, "unit": "GB/s",
@@ -257,6 +277,7 @@ def main():
         },
         "kernel_proportion": {"crossquant": z / n, "per_token": z_pt / n},
         "absmax_quantize_single_read": fused,
+        "graph_replay_ms_per_step": graph_ms,
         "roofline": {"kernel": "gemm_i8_ring_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS if tops else None,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},

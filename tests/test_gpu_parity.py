@@ -681,3 +681,59 @@ def test_end_to_end_full_config_sampled(cq, name):
     # every output equals its own accumulator through the epilogue (checked on the GPU tensors)
     y_from_acc = ((acc.to(torch.float32) * a[:, None]) * s[None, :]).to(torch.float16)
     assert torch.equal(y_from_acc.view(torch.int16), Y.view(torch.int16))
+
+
+# ----------------------------------------------------------------------------- HIP graph replay
+def test_whole_path_replays_from_a_hip_graph(cq):
+    """The calls allocate nothing, never synchronise and clear their accumulators with kernels, so
+    the whole path can be captured once and replayed.  Every replay (with eager work and
+    synchronisations in between, and new input values each time) must equal the eager result."""
+    import torch
+    T, I, O = 300, 1024, 520
+    W = workloads.weight(I, O, seed=5)
+    Wg = gpu(W)
+    Xg = torch.empty((T, I), dtype=torch.float16, device="cuda")
+    t = torch.empty(T, device="cuda"); c = torch.empty(I, device="cuda")
+    a = torch.empty(T, device="cuda"); b = torch.empty(I, device="cuda")
+    a1 = torch.empty(T, device="cuda"); b1 = torch.empty(I, device="cuda")
+    codes = torch.empty((T, I), dtype=torch.int8, device="cuda")
+    xhat = torch.empty((T, I), dtype=torch.float16, device="cuda")
+    zc = torch.empty(1, dtype=torch.int64, device="cuda"); zc1 = torch.empty(1, dtype=torch.int64, device="cuda")
+    qw = torch.empty((O, I), dtype=torch.int8, device="cuda"); ws = torch.empty(O, device="cuda")
+    Y = torch.empty((T, O), dtype=torch.float16, device="cuda")
+
+    def path():
+        cq.crossquant_absmax(Xg, t=t, c=c)
+        cq.crossquant_quantize(Xg, t, c, 0.15, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b, zero_count=zc)
+        cq.crossquant_kernel_count(Xg, t, c, 1.0, 8, row_scale=a1, col_scale=b1, zero_count=zc1)
+        cq.crossquant_weight_quantize(Wg, b, 8, qw=qw, w_scale=ws)
+        cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)
+
+    Xg.copy_(gpu(outliers(T, I, seed=100)))
+    path()                                             # warm up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            path()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        X = outliers(T, I, seed=200 + rep)
+        say("graph replay %d" % rep)
+        Xg.copy_(gpu(X))
+        for buf in (t, c, a, b, codes, xhat, zc, zc1, Y):       # stale contents before every replay
+            buf.fill_(1)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [host(x).copy() for x in (t, c, a, b, codes, xhat, zc, zc1, qw, ws, Y)]
+        t_ref, c_ref = oracle.absmax(X)
+        ref = oracle.quantize(X, t_ref, c_ref, 0.15, 8)
+        assert np.array_equal(got[4], ref["codes"]) and int(got[6][0]) == ref["Z"]
+        assert int(got[7][0]) == oracle.kernel_count(X, t_ref, c_ref, 1.0, 8)
+        path()                                         # eager, same inputs
+        torch.cuda.synchronize()
+        eager = [host(x) for x in (t, c, a, b, codes, xhat, zc, zc1, qw, ws, Y)]
+        for g_, e_ in zip(got, eager):
+            assert np.array_equal(g_.view(np.uint8), e_.view(np.uint8))
