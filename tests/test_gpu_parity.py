@@ -239,6 +239,17 @@ def test_quantize_with_calibrated_maxima_clamps(cq):
         codes, xhat, _, _, zc = cq.crossquant_quantize(gpu(X), gpu(t_small), gpu(c_small), 0.15, bits)
         assert np.array_equal(host(codes), ref["codes"])
         assert np.array_equal(bits16(host(xhat)), bits16(ref["xhat"])) and int(host(zc)[0]) == ref["Z"]
+        zc2 = cq.crossquant_kernel_count(gpu(X), gpu(t_small), gpu(c_small), 0.15, bits)
+        assert int(host(zc2)[0]) == ref["Z"]
+    # a zero maximum handed in for non-zero data: the step is 0 and every code of that row / column is 0
+    t0, c0 = t_ref.copy(), c_ref.copy()
+    t0[3] = 0.0
+    c0[5] = 0.0
+    ref = oracle.quantize(X, t0, c0, 0.15, 8)
+    assert np.all(ref["codes"][3] == 0) and np.all(ref["codes"][:, 5] == 0)
+    codes, _, _, _, zc = cq.crossquant_quantize(gpu(X), gpu(t0), gpu(c0), 0.15, 8)
+    zc2 = cq.crossquant_kernel_count(gpu(X), gpu(t0), gpu(c0), 0.15, 8)
+    assert np.array_equal(host(codes), ref["codes"]) and int(host(zc)[0]) == ref["Z"] == int(host(zc2)[0])
 
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
