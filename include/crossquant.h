@@ -80,14 +80,18 @@ int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const 
 
 /*
  * crossquant_absmax followed by crossquant_quantize, fused: X is read from HBM once and held in
- * the chip's registers across a grid-wide barrier (cooperative launch), which is possible when
- * the matrix fits: ceil(T/256) * ceil(I/512) <= number of CUs (256 on MI355X, i.e. up to
- * 4096 x 8192).  Outputs and arithmetic are exactly those of the two calls (t, c included).
- * Returns CQ_ERR_UNSUPPORTED, with nothing enqueued, if the matrix is too large, if the device
- * cannot launch cooperatively, or if the layout is not the vector one (X and xhat 16-byte
- * aligned, codes 8-byte aligned, ldx % 8 == 0, I % 8 == 0): the caller then uses the two calls.
- * Must not run concurrently with other kernels that occupy CUs of the same device for long
- * (the grid barrier needs all blocks resident; the runtime enforces this at launch).
+ * the chip's registers and LDS across a grid-wide barrier, which is possible when the matrix fits:
+ * ceil(T/256) * ceil(I/512) <= number of CUs (256 on MI355X, i.e. up to 4096 x 8192).  Outputs and
+ * arithmetic are exactly those of the two calls (t, c included).
+ * Returns CQ_ERR_UNSUPPORTED, with nothing enqueued, if the matrix is too large or if the layout
+ * is not the vector one (X and xhat 16-byte aligned, codes 8-byte aligned, ldx % 8 == 0,
+ * I % 8 == 0): the caller then uses the two calls.
+ * The barrier needs all blocks resident at once (one block per CU).  Other kernels running on the
+ * device only delay it; if part of the device stays unavailable for seconds the kernel gives up
+ * (it always terminates) and writes NaN into row_scale and col_scale.  The barrier's arrival
+ * counter is one word of library-owned device memory per device: calls on the same device must
+ * not overlap (use one stream, or order them with events).
+ * Faster than the two calls when X is already in the memory-side cache, slower when it is not.
  */
 int crossquant_absmax_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits,
                                float *t, float *c, void *codes, void *xhat, float *row_scale,
