@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--alpha", type=float, default=0.15)
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from a captured HIP graph and report its time per step")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the plain read / copy / MFMA-only calibration kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", default="all",
                     help="all, or a comma list of absmax,quantize,count,linear (for profiling one stage)")
@@ -77,12 +79,23 @@ def cpu_baseline(cfg, X, W, alpha):
     q_bytes = 2 * n + (2 + 1 + 2) * n            # absmax read + quantize read/codes/xhat
     q_time = (t1 - t0) + (t2 - t1)
     lin_time = (t5 - t4) * (T / slab)
+    # the same quantizer on one thread (the definition as a scalar loop), on a quarter of the rows
+    n_thr = oracle.num_threads()
+    oracle.set_num_threads(1)
+    Xq = X[: max(T // 4, 1)]
+    s0 = time.perf_counter()
+    t1t, c1t = oracle.absmax(Xq)
+    oracle.quantize(Xq, t1t, c1t, alpha, cfg.bits, want_xhat=True)
+    s1 = time.perf_counter()
+    oracle.set_num_threads(n_thr)
+    single_gbs = 7 * Xq.size / (s1 - s0) / 1e9
     return {
         "value": q_bytes / q_time / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
         "sample": "full %dx%d activation for absmax+quantize+count; linear layer on a %d-row slab "
                   "(full %dx%d weights), time scaled by T/%d" % (T, I, slab, I, O, slab),
         "absmax_s": t1 - t0, "quantize_s": t2 - t1, "count_s": t3 - t2,
         "linear_s_extrapolated": lin_time, "w8a8_linear_tops": 2.0 * T * I * O / lin_time / 1e12,
+        "single_thread_value": single_gbs, "single_thread_sample": "absmax + quantize on the first %d rows" % Xq.shape[0],
     }
 
 
@@ -239,6 +252,49 @@ def main():
         except cq.CrossQuantError as e:
             fused = {"unsupported": str(e)}
 
+    def event_ms(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    # the same two quantizer calls back to back (X stays in the memory-side cache): the warm rate
+    warm_ms = None
+    if ran["absmax"] and ran["quantize"]:
+        def quantizer():
+            cq.crossquant_absmax(Xg, t=t, c=c)
+            cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
+                                   zero_count=zc)
+        event_ms(quantizer, 5)
+        warm_ms = event_ms(quantizer, max(args.steps // 2, 1))
+
+    # what the device sustains on a plain read, a plain copy and an MFMA-only loop
+    achievable = None
+    if not args.no_ceilings:
+        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)       # 1 GiB: far beyond the caches
+        big.fill_(1)
+        half = 512 << 20
+        event_ms(lambda: cq.crossquant_calib_read(big), 2)
+        read_ms = event_ms(lambda: cq.crossquant_calib_read(big), 10)
+        event_ms(lambda: cq.crossquant_calib_copy(big[:half], big[half:]), 2)
+        copy_ms = event_ms(lambda: cq.crossquant_calib_copy(big[:half], big[half:]), 10)
+        del big
+        mf = {}
+        for mode, name in ((0, "zero_operands"), (1, "code_like_operands")):
+            ops_ = cq.crossquant_calib_mfma_i8(2000, mode)
+            ms_ = event_ms(lambda: cq.crossquant_calib_mfma_i8(2000, mode), 5)
+            mf[name] = ops_ / (ms_ * 1e-3) / 1e12
+        achievable = {
+            "hbm_read_GBs": (1 << 30) / (read_ms * 1e-3) / 1e9,
+            "hbm_copy_GBs_read_plus_write": 2 * half / (copy_ms * 1e-3) / 1e9,
+            "mfma_i8_TOPs": mf,
+            "quantizer_frac_of_copy": (quant_gbs / (2 * half / (copy_ms * 1e-3) / 1e9)) if quant_gbs else None,
+            "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands"]) if tops else None,
+        }
+
     graph_ms = None
     if args.graph and args.stages == "all":
         g = torch.cuda.CUDAGraph()
@@ -278,6 +334,8 @@ def main():
         "kernel_proportion": {"crossquant": z / n, "per_token": z_pt / n},
         "absmax_quantize_single_read": fused,
         "graph_replay_ms_per_step": graph_ms,
+        "quantizer_warm": {"ms": warm_ms, "GBs": (bytes_absmax + bytes_quant) / (warm_ms * 1e-3) / 1e9} if warm_ms else None,
+        "achievable": achievable,
         "roofline": {"kernel": "gemm_i8_ring_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS if tops else None,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},

@@ -186,6 +186,21 @@ int crossquant_w8a8_linear(const int8_t *qx, const float *row_scale, const int8_
                            const float *w_scale, int64_t T, int64_t I, int64_t O, void *Y,
                            int64_t ldy, int32_t *acc_debug, void *stream);
 
+/*
+ * Roofline calibration, not part of the method: kernels that do nothing but stream, so that a
+ * benchmark can state what this device sustains next to the published peaks (the measurement
+ * plan asks for a plain 16-byte-per-lane read, a copy, and an MFMA-only loop).
+ * crossquant_calib_read: reads `bytes` (multiple of 16, src 16-byte aligned); sink (nullable,
+ *   device, 8-byte aligned) is only there to keep the loads alive and is normally left untouched.
+ * crossquant_calib_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, non-overlapping.
+ * crossquant_calib_mfma_i8: every SIMD issues iters * 16 independent v_mfma_i32_32x32x32_i8 on
+ *   operands held in registers; data_mode 0 = all-zero operands, 1 = bell-shaped int8 codes.
+ *   *ops (HOST pointer, nullable) receives the number of integer operations of the launch.
+ */
+int crossquant_calib_read(const void *src, int64_t bytes, unsigned long long *sink, void *stream);
+int crossquant_calib_copy(const void *src, void *dst, int64_t bytes, void *stream);
+int crossquant_calib_mfma_i8(int iters, int data_mode, int *sink, double *ops, void *stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *crossquant_status_string(int status);
 

@@ -76,6 +76,14 @@ def num_threads() -> int:
     return int(_load().cq_oracle_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads used by the row loops from now on (timing only; results do not depend on it)."""
+    lib = _load()
+    lib.cq_oracle_set_num_threads.restype = None
+    lib.cq_oracle_set_num_threads.argtypes = [ctypes.c_int]
+    lib.cq_oracle_set_num_threads(int(n))
+
+
 def half_to_float(h: int) -> float:
     return float(_load().cq_oracle_half_to_float(int(h)))
 

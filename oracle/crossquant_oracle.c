@@ -87,6 +87,16 @@ int cq_oracle_num_threads(void)
 #endif
 }
 
+/* Number of threads the row loops may use from now on (timing only: no result depends on it). */
+void cq_oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* ---------- row and column absolute maxima (Eq. 1: t_i ; CrossQuant equation: c_j) ---------- */
 /* X: T x I binary16, row-major with leading dimension ldx (elements). */
 void cq_oracle_absmax(const uint16_t *X, int64_t T, int64_t I, int64_t ldx, float *t, float *c)

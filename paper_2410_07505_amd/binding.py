@@ -28,6 +28,9 @@ lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int,
 lib.crossquant_absmax_quantize.argtypes = [_vp, _i64, _i64, _i64, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_absmax_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp]
 lib.crossquant_quantize_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.crossquant_calib_read.argtypes = [_vp, _i64, _vp, _vp]
+lib.crossquant_calib_copy.argtypes = [_vp, _vp, _i64, _vp]
+lib.crossquant_calib_mfma_i8.argtypes = [_int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]
@@ -35,7 +38,7 @@ lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp,
 lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
 for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_absmax_quantize", "crossquant_absmax_batched",
-           "crossquant_quantize_batched", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
+           "crossquant_quantize_batched", "crossquant_calib_read", "crossquant_calib_copy", "crossquant_calib_mfma_i8", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
            "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "crossquant_w8a8_linear",
            "crossquant_version"):
     getattr(lib, _n).restype = _int
@@ -216,6 +219,26 @@ def crossquant_quantize_batched(X: torch.Tensor, t: torch.Tensor, c: torch.Tenso
                                            float(alpha), int(bits), _ptr(codes), _ptr(xhat), row_scale.data_ptr(),
                                            col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
     return codes, xhat, row_scale, col_scale, zero_count
+
+
+def crossquant_calib_read(src: torch.Tensor) -> None:
+    """Plain streaming read of a contiguous GPU tensor (roofline calibration)."""
+    _check(lib.crossquant_calib_read(src.data_ptr(), src.numel() * src.element_size(), 0, _stream(src)))
+
+
+def crossquant_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Plain copy between two contiguous GPU tensors of the same size (roofline calibration)."""
+    if src.numel() * src.element_size() != dst.numel() * dst.element_size():
+        raise ValueError("src and dst must have the same size in bytes")
+    _check(lib.crossquant_calib_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream(src)))
+
+
+def crossquant_calib_mfma_i8(iters: int, data_mode: int) -> float:
+    """MFMA-only loop on the current device and stream; returns the integer operations launched."""
+    ops = ctypes.c_double(0.0)
+    _check(lib.crossquant_calib_mfma_i8(int(iters), int(data_mode), 0, ctypes.byref(ops),
+                                        torch.cuda.current_stream().cuda_stream))
+    return float(ops.value)
 
 
 def crossquant_kernel_count(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,

@@ -200,6 +200,27 @@ int crossquant_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_
                                            static_cast<hipStream_t>(stream)));
 }
 
+int crossquant_calib_read(const void* src, int64_t bytes, unsigned long long* sink, void* stream) {
+    if (!src) return CQ_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0) return CQ_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(sink, 8)) return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_calib_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+}
+
+int crossquant_calib_copy(const void* src, void* dst, int64_t bytes, void* stream) {
+    if (!src || !dst) return CQ_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0) return CQ_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_calib_copy(src, dst, bytes, static_cast<hipStream_t>(stream)));
+}
+
+int crossquant_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops, void* stream) {
+    if (iters < 1 || iters > (1 << 20)) return CQ_ERR_SHAPE;
+    if (data_mode != 0 && data_mode != 1) return CQ_ERR_UNSUPPORTED;
+    if (!aligned(sink, 4)) return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_calib_mfma_i8(iters, data_mode, sink, ops, static_cast<hipStream_t>(stream)));
+}
+
 const char* crossquant_status_string(int status) {
     switch (status) {
         case CQ_OK: return "ok";

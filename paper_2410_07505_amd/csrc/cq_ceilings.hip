@@ -1,0 +1,121 @@
+// Calibration kernels for the rooflines: what this device reaches on a plain streaming read, a
+// plain copy and a loop of nothing but INT8 matrix instructions.  They are not part of the method;
+// the benchmark times them next to the real kernels so that every rate can be read against both
+// the published peak and the rate the part actually sustains.
+#include "cq_kernels.h"
+
+namespace cq {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kCalibThreads = 256;
+
+// 16 bytes per lane per load, four loads in flight, grid-stride.  The xor of everything read
+// is kept so the loads cannot be dropped; it is stored only if it equals a value it cannot have
+// been steered to.
+__global__ void __launch_bounds__(kCalibThreads)
+calib_read_kernel(const u32x4* __restrict__ src, int64_t n16, unsigned long long* __restrict__ sink) {
+    const int64_t stride = (int64_t)gridDim.x * kCalibThreads;
+    int64_t i = (int64_t)blockIdx.x * kCalibThreads + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+        acc ^= v0 ^ v1 ^ v2 ^ v3;
+    }
+    for (; i < n16; i += stride) acc ^= src[i];
+    const uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (x == 0x9E3779B9u && sink) atomicAdd(sink, 1ull);
+}
+
+__global__ void __launch_bounds__(kCalibThreads)
+calib_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * kCalibThreads;
+    int64_t i = (int64_t)blockIdx.x * kCalibThreads + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+        dst[i] = v0;
+        dst[i + stride] = v1;
+        dst[i + 2 * stride] = v2;
+        dst[i + 3 * stride] = v3;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__device__ __forceinline__ uint32_t calib_hash(uint32_t s) {
+    s ^= s >> 13; s *= 0x5bd1e995u; s ^= s >> 15; s *= 2654435761u; s ^= s >> 16;
+    return s;
+}
+
+// One wave per SIMD, 16 independent 32x32 accumulators, operands fixed in registers: the matrix
+// pipe never waits for data.  data_mode 0: all-zero operands; 1: bell-shaped int8 codes (sum of
+// four 6-bit uniforms, |q| up to ~42), about what quantized activations and weights look like.
+// The sustained rate depends on the operands' switching activity, so both are reported.
+__global__ void __launch_bounds__(256)
+calib_mfma_kernel(int iters, int data_mode, int* __restrict__ sink) {
+    v4i a[4], b[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t wa = 0, wb = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t ra = calib_hash(threadIdx.x * 977u + k * 131u + e * 17u + c + blockIdx.x * 7919u);
+                const uint32_t rb = calib_hash(threadIdx.x * 613u + k * 37u + e * 11u + c + 99991u + blockIdx.x * 104729u);
+                const int qa = (int)((ra & 63) + ((ra >> 6) & 63) + ((ra >> 12) & 63) + ((ra >> 18) & 63)) - 126;
+                const int qb = (int)((rb & 63) + ((rb >> 6) & 63) + ((rb >> 12) & 63) + ((rb >> 18) & 63)) - 126;
+                wa |= (uint32_t)(uint8_t)(int8_t)(data_mode ? qa / 3 : 0) << (8 * c);
+                wb |= (uint32_t)(uint8_t)(int8_t)(data_mode ? qb / 3 : 0) << (8 * c);
+            }
+            a[k][e] = (int)wa;
+            b[k][e] = (int)wb;
+        }
+    v16i acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 0x7fffffff && sink) sink[0] = s;
+}
+
+int calib_blocks() {
+    int dev = 0, n_cu = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    return n_cu;
+}
+
+}  // namespace
+
+hipError_t launch_calib_read(const void* src, int64_t bytes, unsigned long long* sink, hipStream_t stream) {
+    calib_read_kernel<<<dim3((unsigned)(calib_blocks() * 8)), dim3(kCalibThreads), 0, stream>>>(
+        static_cast<const u32x4*>(src), bytes / 16, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream) {
+    calib_copy_kernel<<<dim3((unsigned)(calib_blocks() * 8)), dim3(kCalibThreads), 0, stream>>>(
+        static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), bytes / 16);
+    return hipGetLastError();
+}
+
+// returns the number of integer operations (2 per multiply-add) the launch performs through *ops
+hipError_t launch_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops, hipStream_t stream) {
+    const int blocks = calib_blocks();
+    calib_mfma_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(iters, data_mode, sink);
+    if (ops) *ops = (double)blocks * 4.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 32);
+    return hipGetLastError();
+}
+
+}  // namespace cq

@@ -62,4 +62,9 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                               const float* w_scale, int T, int I, int O, uint16_t* Y, int64_t ldy,
                               int32_t* acc_debug, hipStream_t stream);
 
+// Roofline calibration (plain read, plain copy, MFMA-only loop); bytes is a multiple of 16.
+hipError_t launch_calib_read(const void* src, int64_t bytes, unsigned long long* sink, hipStream_t stream);
+hipError_t launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream);
+hipError_t launch_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops, hipStream_t stream);
+
 }  // namespace cq

@@ -165,6 +165,14 @@ def test_unpack_int4_argument_errors(cq):
     assert f(P, 0, 8, P, None) == -2 and f(P, 4, 7, P, None) == -2
 
 
+def test_calibration_argument_errors(cq):
+    r, c, m = cq.raw.crossquant_calib_read, cq.raw.crossquant_calib_copy, cq.raw.crossquant_calib_mfma_i8
+    assert r(0, 1024, None, None) == -1 and r(P, 0, None, None) == -2 and r(P, 1000, None, None) == -2
+    assert r(P + 8, 1024, None, None) == -5
+    assert c(P, 0, 1024, None) == -1 and c(P, P + 4096, 24, None) == -2 and c(P, P + 4, 1024, None) == -5
+    assert m(0, 0, None, None, None) == -2 and m(10, 2, None, None, None) == -6
+
+
 def test_linear_argument_errors(cq):
     f = cq.raw.crossquant_w8a8_linear
 

@@ -748,3 +748,18 @@ def test_whole_path_replays_from_a_hip_graph(cq):
         eager = [host(x) for x in (t, c, a, b, codes, xhat, zc, zc1, qw, ws, Y)]
         for g_, e_ in zip(got, eager):
             assert np.array_equal(g_.view(np.uint8), e_.view(np.uint8))
+
+
+# ----------------------------------------------------------------------------- roofline calibration kernels
+def test_calibration_kernels_run_and_copy_is_exact(cq):
+    import torch
+    n = (3 << 20) + 16 * 7                                  # not a multiple of the grid's stride
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    cq.crossquant_calib_copy(src, dst)
+    cq.crossquant_calib_read(src)
+    ops = cq.crossquant_calib_mfma_i8(10, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    assert ops == n_cu * 4 * 10 * 16 * 65536.0
