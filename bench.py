@@ -57,7 +57,7 @@ def parse():
 
 def cpu_baseline(cfg, X, W, alpha):
     """The CPU oracle, as it stands, timed on the host cores on a bounded sample of the same
-    workload: the full activation matrix for absmax / quantize / count, a 128-row slab of the
+    workload: the full activation matrix for absmax / quantize / count, a 2048-row slab of the
     linear layer (full I x O) scaled to T rows."""
     import numpy as np
     import oracle
@@ -69,7 +69,7 @@ def cpu_baseline(cfg, X, W, alpha):
     t2 = time.perf_counter()
     oracle.kernel_count(X, t, c, 1.0, cfg.bits)
     t3 = time.perf_counter()
-    slab = 128
+    slab = min(2048, T)
     Wslab_cols = O
     qw, s = oracle.weight_quantize(W[:, :Wslab_cols], ref["b"], cfg.bits)
     t4 = time.perf_counter()
