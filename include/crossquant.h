@@ -188,8 +188,8 @@ int crossquant_w8a8_linear(const int8_t *qx, const float *row_scale, const int8_
 
 /*
  * Roofline calibration, not part of the method: kernels that do nothing but stream, so that a
- * benchmark can state what this device sustains next to the published peaks (the measurement
- * plan asks for a plain 16-byte-per-lane read, a copy, and an MFMA-only loop).
+ * benchmark can state what this device sustains next to the published peaks: a plain
+ * 16-byte-per-lane read, a copy, and an MFMA-only loop.
  * crossquant_calib_read: reads `bytes` (multiple of 16, src 16-byte aligned); sink (nullable,
  *   device, 8-byte aligned) is only there to keep the loads alive and is normally left untouched.
  * crossquant_calib_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, non-overlapping.
