@@ -4,19 +4,23 @@
 // Both operands are stored with the contraction axis contiguous (qx [T][I], qw [O][I]), which is
 // the layout v_mfma_i32_32x32x32_i8 wants: every lane supplies 16 consecutive bytes of one row.
 //
-// Tiling for gfx950 (256 CUs, 160 KiB LDS per CU, 64-wide waves):
-//   - block tile 256 x 256, K step 128 bytes, 256 threads = 4 waves in a 2 x 2 arrangement,
-//     each wave owning 128 x 128 = 4 x 4 MFMA tiles of 32 x 32 (256 accumulator registers);
-//   - two LDS stages of (256 + 256) rows x 128 B = 128 KiB; the next K step is fetched from
-//     global memory into registers while the current one is multiplied, then stored to the
-//     other stage: one barrier per K step;
+// Two kernels, same results (integer accumulation is exact, so tiling and order cannot matter):
+//   - gemm_i8_ring_kernel, the fast path: whole 256 x 256 tiles, 16-byte aligned operands, K a
+//     multiple of 128.  512 threads = 8 waves in a 2 x 4 arrangement, each wave owning 128 x 64 =
+//     4 x 2 MFMA tiles of 32 x 32 (128 accumulator registers); operands go from global memory
+//     straight into a five-slot LDS ring (described at the kernel);
+//   - gemm_i8_kernel<true>, any shape and alignment: 256 threads = 4 waves in a 2 x 2 arrangement
+//     (128 x 128 per wave), two LDS stages of (256 + 256) rows x 128 B = 128 KiB; the next K step
+//     is fetched into registers (bounds-checked) while the current one is multiplied, then stored
+//     to the other stage: one barrier per K step.
+// Common to both:
+//   - block tile 256 x 256, K step 128 bytes;
 //   - LDS rows are 128 B = 8 chunks of 16 B, stored at chunk ^ ((row >> 1) & 7) so that the 16
 //     rows a quarter-wave reads (and the row pairs it writes) fall in 16 distinct bank groups;
 //   - block -> tile mapping: consecutive block ids land on different XCDs, so ids are first
 //     de-interleaved by XCD (each XCD gets a contiguous range of tiles, hence its own L2 sees a
 //     compact patch), then walked in groups of 4 tile-rows so that concurrently resident tiles
 //     share A rows and B columns.
-// Integer accumulation is exact, so tiling and order cannot change a result.
 #include <type_traits>
 
 #include "cq_kernels.h"
@@ -31,17 +35,8 @@ constexpr int BM = 256, BN = 256, BK = 128;
 constexpr int kThreads = 256;
 constexpr int kStageBytes = (BM + BN) * BK;       // 64 KiB
 constexpr int kLdsBytes = 2 * kStageBytes;         // 128 KiB
-#ifndef CQ_GEMM_XCDS
-#define CQ_GEMM_XCDS 8
-#endif
-#ifndef CQ_GEMM_GROUP_M
-#define CQ_GEMM_GROUP_M 4
-#endif
-#ifndef CQ_GEMM_WAVES
-#define CQ_GEMM_WAVES 8
-#endif
-constexpr int kXcds = CQ_GEMM_XCDS;       // block ids are dealt round-robin to this many L2 domains
-constexpr int kGroupM = CQ_GEMM_GROUP_M;  // tile-rows walked together
+constexpr int kXcds = 8;      // block ids are dealt round-robin to this many L2 domains
+constexpr int kGroupM = 4;    // tile-rows walked together (8, 16 and 1 measured slower)
 
 __device__ __forceinline__ int swz(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) * 16; }
 
@@ -191,20 +186,8 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
 // p ^ ((R >> 1) & 7) of that row (still the same 128 contiguous bytes per 8 lanes).
 // Software pipeline per K step (4 slabs of 32 bytes, fragment registers F0/F1 alternate):
 //   read slab1 | mfma slab0 ; read slab2 | mfma slab1 ; read slab3 | mfma slab2 ;
-//   wait for the next tile, barrier ; issue the loads of the tile after next into the stage
-//   just released ; read slab0 of the next tile | mfma slab3.
+//   wait for the next tile, barrier ; read slab0 of the next tile | mfma slab3.
 // ---------------------------------------------------------------------------------------------
-#ifdef CQ_GEMM_PROFILE
-// development aid: per-phase cycle totals of wave 0 of block 0 (not compiled into the library)
-__device__ unsigned long long g_phase_cycles[8];
-__device__ unsigned long long g_trace[8][8][8];   // [wave][step - 20][stamp]
-#define CQ_STAMP(i) do { const unsigned long long now_ = __builtin_amdgcn_s_memtime(); \
-                         if (prof_on) { phase_acc[i] += now_ - last_stamp; last_stamp = now_; } \
-                         if (blockIdx.x == 0 && lane == 0 && cur_kt >= 20 && cur_kt < 28 && (i) < 8) \
-                             g_trace[wave][cur_kt - 20][i] = now_; } while (0)
-#else
-#define CQ_STAMP(i) do { } while (0)
-#endif
 
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -293,189 +276,6 @@ __device__ __forceinline__ void epilogue_store(v16i (&acc)[4][NI], int8_t* lds, 
         *reinterpret_cast<uint4*>(dst) = v;
     }
 }
-
-// NWAVES = 8: waves in a 2 x 4 arrangement, each 128 x 64 (4 x 2 MFMA tiles, 128 accumulator
-// registers), two waves per SIMD.  A wave can only start a vector-memory instruction about every
-// 100 ns on this chip, so 8 waves are needed to bring in a 64 KiB tile per K step at the rate the
-// matrix pipes consume it; two resident waves per SIMD also cover each other's barrier and issue
-// stalls.  (NWAVES = 4: 2 x 2 waves of 128 x 128, kept for comparison.)
-template <int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64)
-gemm_i8_direct_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
-                      const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I, int O,
-                      uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
-                      int tiles_n) {
-    constexpr int WN = NWAVES / 2;            // waves along N
-    constexpr int WTN = BN / WN;              // wave tile width (128 or 64)
-    constexpr int NI = WTN / 32;              // MFMA tiles along N per wave
-    constexpr int LROWS = BM / NWAVES;        // LDS rows of each operand a wave fills per K step
-    constexpr int LINST = LROWS / 8;          // load instructions per operand per wave per K step
-    extern __shared__ __align__(16) int8_t lds[];
-
-    const int total = tiles_m * tiles_n;
-    const int per_xcd = (total + kXcds - 1) / kXcds;
-    const int L = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (L >= total) return;
-    const int group_sz = kGroupM * tiles_n;
-    const int g = L / group_sz;
-    const int gm = min(kGroupM, tiles_m - g * kGroupM);
-    const int in_g = L - g * group_sz;
-    const int tile_m = g * kGroupM + in_g % gm;
-    const int tile_n = in_g / gm;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int nk = I / BK;
-
-    // ---- loader: wave w fills LDS rows [LROWS*w, LROWS*(w+1)) of A and of B; instruction ii
-    // covers rows LROWS*w + 8*ii + (lane >> 3), physical chunk lane & 7.
-    const int ld_r = lane >> 3, ld_p = lane & 7;
-    const int8_t* ga[2];
-    const int8_t* gb[2];
-#pragma unroll
-    for (int par = 0; par < 2; ++par) {      // rows of even / odd ii differ in (R >> 1) & 7 by 4
-        const int R = LROWS * wave + 8 * par + ld_r;
-        const int c = ld_p ^ ((R >> 1) & 7);
-        ga[par] = qx + (int64_t)(m0 + R) * I + c * 16;
-        gb[par] = qw + (int64_t)(n0 + R) * I + c * 16;
-    }
-    auto issue_tile = [&](int kt, int stage) {
-        int8_t* As = lds + stage * kStageBytes + wave * (LROWS * BK);
-        int8_t* Bs = As + BM * BK;
-        const int64_t koff = (int64_t)kt * BK;
-#pragma unroll
-        for (int ii = 0; ii < LINST; ++ii) {
-            const int64_t roff = (int64_t)(ii >> 1) * 16 * I + koff;      // rows advance by 16 per pair
-            __builtin_amdgcn_global_load_lds((gptr_t)(ga[ii & 1] + roff), (lptr_t)(As + ii * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(gb[ii & 1] + roff), (lptr_t)(Bs + ii * 1024), 16, 0, 0);
-        }
-    };
-
-    // ---- fragment addressing: lane supplies row (lane & 31), 16-byte half (lane >> 5) of each
-    // 32-byte slab; logical chunk = 2 * ks + half, physical = logical ^ ((row >> 1) & 7).
-    // (row >> 1) & 7 depends only on lane & 15 here because the row bases are multiples of 32.
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    const int sw = (frag_row >> 1) & 7;
-    const int a_off = (wm * 128 + frag_row) * BK + ((frag_half ^ sw) * 16);
-    const int b_off = (wn * WTN + frag_row) * BK + ((frag_half ^ sw) * 16);
-
-    v16i acc[4][NI];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0;
-
-    issue_tile(0, 0);
-    if (nk > 1) issue_tile(1, 1);
-    // tile 0 must have landed; tile 1 (2 * LINST loads per wave) may still be in flight
-    if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LINST, 15));
-    else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
-    __syncthreads();
-
-    v4i af0[4], bf0[NI], af1[4], bf1[NI];
-    load_frags<NI>(af0, bf0, lds, lds + BM * BK, a_off, b_off, 0);
-
-    constexpr int NMF = 4 * NI;               // MFMAs per slab
-    constexpr int NRD = 4 + NI;               // fragment reads per slab
-    // One K step.  ISSUE: refill the stage this step releases with the tile two steps ahead.
-    // PREFETCH: read slab 0 of the next tile while the last slab of this one is multiplied.
-    // The sched_group_barrier sequences ask the scheduler to alternate LDS reads (and the
-    // global -> LDS loads) with MFMAs instead of clustering them, so the matrix pipe keeps
-    // issuing while the fragments of the following slab arrive.
-    auto interleave_reads = [&]() {
-        // reads of the following slab go out first, one per MFMA, so that the rest of this slab's
-        // MFMAs cover their latency
-#pragma unroll
-        for (int i = 0; i < NRD; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-#ifdef CQ_GEMM_PROFILE
-    const bool prof_on = (blockIdx.x == 0 && threadIdx.x == 0);
-    unsigned long long phase_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    unsigned long long last_stamp = __builtin_amdgcn_s_memtime();
-    int cur_kt = 0;
-#endif
-#ifndef CQ_GEMM_SPLIT_ISSUE
-#define CQ_GEMM_SPLIT_ISSUE 1
-#endif
-    // waves w and w + 4 share a SIMD; the upper half issues its loads later (see k_step)
-    const bool late_issuer = CQ_GEMM_SPLIT_ISSUE && NWAVES == 8 && wave >= 4;
-    auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value;
-        constexpr bool PREFETCH = decltype(prefetch_c)::value;
-#ifdef CQ_GEMM_PROFILE
-        cur_kt = kt;
-        CQ_STAMP(7);
-#endif
-        const int8_t* As = lds + (kt & 1) * kStageBytes;
-        const int8_t* Bs = As + BM * BK;
-        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 1);
-        mfma_slab<NI>(acc, af0, bf0);
-        interleave_reads();
-        // second wave group: its share of tile kt+1 goes out here, a quarter step after the first
-        // group's, so the two waves of a SIMD are not both stalled on load issue at the same time
-        if (late_issuer && kt >= 1 && kt + 1 < nk) issue_tile(kt + 1, (kt + 1) & 1);
-        __builtin_amdgcn_sched_barrier(0);
-        CQ_STAMP(0);
-        load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, 2);
-        mfma_slab<NI>(acc, af1, bf1);
-        interleave_reads();
-        CQ_STAMP(1);
-        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 3);
-        mfma_slab<NI>(acc, af0, bf0);
-        interleave_reads();
-        CQ_STAMP(2);
-        // every read of this stage has been issued; the next tile (other stage) must have landed
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
-        CQ_STAMP(3);
-        __syncthreads();
-        CQ_STAMP(4);
-        __builtin_amdgcn_sched_barrier(0);
-        if (ISSUE && !late_issuer) issue_tile(kt + 2, kt & 1);   // refill the stage everyone has finished with
-        if (PREFETCH) {
-            const int8_t* An = lds + ((kt + 1) & 1) * kStageBytes;
-            load_frags<NI>(af0, bf0, An, An + BM * BK, a_off, b_off, 0);
-        }
-        mfma_slab<NI>(acc, af1, bf1);
-#pragma unroll
-        for (int i = 0; i < NMF; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                              // 1 MFMA
-            if (PREFETCH && i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 DS read
-            if (ISSUE && i < 2 * LINST) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global -> LDS load
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        CQ_STAMP(5);
-    };
-    using yes = std::integral_constant<bool, true>;
-    using no = std::integral_constant<bool, false>;
-    int kt = 0;
-    for (; kt + 2 < nk; ++kt) k_step(kt, yes{}, yes{});
-    if (kt + 1 < nk) {
-        k_step(kt, no{}, yes{});
-        ++kt;
-    }
-    k_step(kt, no{}, no{});
-    CQ_STAMP(6);
-#ifdef CQ_GEMM_PROFILE
-    cur_kt = 1000;
-#define CQ_PROFILE_FLUSH() do { CQ_STAMP(7); if (prof_on) for (int i_ = 0; i_ < 8; ++i_) g_phase_cycles[i_] = phase_acc[i_]; } while (0)
-#else
-#define CQ_PROFILE_FLUSH() do { } while (0)
-#endif
-
-    epilogue_store<WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, O, m0 + wm * 128, n0 + wn * WTN,
-                            lane, wave);
-    CQ_PROFILE_FLUSH();
-}
-
 
 // ---------------------------------------------------------------------------------------------
 // Ring variant of the fast path (8 waves): the loads of the two wave groups are taken apart in
@@ -584,40 +384,24 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
         __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
-#ifdef CQ_GEMM_PROFILE
-    const bool prof_on = (blockIdx.x == 0 && threadIdx.x == 0);
-    unsigned long long phase_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    unsigned long long last_stamp = __builtin_amdgcn_s_memtime();
-    int cur_kt = 0;
-#endif
     auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
         constexpr bool ISSUE = decltype(issue_c)::value;        // kt + 2 < nk
         constexpr bool PREFETCH = decltype(prefetch_c)::value;  // kt + 1 < nk
-#ifdef CQ_GEMM_PROFILE
-        cur_kt = kt;
-        CQ_STAMP(7);
-#endif
         const int8_t* As = lds + sa * kSlotBytes;
         const int8_t* Bs = lds + sb * kSlotBytes;
         const int na = adv(sa), nb = adv(sb);                   // slots of tile kt+1
         load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 1);
         mfma_slab<NI>(acc, af0, bf0);
         interleave_reads();
-        CQ_STAMP(0);
         load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, 2);
         mfma_slab<NI>(acc, af1, bf1);
         interleave_reads();
-        CQ_STAMP(1);
         load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 3);
         mfma_slab<NI>(acc, af0, bf0);
         interleave_reads();
-        CQ_STAMP(2);
         // A loaders: A(kt+2) = half tile 2kt+4 -> slot (2kt+4) % 5 = adv(na); its previous tenant
         // B(kt-1) was released at the previous barrier.  Then tile kt+1's A (requested a step ago)
         // must have landed: at most the 8 requests just made may still be in flight.
-#ifdef CQ_GEMM_SETPRIO
-        __builtin_amdgcn_s_setprio(0);
-#endif
         if (!b_loader) {
             if (ISSUE) {
                 issue_half(kt + 2, adv(na));
@@ -628,21 +412,16 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
         } else {
             __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));      // B(kt+1), requested after the last barrier
         }
-        CQ_STAMP(3);
         // a bare barrier: __syncthreads() would add a release fence, i.e. a wait for *all* of this
         // wave's outstanding loads, including the ones requested a moment ago for two steps ahead.
         // LDS needs no fence: this wave's reads are complete (lgkmcnt(0) above) and the loads the
         // next tile depends on are complete in the waves that issued them (their vmcnt wait above).
         __builtin_amdgcn_s_barrier();
-        CQ_STAMP(4);
         __builtin_amdgcn_sched_barrier(0);
         // B loaders: B(kt+2) = half tile 2kt+5 -> slot (2kt+5) % 5 = sa, tile kt's A slot, which
         // nobody reads any more (slab 3's fragments are in registers)
         if (b_loader && ISSUE) issue_half(kt + 2, sa);
         __builtin_amdgcn_sched_barrier(0);
-#ifdef CQ_GEMM_SETPRIO
-        __builtin_amdgcn_s_setprio(1);
-#endif
         if (PREFETCH) load_frags<NI>(af0, bf0, lds + na * kSlotBytes, lds + nb * kSlotBytes, a_off, b_off, 0);
         mfma_slab<NI>(acc, af1, bf1);
 #pragma unroll
@@ -651,7 +430,6 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
             if (PREFETCH && i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-        CQ_STAMP(5);
         sa = na;
         sb = nb;
     };
@@ -686,28 +464,11 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                       al16(w_scale) && al16(acc_debug);
     hipError_t e;
     if (full) {
-#ifndef CQ_GEMM_RING
-#define CQ_GEMM_RING 1
-#endif
-        if (CQ_GEMM_RING) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_ring_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kRingLds);
-            if (e != hipSuccess) return e;
-            gemm_i8_ring_kernel<<<grid, dim3(512), kRingLds, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
-                                                                       acc_debug, tiles_m, tiles_n);
-        } else {
-            constexpr int NW = CQ_GEMM_WAVES;
-            constexpr int kWtn = BN / (NW / 2);
-            // K-loop stages (128 KiB) or the epilogue's staging area, whichever is larger
-            constexpr int kDirectLds =
-                (NW * 128 * (kWtn * 2 + 8) > kLdsBytes) ? NW * 128 * (kWtn * 2 + 8) : kLdsBytes;
-            static_assert(kDirectLds <= 160 * 1024, "LDS budget of a gfx950 CU");
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_direct_kernel<NW>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kDirectLds);
-            if (e != hipSuccess) return e;
-            gemm_i8_direct_kernel<NW><<<grid, dim3(NW * 64), kDirectLds, stream>>>(
-                qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n);
-        }
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_ring_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kRingLds);
+        if (e != hipSuccess) return e;
+        gemm_i8_ring_kernel<<<grid, dim3(512), kRingLds, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
+                                                                   acc_debug, tiles_m, tiles_n);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
