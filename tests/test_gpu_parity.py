@@ -648,7 +648,7 @@ def test_end_to_end_a4w4_config(cq):
     say("C4 kernel proportion: crossquant %.4f per-token %.4f" % (z / X.size, zp / X.size))
 
 
-@pytest.mark.parametrize("name", ["C2", "C5"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C5"])
 def test_end_to_end_full_config_sampled(cq, name):
     """Full-size run in the benchmark's launch configuration.  Weight codes and steps are
     compared in full; accumulators and outputs on sampled rows and columns the oracle recomputes
