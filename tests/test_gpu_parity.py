@@ -276,6 +276,25 @@ def test_quantize_is_deterministic(cq):
     assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1]) and torch.equal(r1[4], r2[4])
 
 
+@pytest.mark.parametrize("T,I", [(3, 70000), (60000, 8), (5, 65536), (20000, 24), (2, 131080)])
+def test_extreme_aspect_ratios(cq, T, I):
+    """Very wide and very tall matrices: many column chunks with few rows, and many row chunks
+    with one partly filled column chunk."""
+    X = outliers(T, I, seed=T % 97 + I % 89)
+    check_quantize(cq, X, 0.15, 8, label="aspect")
+    check_quantize(cq, X, 0.5, 4, label="aspect")
+    check_analysis(cq, X, 0.15, 8, label="aspect")
+
+
+def test_wide_leading_dimension(cq):
+    """A narrow window of a very wide matrix: rows 64 KiB apart."""
+    import torch
+    base = outliers(40, 32768, seed=31)
+    g = gpu(base)
+    for lo, hi in ((1024, 1280), (8191, 8191 + 300)):
+        check_quantize(cq, base[:, lo:hi], 0.15, 8, Xg=g[:, lo:hi], label="window[%d:%d]" % (lo, hi))
+
+
 # ----------------------------------------------------------------------------- single-read fused call
 def check_fused(cq, X, alpha, bits, Xg=None, label="", want_xhat=True):
     say("absmax_quantize %s shape=%s alpha=%g bits=%d xhat=%s" % (label, X.shape, alpha, bits, want_xhat))
