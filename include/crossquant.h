@@ -177,8 +177,9 @@ int crossquant_weight_quantize_grouped(const void *W, int64_t I, int64_t O, cons
 /*
  * W8A8 linear layer Y = X . W on integer codes (Background section), INT8 MFMA, int32 accumulate.
  *   acc_ik = sum_j qx_ij * qw_kj  (exact);  Y_ik = fl16(fl32(fl32(float(acc_ik) * row_scale_i) * w_scale_k))
- * qx: int8 [T][I].  qw: int8 [O][I] (contraction axis contiguous).  Both 16-byte aligned with
- *     I % 16 == 0 for the fast path; other layouts take a slower loader.
+ * qx: int8 [T][I].  qw: int8 [O][I] (contraction axis contiguous).  Fast path: qx, qw, Y and
+ *     w_scale 16-byte aligned, I % 128 == 0, O % 8 == 0, ldy % 8 == 0 (any T); other layouts take a
+ *     slower, fully bounds-checked kernel with identical results.
  * Y: out, binary16 [T][ldy], ldy >= O.  acc_debug: out, nullable, int32 [T][O] raw accumulators.
  * I * 127 * 127 must fit in int32 (I <= 133,000).
  */

@@ -227,7 +227,7 @@ __device__ __forceinline__ void mfma_slab(v16i (&acc)[4][NI], const v4i (&af)[4]
 template <int WTN, int NI>
 __device__ __forceinline__ void epilogue_store(v16i (&acc)[4][NI], int8_t* lds, const float* __restrict__ row_scale,
                                                const float* __restrict__ w_scale, uint16_t* __restrict__ Y,
-                                               int64_t ldy, int32_t* __restrict__ acc_debug, int O, int row0,
+                                               int64_t ldy, int32_t* __restrict__ acc_debug, int T, int O, int row0,
                                                int col0, int lane, int wave) {
     const int frag_half = lane >> 5;
     constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
@@ -235,13 +235,15 @@ __device__ __forceinline__ void epilogue_store(v16i (&acc)[4][NI], int8_t* lds, 
     const int t_lane = lane & 31;
     float a_t[4];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[row0 + mi * 32 + t_lane];
+    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[min(row0 + mi * 32 + t_lane, T - 1)];   // rows >= T are never stored
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
             const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
-            const float4 s4 = *reinterpret_cast<const float4*>(w_scale + col0 + o_loc);
+            // O % 8 == 0 on this path: a group of 4 channels exists or not as a whole
+            const float4 s4 = (col0 + o_loc < O) ? *reinterpret_cast<const float4*>(w_scale + col0 + o_loc)
+                                                 : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi) {
@@ -254,8 +256,8 @@ __device__ __forceinline__ void epilogue_store(v16i (&acc)[4][NI], int8_t* lds, 
                 }
                 *reinterpret_cast<uint2*>(stage + (mi * 32 + t_lane) * kRowPitch + o_loc * 2) =
                     make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                if (acc_debug) {
-                    const int row = row0 + mi * 32 + t_lane;
+                const int row = row0 + mi * 32 + t_lane;
+                if (acc_debug && row < T && col0 + o_loc < O) {
                     int4 v = make_int4(acc[mi][ni][rg * 4 + 0], acc[mi][ni][rg * 4 + 1], acc[mi][ni][rg * 4 + 2],
                                        acc[mi][ni][rg * 4 + 3]);
                     *reinterpret_cast<int4*>(acc_debug + (int64_t)row * O + col0 + o_loc) = v;
@@ -272,8 +274,10 @@ __device__ __forceinline__ void epilogue_store(v16i (&acc)[4][NI], int8_t* lds, 
     for (int i = 0; i < 128 / kRowsPerInst; ++i) {
         const int trow = i * kRowsPerInst + rsub;
         const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
-        uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
-        *reinterpret_cast<uint4*>(dst) = v;
+        if (row0 + trow < T && col0 + piece * 8 < O) {
+            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
+            *reinterpret_cast<uint4*>(dst) = v;
+        }
     }
 }
 
@@ -328,21 +332,25 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     // chunk lane & 7 (the swizzle is applied to the global column).
     const int ld_r = lane >> 3, ld_p = lane & 7;
     const int lw = wave & 3;
-    const int8_t* gsrc[2];
+    // Tiles on the bottom / right edge of a ragged problem read a clamped (valid) row instead of
+    // the rows past the end; what lands in those LDS rows only feeds outputs the epilogue drops.
+    const int8_t* gsrc[8];
+    {
+        const int8_t* base = b_loader ? qw : qx;
+        const int first = b_loader ? n0 : m0, last = (b_loader ? O : T) - 1;
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        const int R = 64 * lw + 8 * par + ld_r;
-        const int c = ld_p ^ ((R >> 1) & 7);
-        gsrc[par] = (b_loader ? qw + (int64_t)(n0 + R) * I : qx + (int64_t)(m0 + R) * I) + c * 16;
+        for (int ii = 0; ii < 8; ++ii) {
+            const int R = 64 * lw + 8 * ii + ld_r;
+            const int c = ld_p ^ ((R >> 1) & 7);
+            gsrc[ii] = base + (int64_t)min(first + R, last) * I + c * 16;
+        }
     }
     auto issue_half = [&](int kt, int slot) {
         int8_t* dst = lds + slot * kSlotBytes + lw * (64 * BK);
         const int64_t koff = (int64_t)kt * BK;
 #pragma unroll
-        for (int ii = 0; ii < 8; ++ii) {
-            const int64_t roff = (int64_t)(ii >> 1) * 16 * I + koff;
-            __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii & 1] + roff), (lptr_t)(dst + ii * 1024), 16, 0, 0);
-        }
+        for (int ii = 0; ii < 8; ++ii)
+            __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii] + koff), (lptr_t)(dst + ii * 1024), 16, 0, 0);
     };
 
     const int frag_row = lane & 31, frag_half = lane >> 5;
@@ -443,7 +451,7 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     }
     k_step(kt, no{}, no{});
 
-    epilogue_store<WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, O, m0 + wm * 128, n0 + wn * WTN,
+    epilogue_store<WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
                             lane, wave);
 }
 
@@ -459,9 +467,10 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
     const bool vec = (reinterpret_cast<uintptr_t>(qx) % 16 == 0) && (reinterpret_cast<uintptr_t>(qw) % 16 == 0) &&
                      (I % 16 == 0);
     auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
-    // fast path: whole tiles and everything the vector loads/stores touch aligned to 16 bytes
-    const bool full = vec && (T % BM == 0) && (O % BN == 0) && (I % BK == 0) && al16(Y) && (ldy % 8 == 0) &&
-                      al16(w_scale) && al16(acc_debug);
+    // fast path: K a multiple of the K step and everything the vector loads/stores touch aligned to 16
+    // bytes (any T; O a multiple of 8)
+    const bool full = vec && (I % BK == 0) && (O % 8 == 0) && al16(Y) && (ldy % 8 == 0) && al16(w_scale) &&
+                      al16(acc_debug);
     hipError_t e;
     if (full) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_ring_kernel),

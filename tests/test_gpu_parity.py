@@ -556,7 +556,9 @@ def test_weight_crossquant_through_the_activation_calls(cq):
 
 # ----------------------------------------------------------------------------- linear
 LINEAR_SHAPES = [(1, 16, 1), (5, 32, 7), (100, 200, 300), (64, 256, 256), (256, 128, 256), (300, 208, 270),
-                 (256, 1024, 512), (513, 384, 257), (33, 100, 65)]
+                 (256, 1024, 512), (513, 384, 257), (33, 100, 65),
+                 # ragged token / channel counts on the MFMA fast path (I % 128 == 0, O % 8 == 0)
+                 (1, 128, 8), (300, 256, 520), (257, 384, 264), (513, 1024, 1000), (700, 512, 776), (255, 128, 248)]
 
 
 @pytest.mark.parametrize("T,I,O", LINEAR_SHAPES)
@@ -605,6 +607,25 @@ def test_linear_strided_output(cq):
     cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), Y=buf[:, :O])
     out = host(buf)
     assert np.array_equal(bits16(out[:, :O]), bits16(Y_ref)) and np.all(out[:, O:] == 7.0)
+
+
+def test_linear_ragged_fast_path_writes_nothing_outside_its_output(cq):
+    """Ragged T and O on the MFMA fast path (edge tiles read clamped rows and drop the surplus
+    outputs): rows past T and columns past O of the surrounding buffer must stay untouched."""
+    import torch
+    say("linear ragged fast path, guarded buffer")
+    T, I, O = 300, 256, 520
+    qx, qw = workloads.int8_codes(T, I, seed=3), workloads.int8_codes(O, I, seed=4)
+    rng = np.random.default_rng(6)
+    a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+    s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    buf = torch.full((T + 20, 640), 7.0, dtype=torch.float16, device="cuda")
+    accbuf = torch.full((T + 20, O), -5, dtype=torch.int32, device="cuda")
+    cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), Y=buf[:T, :O], acc_debug=accbuf[:T])
+    out, acc = host(buf), host(accbuf)
+    assert np.array_equal(bits16(out[:T, :O]), bits16(Y_ref)) and np.array_equal(acc[:T], acc_ref)
+    assert np.all(out[:T, O:] == 7.0) and np.all(out[T:] == 7.0) and np.all(acc[T:] == -5)
 
 
 def test_end_to_end_tiny_config(cq):
