@@ -803,3 +803,44 @@ def test_calibration_kernels_run_and_copy_is_exact(cq):
     assert torch.equal(src, dst)
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     assert ops == n_cu * 4 * 10 * 16 * 65536.0
+
+
+# ----------------------------------------------------------------------------- seeded random shapes
+def test_random_shapes_quantizer(cq):
+    """Sixty seeded random problems (shape, alpha, bits, distribution) through absmax, quantize,
+    count and, where the layout allows, the single-read call."""
+    rng = np.random.default_rng(2024)
+    for case in range(60):
+        T = int(rng.integers(1, 700))
+        I = int(rng.integers(1, 2100))
+        bits = int(rng.choice([4, 8]))
+        if bits == 4:
+            I += I & 1
+        alpha = float(rng.choice([0.0, 0.05, 0.15, 0.3, 0.55, 0.85, 1.0]))
+        dist = str(rng.choice(["normal", "student_t3"]))
+        X = outliers(T, I, seed=1000 + case, n_out=int(rng.integers(0, 4)), scale=float(rng.uniform(5, 200)), dist=dist)
+        check_quantize(cq, X, alpha, bits, label="random %d" % case)
+        if I % 8 == 0:
+            check_fused(cq, X, alpha, bits, label="random %d" % case)
+
+
+def test_random_shapes_linear(cq):
+    """Forty seeded random GEMM shapes, half of them on the MFMA fast path's conditions."""
+    rng = np.random.default_rng(4048)
+    for case in range(40):
+        T = int(rng.integers(1, 900))
+        if case % 2:
+            I = 128 * int(rng.integers(1, 9))
+            O = 8 * int(rng.integers(1, 120))
+        else:
+            I = int(rng.integers(1, 1100))
+            O = int(rng.integers(1, 900))
+        say("random linear %d: T=%d I=%d O=%d" % (case, T, I, O))
+        qx = workloads.int8_codes(T, I, seed=5000 + case)
+        qw = workloads.int8_codes(O, I, seed=6000 + case)
+        a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+        s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+        Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+        Y, acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), want_acc=True)
+        assert np.array_equal(host(acc), acc_ref)
+        assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
