@@ -534,6 +534,15 @@ def test_weight_quantize_grouped(cq, I, O, group, bits):
         assert none_dq is None and np.array_equal(host(qw2), qw_ref) and np.array_equal(host(s2), s_ref)
 
 
+def test_weight_quantize_grouped_at_layer_scale(cq):
+    """The paper's W4-g128 setting on the low-bit configuration's 4096 x 4096 weight."""
+    W = workloads.config_weight("C4")
+    qw_ref, s_ref, dq_ref = oracle.weight_quantize_grouped(W, None, 128, 4)
+    qw, s, dq = cq.crossquant_weight_quantize_grouped(gpu(W), None, 128, 4, want_dq=True)
+    assert np.array_equal(bits32(host(s)), bits32(s_ref)) and np.array_equal(host(qw), qw_ref)
+    assert np.array_equal(bits16(host(dq)), bits16(dq_ref))
+
+
 def test_weight_crossquant_through_the_activation_calls(cq):
     """CrossQuant on weights (alpha_W): the activation calls applied to the weight stored
     output-channel-major; alpha_W = 1 reproduces per-channel quantization (Eq. 2)."""
