@@ -188,6 +188,32 @@ int crossquant_w8a8_linear(const int8_t *qx, const float *row_scale, const int8_
                            int64_t ldy, int32_t *acc_debug, void *stream);
 
 /*
+ * A4W4 linear layer on the FP6 matrix instruction (the W4A4 setting of the paper's accuracy
+ * tables).  gfx950 multiplies 6-bit floats at twice the INT8 rate and every INT4 code in [-7, 7] is
+ * exact in FP6 E2M3; with binary32 accumulation the dot product is exact for I <= 2^18, so
+ *   acc_ik = sum_j qx_ij * qw_kj ;  Y_ik = fl16(fl32(fl32(float(acc_ik) * row_scale_i) * w_scale_k))
+ * equals the integer path (crossquant_unpack_int4 + crossquant_w8a8_linear) bit for bit.
+ *
+ * crossquant_pack_fp6 rewrites codes into the operand format: fragments of 32 rows x 64 columns,
+ *   1536 bytes each, ordered [ceil(R/32)][K/64]; inside a fragment 3 planes x 64 lanes x 8 bytes,
+ *   lane l = row (l & 31), columns [32 (l >> 5), +32), element j of the lane in bits [6j, 6j+6) of
+ *   its 192-bit little-endian stream, plane p = bits [64p, 64p+64).  Rows past R are zero.
+ *   codes: src_format 8 = int8 [R][K] (e.g. qw of crossquant_weight_quantize with bits = 4),
+ *          src_format 4 = packed nibbles [R][K/2] (crossquant_quantize with bits = 4);
+ *          values outside [-7, 7] are clamped.  K % 128 == 0 (else CQ_ERR_UNSUPPORTED).
+ *   packed: out, crossquant_fp6_packed_bytes(R, K) bytes (-1 for invalid sizes), 16-byte aligned.
+ * crossquant_w4a4_linear: qx_fp6 / qw_fp6 are the packed activations (R = T, K = I) and weights
+ *   (R = O, K = I).  Y, acc_debug, row_scale, w_scale as in crossquant_w8a8_linear.  Requires
+ *   I % 128 == 0, O % 8 == 0, ldy % 8 == 0 and 16-byte aligned pointers, else CQ_ERR_UNSUPPORTED
+ *   (the caller then takes the integer path); I <= 2^18.
+ */
+int64_t crossquant_fp6_packed_bytes(int64_t R, int64_t K);
+int crossquant_pack_fp6(const void *codes, int src_format, int64_t R, int64_t K, void *packed, void *stream);
+int crossquant_w4a4_linear(const void *qx_fp6, const float *row_scale, const void *qw_fp6,
+                           const float *w_scale, int64_t T, int64_t I, int64_t O, void *Y, int64_t ldy,
+                           int32_t *acc_debug, void *stream);
+
+/*
  * Roofline calibration, not part of the method: kernels that do nothing but stream, so that a
  * benchmark can state what this device sustains next to the published peaks: a plain
  * 16-byte-per-lane read, a copy, and an MFMA-only loop.

@@ -31,6 +31,10 @@ lib.crossquant_quantize_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _
 lib.crossquant_calib_read.argtypes = [_vp, _i64, _vp, _vp]
 lib.crossquant_calib_copy.argtypes = [_vp, _vp, _i64, _vp]
 lib.crossquant_calib_mfma_i8.argtypes = [_int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
+lib.crossquant_fp6_packed_bytes.argtypes = [_i64, _i64]
+lib.crossquant_fp6_packed_bytes.restype = ctypes.c_int64
+lib.crossquant_pack_fp6.argtypes = [_vp, _int, _i64, _i64, _vp, _vp]
+lib.crossquant_w4a4_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]
@@ -38,7 +42,8 @@ lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp,
 lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
 for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_absmax_quantize", "crossquant_absmax_batched",
-           "crossquant_quantize_batched", "crossquant_calib_read", "crossquant_calib_copy", "crossquant_calib_mfma_i8", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
+           "crossquant_quantize_batched", "crossquant_calib_read", "crossquant_calib_copy", "crossquant_calib_mfma_i8", "crossquant_pack_fp6",
+           "crossquant_w4a4_linear", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
            "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "crossquant_w8a8_linear",
            "crossquant_version"):
     getattr(lib, _n).restype = _int
@@ -219,6 +224,50 @@ def crossquant_quantize_batched(X: torch.Tensor, t: torch.Tensor, c: torch.Tenso
                                            float(alpha), int(bits), _ptr(codes), _ptr(xhat), row_scale.data_ptr(),
                                            col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
     return codes, xhat, row_scale, col_scale, zero_count
+
+
+def crossquant_pack_fp6(codes: torch.Tensor, *, packed: torch.Tensor = None) -> torch.Tensor:
+    """INT4 codes -> FP6 fragments for crossquant_w4a4_linear.  codes: int8 [R][K] (values in
+    [-7, 7]) or uint8 packed nibbles [R][K/2]; returns a uint8 tensor of the packed size."""
+    if not codes.is_cuda or codes.dim() != 2 or not codes.is_contiguous():
+        raise ValueError("codes must be a contiguous 2-D GPU tensor")
+    if codes.dtype == torch.int8:
+        fmt, (R, K) = 8, codes.shape
+    elif codes.dtype == torch.uint8:
+        fmt, R, K = 4, codes.shape[0], codes.shape[1] * 2
+    else:
+        raise TypeError("codes must be int8 (one code per byte) or uint8 (packed nibbles)")
+    n = int(lib.crossquant_fp6_packed_bytes(R, K))
+    if n < 0:
+        raise CrossQuantError(-6)
+    if packed is None:
+        packed = torch.empty(n, dtype=torch.uint8, device=codes.device)
+    elif packed.dtype != torch.uint8 or packed.numel() != n or not packed.is_contiguous():
+        raise ValueError("packed must be a contiguous uint8 tensor of %d bytes" % n)
+    _check(lib.crossquant_pack_fp6(codes.data_ptr(), fmt, R, K, packed.data_ptr(), _stream(codes)))
+    return packed
+
+
+def crossquant_w4a4_linear(qx_fp6: torch.Tensor, row_scale: torch.Tensor, qw_fp6: torch.Tensor, w_scale: torch.Tensor,
+                           T: int, I: int, O: int, *, Y: torch.Tensor = None, acc_debug: torch.Tensor = None,
+                           want_acc: bool = False):
+    """A4W4 linear layer on FP6-packed INT4 codes (exact).  Returns (Y, acc_or_None)."""
+    for ten, name in ((qx_fp6, "qx_fp6"), (qw_fp6, "qw_fp6")):
+        if not ten.is_cuda or ten.dtype != torch.uint8 or not ten.is_contiguous():
+            raise ValueError("%s must be a contiguous uint8 GPU tensor from crossquant_pack_fp6" % name)
+    if qx_fp6.numel() != lib.crossquant_fp6_packed_bytes(T, I) or qw_fp6.numel() != lib.crossquant_fp6_packed_bytes(O, I):
+        raise ValueError("packed operand sizes do not match T, I, O")
+    _req(row_scale, torch.float32, "row_scale", 1)
+    _req(w_scale, torch.float32, "w_scale", 1)
+    if row_scale.numel() != T or w_scale.numel() != O:
+        raise ValueError("shape mismatch")
+    if Y is None:
+        Y = torch.empty((T, O), dtype=torch.float16, device=qx_fp6.device)
+    if acc_debug is None and want_acc:
+        acc_debug = torch.empty((T, O), dtype=torch.int32, device=qx_fp6.device)
+    _check(lib.crossquant_w4a4_linear(qx_fp6.data_ptr(), row_scale.data_ptr(), qw_fp6.data_ptr(), w_scale.data_ptr(),
+                                      T, I, O, Y.data_ptr(), Y.stride(0), _ptr(acc_debug), _stream(qx_fp6)))
+    return Y, acc_debug
 
 
 def crossquant_calib_read(src: torch.Tensor) -> None:

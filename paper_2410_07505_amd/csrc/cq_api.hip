@@ -200,6 +200,36 @@ int crossquant_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_
                                            static_cast<hipStream_t>(stream)));
 }
 
+int64_t crossquant_fp6_packed_bytes(int64_t R, int64_t K) {
+    if (!dim_ok(R) || !dim_ok(K) || K % 128 != 0) return -1;
+    return cq::fp6_packed_bytes(R, K);
+}
+
+int crossquant_pack_fp6(const void* codes, int src_format, int64_t R, int64_t K, void* packed, void* stream) {
+    if (!codes || !packed) return CQ_ERR_NULL;
+    if (!dim_ok(R) || !dim_ok(K) || R * K > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
+    if (src_format != 8 && src_format != 4) return CQ_ERR_BITS;
+    if (K % 128 != 0) return CQ_ERR_UNSUPPORTED;
+    if (!aligned(codes, 16) || !aligned(packed, 16)) return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_pack_fp6(codes, src_format, (int)R, (int)K, packed, static_cast<hipStream_t>(stream)));
+}
+
+int crossquant_w4a4_linear(const void* qx_fp6, const float* row_scale, const void* qw_fp6, const float* w_scale,
+                           int64_t T, int64_t I, int64_t O, void* Y, int64_t ldy, int32_t* acc_debug, void* stream) {
+    if (!qx_fp6 || !row_scale || !qw_fp6 || !w_scale || !Y) return CQ_ERR_NULL;
+    if (!dim_ok(T) || !dim_ok(I) || !dim_ok(O) || ldy < O || ldy > CQ_MAX_DIM) return CQ_ERR_SHAPE;
+    if (T * O > CQ_MAX_ELEMS || T * ldy > CQ_MAX_ELEMS || T * I > CQ_MAX_ELEMS || I * O > CQ_MAX_ELEMS)
+        return CQ_ERR_SHAPE;
+    if (I > (1 << 18)) return CQ_ERR_SHAPE;                 // 49 * I must stay below 2^24 (exact in binary32)
+    if (!aligned(row_scale, 4) || !aligned(w_scale, 4) || !aligned(Y, 2) || !aligned(acc_debug, 4)) return CQ_ERR_ALIGN;
+    if (I % 128 != 0 || O % 8 != 0 || ldy % 8 != 0 || !aligned(qx_fp6, 16) || !aligned(qw_fp6, 16) ||
+        !aligned(Y, 16) || !aligned(w_scale, 16) || !aligned(acc_debug, 16))
+        return CQ_ERR_UNSUPPORTED;
+    return from_hip(cq::launch_w4a4_linear(qx_fp6, row_scale, qw_fp6, w_scale, (int)T, (int)I, (int)O,
+                                           static_cast<uint16_t*>(Y), ldy, acc_debug,
+                                           static_cast<hipStream_t>(stream)));
+}
+
 int crossquant_calib_read(const void* src, int64_t bytes, unsigned long long* sink, void* stream) {
     if (!src) return CQ_ERR_NULL;
     if (bytes < 16 || bytes % 16 != 0) return CQ_ERR_SHAPE;

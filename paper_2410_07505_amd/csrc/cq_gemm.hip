@@ -23,20 +23,15 @@
 //     share A rows and B columns.
 #include <type_traits>
 
-#include "cq_kernels.h"
+#include "cq_gemm_common.h"
 
 namespace cq {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int BK = 128;
 constexpr int kThreads = 256;
 constexpr int kStageBytes = (BM + BN) * BK;       // 64 KiB
 constexpr int kLdsBytes = 2 * kStageBytes;         // 128 KiB
-constexpr int kXcds = 8;      // block ids are dealt round-robin to this many L2 domains
-constexpr int kGroupM = 4;    // tile-rows walked together (8, 16 and 1 measured slower)
 
 __device__ __forceinline__ int swz(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) * 16; }
 
@@ -189,13 +184,6 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
 //   wait for the next tile, barrier ; read slab0 of the next tile | mfma slab3.
 // ---------------------------------------------------------------------------------------------
 
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// s_waitcnt immediate for gfx9-family encodings: vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no
-// wait), lgkmcnt 11:8 (15 = no wait)
-constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
-
 // a_off / b_off: byte offset of this lane's row and swizzled chunk for slab 0; slab ks flips the
 // chunk's bits 1-2, i.e. XORs the byte offset with ks * 32
 template <int NI>
@@ -217,68 +205,6 @@ __device__ __forceinline__ void mfma_slab(v16i (&acc)[4][NI], const v4i (&af)[4]
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
             acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[ni], af[mi], acc[mi][ni], 0, 0, 0);
-}
-
-// Epilogue shared by the fast-path kernels.  Lane l holds token t = l & 31 of each 32-token block
-// and, for register group rg = r / 4, the 4 consecutive channels 8*rg + 4*(l >> 5) + {0..3} of
-// each 32-channel block.  Scaled binary16 results go through LDS (free once the K loop has ended
-// on a barrier with no reads outstanding) so that every global store is a full 16 bytes per lane
-// and a wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
-template <int WTN, int NI>
-__device__ __forceinline__ void epilogue_store(v16i (&acc)[4][NI], int8_t* lds, const float* __restrict__ row_scale,
-                                               const float* __restrict__ w_scale, uint16_t* __restrict__ Y,
-                                               int64_t ldy, int32_t* __restrict__ acc_debug, int T, int O, int row0,
-                                               int col0, int lane, int wave) {
-    const int frag_half = lane >> 5;
-    constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
-    int8_t* stage = lds + wave * (128 * kRowPitch);      // this wave's 128 x WTN staging area
-    const int t_lane = lane & 31;
-    float a_t[4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[min(row0 + mi * 32 + t_lane, T - 1)];   // rows >= T are never stored
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
-            // O % 8 == 0 on this path: a group of 4 channels exists or not as a whole
-            const float4 s4 = (col0 + o_loc < O) ? *reinterpret_cast<const float4*>(w_scale + col0 + o_loc)
-                                                 : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                uint32_t h[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float y = (float)acc[mi][ni][rg * 4 + j] * a_t[mi];
-                    y = rounded_f32(y * sv[j]);
-                    h[j] = f2h(y);
-                }
-                *reinterpret_cast<uint2*>(stage + (mi * 32 + t_lane) * kRowPitch + o_loc * 2) =
-                    make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                const int row = row0 + mi * 32 + t_lane;
-                if (acc_debug && row < T && col0 + o_loc < O) {
-                    int4 v = make_int4(acc[mi][ni][rg * 4 + 0], acc[mi][ni][rg * 4 + 1], acc[mi][ni][rg * 4 + 2],
-                                       acc[mi][ni][rg * 4 + 3]);
-                    *reinterpret_cast<int4*>(acc_debug + (int64_t)row * O + col0 + o_loc) = v;
-                }
-            }
-        }
-    }
-    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
-    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 16)
-    constexpr int kRowsPerInst = 64 / kLanesPerRow;
-    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
-#pragma unroll
-    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
-        const int trow = i * kRowsPerInst + rsub;
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
-        if (row0 + trow < T && col0 + piece * 8 < O) {
-            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
-            *reinterpret_cast<uint4*>(dst) = v;
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -309,16 +235,8 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     constexpr int WN = 4, WTN = 64, NI = 2;
     extern __shared__ __align__(16) int8_t lds[];
 
-    const int total = tiles_m * tiles_n;
-    const int per_xcd = (total + kXcds - 1) / kXcds;
-    const int L = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (L >= total) return;
-    const int group_sz = kGroupM * tiles_n;
-    const int g = L / group_sz;
-    const int gm = min(kGroupM, tiles_m - g * kGroupM);
-    const int in_g = L - g * group_sz;
-    const int tile_m = g * kGroupM + in_g % gm;
-    const int tile_n = in_g / gm;
+    int tile_m, tile_n;
+    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n)) return;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x;
@@ -451,7 +369,7 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     }
     k_step(kt, no{}, no{});
 
-    epilogue_store<WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
+    epilogue_store<v16i, WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
                             lane, wave);
 }
 

@@ -1,0 +1,105 @@
+// Pieces shared by the matrix-core GEMM kernels (INT8 codes, and INT4 codes carried as FP6).
+#pragma once
+#include "cq_kernels.h"
+
+namespace cq {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+constexpr int BM = 256, BN = 256;   // block tile (tokens x output channels)
+constexpr int kXcds = 8;            // block ids are dealt round-robin to this many L2 domains
+constexpr int kGroupM = 4;          // tile-rows walked together (8, 16 and 1 measured slower)
+
+// s_waitcnt immediate for gfx9-family encodings: vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no
+// wait), lgkmcnt 11:8 (15 = no wait)
+constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
+
+// Block id -> output tile.  Consecutive block ids land on different XCDs, so ids are first
+// de-interleaved by XCD (each XCD gets a contiguous range of tiles, hence its own L2 sees a compact
+// patch), then walked in groups of kGroupM tile-rows so that concurrently resident tiles share A
+// rows and B columns.  Returns false for the padding blocks of the last XCD range.
+__device__ __forceinline__ bool tile_of_block(int block, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    const int L = (block % kXcds) * per_xcd + block / kXcds;
+    if (L >= total) return false;
+    const int group_sz = kGroupM * tiles_n;
+    const int g = L / group_sz;
+    const int gm = min(kGroupM, tiles_m - g * kGroupM);
+    const int in_g = L - g * group_sz;
+    tile_m = g * kGroupM + in_g % gm;
+    tile_n = in_g / gm;
+    return true;
+}
+
+// Epilogue shared by the fast-path kernels.  Lane l holds token t = l & 31 of each 32-token block
+// and, for register group rg = r / 4, the 4 consecutive channels 8*rg + 4*(l >> 5) + {0..3} of
+// each 32-channel block.  Scaled binary16 results go through LDS (free once the K loop has ended
+// on a barrier with no reads outstanding) so that every global store is a full 16 bytes per lane
+// and a wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
+template <typename ACC, int WTN, int NI>
+__device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, const float* __restrict__ row_scale,
+                                               const float* __restrict__ w_scale, uint16_t* __restrict__ Y,
+                                               int64_t ldy, int32_t* __restrict__ acc_debug, int T, int O, int row0,
+                                               int col0, int lane, int wave) {
+    const int frag_half = lane >> 5;
+    constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
+    int8_t* stage = lds + wave * (128 * kRowPitch);      // this wave's 128 x WTN staging area
+    const int t_lane = lane & 31;
+    float a_t[4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[min(row0 + mi * 32 + t_lane, T - 1)];   // rows >= T are never stored
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
+            // O % 8 == 0 on this path: a group of 4 channels exists or not as a whole
+            const float4 s4 = (col0 + o_loc < O) ? *reinterpret_cast<const float4*>(w_scale + col0 + o_loc)
+                                                 : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                uint32_t h[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float y = (float)acc[mi][ni][rg * 4 + j] * a_t[mi];
+                    y = rounded_f32(y * sv[j]);
+                    h[j] = f2h(y);
+                }
+                *reinterpret_cast<uint2*>(stage + (mi * 32 + t_lane) * kRowPitch + o_loc * 2) =
+                    make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                const int row = row0 + mi * 32 + t_lane;
+                if (acc_debug && row < T && col0 + o_loc < O) {
+                    int4 v = make_int4((int)acc[mi][ni][rg * 4 + 0], (int)acc[mi][ni][rg * 4 + 1],
+                                       (int)acc[mi][ni][rg * 4 + 2], (int)acc[mi][ni][rg * 4 + 3]);
+                    *reinterpret_cast<int4*>(acc_debug + (int64_t)row * O + col0 + o_loc) = v;
+                }
+            }
+        }
+    }
+    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 16)
+    constexpr int kRowsPerInst = 64 / kLanesPerRow;
+    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+#pragma unroll
+    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
+        const int trow = i * kRowsPerInst + rsub;
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
+        if (row0 + trow < T && col0 + piece * 8 < O) {
+            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
+            *reinterpret_cast<uint4*>(dst) = v;
+        }
+    }
+}
+
+}  // namespace
+}  // namespace cq

@@ -1,0 +1,294 @@
+// A4W4 linear layer on the FP6 matrix instruction (the W4A4 rows of the paper's accuracy tables).
+//
+// gfx950 has no INT4 matrix instruction, but v_mfma_f32_32x32x64_f8f6f4 multiplies 6-bit floats at
+// twice the INT8 rate, and every INT4 code q in [-7, 7] is exactly representable in FP6 E2M3
+// (1 sign, 2 exponent, 3 mantissa bits, bias 1: 0, 1, 2, 3, 4, 5, 6, 7 are 0b000000, 0b001000,
+// 0b010000, 0b010100, 0b011000, 0b011010, 0b011100, 0b011110).  Products are integers of at most
+// 49 and the accumulator is binary32, so a dot product over I <= 2^18 channels stays below 2^24
+// and is exact: the result equals the integer GEMM bit for bit, and the scale epilogue is the
+// same sequence of binary32 operations as in the INT8 path.
+//
+// Operand format ("FP6 fragments"), produced by pack_fp6_kernel.  The instruction wants, in lane
+// l, the 32 consecutive K elements [32 (l >> 5), +32) of row (l & 31) as one 192-bit little-endian
+// stream (element j in bits [6j, 6j + 6)).  A matrix of R rows and K columns is therefore stored
+// as [ceil(R/32)][K/64] fragments of 1536 bytes, each fragment as 3 planes x 64 lanes x 8 bytes
+// (plane p holds bits [64p, 64p + 64) of every lane's stream; rows past R are zero).  A fragment
+// is copied to LDS verbatim and a wave picks its operand up with three 8-byte reads per lane,
+// each read 512 contiguous bytes: no bank conflicts, no swizzle, no register shuffling.
+//
+// The kernel is the INT8 ring kernel's schedule with 6-bit operands: 256 x 256 block tile,
+// 8 waves of 128 x 64, K step 128 elements (two fragments along K, 24 KiB per operand), a ring of
+// five LDS slots, waves 0-3 requesting A(kt+2) before the step's barrier and waves 4-7 B(kt+2)
+// after it.  Per K step a wave issues 16 matrix instructions (half the cycles of the INT8 kernel
+// for the same K) against 18 KiB of LDS reads, so this kernel is bound by LDS bandwidth and load
+// issue rather than by the matrix pipe.
+#include <type_traits>
+
+#include "cq_gemm_common.h"
+
+namespace cq {
+namespace {
+
+constexpr int kFragBytes = 1536;                     // 32 rows x 64 elements x 6 bits
+constexpr int kFragPlane = 512;                      // 64 lanes x 8 bytes
+constexpr int kF6Slot = 8 * 2 * kFragBytes;          // 24 KiB: 256 rows x 128 elements
+constexpr int kF6Slots = 5;
+// the ring needs 120 KiB, the epilogue's staging area 8 waves x 128 rows x 136 bytes = 136 KiB
+constexpr int kF6Lds = 8 * 128 * (64 * 2 + 8);
+static_assert(kF6Lds >= kF6Slots * kF6Slot && kF6Lds <= 160 * 1024, "LDS budget of a gfx950 CU");
+
+// ---- packing ---------------------------------------------------------------------------------
+// One thread builds one lane's 24 bytes of one fragment.  SRC 8: int8 codes [R][K]; SRC 4: packed
+// two's-complement nibbles [R][K/2], even column in the low nibble.  Codes are clamped to +-7.
+template <int SRC>
+__global__ void pack_fp6_kernel(const uint8_t* __restrict__ src, int R, int K, uint8_t* __restrict__ dst,
+                                int64_t n_slots) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_slots) return;
+    const int lane = (int)(idx & 63);
+    const int64_t frag = idx >> 6;
+    const int KB = K / 64;
+    const int kb = (int)(frag % KB), rb = (int)(frag / KB);
+    const int row = rb * 32 + (lane & 31);
+    const int k0 = kb * 64 + 32 * (lane >> 5);
+    uint32_t w[6] = {0u, 0u, 0u, 0u, 0u, 0u};
+    if (row < R) {
+        int8_t q[32];
+        if (SRC == 8) {
+            const uint4* p = reinterpret_cast<const uint4*>(src + (int64_t)row * K + k0);
+            const uint4 v0 = p[0], v1 = p[1];
+            const uint32_t u[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+            for (int j = 0; j < 32; ++j) q[j] = (int8_t)((u[j >> 2] >> (8 * (j & 3))) & 0xFFu);
+        } else {
+            const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)row * (K / 2) + k0 / 2);
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int nib = (int)((u[j >> 3] >> (4 * (j & 7))) & 0xFu);
+                q[j] = (int8_t)((nib ^ 8) - 8);                     // sign-extend 4 bits
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const int v = q[j];
+            const int mag = min(v < 0 ? -v : v, 7);
+            // E2M3 patterns of 0..7, one per byte
+            const uint32_t e = (uint32_t)((0x1E1C1A1814100800ull >> (8 * mag)) & 0xFFu) | (v < 0 ? 32u : 0u);
+            const int bit = 6 * j;
+            w[bit >> 5] |= e << (bit & 31);
+            if ((bit & 31) > 26) w[(bit >> 5) + 1] |= e >> (32 - (bit & 31));
+        }
+    }
+    uint8_t* f = dst + frag * kFragBytes + lane * 8;
+#pragma unroll
+    for (int p = 0; p < 3; ++p) *reinterpret_cast<uint2*>(f + p * kFragPlane) = make_uint2(w[2 * p], w[2 * p + 1]);
+}
+
+// ---- fragments: LDS -> registers ---------------------------------------------------------------
+struct frag6 {
+    uint2 p[3];
+};
+
+__device__ __forceinline__ v8i as_operand(const frag6& f) {
+    v8i v;
+    v[0] = (int)f.p[0].x; v[1] = (int)f.p[0].y;
+    v[2] = (int)f.p[1].x; v[3] = (int)f.p[1].y;
+    v[4] = (int)f.p[2].x; v[5] = (int)f.p[2].y;
+    v[6] = 0; v[7] = 0;
+    return v;
+}
+
+// slot: one operand's 256 rows x 128 elements as [row block 8][k fragment 2][plane 3][lane 64][8 B]
+__device__ __forceinline__ frag6 read_frag(const int8_t* slot, int row_block, int kf, int lane) {
+    const int8_t* f = slot + (row_block * 2 + kf) * kFragBytes + lane * 8;
+    frag6 r;
+#pragma unroll
+    for (int p = 0; p < 3; ++p) r.p[p] = *reinterpret_cast<const uint2*>(f + p * kFragPlane);
+    return r;
+}
+
+template <int NI>
+__device__ __forceinline__ void load_frags6(frag6 (&af)[4], frag6 (&bf)[NI], const int8_t* As, const int8_t* Bs,
+                                            int a_rb, int b_rb, int kf, int lane) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) af[mi] = read_frag(As, a_rb + mi, kf, lane);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) bf[ni] = read_frag(Bs, b_rb + ni, kf, lane);
+}
+
+// Weight fragment first, as in the INT8 kernel: the accumulator tile comes out transposed (lane =
+// token, 4 consecutive channels per register group), which is what the shared epilogue expects.
+// Format 2 = FP6 E2M3 for both operands; scale operands 0 select the unscaled instruction.
+template <int NI>
+__device__ __forceinline__ void mfma_slab6(v16f (&acc)[4][NI], const frag6 (&af)[4], const frag6 (&bf)[NI]) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(bf[ni]), as_operand(af[mi]),
+                                                                          acc[mi][ni], 2, 2, 0, 0, 0, 0);
+}
+
+__global__ void __launch_bounds__(512)
+gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ row_scale,
+                    const uint8_t* __restrict__ qw6, const float* __restrict__ w_scale, int T, int I, int O,
+                    uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
+                    int tiles_n) {
+    constexpr int WN = 4, WTN = 64, NI = 2;
+    extern __shared__ __align__(16) int8_t lds[];
+
+    int tile_m, tile_n;
+    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n)) return;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int KB = I / 64;                        // fragments along K
+    const int nk = I / 128;                       // K steps
+    const bool b_loader = wave >= 4;              // waves 4-7 load B, waves 0-3 load A
+
+    // ---- loader: a slot is 24 instructions of 1 KiB; loader wave lw issues numbers 6 lw .. 6 lw + 5.
+    // Instruction n copies bytes [1024 (n % 3), +1024) of the two consecutive fragments (3072 bytes)
+    // of row block n / 3.  Row blocks past the end of a ragged operand are replaced by the last
+    // valid one: what lands there only feeds outputs the epilogue drops.
+    const int lw = wave & 3;
+    const uint8_t* gsrc[6];
+    {
+        const uint8_t* base = b_loader ? qw6 : qx6;
+        const int first = (b_loader ? n0 : m0) / 32;
+        const int last = ((b_loader ? O : T) + 31) / 32 - 1;
+#pragma unroll
+        for (int ii = 0; ii < 6; ++ii) {
+            const int n = 6 * lw + ii;
+            const int rb = min(first + n / 3, last);
+            gsrc[ii] = base + (int64_t)rb * KB * kFragBytes + (n % 3) * 1024 + lane * 16;
+        }
+    }
+    auto issue_half = [&](int kt, int slot) {
+        int8_t* dst = lds + slot * kF6Slot + lw * (6 * 1024);
+        const int64_t koff = (int64_t)kt * (2 * kFragBytes);
+#pragma unroll
+        for (int ii = 0; ii < 6; ++ii)
+            __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii] + koff), (lptr_t)(dst + ii * 1024), 16, 0, 0);
+    };
+
+    const int a_rb = wm * 4, b_rb = wn * 2;       // first row block of this wave inside the A / B slot
+
+    v16f acc[4][NI];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
+
+    // prologue: A0 A1 (waves 0-3) / B0 B1 (waves 4-7); half tile n -> slot n % 5
+    issue_half(0, b_loader ? 1 : 0);
+    if (nk > 1) issue_half(1, b_loader ? 3 : 2);
+    if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 15));
+    else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    __syncthreads();
+
+    int sa = 0, sb = 1;
+    auto adv = [](int v) { v += 2; return v >= kF6Slots ? v - kF6Slots : v; };
+
+    frag6 af0[4], bf0[NI], af1[4], bf1[NI];
+    load_frags6<NI>(af0, bf0, lds + sa * kF6Slot, lds + sb * kF6Slot, a_rb, b_rb, 0, lane);
+
+    constexpr int NMF = 4 * NI;                   // matrix instructions per slab
+    constexpr int NRD = 3 * (4 + NI);             // 8-byte LDS reads per slab
+    auto interleave_reads = [&]() {
+#pragma unroll
+        for (int i = 0; i < NMF; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value;        // kt + 2 < nk
+        constexpr bool PREFETCH = decltype(prefetch_c)::value;  // kt + 1 < nk
+        const int8_t* As = lds + sa * kF6Slot;
+        const int8_t* Bs = lds + sb * kF6Slot;
+        const int na = adv(sa), nb = adv(sb);                   // slots of tile kt+1
+        load_frags6<NI>(af1, bf1, As, Bs, a_rb, b_rb, 1, lane);
+        mfma_slab6<NI>(acc, af0, bf0);
+        interleave_reads();
+        // A loaders: A(kt+2) goes to slot adv(na), whose previous tenant B(kt-1) was released at the
+        // previous barrier; then tile kt+1's A (requested a step ago) must have landed: at most the
+        // 6 requests just made may still be in flight.  lgkmcnt(0): this wave's reads of tile kt are done.
+        if (!b_loader) {
+            if (ISSUE) {
+                issue_half(kt + 2, adv(na));
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 0));
+            } else {
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+            }
+        } else {
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));      // B(kt+1), requested after the last barrier
+        }
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        // B loaders: B(kt+2) goes to tile kt's A slot, which nobody reads any more
+        if (b_loader && ISSUE) issue_half(kt + 2, sa);
+        __builtin_amdgcn_sched_barrier(0);
+        if (PREFETCH) load_frags6<NI>(af0, bf0, lds + na * kF6Slot, lds + nb * kF6Slot, a_rb, b_rb, 0, lane);
+        mfma_slab6<NI>(acc, af1, bf1);
+        if (PREFETCH) {
+            interleave_reads();
+        } else {
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        sa = na;
+        sb = nb;
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) k_step(kt, yes{}, yes{});
+    if (kt + 1 < nk) {
+        k_step(kt, no{}, yes{});
+        ++kt;
+    }
+    k_step(kt, no{}, no{});
+
+    // every wave's fragments are in registers and all loads have landed: the ring can be reused
+    __syncthreads();
+    epilogue_store<v16f, WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
+                                  lane, wave);
+}
+
+}  // namespace
+
+int64_t fp6_packed_bytes(int64_t R, int64_t K) { return ((R + 31) / 32) * (K / 64) * (int64_t)kFragBytes; }
+
+hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void* packed, hipStream_t stream) {
+    const int64_t n_slots = ((int64_t)(R + 31) / 32) * (K / 64) * 64;
+    const dim3 grid((unsigned)((n_slots + 255) / 256)), block(256);
+    if (src_format == 8)
+        pack_fp6_kernel<8><<<grid, block, 0, stream>>>(static_cast<const uint8_t*>(codes), R, K,
+                                                       static_cast<uint8_t*>(packed), n_slots);
+    else
+        pack_fp6_kernel<4><<<grid, block, 0, stream>>>(static_cast<const uint8_t*>(codes), R, K,
+                                                       static_cast<uint8_t*>(packed), n_slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const void* qw6, const float* w_scale, int T,
+                              int I, int O, uint16_t* Y, int64_t ldy, int32_t* acc_debug, hipStream_t stream) {
+    const int tiles_m = (T + BM - 1) / BM, tiles_n = (O + BN - 1) / BN;
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f6_ring_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kF6Lds);
+    if (e != hipSuccess) return e;
+    gemm_f6_ring_kernel<<<dim3((unsigned)(per_xcd * kXcds)), dim3(512), kF6Lds, stream>>>(
+        static_cast<const uint8_t*>(qx6), row_scale, static_cast<const uint8_t*>(qw6), w_scale, T, I, O, Y, ldy,
+        acc_debug, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace cq

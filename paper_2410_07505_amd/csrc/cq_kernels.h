@@ -62,6 +62,12 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                               const float* w_scale, int T, int I, int O, uint16_t* Y, int64_t ldy,
                               int32_t* acc_debug, hipStream_t stream);
 
+// INT4 codes as FP6 fragments (32 rows x 64 columns per 1536-byte fragment) and the A4W4 linear layer on them.
+int64_t fp6_packed_bytes(int64_t R, int64_t K);
+hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void* packed, hipStream_t stream);
+hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const void* qw6, const float* w_scale, int T,
+                              int I, int O, uint16_t* Y, int64_t ldy, int32_t* acc_debug, hipStream_t stream);
+
 // Roofline calibration (plain read, plain copy, MFMA-only loop); bytes is a multiple of 16.
 hipError_t launch_calib_read(const void* src, int64_t bytes, unsigned long long* sink, hipStream_t stream);
 hipError_t launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream);

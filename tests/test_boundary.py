@@ -165,6 +165,25 @@ def test_unpack_int4_argument_errors(cq):
     assert f(P, 0, 8, P, None) == -2 and f(P, 4, 7, P, None) == -2
 
 
+def test_fp6_argument_errors(cq):
+    n = cq.raw.crossquant_fp6_packed_bytes
+    assert n(32, 128) == 32 * 128 * 6 // 8 and n(33, 128) == 64 * 128 * 6 // 8 and n(300, 256) == 320 * 256 * 6 // 8
+    assert n(0, 128) == -1 and n(32, 64) == -1
+    f = cq.raw.crossquant_pack_fp6
+    assert f(0, 8, 32, 128, P, None) == -1 and f(P, 8, 32, 128, 0, None) == -1
+    assert f(P, 8, 0, 128, P, None) == -2 and f(P, 6, 32, 128, P, None) == -3
+    assert f(P, 8, 32, 100, P, None) == -6 and f(P + 4, 8, 32, 128, P, None) == -5
+    g = cq.raw.crossquant_w4a4_linear
+
+    def call(qx=P, rs=P, qw=P, ws=P, T=4, I=128, O=8, Y=P, ldy=8, acc=None):
+        return g(qx, rs, qw, ws, T, I, O, Y, ldy, acc, None)
+
+    assert call(qx=0) == -1 and call(Y=0) == -1 and call(ws=0) == -1
+    assert call(T=0) == -2 and call(ldy=4) == -2 and call(I=1 << 19) == -2
+    assert call(Y=P + 1) == -5
+    assert call(I=64) == -6 and call(O=12, ldy=16) == -6 and call(ldy=12) == -6 and call(qx=P + 8) == -6
+
+
 def test_calibration_argument_errors(cq):
     r, c, m = cq.raw.crossquant_calib_read, cq.raw.crossquant_calib_copy, cq.raw.crossquant_calib_mfma_i8
     assert r(0, 1024, None, None) == -1 and r(P, 0, None, None) == -2 and r(P, 1000, None, None) == -2

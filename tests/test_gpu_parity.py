@@ -853,3 +853,110 @@ def test_random_shapes_linear(cq):
         Y, acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), want_acc=True)
         assert np.array_equal(host(acc), acc_ref)
         assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+
+
+# ----------------------------------------------------------------------------- A4W4 on the FP6 matrix instruction
+E2M3 = np.array([0, 8, 16, 20, 24, 26, 28, 30], np.uint8)      # bit patterns of 0..7 (1 sign, 2 exponent, 3 mantissa)
+
+
+def fp6_fragments(codes):
+    """The operand format written out with numpy: [ceil(R/32)][K/64] fragments, each 3 planes x 64
+    lanes x 8 bytes; lane l = row l & 31, columns [32 (l >> 5), +32), element j in bits [6j, 6j+6)."""
+    R, K = codes.shape
+    RB, KB = (R + 31) // 32, K // 64
+    padded = np.zeros((RB * 32, K), np.int64)
+    padded[:R] = np.clip(codes.astype(np.int64), -7, 7)
+    pat = E2M3[np.abs(padded)].astype(np.uint64) | np.where(padded < 0, 32, 0).astype(np.uint64)
+    lanes = pat.reshape(RB, 32, KB, 2, 32).transpose(0, 2, 3, 1, 4).reshape(RB, KB, 64, 32)   # [rb][kb][lane][j]
+    out = np.zeros((RB, KB, 3, 64), np.uint64)
+    for j in range(32):
+        bit = 6 * j
+        p, sh = bit // 64, bit % 64
+        out[:, :, p, :] |= (lanes[..., j] << np.uint64(sh)) & np.uint64(0xFFFFFFFFFFFFFFFF)
+        if sh > 58:
+            out[:, :, p + 1, :] |= lanes[..., j] >> np.uint64(64 - sh)
+    return out.reshape(-1).view(np.uint8)
+
+
+def int4_codes(R, K, seed):
+    return np.random.default_rng(seed).integers(-7, 8, (R, K)).astype(np.int8)
+
+
+def nibbles(codes):
+    c = codes.astype(np.uint8) & 0xF
+    return (c[:, 0::2] | (c[:, 1::2] << 4)).astype(np.uint8)
+
+
+@pytest.mark.parametrize("R,K", [(1, 128), (32, 128), (45, 256), (300, 384), (64, 1024)])
+def test_fp6_packing(cq, R, K):
+    codes = int4_codes(R, K, seed=R + K)
+    want = fp6_fragments(codes)
+    got8 = host(cq.crossquant_pack_fp6(gpu(codes)))
+    got4 = host(cq.crossquant_pack_fp6(gpu(nibbles(codes))))
+    assert got8.shape == want.shape and np.array_equal(got8, want)
+    assert np.array_equal(got4, want)
+    # codes outside the INT4 range saturate
+    wide = (codes.astype(np.int16) * 3).clip(-128, 127).astype(np.int8)
+    assert np.array_equal(host(cq.crossquant_pack_fp6(gpu(wide))), fp6_fragments(wide))
+
+
+@pytest.mark.parametrize("T,I,O", [(1, 128, 8), (32, 128, 32), (256, 256, 256), (300, 256, 520), (257, 384, 264),
+                                   (513, 1024, 1000), (700, 512, 776), (64, 2048, 128)])
+def test_w4a4_linear_fp6(cq, T, I, O):
+    say("w4a4 fp6 T=%d I=%d O=%d" % (T, I, O))
+    qx, qw = int4_codes(T, I, seed=T), int4_codes(O, I, seed=O + 7)
+    rng = np.random.default_rng(T + O)
+    a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+    s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    px, pw = cq.crossquant_pack_fp6(gpu(nibbles(qx))), cq.crossquant_pack_fp6(gpu(qw))
+    Y, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, want_acc=True)
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    Y8, _ = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s))          # the integer path agrees
+    assert np.array_equal(bits16(host(Y8)), bits16(host(Y)))
+
+
+def test_w4a4_linear_fp6_extreme_accumulators_and_guarded_output(cq):
+    """All codes at +-7 over 4096 channels (|acc| = 49 * 4096, exact in binary32), written into a
+    window of a larger buffer whose surroundings must stay untouched."""
+    import torch
+    T, I, O = 70, 4096, 72
+    qx = np.full((T, I), 7, np.int8)
+    qx[::2] = -7
+    qw = np.full((O, I), -7, np.int8)
+    qw[::3] = 7
+    a = np.full(T, 0.01, np.float32)
+    s = np.full(O, 0.001, np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    assert np.abs(acc_ref).max() == 49 * I
+    buf = torch.full((T + 5, 96), 7.0, dtype=torch.float16, device="cuda")
+    px, pw = cq.crossquant_pack_fp6(gpu(qx)), cq.crossquant_pack_fp6(gpu(qw))
+    _, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, Y=buf[:T, :O], want_acc=True)
+    out = host(buf)
+    assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(out[:T, :O]), bits16(Y_ref))
+    assert np.all(out[:T, O:] == 7.0) and np.all(out[T:] == 7.0)
+
+
+def test_end_to_end_a4w4_fp6_config(cq):
+    """The low-bit configuration end to end with the FP6 linear layer: CrossQuant INT4 activation
+    codes (packed nibbles) and INT4 per-channel weights, compared with the oracle on sampled rows
+    and in full with the integer path."""
+    import torch
+    cfg = workloads.CONFIGS["C4"]
+    X, W = workloads.config_activation("C4"), workloads.config_weight("C4")
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, 0.15, 4, want_xhat=False)
+    qw_ref, s_ref = oracle.weight_quantize(W, ref["b"], 4)
+    Xg, Wg = gpu(X), gpu(W)
+    t, c = cq.crossquant_absmax(Xg)
+    packed, _, a, b, _ = cq.crossquant_quantize(Xg, t, c, 0.15, 4, want_xhat=False)
+    qw, s = cq.crossquant_weight_quantize(Wg, b, 4)
+    px, pw = cq.crossquant_pack_fp6(packed), cq.crossquant_pack_fp6(qw)
+    Y, acc = cq.crossquant_w4a4_linear(px, a, pw, s, cfg.T, cfg.I, cfg.O, want_acc=True)
+    Y8, acc8 = cq.crossquant_w8a8_linear(cq.crossquant_unpack_int4(packed), a, qw, s, want_acc=True)
+    assert torch.equal(acc, acc8) and torch.equal(Y.view(torch.int16), Y8.view(torch.int16))
+    rows = np.array([0, 255, 256, 1777, cfg.T - 1])
+    Yr, accr = oracle.w8a8_linear(oracle.unpack_int4(ref["codes"])[rows], ref["a"][rows], qw_ref, s_ref)
+    assert np.array_equal(host(acc[torch.from_numpy(rows).cuda()]), accr)
+    assert np.array_equal(bits16(host(Y[torch.from_numpy(rows).cuda()])), bits16(Yr))
