@@ -195,9 +195,10 @@ int crossquant_w8a8_linear(const int8_t *qx, const float *row_scale, const int8_
  * equals the integer path (crossquant_unpack_int4 + crossquant_w8a8_linear) bit for bit.
  *
  * crossquant_pack_fp6 rewrites codes into the operand format: fragments of 32 rows x 64 columns,
- *   1536 bytes each, ordered [ceil(R/32)][K/64]; inside a fragment 3 planes x 64 lanes x 8 bytes,
- *   lane l = row (l & 31), columns [32 (l >> 5), +32), element j of the lane in bits [6j, 6j+6) of
- *   its 192-bit little-endian stream, plane p = bits [64p, 64p+64).  Rows past R are zero.
+ *   1536 bytes each, ordered [ceil(R/32)][K/64].  Lane l = row (l & 31), columns [32 (l >> 5), +32),
+ *   element j of the lane in bits [6j, 6j+6) of its 192-bit little-endian stream; a fragment is 64
+ *   lanes x 16 bytes (bits [0, 128) of each stream) followed by 64 lanes x 8 bytes (bits [128, 192)).
+ *   Rows past R are zero.
  *   codes: src_format 8 = int8 [R][K] (e.g. qw of crossquant_weight_quantize with bits = 4),
  *          src_format 4 = packed nibbles [R][K/2] (crossquant_quantize with bits = 4);
  *          values outside [-7, 7] are clamped.  K % 128 == 0 (else CQ_ERR_UNSUPPORTED).

@@ -11,17 +11,18 @@
 // Operand format ("FP6 fragments"), produced by pack_fp6_kernel.  The instruction wants, in lane
 // l, the 32 consecutive K elements [32 (l >> 5), +32) of row (l & 31) as one 192-bit little-endian
 // stream (element j in bits [6j, 6j + 6)).  A matrix of R rows and K columns is therefore stored
-// as [ceil(R/32)][K/64] fragments of 1536 bytes, each fragment as 3 planes x 64 lanes x 8 bytes
-// (plane p holds bits [64p, 64p + 64) of every lane's stream; rows past R are zero).  A fragment
-// is copied to LDS verbatim and a wave picks its operand up with three 8-byte reads per lane,
-// each read 512 contiguous bytes: no bank conflicts, no swizzle, no register shuffling.
+// as [ceil(R/32)][K/64] fragments of 1536 bytes, each fragment as a 1024-byte plane (64 lanes x
+// 16 bytes: bits [0, 128) of every lane's stream) followed by a 512-byte plane (64 lanes x 8 bytes:
+// bits [128, 192)); rows past R are zero.  A fragment is copied to LDS verbatim and a wave picks
+// its operand up with one 16-byte and one 8-byte read per lane, each a contiguous run across the
+// wave: no bank conflicts, no swizzle, no register shuffling.
 //
-// The kernel is the INT8 ring kernel's schedule with 6-bit operands: 256 x 256 block tile,
-// 8 waves of 128 x 64, K step 128 elements (two fragments along K, 24 KiB per operand), a ring of
-// five LDS slots, waves 0-3 requesting A(kt+2) before the step's barrier and waves 4-7 B(kt+2)
-// after it.  Per K step a wave issues 16 matrix instructions (half the cycles of the INT8 kernel
-// for the same K) against 18 KiB of LDS reads, so this kernel is bound by LDS bandwidth and load
-// issue rather than by the matrix pipe.
+// The kernel follows the INT8 ring kernel's schedule with 6-bit operands: 256 x 256 block tile,
+// 8 waves of 128 x 64, K step 128 elements (two fragments along K, 24 KiB per operand).  The
+// smaller operands leave room for a ring of six LDS slots, i.e. three tiles in flight: requests
+// run two to three steps ahead (described at the kernel).  Per K step a wave issues 16 matrix
+// instructions (half the cycles of the INT8 kernel for the same K) against 18 KiB of LDS reads,
+// so this kernel is bound by operand movement rather than by the matrix pipe.
 #include <type_traits>
 
 #include "cq_gemm_common.h"
@@ -30,12 +31,12 @@ namespace cq {
 namespace {
 
 constexpr int kFragBytes = 1536;                     // 32 rows x 64 elements x 6 bits
-constexpr int kFragPlane = 512;                      // 64 lanes x 8 bytes
+constexpr int kFragLo = 1024;                        // first plane: 64 lanes x 16 bytes
 constexpr int kF6Slot = 8 * 2 * kFragBytes;          // 24 KiB: 256 rows x 128 elements
-constexpr int kF6Slots = 5;
-// the ring needs 120 KiB, the epilogue's staging area 8 waves x 128 rows x 136 bytes = 136 KiB
-constexpr int kF6Lds = 8 * 128 * (64 * 2 + 8);
-static_assert(kF6Lds >= kF6Slots * kF6Slot && kF6Lds <= 160 * 1024, "LDS budget of a gfx950 CU");
+constexpr int kF6Slots = 6;
+// the ring takes 144 KiB; the epilogue's staging area (8 waves x 128 rows x 136 bytes = 136 KiB) reuses it
+constexpr int kF6Lds = kF6Slots * kF6Slot;
+static_assert(kF6Lds >= 8 * 128 * (64 * 2 + 8) && kF6Lds <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 // ---- packing ---------------------------------------------------------------------------------
 // One thread builds one lane's 24 bytes of one fragment.  SRC 8: int8 codes [R][K]; SRC 4: packed
@@ -80,31 +81,31 @@ __global__ void pack_fp6_kernel(const uint8_t* __restrict__ src, int R, int K, u
             if ((bit & 31) > 26) w[(bit >> 5) + 1] |= e >> (32 - (bit & 31));
         }
     }
-    uint8_t* f = dst + frag * kFragBytes + lane * 8;
-#pragma unroll
-    for (int p = 0; p < 3; ++p) *reinterpret_cast<uint2*>(f + p * kFragPlane) = make_uint2(w[2 * p], w[2 * p + 1]);
+    uint8_t* f = dst + frag * kFragBytes;
+    *reinterpret_cast<uint4*>(f + lane * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+    *reinterpret_cast<uint2*>(f + kFragLo + lane * 8) = make_uint2(w[4], w[5]);
 }
 
 // ---- fragments: LDS -> registers ---------------------------------------------------------------
 struct frag6 {
-    uint2 p[3];
+    uint4 lo;
+    uint2 hi;
 };
 
 __device__ __forceinline__ v8i as_operand(const frag6& f) {
     v8i v;
-    v[0] = (int)f.p[0].x; v[1] = (int)f.p[0].y;
-    v[2] = (int)f.p[1].x; v[3] = (int)f.p[1].y;
-    v[4] = (int)f.p[2].x; v[5] = (int)f.p[2].y;
+    v[0] = (int)f.lo.x; v[1] = (int)f.lo.y; v[2] = (int)f.lo.z; v[3] = (int)f.lo.w;
+    v[4] = (int)f.hi.x; v[5] = (int)f.hi.y;
     v[6] = 0; v[7] = 0;
     return v;
 }
 
-// slot: one operand's 256 rows x 128 elements as [row block 8][k fragment 2][plane 3][lane 64][8 B]
+// slot: one operand's 256 rows x 128 elements as [row block 8][k fragment 2] fragments
 __device__ __forceinline__ frag6 read_frag(const int8_t* slot, int row_block, int kf, int lane) {
-    const int8_t* f = slot + (row_block * 2 + kf) * kFragBytes + lane * 8;
+    const int8_t* f = slot + (row_block * 2 + kf) * kFragBytes;
     frag6 r;
-#pragma unroll
-    for (int p = 0; p < 3; ++p) r.p[p] = *reinterpret_cast<const uint2*>(f + p * kFragPlane);
+    r.lo = *reinterpret_cast<const uint4*>(f + lane * 16);
+    r.hi = *reinterpret_cast<const uint2*>(f + kFragLo + lane * 8);
     return r;
 }
 
@@ -147,7 +148,15 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     const int wm = wave / WN, wn = wave % WN;
     const int KB = I / 64;                        // fragments along K
     const int nk = I / 128;                       // K steps
-    const bool b_loader = wave >= 4;              // waves 4-7 load B, waves 0-3 load A
+    // Six LDS slots hold three tiles: half tile h (A(kt) = 2 kt, B(kt) = 2 kt + 1) lives in slot
+    // h % 6, so requests run two to three steps ahead of their use (the loads' latency from the
+    // memory-side cache is longer than one step).
+    //   waves 0-3 ("early"): request B(kt+2) before the barrier of step kt; its slot was B(kt-1)'s,
+    //                        released at barrier kt-1;
+    //   waves 4-7 ("late"):  request A(kt+3) after the barrier of step kt; its slot was A(kt)'s,
+    //                        which nobody reads after that barrier.
+    // One wave of every SIMD multiplies while its mate is held in load issue, as in the INT8 kernel.
+    const bool late = wave >= 4;
 
     // ---- loader: a slot is 24 instructions of 1 KiB; loader wave lw issues numbers 6 lw .. 6 lw + 5.
     // Instruction n copies bytes [1024 (n % 3), +1024) of the two consecutive fragments (3072 bytes)
@@ -156,9 +165,9 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     const int lw = wave & 3;
     const uint8_t* gsrc[6];
     {
-        const uint8_t* base = b_loader ? qw6 : qx6;
-        const int first = (b_loader ? n0 : m0) / 32;
-        const int last = ((b_loader ? O : T) + 31) / 32 - 1;
+        const uint8_t* base = late ? qx6 : qw6;               // early waves fetch weights, late waves activations
+        const int first = (late ? m0 : n0) / 32;
+        const int last = ((late ? T : O) + 31) / 32 - 1;
 #pragma unroll
         for (int ii = 0; ii < 6; ++ii) {
             const int n = 6 * lw + ii;
@@ -184,12 +193,21 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
 
-    // prologue: A0 A1 (waves 0-3) / B0 B1 (waves 4-7); half tile n -> slot n % 5
-    issue_half(0, b_loader ? 1 : 0);
-    if (nk > 1) issue_half(1, b_loader ? 3 : 2);
-    if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 15));
-    else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
-    __syncthreads();
+    // prologue: early waves request B0 B1, late waves A0 A1 A2; tile 0 must have landed
+    if (!late) {
+        issue_half(0, 1);
+        if (nk > 1) issue_half(1, 3);
+        if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 15));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    } else {
+        issue_half(0, 0);
+        if (nk > 1) issue_half(1, 2);
+        if (nk > 2) issue_half(2, 4);
+        if (nk > 2) __builtin_amdgcn_s_waitcnt(waitcnt_imm(12, 15));
+        else if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 15));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    }
+    __builtin_amdgcn_s_barrier();
 
     int sa = 0, sb = 1;
     auto adv = [](int v) { v += 2; return v >= kF6Slots ? v - kF6Slots : v; };
@@ -198,7 +216,7 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     load_frags6<NI>(af0, bf0, lds + sa * kF6Slot, lds + sb * kF6Slot, a_rb, b_rb, 0, lane);
 
     constexpr int NMF = 4 * NI;                   // matrix instructions per slab
-    constexpr int NRD = 3 * (4 + NI);             // 8-byte LDS reads per slab
+    constexpr int NRD = 2 * (4 + NI);             // LDS reads per slab (one 16-byte, one 8-byte per fragment)
     auto interleave_reads = [&]() {
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
@@ -208,8 +226,9 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value;        // kt + 2 < nk
+    auto k_step = [&](int kt, auto ahead2_c, auto ahead3_c, auto prefetch_c) {
+        constexpr bool AHEAD2 = decltype(ahead2_c)::value;      // kt + 2 < nk
+        constexpr bool AHEAD3 = decltype(ahead3_c)::value;      // kt + 3 < nk
         constexpr bool PREFETCH = decltype(prefetch_c)::value;  // kt + 1 < nk
         const int8_t* As = lds + sa * kF6Slot;
         const int8_t* Bs = lds + sb * kF6Slot;
@@ -217,23 +236,23 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         load_frags6<NI>(af1, bf1, As, Bs, a_rb, b_rb, 1, lane);
         mfma_slab6<NI>(acc, af0, bf0);
         interleave_reads();
-        // A loaders: A(kt+2) goes to slot adv(na), whose previous tenant B(kt-1) was released at the
-        // previous barrier; then tile kt+1's A (requested a step ago) must have landed: at most the
-        // 6 requests just made may still be in flight.  lgkmcnt(0): this wave's reads of tile kt are done.
-        if (!b_loader) {
-            if (ISSUE) {
-                issue_half(kt + 2, adv(na));
+        // Before the barrier every loader makes sure its half of tile kt+1 has landed; requests are
+        // served in order, so it is enough that at most the newest 6 are still in flight.
+        // lgkmcnt(0): this wave's reads of tile kt are done (its slots are handed over at the barrier).
+        if (!late) {
+            if (AHEAD2) {
+                issue_half(kt + 2, adv(nb));                    // B(kt+2) -> slot of B(kt-1)
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 0));
             } else {
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
             }
         } else {
-            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));      // B(kt+1), requested after the last barrier
+            if (AHEAD2) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 0));   // A(kt+2) may still be in flight
+            else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
         }
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        // B loaders: B(kt+2) goes to tile kt's A slot, which nobody reads any more
-        if (b_loader && ISSUE) issue_half(kt + 2, sa);
+        if (late && AHEAD3) issue_half(kt + 3, sa);            // A(kt+3) -> slot of A(kt)
         __builtin_amdgcn_sched_barrier(0);
         if (PREFETCH) load_frags6<NI>(af0, bf0, lds + na * kF6Slot, lds + nb * kF6Slot, a_rb, b_rb, 0, lane);
         mfma_slab6<NI>(acc, af1, bf1);
@@ -248,12 +267,16 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     int kt = 0;
-    for (; kt + 2 < nk; ++kt) k_step(kt, yes{}, yes{});
-    if (kt + 1 < nk) {
-        k_step(kt, no{}, yes{});
+    for (; kt + 3 < nk; ++kt) k_step(kt, yes{}, yes{}, yes{});
+    if (kt + 2 < nk) {
+        k_step(kt, yes{}, no{}, yes{});
         ++kt;
     }
-    k_step(kt, no{}, no{});
+    if (kt + 1 < nk) {
+        k_step(kt, no{}, no{}, yes{});
+        ++kt;
+    }
+    k_step(kt, no{}, no{}, no{});
 
     // every wave's fragments are in registers and all loads have landed: the ring can be reused
     __syncthreads();

@@ -860,22 +860,25 @@ E2M3 = np.array([0, 8, 16, 20, 24, 26, 28, 30], np.uint8)      # bit patterns of
 
 
 def fp6_fragments(codes):
-    """The operand format written out with numpy: [ceil(R/32)][K/64] fragments, each 3 planes x 64
-    lanes x 8 bytes; lane l = row l & 31, columns [32 (l >> 5), +32), element j in bits [6j, 6j+6)."""
+    """The operand format written out with numpy: [ceil(R/32)][K/64] fragments; lane l = row l & 31,
+    columns [32 (l >> 5), +32), element j in bits [6j, 6j+6) of the lane's 192-bit stream; a
+    fragment is 64 lanes x 16 bytes (bits 0..127) followed by 64 lanes x 8 bytes (bits 128..191)."""
     R, K = codes.shape
     RB, KB = (R + 31) // 32, K // 64
     padded = np.zeros((RB * 32, K), np.int64)
     padded[:R] = np.clip(codes.astype(np.int64), -7, 7)
     pat = E2M3[np.abs(padded)].astype(np.uint64) | np.where(padded < 0, 32, 0).astype(np.uint64)
     lanes = pat.reshape(RB, 32, KB, 2, 32).transpose(0, 2, 3, 1, 4).reshape(RB, KB, 64, 32)   # [rb][kb][lane][j]
-    out = np.zeros((RB, KB, 3, 64), np.uint64)
+    words = np.zeros((RB, KB, 64, 3), np.uint64)                                              # three 64-bit words per lane
     for j in range(32):
         bit = 6 * j
         p, sh = bit // 64, bit % 64
-        out[:, :, p, :] |= (lanes[..., j] << np.uint64(sh)) & np.uint64(0xFFFFFFFFFFFFFFFF)
+        words[..., p] |= (lanes[..., j] << np.uint64(sh)) & np.uint64(0xFFFFFFFFFFFFFFFF)
         if sh > 58:
-            out[:, :, p + 1, :] |= lanes[..., j] >> np.uint64(64 - sh)
-    return out.reshape(-1).view(np.uint8)
+            words[..., p + 1] |= lanes[..., j] >> np.uint64(64 - sh)
+    lo = np.ascontiguousarray(words[..., 0:2]).reshape(RB, KB, 64 * 2)
+    hi = np.ascontiguousarray(words[..., 2]).reshape(RB, KB, 64)
+    return np.concatenate([lo, hi], axis=2).reshape(-1).view(np.uint8)
 
 
 def int4_codes(R, K, seed):
