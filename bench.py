@@ -295,6 +295,28 @@ def main():
             "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands"]) if tops else None,
         }
 
+    # The same layer in the paper's W4A4 setting: INT4 codes of the same X and W, multiplied on the
+    # FP6 matrix instruction (exact) and, for comparison, unpacked to int8 on the INT8 kernel.
+    a4w4 = None
+    if args.stages == "all":
+        Wg4 = torch.from_numpy(W).to(dev)
+        nib, _, a4, b4, _ = cq.crossquant_quantize(Xg, t, c, alpha, 4, want_xhat=False)
+        qw4, ws4 = cq.crossquant_weight_quantize(Wg4, b4, 4)
+        del Wg4
+        px, pw = cq.crossquant_pack_fp6(nib), cq.crossquant_pack_fp6(qw4)
+        q8 = cq.crossquant_unpack_int4(nib)
+        event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=Y), 10)
+        fp6_ms = event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=Y), max(args.steps // 4, 1))
+        y6 = Y.clone()
+        event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=Y), 10)
+        i8_ms = event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=Y), max(args.steps // 4, 1))
+        pack_ms = event_ms(lambda: cq.crossquant_pack_fp6(nib, packed=px), 10)
+        a4w4 = {"fp6_ms": fp6_ms, "fp6_TOPs": ops_linear / (fp6_ms * 1e-3) / 1e12, "int8_path_ms": i8_ms,
+                "int8_path_TOPs": ops_linear / (i8_ms * 1e-3) / 1e12, "pack_activations_ms": pack_ms,
+                "identical_outputs": bool(torch.equal(y6.view(torch.int16), Y.view(torch.int16)))}
+        del px, pw, q8, nib, qw4, y6
+        cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)      # leave Y as the W8A8 result
+
     graph_ms = None
     if args.graph and args.stages == "all":
         g = torch.cuda.CUDAGraph()
@@ -336,6 +358,7 @@ def main():
         "graph_replay_ms_per_step": graph_ms,
         "quantizer_warm": {"ms": warm_ms, "GBs": (bytes_absmax + bytes_quant) / (warm_ms * 1e-3) / 1e9} if warm_ms else None,
         "achievable": achievable,
+        "a4w4_linear": a4w4,
         "roofline": {"kernel": "gemm_i8_ring_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS if tops else None,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},
