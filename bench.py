@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--alpha", type=float, default=0.15)
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from a captured HIP graph and report its time per step")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed step loop: no single-read / warm / calibration / A4W4 comparisons "
+                         "(the form the committed profiles are taken with)")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the plain read / copy / MFMA-only calibration kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -225,7 +228,7 @@ def main():
     # inside the same step (X cold: the linear layer has just swept the caches) and back to back
     # (X still in the Infinity Cache).  It is not part of `value`, which stays on the two named calls.
     fused = None
-    if args.stages == "all":
+    if args.stages == "all" and not args.no_extras:
         try:
             for _ in range(max(args.warmup, 3)):
                 step(single_read=True)
@@ -263,7 +266,7 @@ def main():
 
     # the same two quantizer calls back to back (X stays in the memory-side cache): the warm rate
     warm_ms = None
-    if ran["absmax"] and ran["quantize"]:
+    if ran["absmax"] and ran["quantize"] and not args.no_extras:
         def quantizer():
             cq.crossquant_absmax(Xg, t=t, c=c)
             cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
@@ -273,7 +276,7 @@ def main():
 
     # what the device sustains on a plain read, a plain copy and an MFMA-only loop
     achievable = None
-    if not args.no_ceilings:
+    if not args.no_ceilings and not args.no_extras:
         big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)       # 1 GiB: far beyond the caches
         big.fill_(1)
         half = 512 << 20
@@ -298,7 +301,7 @@ def main():
     # The same layer in the paper's W4A4 setting: INT4 codes of the same X and W, multiplied on the
     # FP6 matrix instruction (exact) and, for comparison, unpacked to int8 on the INT8 kernel.
     a4w4 = None
-    if args.stages == "all":
+    if args.stages == "all" and not args.no_extras:
         Wg4 = torch.from_numpy(W).to(dev)
         nib, _, a4, b4, _ = cq.crossquant_quantize(Xg, t, c, alpha, 4, want_xhat=False)
         qw4, ws4 = cq.crossquant_weight_quantize(Wg4, b4, 4)
