@@ -941,6 +941,24 @@ def test_w4a4_linear_fp6_extreme_accumulators_and_guarded_output(cq):
     assert np.all(out[:T, O:] == 7.0) and np.all(out[T:] == 7.0)
 
 
+def test_w4a4_linear_fp6_longest_contraction(cq):
+    """I = 2^18, the documented limit: |acc| reaches 49 * 2^18 = 12 845 056 < 2^24, still exact."""
+    T, I, O = 3, 1 << 18, 8
+    qx = np.full((T, I), 7, np.int8)
+    qx[1] = -7
+    qx[2, ::2] = 3
+    qw = np.full((O, I), 7, np.int8)
+    qw[1::2] = -7
+    qw[3, 5::7] = -2
+    a = np.array([1e-6, 2e-6, 3e-6], np.float32)
+    s = np.full(O, 1e-3, np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    assert np.abs(acc_ref).max() == 49 * I
+    px, pw = cq.crossquant_pack_fp6(gpu(qx)), cq.crossquant_pack_fp6(gpu(qw))
+    Y, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, want_acc=True)
+    assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(host(Y)), bits16(Y_ref))
+
+
 def test_end_to_end_a4w4_fp6_config(cq):
     """The low-bit configuration end to end with the FP6 linear layer: CrossQuant INT4 activation
     codes (packed nibbles) and INT4 per-channel weights, compared with the oracle on sampled rows
