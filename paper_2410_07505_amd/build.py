@@ -22,7 +22,7 @@ SOURCES = ["cq_api.hip", "cq_absmax.hip", "cq_quantize.hip", "cq_fused.hip", "cq
 # bit).  -packed-fp32-ops off: packed FP32 VALU forms are not used on the test machines.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
                "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wall", "-Wno-unused-function"]
+               "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
 def _hipcc() -> str:

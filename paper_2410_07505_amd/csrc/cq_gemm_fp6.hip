@@ -86,6 +86,21 @@ __global__ void pack_fp6_kernel(const uint8_t* __restrict__ src, int R, int K, u
     *reinterpret_cast<uint2*>(f + kFragLo + lane * 8) = make_uint2(w[4], w[5]);
 }
 
+// ---- global -> LDS ------------------------------------------------------------------------------
+// One request: every lane's 16 bytes at `src` go to LDS at dst + 16 * lane (1 KiB per wave), without
+// passing through registers; completion is counted by vmcnt.  Written as inline assembly rather
+// than with the compiler's builtin: for the builtin the compiler makes every later LDS read wait
+// until all such requests have landed (it cannot tell that the ring's slots differ), which would
+// serialise the requests made two and three steps ahead with the reads of the current step.  The
+// kernel orders reads and in-flight writes itself (slot discipline, explicit vmcnt waits, barriers).
+__device__ __forceinline__ void dma_1k(const uint8_t* src, const int8_t* dst) {
+    const uint32_t lds_off = (uint32_t)(uintptr_t)((lptr_t)dst);     // wave-uniform
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(lds_off)
+                 : "m0");
+}
+
 // ---- fragments: LDS -> registers ---------------------------------------------------------------
 struct frag6 {
     uint4 lo;
@@ -179,8 +194,7 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         int8_t* dst = lds + slot * kF6Slot + lw * (6 * 1024);
         const int64_t koff = (int64_t)kt * (2 * kFragBytes);
 #pragma unroll
-        for (int ii = 0; ii < 6; ++ii)
-            __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii] + koff), (lptr_t)(dst + ii * 1024), 16, 0, 0);
+        for (int ii = 0; ii < 6; ++ii) dma_1k(gsrc[ii] + koff, dst + ii * 1024);
     };
 
     const int a_rb = wm * 4, b_rb = wn * 2;       // first row block of this wave inside the A / B slot
