@@ -101,6 +101,25 @@ __device__ __forceinline__ void dma_1k(const uint8_t* src, const int8_t* dst) {
                  : "m0");
 }
 
+// s_waitcnt vmcnt(n), lgkmcnt(0) for a wave-uniform n in [0, 12] (the instruction takes an immediate)
+__device__ __forceinline__ void wait_vmcnt_upto(int n) {
+    switch (n) {
+        case 0: __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0)); break;
+        case 1: __builtin_amdgcn_s_waitcnt(waitcnt_imm(1, 0)); break;
+        case 2: __builtin_amdgcn_s_waitcnt(waitcnt_imm(2, 0)); break;
+        case 3: __builtin_amdgcn_s_waitcnt(waitcnt_imm(3, 0)); break;
+        case 4: __builtin_amdgcn_s_waitcnt(waitcnt_imm(4, 0)); break;
+        case 5: __builtin_amdgcn_s_waitcnt(waitcnt_imm(5, 0)); break;
+        case 6: __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 0)); break;
+        case 7: __builtin_amdgcn_s_waitcnt(waitcnt_imm(7, 0)); break;
+        case 8: __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 0)); break;
+        case 9: __builtin_amdgcn_s_waitcnt(waitcnt_imm(9, 0)); break;
+        case 10: __builtin_amdgcn_s_waitcnt(waitcnt_imm(10, 0)); break;
+        case 11: __builtin_amdgcn_s_waitcnt(waitcnt_imm(11, 0)); break;
+        default: __builtin_amdgcn_s_waitcnt(waitcnt_imm(12, 0)); break;
+    }
+}
+
 // ---- fragments: LDS -> registers ---------------------------------------------------------------
 struct frag6 {
     uint4 lo;
@@ -173,29 +192,49 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     // One wave of every SIMD multiplies while its mate is held in load issue, as in the INT8 kernel.
     const bool late = wave >= 4;
 
-    // ---- loader: a slot is 24 instructions of 1 KiB; loader wave lw issues numbers 6 lw .. 6 lw + 5.
-    // Instruction n copies bytes [1024 (n % 3), +1024) of the two consecutive fragments (3072 bytes)
-    // of row block n / 3.  Row blocks past the end of a ragged operand are replaced by the last
-    // valid one: what lands there only feeds outputs the epilogue drops.
+    // ---- loader: a slot (half tile) is 24 instructions of 1 KiB.  Instruction n copies bytes
+    // [1024 (n % 3), +1024) of the two consecutive fragments (3072 bytes) of row block n / 3.  Row
+    // blocks past the end of a ragged operand are replaced by the last valid one: what lands there
+    // only feeds outputs the epilogue drops.
+    //   B(kt+2), before the barrier: early wave lw issues instructions 6 lw .. 6 lw + 5;
+    //   A(kt+3), after the barrier:  late wave lw issues kLateA of them, early wave lw the other
+    //                                kEarlyA = 6 - kLateA (the late waves are the critical path of a
+    //                                step, the early ones would otherwise idle at the barrier).
     const int lw = wave & 3;
-    const uint8_t* gsrc[6];
-    {
-        const uint8_t* base = late ? qx6 : qw6;               // early waves fetch weights, late waves activations
-        const int first = (late ? m0 : n0) / 32;
-        const int last = ((late ? T : O) + 31) / 32 - 1;
+    constexpr int kEarlyA = 2, kLateA = 6 - kEarlyA;   // 0 / 6 measured ~4 % slower, 1..3 alike
+    auto src_of = [&](const uint8_t* base, int first_rb, int last_rb, int n) {
+        const int rb = min(first_rb + n / 3, last_rb);
+        return base + (int64_t)rb * KB * kFragBytes + (n % 3) * 1024 + lane * 16;
+    };
+    const uint8_t* src_b[6];                      // early waves only
+    const uint8_t* src_a[kLateA > kEarlyA ? kLateA : kEarlyA];
+    const int n_a = late ? kLateA : kEarlyA;      // this wave's share of an A half tile ...
+    const int a_first = late ? kLateA * lw : 4 * kLateA + kEarlyA * lw;   // ... starting at this instruction
 #pragma unroll
-        for (int ii = 0; ii < 6; ++ii) {
-            const int n = 6 * lw + ii;
-            const int rb = min(first + n / 3, last);
-            gsrc[ii] = base + (int64_t)rb * KB * kFragBytes + (n % 3) * 1024 + lane * 16;
-        }
-    }
-    auto issue_half = [&](int kt, int slot) {
+    for (int ii = 0; ii < 6; ++ii) src_b[ii] = src_of(qw6, n0 / 32, (O + 31) / 32 - 1, 6 * lw + ii);
+#pragma unroll
+    for (int ii = 0; ii < (kLateA > kEarlyA ? kLateA : kEarlyA); ++ii)
+        src_a[ii] = src_of(qx6, m0 / 32, (T + 31) / 32 - 1, a_first + min(ii, n_a > 0 ? n_a - 1 : 0));
+    auto issue_b = [&](int kt, int slot) {        // early waves
         int8_t* dst = lds + slot * kF6Slot + lw * (6 * 1024);
         const int64_t koff = (int64_t)kt * (2 * kFragBytes);
 #pragma unroll
-        for (int ii = 0; ii < 6; ++ii) dma_1k(gsrc[ii] + koff, dst + ii * 1024);
+        for (int ii = 0; ii < 6; ++ii) dma_1k(src_b[ii] + koff, dst + ii * 1024);
     };
+    auto issue_a = [&](int kt, int slot) {        // all waves, n_a instructions each
+        int8_t* dst = lds + slot * kF6Slot + a_first * 1024;
+        const int64_t koff = (int64_t)kt * (2 * kFragBytes);
+        if (late) {
+#pragma unroll
+            for (int ii = 0; ii < kLateA; ++ii) dma_1k(src_a[ii] + koff, dst + ii * 1024);
+        } else {
+#pragma unroll
+            for (int ii = 0; ii < kEarlyA; ++ii) dma_1k(src_a[ii] + koff, dst + ii * 1024);
+        }
+    };
+    // requests of this wave that may still be in flight when tile kt+1 has to be complete: its share
+    // of A(kt+2) and, for the early waves, B(kt+2)
+    const int pend_a = n_a;
 
     const int a_rb = wm * 4, b_rb = wn * 2;       // first row block of this wave inside the A / B slot
 
@@ -207,19 +246,18 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
 
-    // prologue: early waves request B0 B1, late waves A0 A1 A2; tile 0 must have landed
-    if (!late) {
-        issue_half(0, 1);
-        if (nk > 1) issue_half(1, 3);
-        if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 15));
-        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
-    } else {
-        issue_half(0, 0);
-        if (nk > 1) issue_half(1, 2);
-        if (nk > 2) issue_half(2, 4);
-        if (nk > 2) __builtin_amdgcn_s_waitcnt(waitcnt_imm(12, 15));
-        else if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 15));
-        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    // prologue, oldest first: B0 A0 B1 A1 A2 (B by the early waves only); tile 0 must have landed,
+    // the rest may still be in flight
+    if (!late) issue_b(0, 1);
+    issue_a(0, 0);
+    if (nk > 1) {
+        if (!late) issue_b(1, 3);
+        issue_a(1, 2);
+    }
+    if (nk > 2) issue_a(2, 4);
+    {
+        const int later = (nk > 1 ? (late ? 0 : 6) + pend_a : 0) + (nk > 2 ? pend_a : 0);
+        wait_vmcnt_upto(later);
     }
     __builtin_amdgcn_s_barrier();
 
@@ -250,23 +288,16 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         load_frags6<NI>(af1, bf1, As, Bs, a_rb, b_rb, 1, lane);
         mfma_slab6<NI>(acc, af0, bf0);
         interleave_reads();
-        // Before the barrier every loader makes sure its half of tile kt+1 has landed; requests are
-        // served in order, so it is enough that at most the newest 6 are still in flight.
-        // lgkmcnt(0): this wave's reads of tile kt are done (its slots are handed over at the barrier).
-        if (!late) {
-            if (AHEAD2) {
-                issue_half(kt + 2, adv(nb));                    // B(kt+2) -> slot of B(kt-1)
-                __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 0));
-            } else {
-                __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
-            }
-        } else {
-            if (AHEAD2) __builtin_amdgcn_s_waitcnt(waitcnt_imm(6, 0));   // A(kt+2) may still be in flight
-            else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
-        }
+        // Before the barrier every wave makes sure its share of tile kt+1 has landed; requests are
+        // served in order, so it is enough that at most the newest ones (its share of A(kt+2) and
+        // B(kt+2)) are still in flight.  lgkmcnt(0): this wave's reads of tile kt are done (its slots
+        // are handed over at the barrier).
+        if (!late && AHEAD2) issue_b(kt + 2, adv(nb));          // B(kt+2) -> slot of B(kt-1)
+        if (AHEAD2) wait_vmcnt_upto(pend_a + (late ? 0 : 6));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        if (late && AHEAD3) issue_half(kt + 3, sa);            // A(kt+3) -> slot of A(kt)
+        if (AHEAD3) issue_a(kt + 3, sa);                        // A(kt+3) -> slot of A(kt)
         __builtin_amdgcn_sched_barrier(0);
         if (PREFETCH) load_frags6<NI>(af0, bf0, lds + na * kF6Slot, lds + nb * kF6Slot, a_rb, b_rb, 0, lane);
         mfma_slab6<NI>(acc, af1, bf1);
