@@ -981,3 +981,22 @@ def test_end_to_end_a4w4_fp6_config(cq):
     Yr, accr = oracle.w8a8_linear(oracle.unpack_int4(ref["codes"])[rows], ref["a"][rows], qw_ref, s_ref)
     assert np.array_equal(host(acc[torch.from_numpy(rows).cuda()]), accr)
     assert np.array_equal(bits16(host(Y[torch.from_numpy(rows).cuda()])), bits16(Yr))
+
+
+def test_random_shapes_w4a4_fp6(cq):
+    """Thirty seeded random shapes for the FP6 linear layer (I a multiple of 128, O of 8, any T),
+    including contractions of one, two and three K steps (the pipeline's start-up cases)."""
+    rng = np.random.default_rng(8096)
+    for case in range(30):
+        T = int(rng.integers(1, 700))
+        I = 128 * int(rng.integers(1, 13)) if case >= 6 else 128 * (1 + case % 3)
+        O = 8 * int(rng.integers(1, 100))
+        say("random w4a4 %d: T=%d I=%d O=%d" % (case, T, I, O))
+        qx, qw = int4_codes(T, I, seed=9000 + case), int4_codes(O, I, seed=9500 + case)
+        a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+        s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+        Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+        px, pw = cq.crossquant_pack_fp6(gpu(nibbles(qx))), cq.crossquant_pack_fp6(gpu(qw))
+        Y, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, want_acc=True)
+        assert np.array_equal(host(acc), acc_ref)
+        assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
