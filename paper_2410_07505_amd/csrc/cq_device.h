@@ -120,9 +120,10 @@ __device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_
 // q_e = clamp(rne(fl32(x_e / fl32(a * b[e]))), +-qmax), identical to dividing every element.
 // The quotient is first approximated as x * (1/a) * (1/b) (ra, rb: reciprocals within 1 ulp, 0
 // where the factor is 0), which lies within 2^-21 relative of the correctly rounded quotient
-// (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own); the rounded
+// (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own; 2^-20.7 even if each
+// reciprocal were a further half ulp off); the rounded
 // integer can differ from the exact one only if the approximation lies within that distance of
-// a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2 (a 4x margin) and a wave in
+// a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2 (a 3x to 4x margin) and a wave in
 // which any lane trips recomputes its eight elements with the exact division.
 __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, const float (&b)[8],
                                           const float (&rb)[8], float qmax, float (&m)[8]) {

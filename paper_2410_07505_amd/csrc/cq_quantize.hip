@@ -9,10 +9,11 @@
 // costs more than the rest of the element's work together, so it is taken only where it can
 // matter: the quotient is first approximated as x * (1/a_i) * (1/b_j) (reciprocals formed once
 // per row / per lane, each within 1 ulp), which lies within 2^-21 relative of the correctly
-// rounded quotient (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own);
+// rounded quotient (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own;
+// 2^-20.7 even if each reciprocal were a further half ulp off);
 // the rounded integer can differ from the one the exact quotient gives only if the approximation
 // lies within that distance of a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2
-// (a 4x margin over the bound) and a wave in which any lane trips recomputes its eight elements
+// (a 3x to 4x margin over the bound) and a wave in which any lane trips recomputes its eight elements
 // with the exact division.  The result is therefore identical, bit for bit, to dividing every
 // element.
 //

@@ -1,0 +1,55 @@
+"""The error bound the quantize kernel's fast quotient relies on, checked on the CPU.
+
+The kernel replaces fl32(x / fl32(a * b)) by x * (ra * rb) with ra, rb reciprocals accurate to
+1 ulp, and falls back to the exact division whenever |frac| + |r| * 2^-19 >= 1/2.  That is sound
+if the approximation stays within 2^-19 (relative) of the correctly rounded quotient; the
+analysis gives 2^-20 (two reciprocals at up to 1.5 * 2^-23 each as modelled here, three roundings
+at 2^-24, and the quotient's own).  Here the bound is measured with numpy binary32 arithmetic, with
+the correctly rounded reciprocals perturbed by +-1 ulp in every combination (the hardware
+reciprocal is within 1 ulp of the true value; its exact rounding is not specified)."""
+from __future__ import annotations
+
+import numpy as np
+
+
+def ulp_shift(v: np.ndarray, k: int) -> np.ndarray:
+    return (v.view(np.int32) + np.int32(k)).view(np.float32)
+
+
+def test_fast_quotient_stays_within_the_fallback_margin():
+    rng = np.random.default_rng(123)
+    n = 400_000
+    # x: binary16 values; a, b: positive binary32 scale factors over many magnitudes
+    x = rng.standard_normal(n).astype(np.float16).astype(np.float32) * np.float32(8.0)
+    a = np.exp(rng.uniform(-12, 4, n)).astype(np.float32)
+    b = np.exp(rng.uniform(-6, 6, n)).astype(np.float32)
+    D = (a * b).astype(np.float32)
+    exact = (x.astype(np.float64) / D.astype(np.float64))          # the real quotient by fl32(a*b)
+    rounded = (x / D).astype(np.float32).astype(np.float64)        # what the oracle rounds
+    ra0 = (np.float32(1.0) / a).astype(np.float32)
+    rb0 = (np.float32(1.0) / b).astype(np.float32)
+    worst = 0.0
+    for da in (-1, 0, 1):
+        for db in (-1, 0, 1):
+            ra, rb = ulp_shift(ra0, da), ulp_shift(rb0, db)
+            approx = (x * (ra * rb).astype(np.float32)).astype(np.float32).astype(np.float64)
+            nz = exact != 0
+            rel = np.abs(approx[nz] - rounded[nz]) / np.abs(exact[nz])
+            worst = max(worst, float(rel.max()))
+    assert worst <= 2.0 ** -20, worst            # the analysed bound (measured: 2^-20.97)
+    assert worst <= 2.0 ** -19 / 2               # at most half of the kernel's fallback margin
+
+
+def test_rounding_can_only_differ_near_a_tie():
+    """If |approx - exact| <= 2^-20 * |exact| (the bound above) then rne(approx) != rne(exact)
+    implies the kernel's tie test fires for approx: brute force on quotients around every tie."""
+    ks = np.arange(0, 127, dtype=np.float64) + 0.5
+    for eps in (2.0 ** -20, -(2.0 ** -20), 2.0 ** -22, -(2.0 ** -22)):
+        for off in np.linspace(-3e-5, 3e-5, 241):
+            exact = ks * (1 + off)
+            approx = (exact * (1 + eps)).astype(np.float32)
+            differs = np.rint(approx.astype(np.float64)) != np.rint(exact)
+            r = approx.astype(np.float64)
+            frac = np.abs(r - np.rint(r))
+            fires = frac + np.abs(r) * 2.0 ** -19 >= 0.5 - 1e-12
+            assert not np.any(differs & ~fires)
