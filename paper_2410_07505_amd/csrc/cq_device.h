@@ -125,8 +125,15 @@ __device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_
 // integer can differ from the exact one only if the approximation lies within that distance of
 // a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2 (a 3x to 4x margin) and a wave in
 // which any lane trips recomputes its eight elements with the exact division.
+// The bound needs ra * rb and a * b to be normal numbers: `tiny` (any factor of this lane's piece
+// below kTinyFactor, possible only with caller-supplied maxima far below anything binary16 data
+// can produce) sends the piece to the exact division as well.
+constexpr float kTinyFactor = 8.673617379884035e-19f;   // 2^-60: both products stay within 2^+-120
+
+__device__ __forceinline__ bool tiny_factor(float f) { return f != 0.0f && f < kTinyFactor; }
+
 __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, const float (&b)[8],
-                                          const float (&rb)[8], float qmax, float (&m)[8]) {
+                                          const float (&rb)[8], float qmax, float (&m)[8], bool tiny) {
     float x[8];
     x[0] = half_lo(v.x); x[1] = half_hi(v.x);
     x[2] = half_lo(v.y); x[3] = half_hi(v.y);
@@ -141,7 +148,7 @@ __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, con
         const float f = rt - (m[e] - kMagic);
         score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)));
     }
-    if (__any(score >= 0.5f)) {                         // rare: exact division for this wave's row piece
+    if (__any(score >= 0.5f || tiny)) {                 // rare: exact division for this wave's row piece
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float D = a * b[e];

@@ -200,6 +200,7 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) rb[e] = safe_rcp(b[e]);
+    // (the maxima are the data's own here, so no factor can be tiny: see quantize8)
     // the wave's 32 row factors, one per lane, handed out with readlane (scalar registers)
     const float a_lane = lds_a[wave * kFRows + (lane & (kFRows - 1))];
     float nonzero = 0.0f;
@@ -216,7 +217,7 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
             const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), k));
             float m[8];
             const uint4 xv = (k < kFRegRows) ? v[k < kFRegRows ? k : 0] : lds_tile[(k - kFRegRows) * kFThreads + threadIdx.x];
-            quantize8(xv, a, safe_rcp(a), b, rb, qmax, m);
+            quantize8(xv, a, safe_rcp(a), b, rb, qmax, m, false);
             nonzero += count_nonzero8(m);
             if (col_ok) {
                 if (MODE == 1) store_codes_i8(m, cp, true, 8);

@@ -73,6 +73,9 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
         b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
         rb[e] = safe_rcp(b[e]);
     }
+    bool b_tiny = false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b_tiny |= tiny_factor(b[e]);
     int nvalid = I - j0;                                    // columns of this lane that exist
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
     // the wave's row factors, one per lane, handed out with readlane as the rows come up
@@ -95,7 +98,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             const float a = __builtin_bit_cast(
                 float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), bi * kU + u));
             float m[8];
-            quantize8(v[u], a, safe_rcp(a), b, rb, qmax, m);
+            quantize8(v[u], a, safe_rcp(a), b, rb, qmax, m, b_tiny || tiny_factor(a));
             nonzero += count_nonzero8(m);
             if (MODE == 1) store_codes_i8(m, codes + (int64_t)r * I + j0, out_vec, nvalid);
             if (MODE == 2) store_codes_i4(m, codes + (int64_t)r * (I / 2) + j0 / 2, out_vec, nvalid);

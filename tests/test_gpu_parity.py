@@ -252,6 +252,25 @@ def test_quantize_with_calibrated_maxima_clamps(cq):
     assert np.array_equal(host(codes), ref["codes"]) and int(host(zc)[0]) == ref["Z"] == int(host(zc2)[0])
 
 
+def test_quantize_with_absurdly_small_calibrated_maxima(cq):
+    """Maxima so small that a * b underflows (to a subnormal, or to zero: then every code is 0 by
+    definition) or 1/a * 1/b overflows: the quotient shortcut must hand these to the exact division."""
+    X = outliers(24, 64, seed=19)
+    for tv, cv, alpha in ((1e-30, 1e-30, 0.5), (1e-42, 1e-42, 0.5), (3e-39, 2e-38, 0.15), (1e-44, 1.0, 0.5), (1e-44, 1e-44, 0.5),
+                          (1.0, 1e-44, 0.15), (1e-20, 1e-36, 0.5)):
+        t = np.full(24, tv, np.float32)
+        c = np.full(64, cv, np.float32)
+        for bits in (8, 4):
+            ref = oracle.quantize(X, t, c, alpha, bits)
+            codes, xhat, a, b, zc = cq.crossquant_quantize(gpu(X), gpu(t), gpu(c), alpha, bits)
+            assert np.array_equal(bits32(host(a)), bits32(ref["a"])) and np.array_equal(bits32(host(b)), bits32(ref["b"]))
+            assert np.array_equal(host(codes), ref["codes"]), (tv, cv, alpha, bits)
+            assert int(host(zc)[0]) == ref["Z"]
+            assert np.array_equal(bits16(host(xhat)), bits16(ref["xhat"]))
+            zc2 = cq.crossquant_kernel_count(gpu(X), gpu(t), gpu(c), alpha, bits)
+            assert int(host(zc2)[0]) == ref["Z"]
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
 def test_quantize_full_configs(cq, name):
     cfg = workloads.CONFIGS[name]
