@@ -24,9 +24,6 @@
 
 #include "cq_device.h"
 
-#ifndef CQ_FUSED_REG_ROWS
-#define CQ_FUSED_REG_ROWS 16
-#endif
 
 namespace cq {
 namespace {
@@ -38,7 +35,7 @@ namespace {
 // bank conflicts) and only kFRegRows stay in registers.
 constexpr int kFWaves = 8;           // waves per block
 constexpr int kFRows = 32;           // rows per wave
-constexpr int kFRegRows = CQ_FUSED_REG_ROWS;          // ... of which held in registers
+constexpr int kFRegRows = 16;                         // ... of which held in registers (24: spills)
 constexpr int kFLdsRows = kFRows - kFRegRows;         // ... and in LDS
 constexpr int kFBlockRows = kFWaves * kFRows;   // 256
 constexpr int kFThreads = kFWaves * kLanes;
