@@ -98,6 +98,14 @@ int crossquant_absmax_quantize(const void *X, int64_t T, int64_t I, int64_t ldx,
                                float *col_scale, unsigned long long *zero_count, void *stream);
 
 /*
+ * Test hook for crossquant_absmax_quantize: the number of polls a block makes at the grid barrier
+ * before it gives up (default 2^22, seconds).  0 makes every block give up at once, so the failure
+ * path (NaN in row_scale / col_scale, codes not written) can be exercised without a GPU ever
+ * waiting.  Process-wide, not thread-safe; pass 1u << 22 to restore the default.
+ */
+void crossquant_debug_set_barrier_polls(unsigned polls);
+
+/*
  * Batched forms for a [B][S][I] activation tensor (the shape the appendix fake-quant listing is
  * written for: the row maximum runs over the last axis, the column maximum over the second to
  * last, i.e. over the S tokens of ONE sequence).  Every sequence b is an independent S x I

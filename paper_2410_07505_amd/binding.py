@@ -35,6 +35,8 @@ lib.crossquant_fp6_packed_bytes.argtypes = [_i64, _i64]
 lib.crossquant_fp6_packed_bytes.restype = ctypes.c_int64
 lib.crossquant_pack_fp6.argtypes = [_vp, _int, _i64, _i64, _vp, _vp]
 lib.crossquant_w4a4_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
+lib.crossquant_debug_set_barrier_polls.argtypes = [ctypes.c_uint]
+lib.crossquant_debug_set_barrier_polls.restype = None
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]

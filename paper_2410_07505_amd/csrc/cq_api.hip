@@ -116,6 +116,8 @@ int crossquant_absmax_quantize(const void* X, int64_t T, int64_t I, int64_t ldx,
     return from_hip(e);
 }
 
+void crossquant_debug_set_barrier_polls(unsigned polls) { cq::set_fused_barrier_polls(polls); }
+
 int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
                             float alpha, int bits, float* row_scale, float* col_scale,
                             unsigned long long* zero_count, void* stream) {

@@ -18,7 +18,7 @@
 // a block fills a CU (128 KiB of LDS, ~250 registers x 512 threads), so the host side refuses
 // grids with more blocks than the device has CUs (CQ_ERR_UNSUPPORTED: the caller uses the
 // two-call path).  Blocks of other kernels still running on the device only delay the barrier.
-// The wait is bounded: a block that does not see the barrier open within kFSpinLimit polls (seconds;
+// The wait is bounded: a block that does not see the barrier open within the poll limit (seconds;
 // only possible if part of the device is unavailable to this process) stops waiting, skips the
 // quantize phase and writes NaN scale factors for its tile, so the kernel always terminates.
 
@@ -40,7 +40,7 @@ constexpr int kFLdsRows = kFRows - kFRegRows;         // ... and in LDS
 constexpr int kFBlockRows = kFWaves * kFRows;   // 256
 constexpr int kFThreads = kFWaves * kLanes;
 constexpr int kFLdsBytes = kFLdsRows * kFThreads * 16;
-constexpr unsigned kFSpinLimit = 1u << 22;        // polls of a microsecond or two each
+constexpr unsigned kFSpinLimit = 1u << 22;        // default poll limit; a poll takes a microsecond or two
 
 // Arrival counter of the grid barrier.  One per device (each device has its own copy of the
 // variable); cleared on the stream before every launch, so calls that overlap on one device race.
@@ -63,7 +63,7 @@ __global__ void __launch_bounds__(kFThreads)
 fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float alpha, int qmax_i,
              uint32_t* t_bits, uint32_t* c_bits, float* __restrict__ a_out, float* __restrict__ b_out,
              uint8_t* __restrict__ codes, uint16_t* __restrict__ xhat, unsigned long long* __restrict__ zero_count,
-             int n_col_chunks) {
+             int n_col_chunks, unsigned spin_limit) {
     __shared__ uint32_t lds_col[kFWaves][4][kLanes];
     __shared__ float lds_a[kFBlockRows];
     __shared__ __align__(16) float lds_b[kColsPerWave];
@@ -146,7 +146,7 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
     if (threadIdx.x == 0) {
         __hip_atomic_fetch_add(&g_fused_arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int open = 0;
-        for (unsigned spin = 0; spin < kFSpinLimit; ++spin) {
+        for (unsigned spin = 0; spin < spin_limit; ++spin) {
             if (__hip_atomic_load(&g_fused_arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= gridDim.x) {
                 open = 1;
                 break;
@@ -241,6 +241,9 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
     }
 }
 
+// Host-side poll limit handed to every launch (see set_fused_barrier_polls).
+unsigned g_spin_limit = kFSpinLimit;
+
 template <int MODE, bool XHAT>
 hipError_t launch_fused_mode(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int qmax, float* t, float* c,
                              float* a, float* b, uint8_t* codes, uint16_t* xhat, unsigned long long* zc, int ncc,
@@ -250,11 +253,15 @@ hipError_t launch_fused_mode(const uint16_t* X, int T, int I, int64_t ldx, float
     if (e != hipSuccess) return e;
     fused_kernel<MODE, XHAT><<<dim3((unsigned)nblocks), dim3(kFThreads), kFLdsBytes, stream>>>(
         X, T, I, ldx, alpha, qmax, reinterpret_cast<uint32_t*>(t), reinterpret_cast<uint32_t*>(c), a, b, codes, xhat, zc,
-        ncc);
+        ncc, g_spin_limit);
     return hipGetLastError();
 }
 
 }  // namespace
+
+// Test hook: polls a block makes at the grid barrier before it gives up.  0 makes every block give
+// up at once, which exercises the failure path without ever making a GPU wait.
+void set_fused_barrier_polls(unsigned polls) { g_spin_limit = polls; }
 
 // returns hipErrorNotSupported (without launching) when the matrix does not fit on chip
 hipError_t launch_absmax_quantize(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int bits, float* t,

@@ -48,6 +48,7 @@ hipError_t launch_unpack_int4(const uint8_t* packed, int64_t n_bytes, int8_t* co
 
 // Single-read fused maxima + quantize (cooperative launch).  hipErrorNotSupported, with nothing
 // enqueued, if the matrix does not fit in the chip's registers.
+void set_fused_barrier_polls(unsigned polls);
 hipError_t launch_absmax_quantize(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int bits, float* t,
                                   float* c, float* a, float* b, void* codes, uint16_t* xhat,
                                   unsigned long long* zero_count, hipStream_t stream);

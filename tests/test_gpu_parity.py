@@ -389,6 +389,25 @@ def test_fused_reports_unsupported_requests(cq):
     torch.cuda.synchronize()
 
 
+def test_fused_barrier_gives_up_cleanly(cq):
+    """The grid barrier's bounded wait, forced from the host: with a poll limit of 0 every block
+    gives up at once, the kernel ends normally, flags the failure with NaN scale factors and
+    writes no codes; with the default limit the same call is correct again."""
+    import torch
+    X = outliers(300, 1024, seed=55)
+    Xg = gpu(X)
+    codes = torch.full((300, 1024), 99, dtype=torch.int8, device="cuda")
+    try:
+        cq.raw.crossquant_debug_set_barrier_polls(0)
+        _, _, codes_out, _, a, b, _ = cq.crossquant_absmax_quantize(Xg, 0.15, 8, codes=codes)
+        torch.cuda.synchronize()
+    finally:
+        cq.raw.crossquant_debug_set_barrier_polls(1 << 22)
+    assert bool(torch.isnan(a).all()) and bool(torch.isnan(b).all())
+    assert bool((codes_out == 99).all())
+    check_fused(cq, X, 0.15, 8, Xg=Xg, label="after the forced failure")
+
+
 @pytest.mark.parametrize("name", ["C2", "C5"])
 def test_fused_full_configs(cq, name):
     import torch
