@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published (5.0 POP/s)
+FP6_PEAK_TOPS = 10100.0      # MI355X dense FP6 / FP4 MFMA, published (10.1 PFLOP/s): the A4W4 path
 METRIC = "CrossQuant quantize GB/s (% HBM peak) + W8A8 linear TOPS (% INT8 MFMA peak)"
 
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
@@ -131,9 +132,7 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     cfg = workloads.CONFIGS[args.config]
-    if cfg.bits != 8:
-        print("bench.py: the timed step includes the W8A8 linear; pick an INT8 configuration", file=sys.stderr)
-        sys.exit(2)
+    bits = cfg.bits                 # 8: W8A8 on the INT8 kernel; 4: A4W4 on the FP6 kernel (codes packed per step)
     T, I, O = cfg.T, cfg.I, cfg.O
     alpha = args.alpha
     stages = ("absmax", "quantize", "count", "linear") if args.stages == "all" else tuple(args.stages.split(","))
@@ -150,7 +149,8 @@ def main():
     b = torch.empty(I, dtype=torch.float32, device=dev)
     a_pt = torch.empty(T, dtype=torch.float32, device=dev)
     b_pt = torch.empty(I, dtype=torch.float32, device=dev)
-    codes = torch.empty((T, I), dtype=torch.int8, device=dev)
+    codes = (torch.empty((T, I), dtype=torch.int8, device=dev) if bits == 8
+             else torch.empty((T, I // 2), dtype=torch.uint8, device=dev))
     xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
     zc = torch.zeros(1, dtype=torch.int64, device=dev)
     zc_pt = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -160,8 +160,12 @@ def main():
 
     # weight preparation (once): needs the column factors of this activation
     cq.crossquant_absmax(Xg, t=t, c=c)
-    cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b, zero_count=zc)
-    cq.crossquant_weight_quantize(Wg, b, 8, qw=qw, w_scale=ws)
+    cq.crossquant_quantize(Xg, t, c, alpha, bits, codes=codes, xhat=xhat, row_scale=a, col_scale=b, zero_count=zc)
+    cq.crossquant_weight_quantize(Wg, b, bits, qw=qw, w_scale=ws)
+    px = pw = None
+    if bits == 4:
+        pw = cq.crossquant_pack_fp6(qw)
+        px = cq.crossquant_pack_fp6(codes)
     torch.cuda.synchronize()
     del Wg
 
@@ -169,23 +173,27 @@ def main():
         if ev is not None:
             ev[0].record()
         if single_read:
-            cq.crossquant_absmax_quantize(Xg, alpha, 8, t=t, c=c, codes=codes, xhat=xhat, row_scale=a,
+            cq.crossquant_absmax_quantize(Xg, alpha, bits, t=t, c=c, codes=codes, xhat=xhat, row_scale=a,
                                           col_scale=b, zero_count=zc)
         elif "absmax" in stages:
             cq.crossquant_absmax(Xg, t=t, c=c)
         if ev is not None:
             ev[1].record()
         if "quantize" in stages and not single_read:
-            cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
+            cq.crossquant_quantize(Xg, t, c, alpha, bits, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
                                    zero_count=zc)
         if ev is not None:
             ev[2].record()
         if "count" in stages:
-            cq.crossquant_kernel_count(Xg, t, c, 1.0, 8, row_scale=a_pt, col_scale=b_pt, zero_count=zc_pt)
+            cq.crossquant_kernel_count(Xg, t, c, 1.0, bits, row_scale=a_pt, col_scale=b_pt, zero_count=zc_pt)
         if ev is not None:
             ev[3].record()
         if "linear" in stages:
-            cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)
+            if bits == 8:
+                cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)
+            else:
+                cq.crossquant_pack_fp6(codes, packed=px)
+                cq.crossquant_w4a4_linear(px, a, pw, ws, T, I, O, Y=Y)
         if ev is not None:
             ev[4].record()
 
@@ -210,7 +218,8 @@ def main():
 
     n = T * I
     bytes_absmax = 2 * n + 4 * (T + I)
-    bytes_quant = (2 + 1 + 2) * n + 4 * (T + I)
+    code_bytes = 1.0 if bits == 8 else 0.5
+    bytes_quant = (2 + code_bytes + 2) * n + 4 * (T + I)
     bytes_count = 2 * n
     ops_linear = 2.0 * T * I * O
     # a stage that was switched off (--stages) only measures the gap between two event records
@@ -221,6 +230,7 @@ def main():
     quant_gbs = (bytes_absmax + bytes_quant) / ((stage_ms[0] + stage_ms[1]) * 1e-3) / 1e9 \
         if (ran["absmax"] and ran["quantize"]) else None
     tops = ops_linear / (stage_ms[3] * 1e-3) / 1e12 if ran["linear"] else None
+    mfma_peak = INT8_PEAK_TOPS if bits == 8 else FP6_PEAK_TOPS
 
     z, z_pt = int(zc.item()), int(zc_pt.item())
 
@@ -243,12 +253,12 @@ def main():
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(n_f):
-                cq.crossquant_absmax_quantize(Xg, alpha, 8, t=t, c=c, codes=codes, xhat=xhat, row_scale=a,
+                cq.crossquant_absmax_quantize(Xg, alpha, bits, t=t, c=c, codes=codes, xhat=xhat, row_scale=a,
                                               col_scale=b, zero_count=zc)
             e1.record()
             torch.cuda.synchronize()
             warm_ms = e0.elapsed_time(e1) / n_f
-            f_bytes = (2 + 1 + 2) * n + 8 * (T + I)
+            f_bytes = (2 + code_bytes + 2) * n + 8 * (T + I)
             fused = {"in_step_ms": in_step_ms, "in_step_algorithmic_GBs": f_bytes / (in_step_ms * 1e-3) / 1e9,
                      "back_to_back_ms": warm_ms, "two_call_in_step_ms": float(stage_ms[0] + stage_ms[1]),
                      "zero_count_matches": z_f == z}
@@ -269,7 +279,7 @@ def main():
     if ran["absmax"] and ran["quantize"] and not args.no_extras:
         def quantizer():
             cq.crossquant_absmax(Xg, t=t, c=c)
-            cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
+            cq.crossquant_quantize(Xg, t, c, alpha, bits, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
                                    zero_count=zc)
         event_ms(quantizer, 5)
         warm_ms = event_ms(quantizer, max(args.steps // 2, 1))
@@ -295,13 +305,13 @@ def main():
             "hbm_copy_GBs_read_plus_write": 2 * half / (copy_ms * 1e-3) / 1e9,
             "mfma_i8_TOPs": mf,
             "quantizer_frac_of_copy": (quant_gbs / (2 * half / (copy_ms * 1e-3) / 1e9)) if quant_gbs else None,
-            "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands"]) if tops else None,
+            "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands"]) if (tops and bits == 8) else None,
         }
 
     # The same layer in the paper's W4A4 setting: INT4 codes of the same X and W, multiplied on the
     # FP6 matrix instruction (exact) and, for comparison, unpacked to int8 on the INT8 kernel.
     a4w4 = None
-    if args.stages == "all" and not args.no_extras:
+    if args.stages == "all" and not args.no_extras and bits == 8:
         Wg4 = torch.from_numpy(W).to(dev)
         nib, _, a4, b4, _ = cq.crossquant_quantize(Xg, t, c, alpha, 4, want_xhat=False)
         qw4, ws4 = cq.crossquant_weight_quantize(Wg4, b4, 4)
@@ -342,15 +352,18 @@ def main():
         "metric": METRIC,
         "value": quant_gbs, "unit": "GB/s",
         "quantize_frac_hbm_peak": quant_gbs / HBM_PEAK_GBS if quant_gbs else None,
-        "w8a8_linear_tops": tops, "w8a8_linear_frac_int8_peak": tops / INT8_PEAK_TOPS if tops else None,
+        "w8a8_linear_tops": tops if bits == 8 else None,
+        "w8a8_linear_frac_int8_peak": (tops / INT8_PEAK_TOPS) if (tops and bits == 8) else None,
+        "a4w4_linear_tops": tops if bits == 4 else None,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp16 in, fp32 scale arithmetic, int8 codes, int32 accumulate",
+        "dtype": ("fp16 in, fp32 scale arithmetic, int8 codes, int32 accumulate" if bits == 8 else
+                  "fp16 in, fp32 scale arithmetic, int4 codes as fp6 (exact), fp32 accumulate (exact)"),
         "data": "synthetic (seeded N(0,1) activations with outlier channels, N(0,0.02) weights)",
-        "config": {"workload": "%s: %s" % (cfg.name, cfg.label), "T": T, "I": I, "O": O, "bits": 8,
+        "config": {"workload": "%s: %s" % (cfg.name, cfg.label), "T": T, "I": I, "O": O, "bits": bits,
                    "alpha": alpha, "stages": list(stages)},
         "stage_ms": {"absmax": stage_ms[0], "quantize": stage_ms[1], "count_per_token": stage_ms[2],
-                     "w8a8_linear": stage_ms[3]},
+                     ("w8a8_linear" if bits == 8 else "a4w4_linear_with_packing"): stage_ms[3]},
         "stage_rate": {
             "absmax_GBs": bytes_absmax / (stage_ms[0] * 1e-3) / 1e9 if stage_ms[0] > 0 else None,
             "quantize_GBs": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
@@ -362,8 +375,10 @@ def main():
         "quantizer_warm": {"ms": warm_ms, "GBs": (bytes_absmax + bytes_quant) / (warm_ms * 1e-3) / 1e9} if warm_ms else None,
         "achievable": achievable,
         "a4w4_linear": a4w4,
-        "roofline": {"kernel": "gemm_i8_ring_kernel (W8A8 linear)", "bound": "mfma", "achieved": tops,
-                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": tops / INT8_PEAK_TOPS if tops else None,
+        "roofline": {"kernel": ("gemm_i8_ring_kernel (W8A8 linear)" if bits == 8 else
+                                "gemm_f6_ring_kernel (A4W4 linear, incl. packing the activation codes)"),
+                     "bound": "mfma", "achieved": tops, "peak": mfma_peak, "unit": "TOP/s",
+                     "frac": tops / mfma_peak if tops else None,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},
         "roofline_quantize": {"kernel": "quantize_kernel (codes + xhat + zero count) incl. scale finalize",
                               "bound": "hbm",
