@@ -187,8 +187,9 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     // memory-side cache is longer than one step).
     //   waves 0-3 ("early"): request B(kt+2) before the barrier of step kt; its slot was B(kt-1)'s,
     //                        released at barrier kt-1;
-    //   waves 4-7 ("late"):  request A(kt+3) after the barrier of step kt; its slot was A(kt)'s,
-    //                        which nobody reads after that barrier.
+    //   waves 4-7 ("late"):  request A(kt+3) after the barrier of step kt (the early waves take a
+    //                        share of it, see the loader below); its slot was A(kt)'s, which nobody
+    //                        reads after that barrier.
     // One wave of every SIMD multiplies while its mate is held in load issue, as in the INT8 kernel.
     const bool late = wave >= 4;
 
