@@ -180,8 +180,12 @@ def main():
         if ev is not None:
             ev[1].record()
         if "quantize" in stages and not single_read:
-            cq.crossquant_quantize(Xg, t, c, alpha, bits, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
-                                   zero_count=zc)
+            if bits == 8:
+                cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
+                                       zero_count=zc)
+            else:       # INT4 codes leave the quantizer already in the FP6 kernel's operand format
+                cq.crossquant_quantize_fp6(Xg, t, c, alpha, packed=px, xhat=xhat, row_scale=a, col_scale=b,
+                                           zero_count=zc)
         if ev is not None:
             ev[2].record()
         if "count" in stages:
@@ -192,7 +196,6 @@ def main():
             if bits == 8:
                 cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)
             else:
-                cq.crossquant_pack_fp6(codes, packed=px)
                 cq.crossquant_w4a4_linear(px, a, pw, ws, T, I, O, Y=Y)
         if ev is not None:
             ev[4].record()
@@ -218,7 +221,7 @@ def main():
 
     n = T * I
     bytes_absmax = 2 * n + 4 * (T + I)
-    code_bytes = 1.0 if bits == 8 else 0.5
+    code_bytes = 1.0 if bits == 8 else 0.75     # int8 codes, or 6-bit fields of the FP6 fragments
     bytes_quant = (2 + code_bytes + 2) * n + 4 * (T + I)
     bytes_count = 2 * n
     ops_linear = 2.0 * T * I * O
@@ -238,7 +241,7 @@ def main():
     # inside the same step (X cold: the linear layer has just swept the caches) and back to back
     # (X still in the Infinity Cache).  It is not part of `value`, which stays on the two named calls.
     fused = None
-    if args.stages == "all" and not args.no_extras:
+    if args.stages == "all" and not args.no_extras and bits == 8:
         try:
             for _ in range(max(args.warmup, 3)):
                 step(single_read=True)
@@ -279,8 +282,12 @@ def main():
     if ran["absmax"] and ran["quantize"] and not args.no_extras:
         def quantizer():
             cq.crossquant_absmax(Xg, t=t, c=c)
-            cq.crossquant_quantize(Xg, t, c, alpha, bits, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
-                                   zero_count=zc)
+            if bits == 8:
+                cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
+                                       zero_count=zc)
+            else:
+                cq.crossquant_quantize_fp6(Xg, t, c, alpha, packed=px, xhat=xhat, row_scale=a, col_scale=b,
+                                           zero_count=zc)
         event_ms(quantizer, 5)
         warm_ms = event_ms(quantizer, max(args.steps // 2, 1))
 
@@ -363,7 +370,7 @@ def main():
         "config": {"workload": "%s: %s" % (cfg.name, cfg.label), "T": T, "I": I, "O": O, "bits": bits,
                    "alpha": alpha, "stages": list(stages)},
         "stage_ms": {"absmax": stage_ms[0], "quantize": stage_ms[1], "count_per_token": stage_ms[2],
-                     ("w8a8_linear" if bits == 8 else "a4w4_linear_with_packing"): stage_ms[3]},
+                     ("w8a8_linear" if bits == 8 else "a4w4_linear"): stage_ms[3]},
         "stage_rate": {
             "absmax_GBs": bytes_absmax / (stage_ms[0] * 1e-3) / 1e9 if stage_ms[0] > 0 else None,
             "quantize_GBs": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
@@ -376,7 +383,7 @@ def main():
         "achievable": achievable,
         "a4w4_linear": a4w4,
         "roofline": {"kernel": ("gemm_i8_ring_kernel (W8A8 linear)" if bits == 8 else
-                                "gemm_f6_ring_kernel (A4W4 linear, incl. packing the activation codes)"),
+                                "gemm_f6_ring_kernel (A4W4 linear)"),
                      "bound": "mfma", "achieved": tops, "peak": mfma_peak, "unit": "TOP/s",
                      "frac": tops / mfma_peak if tops else None,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},

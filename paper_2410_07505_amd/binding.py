@@ -34,6 +34,7 @@ lib.crossquant_calib_mfma_i8.argtypes = [_int, _int, _vp, ctypes.POINTER(ctypes.
 lib.crossquant_fp6_packed_bytes.argtypes = [_i64, _i64]
 lib.crossquant_fp6_packed_bytes.restype = ctypes.c_int64
 lib.crossquant_pack_fp6.argtypes = [_vp, _int, _i64, _i64, _vp, _vp]
+lib.crossquant_quantize_fp6.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_w4a4_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
 lib.crossquant_debug_set_barrier_polls.argtypes = [ctypes.c_uint]
 lib.crossquant_debug_set_barrier_polls.restype = None
@@ -45,7 +46,7 @@ lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
 for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_absmax_quantize", "crossquant_absmax_batched",
            "crossquant_quantize_batched", "crossquant_calib_read", "crossquant_calib_copy", "crossquant_calib_mfma_i8", "crossquant_pack_fp6",
-           "crossquant_w4a4_linear", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
+           "crossquant_w4a4_linear", "crossquant_quantize_fp6", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
            "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "crossquant_w8a8_linear",
            "crossquant_version"):
     getattr(lib, _n).restype = _int
@@ -248,6 +249,39 @@ def crossquant_pack_fp6(codes: torch.Tensor, *, packed: torch.Tensor = None) -> 
         raise ValueError("packed must be a contiguous uint8 tensor of %d bytes" % n)
     _check(lib.crossquant_pack_fp6(codes.data_ptr(), fmt, R, K, packed.data_ptr(), _stream(codes)))
     return packed
+
+
+def crossquant_quantize_fp6(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, *,
+                            want_xhat: bool = False, want_count: bool = True, packed: torch.Tensor = None,
+                            xhat: torch.Tensor = None, row_scale: torch.Tensor = None,
+                            col_scale: torch.Tensor = None, zero_count: torch.Tensor = None):
+    """INT4 CrossQuant codes written directly as FP6 fragments for crossquant_w4a4_linear.
+
+    Returns (packed, xhat_or_None, row_scale, col_scale, zero_count_or_None)."""
+    _req(X, torch.float16, "X", 2)
+    T, I = X.shape
+    dev = X.device
+    n = int(lib.crossquant_fp6_packed_bytes(T, I))
+    if n < 0:
+        raise CrossQuantError(-6)
+    if packed is None:
+        packed = torch.zeros(n, dtype=torch.uint8, device=dev)
+    elif packed.dtype != torch.uint8 or packed.numel() != n or not packed.is_contiguous():
+        raise ValueError("packed must be a contiguous uint8 tensor of %d bytes" % n)
+    if xhat is None and want_xhat:
+        xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
+    if row_scale is None:
+        row_scale = torch.empty(T, dtype=torch.float32, device=dev)
+    if col_scale is None:
+        col_scale = torch.empty(I, dtype=torch.float32, device=dev)
+    if zero_count is None and want_count:
+        zero_count = torch.empty(1, dtype=torch.int64, device=dev)
+    for ten, name in ((t, "t"), (c, "c"), (row_scale, "row_scale"), (col_scale, "col_scale")):
+        _req(ten, torch.float32, name, 1)
+    _check(lib.crossquant_quantize_fp6(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(), float(alpha),
+                                       packed.data_ptr(), _ptr(xhat), row_scale.data_ptr(), col_scale.data_ptr(),
+                                       _ptr(zero_count), _stream(X)))
+    return packed, xhat, row_scale, col_scale, zero_count
 
 
 def crossquant_w4a4_linear(qx_fp6: torch.Tensor, row_scale: torch.Tensor, qw_fp6: torch.Tensor, w_scale: torch.Tensor,

@@ -216,6 +216,24 @@ int crossquant_pack_fp6(const void* codes, int src_format, int64_t R, int64_t K,
     return from_hip(cq::launch_pack_fp6(codes, src_format, (int)R, (int)K, packed, static_cast<hipStream_t>(stream)));
 }
 
+int crossquant_quantize_fp6(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
+                            float alpha, void* packed, void* xhat, float* row_scale, float* col_scale,
+                            unsigned long long* zero_count, void* stream) {
+    if (!t || !c || !packed || !row_scale || !col_scale) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
+        !aligned(xhat, 2) || !aligned(zero_count, 8))
+        return CQ_ERR_ALIGN;
+    if (I % 128 != 0 || !aligned(packed, 16)) return CQ_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, 7, row_scale, col_scale,
+                                                   zero_count, 1, st)))
+        return s;
+    return from_hip(cq::launch_quantize_fp6(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
+                                            col_scale, packed, static_cast<uint16_t*>(xhat), zero_count, st));
+}
+
 int crossquant_w4a4_linear(const void* qx_fp6, const float* row_scale, const void* qw_fp6, const float* w_scale,
                            int64_t T, int64_t I, int64_t O, void* Y, int64_t ldy, int32_t* acc_debug, void* stream) {
     if (!qx_fp6 || !row_scale || !qw_fp6 || !w_scale || !Y) return CQ_ERR_NULL;

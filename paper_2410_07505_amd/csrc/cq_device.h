@@ -201,6 +201,40 @@ __device__ __forceinline__ void store_codes_i4(const float (&m)[8], uint8_t* dst
     }
 }
 
+// INT4 codes as FP6 E2M3 fragments, the operand format of the A4W4 matrix kernel: a fragment is 32
+// rows x 64 columns = 1536 bytes, fragments ordered [row / 32][column / 64]; fragment lane
+// (row & 31) + 32 * ((column / 32) & 1) holds 32 consecutive columns as a 192-bit little-endian
+// stream of 6-bit fields, its first 16 bytes at fragment + 16 * lane, the last 8 at fragment + 1024
+// + 8 * lane.  The wave's lanes 4g .. 4g+3 hold the 32 columns of group g (8 each): their 48-bit
+// pieces are gathered with three shuffles; lane 4g stores the 16 bytes, lane 4g+2 the 8 bytes.
+// E2M3 of an integer 0..7 is the top of its binary32 pattern: (bits >> 20) - 0x3F0 (0 for 0).
+// `group_ok`: the group's columns exist (I % 64 == 0: all or none).  frags_per_row = I / 64.
+__device__ __forceinline__ void store_codes_fp6(const float (&m)[8], uint8_t* packed, int row, int first_col,
+                                                int lane, int frags_per_row, bool group_ok) {
+    uint32_t e[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float q = m[k] - kMagic;                                   // the code, exact
+        const int mag = (int)(__float_as_uint(__builtin_fabsf(q)) >> 20) - 0x3F0;
+        e[k] = (uint32_t)max(mag, 0) | (q < 0.0f ? 32u : 0u);
+    }
+    const uint32_t lo = e[0] | (e[1] << 6) | (e[2] << 12) | (e[3] << 18) | (e[4] << 24) | (e[5] << 30);
+    const uint32_t hi = (e[5] >> 2) | (e[6] << 4) | (e[7] << 10);        // 16 bits
+    const uint32_t lo1 = (uint32_t)__shfl_down((int)lo, 1, kLanes), hi1 = (uint32_t)__shfl_down((int)hi, 1, kLanes);
+    const uint32_t lo2 = (uint32_t)__shfl_down((int)lo, 2, kLanes);
+    const int q4 = lane & 3, g = lane >> 2;
+    const int col = first_col + 32 * g;                                  // first column of the group
+    const int64_t frag = (int64_t)(row >> 5) * frags_per_row + (col >> 6);
+    const int flane = (row & 31) + 32 * ((col >> 5) & 1);
+    uint8_t* f = packed + frag * 1536;
+    // plain (cacheable) stores: a 128-byte line of a fragment is completed by 8 (or 16) different rows,
+    // so the pieces have to meet in L2 before they leave for memory
+    if (group_ok && q4 == 0)
+        *reinterpret_cast<u32x4*>(f + flane * 16) = u32x4{lo, hi | (lo1 << 16), (lo1 >> 16) | (hi1 << 16), lo2};
+    if (group_ok && q4 == 2)
+        *reinterpret_cast<u32x2*>(f + 1024 + flane * 8) = u32x2{hi | (lo1 << 16), (lo1 >> 16) | (hi1 << 16)};
+}
+
 // dequantized values fl16(fl32(q * fl32(a * b))): 16 bytes at dst
 __device__ __forceinline__ void store_xhat(const float (&m)[8], float a, const float (&b)[8], uint16_t* dst,
                                            bool vec_ok, int nvalid) {

@@ -64,6 +64,8 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                               int32_t* acc_debug, hipStream_t stream);
 
 // INT4 codes as FP6 fragments (32 rows x 64 columns per 1536-byte fragment) and the A4W4 linear layer on them.
+hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
+                               void* packed, uint16_t* xhat, unsigned long long* zero_count, hipStream_t stream);
 int64_t fp6_packed_bytes(int64_t R, int64_t K);
 hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void* packed, hipStream_t stream);
 hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const void* qw6, const float* w_scale, int T,

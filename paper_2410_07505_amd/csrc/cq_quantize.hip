@@ -38,7 +38,8 @@ __global__ void scale_finalize_kernel(const float* __restrict__ t, const float* 
 constexpr int kWaves = 8;   // waves per block
 constexpr int kU = 4;       // rows a wave has in flight
 
-// MODE 0: count only; 1: INT8 codes; 2: packed INT4 codes.
+// MODE 0: count only; 1: INT8 codes; 2: packed INT4 codes; 3: INT4 codes as FP6 fragments (one matrix,
+// I % 64 == 0).
 // Block: 8 waves sharing 512 columns; each wave streams over nb batches of 4 consecutive rows.
 // Outputs are written with non-temporal stores: they are not read again by this kernel, and
 // keeping them out of the caches leaves room for the X rows still to be read.
@@ -102,6 +103,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             nonzero += count_nonzero8(m);
             if (MODE == 1) store_codes_i8(m, codes + (int64_t)r * I + j0, out_vec, nvalid);
             if (MODE == 2) store_codes_i4(m, codes + (int64_t)r * (I / 2) + j0 / 2, out_vec, nvalid);
+            if (MODE == 3) store_codes_fp6(m, codes, r, col_chunk * kColsPerWave, lane, I / 64, j0 < I);
             if (XHAT) store_xhat(m, a, b, xhat + (int64_t)r * I + j0, out_vec, nvalid);
         }
     }
@@ -219,6 +221,14 @@ hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, 
                     : launch_mode<1, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, nullptr, zero_count, stream);
     return xhat ? launch_mode<2, true>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, xhat, zero_count, stream)
                 : launch_mode<2, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, nullptr, zero_count, stream);
+}
+
+// INT4 codes written straight into the FP6 operand format (I % 64 == 0, packed 16-byte aligned)
+hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
+                               void* packed, uint16_t* xhat, unsigned long long* zero_count, hipStream_t stream) {
+    uint8_t* cp = static_cast<uint8_t*>(packed);
+    return xhat ? launch_mode<3, true>(X, 1, T, I, ldx, 0, a, b, 7.0f, cp, xhat, zero_count, stream)
+                : launch_mode<3, false>(X, 1, T, I, ldx, 0, a, b, 7.0f, cp, nullptr, zero_count, stream);
 }
 
 }  // namespace cq

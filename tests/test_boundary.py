@@ -173,6 +173,12 @@ def test_fp6_argument_errors(cq):
     assert f(0, 8, 32, 128, P, None) == -1 and f(P, 8, 32, 128, 0, None) == -1
     assert f(P, 8, 0, 128, P, None) == -2 and f(P, 6, 32, 128, P, None) == -3
     assert f(P, 8, 32, 100, P, None) == -6 and f(P + 4, 8, 32, 128, P, None) == -5
+    q = cq.raw.crossquant_quantize_fp6
+    assert q(P, 4, 128, 128, P, P, 0.15, 0, None, P, P, None, None) == -1
+    assert q(P, 4, 128, 100, P, P, 0.15, P, None, P, P, None, None) == -2
+    assert q(P, 4, 128, 128, P, P, 1.5, P, None, P, P, None, None) == -4
+    assert q(P, 4, 64, 64, P, P, 0.15, P, None, P, P, None, None) == -6
+    assert q(P, 4, 128, 128, P, P, 0.15, P + 8, None, P, P, None, None) == -6
     g = cq.raw.crossquant_w4a4_linear
 
     def call(qx=P, rs=P, qw=P, ws=P, T=4, I=128, O=8, Y=P, ldy=8, acc=None):

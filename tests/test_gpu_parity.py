@@ -997,6 +997,25 @@ def test_w4a4_linear_fp6_longest_contraction(cq):
     assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(host(Y)), bits16(Y_ref))
 
 
+@pytest.mark.parametrize("T,I", [(1, 128), (32, 128), (45, 256), (300, 640), (257, 1024), (64, 2048)])
+def test_quantize_straight_to_fp6(cq, T, I):
+    """INT4 CrossQuant codes leaving the quantizer already as FP6 fragments: same bytes as
+    quantize (bits = 4) followed by the packing kernel, same zero count, same dequantized matrix."""
+    X = outliers(T, I, seed=T * 7 + I)
+    Xg = gpu(X)
+    t_ref, c_ref = oracle.absmax(X)
+    for alpha in (0.15, 1.0):
+        ref = oracle.quantize(X, t_ref, c_ref, alpha, 4)
+        want = fp6_fragments(oracle.unpack_int4(ref["codes"]))
+        t, c = cq.crossquant_absmax(Xg)
+        packed, xhat, a, b, zc = cq.crossquant_quantize_fp6(Xg, t, c, alpha, want_xhat=True)
+        assert np.array_equal(host(packed), want)
+        assert int(host(zc)[0]) == ref["Z"] and np.array_equal(bits16(host(xhat)), bits16(ref["xhat"]))
+        assert np.array_equal(bits32(host(a)), bits32(ref["a"])) and np.array_equal(bits32(host(b)), bits32(ref["b"]))
+        nib, _, _, _, _ = cq.crossquant_quantize(Xg, t, c, alpha, 4, want_xhat=False)
+        assert np.array_equal(host(cq.crossquant_pack_fp6(nib)), want)
+
+
 def test_end_to_end_a4w4_fp6_config(cq):
     """The low-bit configuration end to end with the FP6 linear layer: CrossQuant INT4 activation
     codes (packed nibbles) and INT4 per-channel weights, compared with the oracle on sampled rows
@@ -1012,6 +1031,8 @@ def test_end_to_end_a4w4_fp6_config(cq):
     packed, _, a, b, _ = cq.crossquant_quantize(Xg, t, c, 0.15, 4, want_xhat=False)
     qw, s = cq.crossquant_weight_quantize(Wg, b, 4)
     px, pw = cq.crossquant_pack_fp6(packed), cq.crossquant_pack_fp6(qw)
+    px_direct, _, a_d, _, _ = cq.crossquant_quantize_fp6(Xg, t, c, 0.15)
+    assert torch.equal(px, px_direct) and torch.equal(a, a_d)
     Y, acc = cq.crossquant_w4a4_linear(px, a, pw, s, cfg.T, cfg.I, cfg.O, want_acc=True)
     Y8, acc8 = cq.crossquant_w8a8_linear(cq.crossquant_unpack_int4(packed), a, qw, s, want_acc=True)
     assert torch.equal(acc, acc8) and torch.equal(Y.view(torch.int16), Y8.view(torch.int16))
