@@ -39,7 +39,8 @@ typedef enum {
     CQ_ERR_ALPHA = -4,       /* alpha outside [0, 1] or not a number */
     CQ_ERR_ALIGN = -5,       /* a pointer violates the stated alignment */
     CQ_ERR_UNSUPPORTED = -6, /* valid request this build does not implement */
-    CQ_ERR_HIP = -7          /* a kernel launch failed (hipGetLastError) */
+    CQ_ERR_HIP = -7,         /* a kernel launch failed (hipGetLastError) */
+    CQ_ERR_ALIAS = -8        /* an output vector overlaps an input vector it must not overlap */
 } cq_status;
 
 /* Upper limits on sizes (keeps every index in 32 bits inside the kernels). */
@@ -69,9 +70,13 @@ int crossquant_absmax(const void *X, int64_t T, int64_t I, int64_t ldx, float *t
  * codes: out.  bits == 8: int8 [T][I].  bits == 4: I must be even; packed two's-complement
  *        nibbles [T][I/2], even column in the low nibble.
  * xhat: out, nullable, binary16 [T][I].
- * row_scale: out, float[T] (a).  col_scale: out, float[I] (b).  Required: they are also the
- *        kernel's own inputs and what the linear layer / weight folding consume.
- * zero_count: out, nullable, one unsigned 64-bit counter.
+ * row_scale: out, float[T] (a).  col_scale: out, float[I] (b).  Required: the linear layer and
+ *        the weight folding consume them.  They must not overlap t or c (CQ_ERR_ALIAS): the one
+ *        kernel of this call reads t and c in every block while some blocks write a and b.
+ * zero_count: out, nullable, one unsigned 64-bit counter.  It is accumulated in one word of
+ *        library-owned device memory per device and stored by the last block to finish, so calls
+ *        that count must not overlap on one device (use one stream, or order them with events);
+ *        the same holds for the batched, FP6 and count-only forms below.
  */
 int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
                         const float *c, float alpha, int bits, void *codes, void *xhat,

@@ -35,6 +35,9 @@ int check_quant_params(float alpha, int bits, int64_t I) {
     return CQ_OK;
 }
 
+// do two float vectors share any element?
+inline bool overlap(const float* p, int64_t n, const float* q, int64_t m) { return p < q + m && q < p + n; }
+
 inline int from_hip(hipError_t e) { return e == hipSuccess ? CQ_OK : CQ_ERR_HIP; }
 
 }  // namespace
@@ -67,13 +70,10 @@ int crossquant_quantize(const void* X, int64_t T, int64_t I, int64_t ldx, const 
     if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
         !aligned(xhat, 2) || !aligned(zero_count, 8))
         return CQ_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int qmax = (1 << (bits - 1)) - 1;
-    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
-                                                   zero_count, 1, st)))
-        return s;
-    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, row_scale,
-                                        col_scale, bits, codes, static_cast<uint16_t*>(xhat), zero_count, st));
+    if (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I)) return CQ_ERR_ALIAS;
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, t, c, alpha, bits,
+                                        row_scale, col_scale, codes, static_cast<uint16_t*>(xhat), zero_count,
+                                        static_cast<hipStream_t>(stream)));
 }
 
 int crossquant_quantize_batched(const void* X, int64_t B, int64_t S, int64_t I, int64_t ldx, int64_t batch_stride,
@@ -86,15 +86,10 @@ int crossquant_quantize_batched(const void* X, int64_t B, int64_t S, int64_t I, 
     if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
         !aligned(xhat, 2) || !aligned(zero_count, 8))
         return CQ_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int qmax = (1 << (bits - 1)) - 1;
-    // the scale factors are element-wise in t and c: the batch is just longer vectors
-    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)(B * S), (int)(B * I), alpha, qmax, row_scale, col_scale,
-                                                   zero_count, 1, st)))
-        return s;
-    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)B, (int)S, (int)I, ldx, batch_stride,
-                                        row_scale, col_scale, bits, codes, static_cast<uint16_t*>(xhat), zero_count,
-                                        st));
+    if (overlap(t, B * S, row_scale, B * S) || overlap(c, B * I, col_scale, B * I)) return CQ_ERR_ALIAS;
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), (int)B, (int)S, (int)I, ldx, batch_stride, t, c,
+                                        alpha, bits, row_scale, col_scale, codes, static_cast<uint16_t*>(xhat),
+                                        zero_count, static_cast<hipStream_t>(stream)));
 }
 
 int crossquant_absmax_quantize(const void* X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits, float* t,
@@ -128,13 +123,10 @@ int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, co
     if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
         !aligned(zero_count, 8))
         return CQ_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int qmax = (1 << (bits - 1)) - 1;
-    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
-                                                   zero_count, 1, st)))
-        return s;
-    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, row_scale,
-                                        col_scale, bits, nullptr, nullptr, zero_count, st));
+    if (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I)) return CQ_ERR_ALIAS;
+    return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, t, c, alpha, bits,
+                                        row_scale, col_scale, nullptr, nullptr, zero_count,
+                                        static_cast<hipStream_t>(stream)));
 }
 
 int crossquant_kernel_analysis(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
@@ -226,12 +218,10 @@ int crossquant_quantize_fp6(const void* X, int64_t T, int64_t I, int64_t ldx, co
         !aligned(xhat, 2) || !aligned(zero_count, 8))
         return CQ_ERR_ALIGN;
     if (I % 128 != 0 || !aligned(packed, 16)) return CQ_ERR_UNSUPPORTED;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, 7, row_scale, col_scale,
-                                                   zero_count, 1, st)))
-        return s;
-    return from_hip(cq::launch_quantize_fp6(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, row_scale,
-                                            col_scale, packed, static_cast<uint16_t*>(xhat), zero_count, st));
+    if (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I)) return CQ_ERR_ALIAS;
+    return from_hip(cq::launch_quantize_fp6(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, t, c, alpha, row_scale,
+                                            col_scale, packed, static_cast<uint16_t*>(xhat), zero_count,
+                                            static_cast<hipStream_t>(stream)));
 }
 
 int crossquant_w4a4_linear(const void* qx_fp6, const float* row_scale, const void* qw_fp6, const float* w_scale,
@@ -281,6 +271,7 @@ const char* crossquant_status_string(int status) {
         case CQ_ERR_ALIGN: return "pointer alignment violated";
         case CQ_ERR_UNSUPPORTED: return "unsupported request";
         case CQ_ERR_HIP: return "kernel launch failed";
+        case CQ_ERR_ALIAS: return "an output vector overlaps an input vector";
         default: return "unknown status";
     }
 }

@@ -37,10 +37,11 @@ hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, 
                                   const float* c, const float* a, const float* b, int qmax,
                                   uint16_t* xrk, unsigned long long* counters, hipStream_t stream);
 
-// Fused quantize / dequantize / zero count.  codes or xhat may be null (count only = both null).
-// B matrices as in launch_absmax; a is [B*T], b is [B*I], codes / xhat are [B*T][...].
-hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* a,
-                           const float* b, int bits, void* codes, uint16_t* xhat,
+// Scale factors (as launch_scale_finalize: a, b are outputs), then fused quantize / dequantize / zero
+// count, in one kernel.  codes or xhat may be null (count only = both null).
+// B matrices as in launch_absmax; t, a are [B*T], c, b are [B*I], codes / xhat are [B*T][...].
+hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* t,
+                           const float* c, float alpha, int bits, float* a, float* b, void* codes, uint16_t* xhat,
                            unsigned long long* zero_count, hipStream_t stream);
 
 // packed nibbles [n_bytes] -> int8 codes [2 * n_bytes]
@@ -64,8 +65,9 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                               int32_t* acc_debug, hipStream_t stream);
 
 // INT4 codes as FP6 fragments (32 rows x 64 columns per 1536-byte fragment) and the A4W4 linear layer on them.
-hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
-                               void* packed, uint16_t* xhat, unsigned long long* zero_count, hipStream_t stream);
+hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, const float* t, const float* c, float alpha,
+                               float* a, float* b, void* packed, uint16_t* xhat, unsigned long long* zero_count,
+                               hipStream_t stream);
 int64_t fp6_packed_bytes(int64_t R, int64_t K);
 hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void* packed, hipStream_t stream);
 hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const void* qw6, const float* w_scale, int T,

@@ -38,27 +38,47 @@ __global__ void scale_finalize_kernel(const float* __restrict__ t, const float* 
 constexpr int kWaves = 8;   // waves per block
 constexpr int kU = 4;       // rows a wave has in flight
 
+// Zero-count accumulator of the quantize kernel: library-owned, one per device, zero between
+// launches.  Bits 0..40 hold the running count (at most 2^40 elements), bits 41..63 the number
+// of blocks that have added theirs.  The block whose add brings the second field to the grid
+// size knows the total, stores it to the caller's counter and clears the accumulator again, so
+// no kernel has to run beforehand to clear anything.
+constexpr int kTicketShift = 41;
+constexpr unsigned kMaxTicketBlocks = 1u << (64 - kTicketShift);
+__device__ unsigned long long g_zero_state;
+
+__global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
+
 // MODE 0: count only; 1: INT8 codes; 2: packed INT4 codes; 3: INT4 codes as FP6 fragments (one matrix,
 // I % 64 == 0).
 // Block: 8 waves sharing 512 columns; each wave streams over nb batches of 4 consecutive rows.
+// The block first forms the scale factors of its own rows and columns from t and c (binary64
+// pow, one per thread for the columns, one per lane for a wave's rows; the first batch of X rows
+// is requested before, so the memory system is busy meanwhile); the blocks of column chunk 0 /
+// row chunk 0 also write them to a_out / b_out for the caller.  Every block that needs a factor
+// computes the same bits from the same inputs, so no kernel has to run beforehand.
 // Outputs are written with non-temporal stores: they are not read again by this kernel, and
 // keeping them out of the caches leaves room for the X rows still to be read.
 // A batch of B matrices (each with its own column factors) is one launch: B copies of the
 // one-matrix grid; a block first steps its pointers to its own matrix.
 template <int MODE, bool XHAT, bool VEC>
 __global__ void __launch_bounds__(kWaves * kLanes)
-quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ a_vec,
-                const float* __restrict__ b_vec, float qmax, uint8_t* __restrict__ codes,
-                uint16_t* __restrict__ xhat, unsigned long long* __restrict__ zero_count,
+quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ t_vec,
+                const float* __restrict__ c_vec, double alpha, int qmax_i, float* __restrict__ a_out,
+                float* __restrict__ b_out, uint8_t* __restrict__ codes, uint16_t* __restrict__ xhat,
+                unsigned long long* __restrict__ zero_count, bool ticket,
                 int n_col_chunks, int nb, bool out_vec, int blocks_per_matrix, int64_t matrix_stride) {
     __shared__ uint32_t lds_cnt[kWaves];
+    __shared__ float lds_b[kColsPerWave];
     const int lane = threadIdx.x & (kLanes - 1);
     const int wave = threadIdx.x / kLanes;
     const int matrix = blockIdx.x / blocks_per_matrix;
     const int blk = blockIdx.x - matrix * blocks_per_matrix;
     X += (int64_t)matrix * matrix_stride;
-    a_vec += (int64_t)matrix * T;
-    b_vec += (int64_t)matrix * I;
+    t_vec += (int64_t)matrix * T;
+    c_vec += (int64_t)matrix * I;
+    a_out += (int64_t)matrix * T;
+    b_out += (int64_t)matrix * I;
     if (MODE == 1) codes += (int64_t)matrix * T * I;
     if (MODE == 2) codes += (int64_t)matrix * T * (I / 2);
     if (XHAT) xhat += (int64_t)matrix * T * I;
@@ -67,11 +87,36 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const int j0 = col_chunk * kColsPerWave + lane * 8;
     const int rows_per_wave = nb * kU;                      // <= 64
     const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
+    const float qmax = (float)qmax_i;
+
+    // first batch of rows: in flight while the scale factors are formed
+    uint4 v[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u)
+        v[u] = (row0 + u < T) ? load8<VEC>(X + (int64_t)(row0 + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
+
+    {
+        // thread k of the block: column k of the chunk
+        const int j = col_chunk * kColsPerWave + (int)threadIdx.x;
+        float bj = 0.0f;
+        if (j < I) {
+            bj = col_factor(c_vec[j], alpha);
+            if (row_chunk == 0) b_out[j] = bj;
+        }
+        lds_b[threadIdx.x] = bj;
+    }
+    // the wave's row factors, one per lane, handed out with readlane as the rows come up
+    float a_lane = 0.0f;
+    if (lane < rows_per_wave && row0 + lane < T) {
+        a_lane = row_factor(t_vec[row0 + lane], alpha, qmax_i);
+        if (col_chunk == 0) a_out[row0 + lane] = a_lane;
+    }
+    __syncthreads();
 
     float b[8], rb[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
+        b[e] = lds_b[lane * 8 + e];                         // 0 for columns past the end
         rb[e] = safe_rcp(b[e]);
     }
     bool b_tiny = false;
@@ -79,18 +124,17 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     for (int e = 0; e < 8; ++e) b_tiny |= tiny_factor(b[e]);
     int nvalid = I - j0;                                    // columns of this lane that exist
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
-    // the wave's row factors, one per lane, handed out with readlane as the rows come up
-    const float a_lane = (lane < rows_per_wave && row0 + lane < T) ? a_vec[row0 + lane] : 0.0f;
 
     float nonzero = 0.0f;     // codes != 0 seen by this lane (exact: far below 2^24)
     int rows_done = 0;
     for (int bi = 0; bi < nb; ++bi) {
         const int rbase = row0 + bi * kU;
         if (rbase >= T) break;                              // wave-uniform
-        uint4 v[kU];
+        if (bi > 0) {
 #pragma unroll
-        for (int u = 0; u < kU; ++u)
-            v[u] = (rbase + u < T) ? load8<VEC>(X + (int64_t)(rbase + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
+            for (int u = 0; u < kU; ++u)
+                v[u] = (rbase + u < T) ? load8<VEC>(X + (int64_t)(rbase + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
+        }
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int r = rbase + u;
@@ -120,31 +164,47 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) s += lds_cnt[w];
             // one atomic per block: same-address atomics serialise, so the grid is kept small
-            if (s) atomicAdd(zero_count, (unsigned long long)s);
+            if (ticket) {
+                unsigned long long* zero_state = &g_zero_state;
+                const unsigned long long add = (1ull << kTicketShift) | (unsigned long long)s;
+                const unsigned long long old =
+                    __hip_atomic_fetch_add(zero_state, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((unsigned)(old >> kTicketShift) == gridDim.x - 1u) {        // every other block has added
+                    *zero_count = (old + add) & ((1ull << kTicketShift) - 1ull);
+                    __hip_atomic_store(zero_state, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else if (s) {
+                atomicAdd(zero_count, (unsigned long long)s);                    // caller's counter, cleared before
+            }
         }
     }
 }
 
 template <int MODE, bool XHAT>
-hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* a,
-                       const float* b, float qmax, uint8_t* codes, uint16_t* xhat, unsigned long long* zc,
-                       hipStream_t stream) {
+hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* t,
+                       const float* c, double alpha, int qmax, float* a, float* b, uint8_t* codes, uint16_t* xhat,
+                       unsigned long long* zc, hipStream_t stream) {
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
     // rows per block = 32 * nb; keep about 512 blocks in flight
     int nb = 16;
     while (nb > 1 && (int64_t)B * ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
-    const dim3 grid((unsigned)(B * ncc * nrc)), block(kWaves * kLanes);
+    const unsigned n_blocks = (unsigned)(B * ncc * nrc);
+    const dim3 grid(n_blocks), block(kWaves * kLanes);
     const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0) && (B == 1 || matrix_stride % 8 == 0);
     // vector stores need every lane's piece aligned: I % 8 == 0 and aligned bases
     const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 8 == 0) &&
                          (reinterpret_cast<uintptr_t>(xhat) % 16 == 0);
+    const bool state = n_blocks < kMaxTicketBlocks;
+    if (zc && !state) zero_u64_kernel<<<dim3(1), dim3(1), 0, stream>>>(zc);   // more blocks than the block field counts
     if (vec)
-        quantize_kernel<MODE, XHAT, true><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat, zc,
-                                                                     ncc, nb, out_vec, ncc * nrc, matrix_stride);
+        quantize_kernel<MODE, XHAT, true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, alpha, qmax, a, b, codes, xhat,
+                                                                     zc, state, ncc, nb, out_vec, ncc * nrc,
+                                                                     matrix_stride);
     else
-        quantize_kernel<MODE, XHAT, false><<<grid, block, 0, stream>>>(X, T, I, ldx, a, b, qmax, codes, xhat, zc,
-                                                                      ncc, nb, out_vec, ncc * nrc, matrix_stride);
+        quantize_kernel<MODE, XHAT, false><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, alpha, qmax, a, b, codes,
+                                                                      xhat, zc, state, ncc, nb, out_vec, ncc * nrc,
+                                                                      matrix_stride);
     return hipGetLastError();
 }
 
@@ -210,25 +270,32 @@ hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, f
     return hipGetLastError();
 }
 
-hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* a,
-                           const float* b, int bits, void* codes, uint16_t* xhat, unsigned long long* zero_count,
-                           hipStream_t stream) {
-    const float qmax = (float)((1 << (bits - 1)) - 1);
+hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* t,
+                           const float* c, float alpha, int bits, float* a, float* b, void* codes, uint16_t* xhat,
+                           unsigned long long* zero_count, hipStream_t stream) {
+    const int qmax = (1 << (bits - 1)) - 1;
+    const double al = (double)alpha;
     uint8_t* cp = static_cast<uint8_t*>(codes);
-    if (!cp) return launch_mode<0, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, nullptr, nullptr, zero_count, stream);
+    if (!cp)
+        return launch_mode<0, false>(X, B, T, I, ldx, matrix_stride, t, c, al, qmax, a, b, nullptr, nullptr, zero_count,
+                                     stream);
     if (bits == 8)
-        return xhat ? launch_mode<1, true>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, xhat, zero_count, stream)
-                    : launch_mode<1, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, nullptr, zero_count, stream);
-    return xhat ? launch_mode<2, true>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, xhat, zero_count, stream)
-                : launch_mode<2, false>(X, B, T, I, ldx, matrix_stride, a, b, qmax, cp, nullptr, zero_count, stream);
+        return xhat ? launch_mode<1, true>(X, B, T, I, ldx, matrix_stride, t, c, al, qmax, a, b, cp, xhat, zero_count, stream)
+                    : launch_mode<1, false>(X, B, T, I, ldx, matrix_stride, t, c, al, qmax, a, b, cp, nullptr, zero_count,
+                                            stream);
+    return xhat ? launch_mode<2, true>(X, B, T, I, ldx, matrix_stride, t, c, al, qmax, a, b, cp, xhat, zero_count, stream)
+                : launch_mode<2, false>(X, B, T, I, ldx, matrix_stride, t, c, al, qmax, a, b, cp, nullptr, zero_count,
+                                        stream);
 }
 
 // INT4 codes written straight into the FP6 operand format (I % 64 == 0, packed 16-byte aligned)
-hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, const float* a, const float* b,
-                               void* packed, uint16_t* xhat, unsigned long long* zero_count, hipStream_t stream) {
+hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, const float* t, const float* c, float alpha,
+                               float* a, float* b, void* packed, uint16_t* xhat, unsigned long long* zero_count,
+                               hipStream_t stream) {
     uint8_t* cp = static_cast<uint8_t*>(packed);
-    return xhat ? launch_mode<3, true>(X, 1, T, I, ldx, 0, a, b, 7.0f, cp, xhat, zero_count, stream)
-                : launch_mode<3, false>(X, 1, T, I, ldx, 0, a, b, 7.0f, cp, nullptr, zero_count, stream);
+    const double al = (double)alpha;
+    return xhat ? launch_mode<3, true>(X, 1, T, I, ldx, 0, t, c, al, 7, a, b, cp, xhat, zero_count, stream)
+                : launch_mode<3, false>(X, 1, T, I, ldx, 0, t, c, al, 7, a, b, cp, nullptr, zero_count, stream);
 }
 
 }  // namespace cq

@@ -39,11 +39,11 @@ def test_library_exports_every_declared_symbol(cq):
 def test_version_and_status_strings(cq):
     assert cq.crossquant_version() >= 100
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = cq.crossquant_status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 9
     assert cq.crossquant_status_string(-99) == "unknown status"
 
 
@@ -79,6 +79,12 @@ def test_quantize_argument_errors(cq):
     assert call(bits=4, I=7, ldx=8) == -3              # INT4 packs two channels per byte
     assert call(alpha=-0.01) == -4 and call(alpha=1.01) == -4 and call(alpha=float("nan")) == -4
     assert call(zc=P + 4) == -5 and call(xhat=P + 1) == -5
+    # the factors are written while t and c are still being read: no overlap allowed
+    far = dict(t=P, c=P + 0x1000, rs=P + 0x2000, cs=P + 0x3000)
+    assert call(**{**far, "rs": P}) == -8
+    assert call(**{**far, "rs": P + 12}) == -8           # last element of t (T = 4)
+    assert call(**{**far, "cs": P + 0x1000 + 28}) == -8  # last element of c (I = 8)
+    assert call(**{**far, "cs": P + 0x1000 - 28}) == -8  # cs's last element is c's first
 
 
 def test_absmax_quantize_argument_errors(cq):
@@ -112,6 +118,8 @@ def test_batched_argument_errors(cq):
     assert call(B=0) == -2 and call(bs=8) == -2
     assert call(bits=7) == -3 and call(bits=4, I=7, ldx=8) == -3 and call(alpha=-0.5) == -4
     assert call(zc=P + 4) == -5
+    assert call(t=P, c=P + 0x1000, rs=P + 28, cs=P + 0x3000) == -8     # B*S = 8 row factors
+    assert call(t=P, c=P + 0x1000, rs=P + 0x2000, cs=P + 0x1000 + 60) == -8   # B*I = 16 column factors
 
 
 def test_kernel_count_argument_errors(cq):
@@ -124,6 +132,8 @@ def test_kernel_count_argument_errors(cq):
     assert call(T=0) == -2
     assert call(bits=5) == -3
     assert call(alpha=2.0) == -4
+    assert call(t=P, c=P + 0x1000, rs=P, cs=P + 0x3000) == -8
+    assert call(t=P, c=P + 0x1000, rs=P + 0x2000, cs=P + 0x1000) == -8
 
 
 def test_kernel_analysis_argument_errors(cq):
@@ -179,6 +189,7 @@ def test_fp6_argument_errors(cq):
     assert q(P, 4, 128, 128, P, P, 1.5, P, None, P, P, None, None) == -4
     assert q(P, 4, 64, 64, P, P, 0.15, P, None, P, P, None, None) == -6
     assert q(P, 4, 128, 128, P, P, 0.15, P + 8, None, P, P, None, None) == -6
+    assert q(P, 4, 128, 128, P, P + 0x1000, 0.15, P, None, P, P + 0x3000, None, None) == -8
     g = cq.raw.crossquant_w4a4_linear
 
     def call(qx=P, rs=P, qw=P, ws=P, T=4, I=128, O=8, Y=P, ldy=8, acc=None):
