@@ -73,10 +73,13 @@ int crossquant_absmax(const void *X, int64_t T, int64_t I, int64_t ldx, float *t
  * row_scale: out, float[T] (a).  col_scale: out, float[I] (b).  Required: the linear layer and
  *        the weight folding consume them.  They must not overlap t or c (CQ_ERR_ALIAS): the one
  *        kernel of this call reads t and c in every block while some blocks write a and b.
- * zero_count: out, nullable, one unsigned 64-bit counter.  It is accumulated in one word of
- *        library-owned device memory per device and stored by the last block to finish, so calls
- *        that count must not overlap on one device (use one stream, or order them with events);
- *        the same holds for the batched, FP6 and count-only forms below.
+ * zero_count: out, nullable, one unsigned 64-bit counter.  It is accumulated in a word of
+ *        library-owned device memory and stored by the last block to finish.  Every stream handle
+ *        gets a word of its own (16 per process; calls on further streams, and on the per-thread
+ *        default stream, clear the caller's counter with a small kernel first and add to it
+ *        directly), so calls on different streams may overlap.  A call captured into a graph keeps
+ *        the word of the stream it was captured on: replays of that graph must not overlap each
+ *        other or calls on that stream.  The same holds for the batched, FP6 and count-only forms.
  */
 int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
                         const float *c, float alpha, int bits, void *codes, void *xhat,

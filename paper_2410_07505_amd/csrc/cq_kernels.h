@@ -22,6 +22,12 @@ __device__ __forceinline__ float rounded_f32(float v) {
     return v;
 }
 
+// Library-owned device state comes in kStateSlots pieces; a stream keeps the slot it is given on
+// first use (-1: none left, or a handle that stands for several streams -- the caller then takes
+// the path that clears its accumulators with a kernel of its own first).
+constexpr int kStateSlots = 16;
+int stream_slot(hipStream_t stream);
+
 // t[0..T), c[0..I) <- 0 ; then one pass over X accumulating both maxima.
 // B matrices of T rows, matrix_stride elements apart (B = 1: a plain matrix); t is [B*T], c is [B*I].
 hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, float* t,

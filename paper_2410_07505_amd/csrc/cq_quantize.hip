@@ -38,14 +38,14 @@ __global__ void scale_finalize_kernel(const float* __restrict__ t, const float* 
 constexpr int kWaves = 8;   // waves per block
 constexpr int kU = 4;       // rows a wave has in flight
 
-// Zero-count accumulator of the quantize kernel: library-owned, one per device, zero between
-// launches.  Bits 0..40 hold the running count (at most 2^40 elements), bits 41..63 the number
-// of blocks that have added theirs.  The block whose add brings the second field to the grid
-// size knows the total, stores it to the caller's counter and clears the accumulator again, so
-// no kernel has to run beforehand to clear anything.
+// Zero-count accumulators of the quantize kernel: library-owned (one array per device, one word
+// per stream slot), zero between launches.  Bits 0..40 hold the running count (at most 2^40
+// elements), bits 41..63 the number of blocks that have added theirs.  The block whose add
+// brings the second field to the grid size knows the total, stores it to the caller's counter
+// and clears the accumulator again, so no kernel has to run beforehand to clear anything.
 constexpr int kTicketShift = 41;
 constexpr unsigned kMaxTicketBlocks = 1u << (64 - kTicketShift);
-__device__ unsigned long long g_zero_state;
+__device__ unsigned long long g_zero_state[kStateSlots];
 
 __global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
 
@@ -66,7 +66,7 @@ __global__ void __launch_bounds__(kWaves * kLanes)
 quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ t_vec,
                 const float* __restrict__ c_vec, double alpha, int qmax_i, float* __restrict__ a_out,
                 float* __restrict__ b_out, uint8_t* __restrict__ codes, uint16_t* __restrict__ xhat,
-                unsigned long long* __restrict__ zero_count, bool ticket,
+                unsigned long long* __restrict__ zero_count, int slot,
                 int n_col_chunks, int nb, bool out_vec, int blocks_per_matrix, int64_t matrix_stride) {
     __shared__ uint32_t lds_cnt[kWaves];
     __shared__ float lds_b[kColsPerWave];
@@ -164,8 +164,8 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) s += lds_cnt[w];
             // one atomic per block: same-address atomics serialise, so the grid is kept small
-            if (ticket) {
-                unsigned long long* zero_state = &g_zero_state;
+            if (slot >= 0) {
+                unsigned long long* zero_state = &g_zero_state[slot];
                 const unsigned long long add = (1ull << kTicketShift) | (unsigned long long)s;
                 const unsigned long long old =
                     __hip_atomic_fetch_add(zero_state, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -195,8 +195,9 @@ hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int6
     // vector stores need every lane's piece aligned: I % 8 == 0 and aligned bases
     const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 8 == 0) &&
                          (reinterpret_cast<uintptr_t>(xhat) % 16 == 0);
-    const bool state = n_blocks < kMaxTicketBlocks;
-    if (zc && !state) zero_u64_kernel<<<dim3(1), dim3(1), 0, stream>>>(zc);   // more blocks than the block field counts
+    // no slot, or more blocks than the block field counts: clear the caller's counter and add to it directly
+    const int state = (zc && n_blocks < kMaxTicketBlocks) ? stream_slot(stream) : -1;
+    if (zc && state < 0) zero_u64_kernel<<<dim3(1), dim3(1), 0, stream>>>(zc);
     if (vec)
         quantize_kernel<MODE, XHAT, true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, alpha, qmax, a, b, codes, xhat,
                                                                      zc, state, ncc, nb, out_vec, ncc * nrc,

@@ -305,6 +305,44 @@ def test_extreme_aspect_ratios(cq, T, I):
     check_analysis(cq, X, 0.15, 8, label="aspect")
 
 
+@pytest.mark.parametrize("T,I", [(270000, 8), (4, 262200)])
+def test_very_long_maxima_vectors(cq, T, I):
+    """More than 2^18 rows, or columns: thousands of row chunks / column chunks in one launch."""
+    X = outliers(T, I, seed=3 + T % 11)
+    check_quantize(cq, X, 0.15, 8, label="long vectors")
+
+
+def test_calls_overlapping_on_many_streams(cq):
+    """Calls on different streams may run at the same time; each stream has its own word of the
+    library-owned zero-count accumulators (more streams than words: the rest clear the caller's
+    counter with a kernel first).  Everything is enqueued first, then checked."""
+    import torch
+    say("20 streams, absmax + quantize + count enqueued without waiting")
+    n = 20
+    streams = [torch.cuda.Stream() for _ in range(n)]
+    Xs = [outliers(200 + 37 * k, 600 + 130 * k, seed=700 + k) for k in range(n)]
+    Xg = [gpu(X) for X in Xs]
+    torch.cuda.synchronize()
+    out = []
+    for rep in range(2):                      # second round: every stream reuses its piece
+        for k, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                t, c = cq.crossquant_absmax(Xg[k])
+                res = cq.crossquant_quantize(Xg[k], t, c, 0.15, 8)
+                zc = cq.crossquant_kernel_count(Xg[k], t, c, 1.0, 8)
+            if rep == 1:
+                out.append((t, c, res, zc))
+    torch.cuda.synchronize()
+    for k in range(n):
+        t_ref, c_ref = oracle.absmax(Xs[k])
+        ref = oracle.quantize(Xs[k], t_ref, c_ref, 0.15, 8)
+        t, c, (codes, xhat, a, b, z), zc = out[k]
+        assert np.array_equal(bits32(host(t)), bits32(t_ref)) and np.array_equal(bits32(host(c)), bits32(c_ref)), k
+        assert np.array_equal(host(codes), ref["codes"]) and int(host(z)[0]) == ref["Z"], k
+        assert np.array_equal(bits16(host(xhat)), bits16(ref["xhat"])), k
+        assert int(host(zc)[0]) == oracle.kernel_count(Xs[k], t_ref, c_ref, 1.0, 8), k
+
+
 def test_wide_leading_dimension(cq):
     """A narrow window of a very wide matrix: rows 64 KiB apart."""
     import torch
