@@ -9,6 +9,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -96,7 +97,10 @@ __device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, c
         const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
         if (row0 + trow < T && col0 + piece * 8 < O) {
             uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
-            *reinterpret_cast<uint4*>(dst) = v;
+            // non-temporal: Y is not read again here, and whole 128-byte pieces leave at once.  The GEMM
+            // itself does not care, but the memory-side cache is left with fewer dirty lines, so the
+            // kernel that runs next reads its cold input faster (64 MiB: 4 us less).
+            __builtin_nontemporal_store(u32x4v{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4v*>(dst));
         }
     }
 }
