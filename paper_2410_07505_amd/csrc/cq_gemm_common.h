@@ -97,10 +97,16 @@ __device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, c
         const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
         if (row0 + trow < T && col0 + piece * 8 < O) {
             uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
-            // non-temporal: Y is not read again here, and whole 128-byte pieces leave at once.  The GEMM
-            // itself does not care, but the memory-side cache is left with fewer dirty lines, so the
-            // kernel that runs next reads its cold input faster (64 MiB: 4 us less).
-            __builtin_nontemporal_store(u32x4v{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4v*>(dst));
+            // Y is not read again here and whole 128-byte pieces leave at once: written through to memory
+            // as a stream (sc1 nt).  The GEMM itself does not care, but the memory-side cache is left
+            // without 224 MiB of dirty lines, so the kernel that runs next reads its cold input faster
+            // (64 MiB: 4 us less; of the policies tried -- plain, nt, sc1, sc1 nt, sc0 nt, sc0 sc1 nt --
+            // this one gave the shortest following absmax + quantize calls).
+            // (The compiler offers no way to ask for this policy, hence the assembly; it cannot see a
+            // store in it, so the two wait states the hardware needs before the data registers of a
+            // 16-byte store may be overwritten are added by hand.)
+            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(u32x4v{v.x, v.y, v.z, v.w})
+                         : "memory");
         }
     }
 }
