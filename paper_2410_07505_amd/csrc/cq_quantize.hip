@@ -57,8 +57,7 @@ __global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
 // is requested before, so the memory system is busy meanwhile); the blocks of column chunk 0 /
 // row chunk 0 also write them to a_out / b_out for the caller.  Every block that needs a factor
 // computes the same bits from the same inputs, so no kernel has to run beforehand.
-// The dequantized matrix is written with non-temporal stores (nothing reads it back), the codes
-// with plain ones (the matrix kernel reads them next).
+// Codes and the dequantized matrix are written through to memory (store_through).
 // A batch of B matrices (each with its own column factors) is one launch: B copies of the
 // one-matrix grid; a block first steps its pointers to its own matrix.
 template <int MODE, bool XHAT, bool VEC>
