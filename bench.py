@@ -32,7 +32,7 @@ METRIC = "CrossQuant quantize GB/s (% HBM peak) + W8A8 linear TOPS (% INT8 MFMA 
 # counters read for a plain copy of known size (profiles/bench_c5_hbm_traffic_pmc.txt).  Measured
 # once per workload; null for workloads that have not been profiled.
 MEASURED_TRAFFIC_BYTES = {
-    "C5": {"gemm": (1347.6 + 224.0) * 2 ** 20, "quantize": (64.4 + 96.2) * 2 ** 20},
+    "C5": {"gemm": (1344.9 + 224.0) * 2 ** 20, "quantize": (64.4 + 96.1) * 2 ** 20},
 }
 
 
