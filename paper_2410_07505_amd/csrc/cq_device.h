@@ -93,7 +93,12 @@ __device__ __forceinline__ float safe_rcp(float v) { return (v == 0.0f) ? 0.0f :
 
 __device__ __forceinline__ float half_lo(uint32_t w) { return h2f(w & 0xFFFFu); }
 __device__ __forceinline__ float half_hi(uint32_t w) { return h2f(w >> 16); }
-__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) { return f2h(lo) | (f2h(hi) << 16); }
+// two binary32 values -> packed binary16 pair, each rounded to nearest even (one v_cvt_pk_f16_f32)
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
+}
 
 // Output stores of the streaming kernels: written through to memory at device scope (sc1) instead
 // of being left dirty in the caches.  Measured on the 4096 x 8192 layer against plain and
@@ -159,6 +164,50 @@ __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, con
             m[e] = rt + kMagic;
         }
     }
+}
+
+// Count-only form of quantize8: how many of the wave's 8 x 64 elements of one row have a non-zero code.
+// q = rne(fl32(x / fl32(a b))) is 0 exactly when the quotient is at most 1/2 (a tie rounds to the even
+// 0), so the sign of d = fma(|x|, 1/b, -a/2) decides, unless the two sides are within 2^-20 of each
+// other: |x| / b differs from (x / fl32(a b)) a by at most 2^-22 relative (reciprocal, rounding of
+// a b, the quotient's own rounding; the fma's single rounding never changes its sign).  A wave in
+// which any lane comes that close, or has a factor so small that products leave the normal range,
+// recounts the row piece with the exact division.  ha = a / 2 (exact), tol = ha * 2^-19.
+__device__ __forceinline__ uint32_t count_row8_wave(const uint4& v, float a, float ha, float tol, const float (&b)[8],
+                                                    const float (&rb)[8], float qmax, bool tiny) {
+    float x[8];
+    x[0] = half_lo(v.x); x[1] = half_hi(v.x);
+    x[2] = half_lo(v.y); x[3] = half_hi(v.y);
+    x[4] = half_lo(v.z); x[5] = half_hi(v.z);
+    x[6] = half_lo(v.w); x[7] = half_hi(v.w);
+    uint32_t nz = 0u;
+    unsigned long long close = 0ull;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float d = __builtin_fmaf(__builtin_fabsf(x[e]), rb[e], -ha);
+        nz += (uint32_t)__builtin_popcountll(__ballot(d > 0.0f));
+        close |= __ballot(__builtin_fabsf(d) <= tol);
+    }
+    if (close != 0ull || __any(tiny)) {                 // rare: exact division for this wave's row piece
+        nz = 0u;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float D = a * b[e];
+            float rt = (D == 0.0f) ? 0.0f : x[e] / D;
+            rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
+            nz += (uint32_t)__builtin_popcountll(__ballot(rt + kMagic != kMagic));
+        }
+    }
+    return nz;
+}
+
+// number of non-zero codes among the whole wave's m[0..8): one compare per element, the counting is
+// scalar (population count of the compare mask).  Only active lanes are counted.
+__device__ __forceinline__ uint32_t count_nonzero8_wave(const float (&m)[8]) {
+    uint32_t nz = 0u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) nz += (uint32_t)__builtin_popcountll(__ballot(m[e] != kMagic));
+    return nz;
 }
 
 // number of non-zero codes among m[0..8) (as a float: exact far below 2^24)

@@ -36,7 +36,7 @@ __global__ void scale_finalize_kernel(const float* __restrict__ t, const float* 
 }
 
 constexpr int kWaves = 8;   // waves per block
-constexpr int kU = 4;       // rows a wave has in flight
+constexpr int kU = 4;       // rows a wave has in flight (8 and 16 measured slower, also for the count-only form)
 
 // Zero-count accumulators of the quantize kernel: library-owned (one array per device, one word
 // per stream slot), zero between launches.  Bits 0..40 hold the running count (at most 2^40
@@ -52,10 +52,10 @@ __global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
 // MODE 0: count only; 1: INT8 codes; 2: packed INT4 codes; 3: INT4 codes as FP6 fragments (one matrix,
 // I % 64 == 0).
 // Block: 8 waves sharing 512 columns; each wave streams over nb batches of 4 consecutive rows.
-// The block first forms the scale factors of its own rows and columns from t and c (binary64
-// pow, one per thread for the columns, one per lane for a wave's rows; the first batch of X rows
-// is requested before, so the memory system is busy meanwhile); the blocks of column chunk 0 /
-// row chunk 0 also write them to a_out / b_out for the caller.  Every block that needs a factor
+// The block first forms the scale factors of its own columns and rows from t and c (binary64
+// pow: thread k takes column k, then row k if the block has that many rows; the first batch of X
+// rows is requested before, so the memory system is busy meanwhile) and shares them through LDS;
+// the blocks of column chunk 0 / row chunk 0 also write them to a_out / b_out for the caller.  Every block that needs a factor
 // computes the same bits from the same inputs, so no kernel has to run beforehand.
 // Codes and the dequantized matrix are written through to memory (store_through).
 // A batch of B matrices (each with its own column factors) is one launch: B copies of the
@@ -69,6 +69,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
                 int n_col_chunks, int nb, bool out_vec, int blocks_per_matrix, int64_t matrix_stride) {
     __shared__ uint32_t lds_cnt[kWaves];
     __shared__ float lds_b[kColsPerWave];
+    __shared__ float lds_a[kWaves * kLanes];                // row factors of the block's (at most 512) rows
     const int lane = threadIdx.x & (kLanes - 1);
     const int wave = threadIdx.x / kLanes;
     const int matrix = blockIdx.x / blocks_per_matrix;
@@ -85,7 +86,8 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const int row_chunk = blk / n_col_chunks;
     const int j0 = col_chunk * kColsPerWave + lane * 8;
     const int rows_per_wave = nb * kU;                      // <= 64
-    const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
+    const int rows_per_block = kWaves * rows_per_wave;      // <= 512 = the block's thread count
+    const int row0 = row_chunk * rows_per_block + wave * rows_per_wave;
     const float qmax = (float)qmax_i;
 
     // first batch of rows: in flight while the scale factors are formed
@@ -95,7 +97,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
         v[u] = (row0 + u < T) ? load8<VEC>(X + (int64_t)(row0 + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
 
     {
-        // thread k of the block: column k of the chunk
+        // thread k of the block: column k of the chunk, and row k of the block
         const int j = col_chunk * kColsPerWave + (int)threadIdx.x;
         float bj = 0.0f;
         if (j < I) {
@@ -103,14 +105,17 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             if (row_chunk == 0) b_out[j] = bj;
         }
         lds_b[threadIdx.x] = bj;
-    }
-    // the wave's row factors, one per lane, handed out with readlane as the rows come up
-    float a_lane = 0.0f;
-    if (lane < rows_per_wave && row0 + lane < T) {
-        a_lane = row_factor(t_vec[row0 + lane], alpha, qmax_i);
-        if (col_chunk == 0) a_out[row0 + lane] = a_lane;
+        const int r = row_chunk * rows_per_block + (int)threadIdx.x;
+        float ar = 0.0f;
+        if ((int)threadIdx.x < rows_per_block && r < T) {
+            ar = row_factor(t_vec[r], alpha, qmax_i);
+            if (col_chunk == 0) a_out[r] = ar;
+        }
+        lds_a[threadIdx.x] = ar;
     }
     __syncthreads();
+    // the wave's row factors, one per lane, handed out with readlane as the rows come up
+    const float a_lane = lds_a[wave * rows_per_wave + (lane < rows_per_wave ? lane : 0)];
 
     float b[8], rb[8];
 #pragma unroll
@@ -124,7 +129,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     int nvalid = I - j0;                                    // columns of this lane that exist
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
 
-    float nonzero = 0.0f;     // codes != 0 seen by this lane (exact: far below 2^24)
+    uint32_t nonzero = 0u;    // codes != 0 seen by this wave (uniform)
     int rows_done = 0;
     for (int bi = 0; bi < nb; ++bi) {
         const int rbase = row0 + bi * kU;
@@ -141,9 +146,15 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             ++rows_done;
             const float a = __builtin_bit_cast(
                 float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), bi * kU + u));
+            if (MODE == 0) {
+                // a == 0 means D = 0 and every code of the row is 0 by definition: left to the exact path
+                nonzero += count_row8_wave(v[u], a, 0.5f * a, 0.5f * a * kTieTol, b, rb, qmax,
+                                           b_tiny || tiny_factor(a) || a == 0.0f);
+                continue;
+            }
             float m[8];
             quantize8(v[u], a, safe_rcp(a), b, rb, qmax, m, b_tiny || tiny_factor(a));
-            nonzero += count_nonzero8(m);
+            nonzero += count_nonzero8_wave(m);
             if (MODE == 1) store_codes_i8(m, codes + (int64_t)r * I + j0, out_vec, nvalid);
             if (MODE == 2) store_codes_i4(m, codes + (int64_t)r * (I / 2) + j0 / 2, out_vec, nvalid);
             if (MODE == 3) store_codes_fp6(m, codes, r, col_chunk * kColsPerWave, lane, I / 64, j0 < I);
@@ -152,10 +163,10 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     }
 
     if (zero_count) {
-        // padded columns and rows hold x = 0 and add nothing to `nonzero`
-        uint32_t zeros = (uint32_t)(rows_done * nvalid) - (uint32_t)nonzero;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) zeros += (uint32_t)__shfl_xor((int)zeros, off, kLanes);
+        // padded columns hold x = 0 and add nothing to `nonzero`
+        int wave_cols = I - col_chunk * kColsPerWave;       // columns of this wave that exist
+        wave_cols = wave_cols > kColsPerWave ? kColsPerWave : wave_cols;
+        const uint32_t zeros = (uint32_t)(rows_done * wave_cols) - nonzero;
         if (lane == 0) lds_cnt[wave] = zeros;
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -184,7 +195,8 @@ hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int6
                        const float* c, double alpha, int qmax, float* a, float* b, uint8_t* codes, uint16_t* xhat,
                        unsigned long long* zc, hipStream_t stream) {
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
-    // rows per block = 32 * nb; keep about 512 blocks in flight
+    // rows per block = 32 * nb; keep about 512 blocks in flight (256, 1024 and 2048 measured slower, also for
+    // the count-only form: every block ends with one atomic on the same word)
     int nb = 16;
     while (nb > 1 && (int64_t)B * ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);

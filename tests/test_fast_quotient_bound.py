@@ -53,3 +53,39 @@ def test_rounding_can_only_differ_near_a_tie():
             frac = np.abs(r - np.rint(r))
             fires = frac + np.abs(r) * 2.0 ** -19 >= 0.5 - 1e-12
             assert not np.any(differs & ~fires)
+
+
+def test_count_only_sign_test_agrees_with_the_exact_code_unless_flagged():
+    """The count-only kernel decides "code == 0" from the sign of d = fma(|x|, rb, -a/2) and takes
+    the exact division whenever |d| <= (a/2) * 2^-19.  Model of that test in numpy (the fma is
+    formed exactly in binary64 and rounded once), with the reciprocal perturbed by +-1 ulp, on
+    inputs steered towards the boundary quotient 1/2: wherever the flag is not raised the sign
+    test must agree with rne(fl32(x / fl32(a b))) == 0."""
+    rng = np.random.default_rng(321)
+    n = 300_000
+    a = np.exp(rng.uniform(-10, 3, n)).astype(np.float32)
+    b = np.exp(rng.uniform(-5, 5, n)).astype(np.float32)
+    D = (a * b).astype(np.float32)
+    # |x| / D close to 1/2: relative offsets from 2^-26 to 2^-12 on either side, and exact halves
+    off = np.exp(rng.uniform(np.log(2.0 ** -26), np.log(2.0 ** -12), n)) * rng.choice([-1.0, 1.0], n)
+    off[: n // 20] = 0.0
+    x = (0.5 * D.astype(np.float64) * (1.0 + off)).astype(np.float32)      # binary32 stands in for the data grid
+    q_exact = np.rint((x / D).astype(np.float32).astype(np.float64))        # rint: ties to even, as the kernel
+    is_zero = q_exact == 0
+    rb0 = (np.float32(1.0) / b).astype(np.float32)
+    ha = (np.float32(0.5) * a).astype(np.float32)
+    tol = (ha * np.float32(2.0 ** -19)).astype(np.float32)
+    flagged_total = 0
+    for db in (-1, 0, 1):
+        rb = ulp_shift(rb0, db)
+        d = (np.abs(x).astype(np.float64) * rb.astype(np.float64) - ha.astype(np.float64)).astype(np.float32)
+        flagged = np.abs(d) <= tol
+        says_zero = ~(d > 0)
+        wrong = (says_zero != is_zero) & ~flagged
+        assert not wrong.any(), (int(wrong.sum()), db)
+        flagged_total += int(flagged.sum())
+    # the flag is a narrow band, not a catch-all: offsets beyond 2^-17 never raise it
+    far = np.abs(off) > 2.0 ** -17
+    d = (np.abs(x).astype(np.float64) * rb0.astype(np.float64) - ha.astype(np.float64)).astype(np.float32)
+    assert not (np.abs(d[far]) <= tol[far]).any()
+    assert flagged_total > 0
