@@ -123,7 +123,7 @@ __device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_
     return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
 }
 
-// ---- one lane's 8 elements of one row.  On return m[e] = kMagic + q_e with
+// ---- one lane's 8 elements of one row.  On return q[e] = q_e and m[e] = kMagic + q_e with
 // q_e = clamp(rne(fl32(x_e / fl32(a * b[e]))), +-qmax), identical to dividing every element.
 // The quotient is first approximated as x * (1/a) * (1/b) (ra, rb: reciprocals within 1 ulp, 0
 // where the factor is 0), which lies within 2^-21 relative of the correctly rounded quotient
@@ -140,7 +140,8 @@ constexpr float kTinyFactor = 8.673617379884035e-19f;   // 2^-60: both products 
 __device__ __forceinline__ bool tiny_factor(float f) { return f != 0.0f && f < kTinyFactor; }
 
 __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, const float (&b)[8],
-                                          const float (&rb)[8], float qmax, float (&m)[8], bool tiny) {
+                                          const float (&rb)[8], float qmax, float (&m)[8], float (&q)[8],
+                                          bool tiny) {
     float x[8];
     x[0] = half_lo(v.x); x[1] = half_hi(v.x);
     x[2] = half_lo(v.y); x[3] = half_hi(v.y);
@@ -152,7 +153,8 @@ __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, con
         float rt = x[e] * (ra * rb[e]);
         rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
         m[e] = rt + kMagic;
-        const float f = rt - (m[e] - kMagic);
+        q[e] = m[e] - kMagic;
+        const float f = rt - q[e];
         score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)));
     }
     if (__any(score >= 0.5f || tiny)) {                 // rare: exact division for this wave's row piece
@@ -162,6 +164,7 @@ __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, con
             float rt = (D == 0.0f) ? 0.0f : x[e] / D;
             rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
             m[e] = rt + kMagic;
+            q[e] = m[e] - kMagic;
         }
     }
 }
@@ -287,11 +290,11 @@ __device__ __forceinline__ void store_codes_fp6(const float (&m)[8], uint8_t* pa
 }
 
 // dequantized values fl16(fl32(q * fl32(a * b))): 16 bytes at dst
-__device__ __forceinline__ void store_xhat(const float (&m)[8], float a, const float (&b)[8], uint16_t* dst,
+__device__ __forceinline__ void store_xhat(const float (&q)[8], float a, const float (&b)[8], uint16_t* dst,
                                            bool vec_ok, int nvalid) {
     float y[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) y[e] = rounded_f32((m[e] - kMagic) * (a * b[e]));
+    for (int e = 0; e < 8; ++e) y[e] = rounded_f32(q[e] * (a * b[e]));
     if (vec_ok && nvalid == 8) {
         store_through(u32x4{pack_half2(y[0], y[1]), pack_half2(y[2], y[3]), pack_half2(y[4], y[5]), pack_half2(y[6], y[7])},
                       reinterpret_cast<u32x4*>(dst));

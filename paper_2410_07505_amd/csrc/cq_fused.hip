@@ -212,14 +212,14 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
         if (row0 + k < T) {                            // wave-uniform
             ++rows_done;
             const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), k));
-            float m[8];
+            float m[8], q[8];
             const uint4 xv = (k < kFRegRows) ? v[k < kFRegRows ? k : 0] : lds_tile[(k - kFRegRows) * kFThreads + threadIdx.x];
-            quantize8(xv, a, safe_rcp(a), b, rb, qmax, m, false);
+            quantize8(xv, a, safe_rcp(a), b, rb, qmax, m, q, false);
             nonzero += count_nonzero8(m);
             if (col_ok) {
                 if (MODE == 1) store_codes_i8(m, cp, true, 8);
                 if (MODE == 2) store_codes_i4(m, cp, true, 8);
-                if (XHAT) store_xhat(m, a, b, hp, true, 8);
+                if (XHAT) store_xhat(q, a, b, hp, true, 8);
             }
         }
         cp += c_step;

@@ -90,11 +90,15 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const int row0 = row_chunk * rows_per_block + wave * rows_per_wave;
     const float qmax = (float)qmax_i;
 
-    // first batch of rows: in flight while the scale factors are formed
-    uint4 v[kU];
+    // first two batches of rows: in flight while the scale factors are formed
+    uint4 v[kU], w[kU];
 #pragma unroll
     for (int u = 0; u < kU; ++u)
         v[u] = (row0 + u < T) ? load8<VEC>(X + (int64_t)(row0 + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int u = 0; u < kU; ++u)
+        w[u] = (nb > 1 && row0 + kU + u < T) ? load8<VEC>(X + (int64_t)(row0 + kU + u) * ldx, j0, I)
+                                              : make_uint4(0u, 0u, 0u, 0u);
 
     {
         // thread k of the block: column k of the chunk, and row k of the block
@@ -134,7 +138,10 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     for (int bi = 0; bi < nb; ++bi) {
         const int rbase = row0 + bi * kU;
         if (rbase >= T) break;                              // wave-uniform
-        if (bi > 0) {
+        if (bi == 1) {
+#pragma unroll
+            for (int u = 0; u < kU; ++u) v[u] = w[u];
+        } else if (bi > 1) {
 #pragma unroll
             for (int u = 0; u < kU; ++u)
                 v[u] = (rbase + u < T) ? load8<VEC>(X + (int64_t)(rbase + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
@@ -152,13 +159,13 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
                                            b_tiny || tiny_factor(a) || a == 0.0f);
                 continue;
             }
-            float m[8];
-            quantize8(v[u], a, safe_rcp(a), b, rb, qmax, m, b_tiny || tiny_factor(a));
+            float m[8], q[8];
+            quantize8(v[u], a, safe_rcp(a), b, rb, qmax, m, q, b_tiny || tiny_factor(a));
             nonzero += count_nonzero8_wave(m);
             if (MODE == 1) store_codes_i8(m, codes + (int64_t)r * I + j0, out_vec, nvalid);
             if (MODE == 2) store_codes_i4(m, codes + (int64_t)r * (I / 2) + j0 / 2, out_vec, nvalid);
             if (MODE == 3) store_codes_fp6(m, codes, r, col_chunk * kColsPerWave, lane, I / 64, j0 < I);
-            if (XHAT) store_xhat(m, a, b, xhat + (int64_t)r * I + j0, out_vec, nvalid);
+            if (XHAT) store_xhat(q, a, b, xhat + (int64_t)r * I + j0, out_vec, nvalid);
         }
     }
 
