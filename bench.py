@@ -387,7 +387,7 @@ def main():
                      "bound": "mfma", "achieved": tops, "peak": mfma_peak, "unit": "TOP/s",
                      "frac": tops / mfma_peak if tops else None,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},
-        "roofline_quantize": {"kernel": "quantize_kernel (codes + xhat + zero count) incl. scale finalize",
+        "roofline_quantize": {"kernel": "quantize_kernel (scale factors + codes + xhat + zero count)",
                               "bound": "hbm",
                               "achieved": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
                               "peak": HBM_PEAK_GBS, "unit": "GB/s",
