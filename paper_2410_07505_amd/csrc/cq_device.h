@@ -127,11 +127,15 @@ __device__ __forceinline__ uint32_t pack_bytes(uint32_t u0, uint32_t u1, uint32_
 // q_e = clamp(rne(fl32(x_e / fl32(a * b[e]))), +-qmax), identical to dividing every element.
 // The quotient is first approximated as x * (1/a) * (1/b) (ra, rb: reciprocals within 1 ulp, 0
 // where the factor is 0), which lies within 2^-21 relative of the correctly rounded quotient
-// (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own; 2^-20.7 even if each
-// reciprocal were a further half ulp off); the rounded
-// integer can differ from the exact one only if the approximation lies within that distance of
-// a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2 (a 3x to 4x margin) and a wave in
-// which any lane trips recomputes its eight elements with the exact division.
+// (two reciprocals at 2^-23, the rounding of their product and of a * b at 2^-24, and the
+// quotient's own; 2^-20.7 even if each reciprocal were a further half ulp off).  The product is
+// never formed on its own: fma(x, k, 1.5 * 2^23) rounds it straight to the nearest-even integer
+// (the sum's ulp is 1), q = that - 1.5 * 2^23 is the code, and a second fma, x * k - q, gives the
+// distance from it.  The integer can differ from the exact one only if the approximation lies
+// within the bound of a rounding tie k + 1/2: lanes test |x k - q| + (|q| + 1) * 2^-19 >= 1/2
+// (a 3x to 4x margin) and also |q| > qmax (a code that needs clamping: only with caller-supplied
+// maxima below the data's), and a wave in which any lane trips recomputes its eight elements with
+// the exact division and the clamp.  Both fmas read the binary16 value directly (v_fma_mix_f32).
 // The bound needs ra * rb and a * b to be normal numbers: `tiny` (any factor of this lane's piece
 // below kTinyFactor, possible only with caller-supplied maxima far below anything binary16 data
 // can produce) sends the piece to the exact division as well.
@@ -142,26 +146,27 @@ __device__ __forceinline__ bool tiny_factor(float f) { return f != 0.0f && f < k
 __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, const float (&b)[8],
                                           const float (&rb)[8], float qmax, float (&m)[8], float (&q)[8],
                                           bool tiny) {
-    float x[8];
-    x[0] = half_lo(v.x); x[1] = half_hi(v.x);
-    x[2] = half_lo(v.y); x[3] = half_hi(v.y);
-    x[4] = half_lo(v.z); x[5] = half_hi(v.z);
-    x[6] = half_lo(v.w); x[7] = half_hi(v.w);
-    float score = 0.0f;                                 // max over the 8 elements of |frac| + |r| * tol
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    _Float16 h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = __builtin_bit_cast(_Float16, (unsigned short)(w[e >> 1] >> (16 * (e & 1))));
+    float score = 0.0f;                                 // max over the 8 elements of |x k - q| + |q| * tol
+    float big = 0.0f;                                   // max over the 8 elements of |q|
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        float rt = x[e] * (ra * rb[e]);
-        rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
-        m[e] = rt + kMagic;
+        const float k = ra * rb[e];
+        m[e] = __builtin_fmaf((float)h[e], k, kMagic);
         q[e] = m[e] - kMagic;
-        const float f = rt - q[e];
-        score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(rt), kTieTol, __builtin_fabsf(f)));
+        const float f = __builtin_fmaf((float)h[e], k, -q[e]);
+        score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(q[e]), kTieTol, __builtin_fabsf(f)));
+        big = __builtin_fmaxf(big, __builtin_fabsf(q[e]));
     }
-    if (__any(score >= 0.5f || tiny)) {                 // rare: exact division for this wave's row piece
+    // !(big <= qmax) also catches a NaN from an overflowed product
+    if (__any(score >= 0.5f - kTieTol || !(big <= qmax) || tiny)) {     // rare: exact division for this wave's row piece
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float D = a * b[e];
-            float rt = (D == 0.0f) ? 0.0f : x[e] / D;
+            float rt = (D == 0.0f) ? 0.0f : (float)h[e] / D;
             rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
             m[e] = rt + kMagic;
             q[e] = m[e] - kMagic;

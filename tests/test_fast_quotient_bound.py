@@ -1,7 +1,7 @@
 """The error bound the quantize kernel's fast quotient relies on, checked on the CPU.
 
 The kernel replaces fl32(x / fl32(a * b)) by x * (ra * rb) with ra, rb reciprocals accurate to
-1 ulp, and falls back to the exact division whenever |frac| + |r| * 2^-19 >= 1/2.  That is sound
+1 ulp, and falls back to the exact division whenever |frac| + (|q| + 1) * 2^-19 >= 1/2.  That is sound
 if the approximation stays within 2^-19 (relative) of the correctly rounded quotient; the
 analysis gives 2^-20 (two reciprocals at up to 1.5 * 2^-23 each as modelled here, three roundings
 at 2^-24, and the quotient's own).  Here the bound is measured with numpy binary32 arithmetic, with
@@ -41,17 +41,21 @@ def test_fast_quotient_stays_within_the_fallback_margin():
 
 
 def test_rounding_can_only_differ_near_a_tie():
-    """If |approx - exact| <= 2^-20 * |exact| (the bound above) then rne(approx) != rne(exact)
-    implies the kernel's tie test fires for approx: brute force on quotients around every tie."""
+    """The kernel rounds the approximate quotient p = x * (ra * rb) straight to an integer q (one
+    fma against 1.5 * 2^23), forms p - q with a second fma and falls back to the exact division when
+    |p - q| + (|q| + 1) * 2^-19 >= 1/2.  If |p - exact| <= 2^-20 * |exact| (the bound above) then
+    q != rne(exact) implies that the test fires: brute force on quotients around every tie,
+    including the first one, where q may be 0."""
     ks = np.arange(0, 127, dtype=np.float64) + 0.5
+    tol = 2.0 ** -19
     for eps in (2.0 ** -20, -(2.0 ** -20), 2.0 ** -22, -(2.0 ** -22)):
         for off in np.linspace(-3e-5, 3e-5, 241):
             exact = ks * (1 + off)
-            approx = (exact * (1 + eps)).astype(np.float32)
-            differs = np.rint(approx.astype(np.float64)) != np.rint(exact)
-            r = approx.astype(np.float64)
-            frac = np.abs(r - np.rint(r))
-            fires = frac + np.abs(r) * 2.0 ** -19 >= 0.5 - 1e-12
+            p = exact * (1 + eps)                              # the product inside the fma is exact
+            q = np.rint(p)
+            differs = q != np.rint(exact)
+            f = (p - q).astype(np.float32).astype(np.float64)  # the second fma rounds once
+            fires = np.abs(f) + np.abs(q) * tol >= 0.5 - tol
             assert not np.any(differs & ~fires)
 
 
