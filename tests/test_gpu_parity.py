@@ -212,6 +212,33 @@ def test_quantize_rounding_ties(cq):
     check_quantize(cq, X4, 0.0, 8, label="ties alpha=0 int8")
 
 
+def test_quotients_just_off_a_rounding_tie(cq):
+    """Calibrated maxima chosen so that every element of row i has the quotient (k_i + 1/2)(1 + d_i)
+    with |d_i| from 2^-24 to 2^-10 on either side: the band in which the fast quotient (and the
+    count-only sign test, for k = 0) must either be right or hand over to the exact division."""
+    import torch
+    ks = np.array([0, 0, 1, 2, 5, 31, 63, 100, 126], dtype=np.float64)
+    ds = np.concatenate([[0.0], 2.0 ** -np.arange(10, 25), -(2.0 ** -np.arange(10, 25))])
+    rows = [(k, d) for k in ks for d in ds]
+    T, I = len(rows), 72
+    rng = np.random.default_rng(11)
+    X = np.full((T, I), 3.0, np.float16)
+    X[:, ::3] = -3.0
+    X[:, 5] = rng.standard_normal(T).astype(np.float16)                  # some ordinary elements too
+    t_cal = np.array([127.0 * 3.0 / ((k + 0.5) * (1.0 + d)) for k, d in rows]).astype(np.float32)
+    c_cal = np.full(I, 3.0, np.float32)
+    Xg = gpu(X)
+    for alpha, tt, cc in ((1.0, t_cal, c_cal), (0.5, t_cal, (c_cal * c_cal / t_cal.mean()).astype(np.float32))):
+        ref = oracle.quantize(X, tt, cc, alpha, 8)
+        say("near ties alpha=%g: %d distinct codes in the reference" % (alpha, len(np.unique(ref["codes"]))))
+        codes, xhat, _, _, zc = cq.crossquant_quantize(Xg, gpu(tt), gpu(cc), alpha, 8)
+        neq = host(codes) != ref["codes"]
+        assert not neq.any(), (alpha, int(neq.sum()), np.argwhere(neq)[:4].tolist())
+        assert np.array_equal(bits16(host(xhat)), bits16(ref["xhat"])) and int(host(zc)[0]) == ref["Z"]
+        zc2 = cq.crossquant_kernel_count(Xg, gpu(tt), gpu(cc), alpha, 8)
+        assert int(host(zc2)[0]) == ref["Z"] == oracle.kernel_count(X, tt, cc, alpha, 8)
+
+
 def test_quantize_golden_cases(cq):
     from test_oracle_pins import read_golden
     for case in read_golden():
