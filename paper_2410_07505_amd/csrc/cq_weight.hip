@@ -33,25 +33,39 @@ weight_colmax_kernel(const uint16_t* __restrict__ W, int I, int O, const float* 
     float m[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) m[e] = 0.0f;
-    for (int jj = 0; jj < RPW; ++jj) {
-        const int j = j_begin + jj;
-        if (j >= I) break;
-        const float f = fold ? fold[j] : 1.0f;
-        const uint16_t* row = W + (int64_t)j * O;
-        uint32_t h[8];
-        if (vec && k0 + 8 <= O) {
-            const uint4 v = *reinterpret_cast<const uint4*>(row + k0);
-            h[0] = v.x & 0xFFFFu; h[1] = v.x >> 16; h[2] = v.y & 0xFFFFu; h[3] = v.y >> 16;
-            h[4] = v.z & 0xFFFFu; h[5] = v.z >> 16; h[6] = v.w & 0xFFFFu; h[7] = v.w >> 16;
-        } else {
+    // batches of 8 rows: all eight loads are issued before the first value is used
+    for (int jb = 0; jb < RPW; jb += 8) {
+        const int j8 = j_begin + jb;
+        if (j8 >= I) break;                              // wave-uniform
+        uint4 v[8];
+        float f[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = (k0 + e < O) ? row[k0 + e] : 0u;
+        for (int r = 0; r < 8; ++r) {
+            const int j = j8 + r;
+            v[r] = make_uint4(0u, 0u, 0u, 0u);
+            f[r] = 1.0f;
+            if (j < I) {
+                const uint16_t* row = W + (int64_t)j * O;
+                if (fold) f[r] = fold[j];
+                if (vec && k0 + 8 <= O) {
+                    v[r] = *reinterpret_cast<const uint4*>(row + k0);
+                } else {
+                    uint32_t h[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) h[e] = (k0 + e < O) ? row[k0 + e] : 0u;
+                    v[r] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+                }
+            }
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float w = half_bits_to_float(h[e]);
-            if (fold) w = f * w;
-            m[e] = __builtin_fmaxf(m[e], __builtin_fabsf(w));
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t w32[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float w = half_bits_to_float((w32[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+                if (fold) w = f[r] * w;
+                m[e] = __builtin_fmaxf(m[e], __builtin_fabsf(w));
+            }
         }
     }
 #pragma unroll
@@ -81,9 +95,21 @@ weight_quant_kernel(const uint16_t* __restrict__ W, int I, int O, const float* _
     const int k_base = kt * 64, j_base = jt * 128;
     const int c8 = threadIdx.x & 7;          // which group of 8 output channels
     const int k0 = k_base + c8 * 8;
-    float sk[8];
+    // The correctly rounded division is taken only where it can matter (as in the activation
+    // quantizer): w * (1/s) is rounded to an integer by one fma against 1.5 * 2^23 (the sum's ulp is
+    // 1), a second fma gives the distance from it, and a wave in which any lane is within the
+    // approximation's error of a rounding tie (or has a step so small that its reciprocal leaves the
+    // normal range) redoes its eight elements with the division.
+    constexpr float kRound = 12582912.0f;             // 1.5 * 2^23
+    constexpr float kTol = 1.9073486328125e-06f;      // 2^-19; the approximation is within 2^-22
+    float sk[8], rs[8];
+    bool odd_step = false;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sk[e] = (k0 + e < O) ? s[k0 + e] : 0.0f;
+    for (int e = 0; e < 8; ++e) {
+        sk[e] = (k0 + e < O) ? s[k0 + e] : 0.0f;
+        rs[e] = (sk[e] == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(sk[e]);
+        odd_step |= sk[e] != 0.0f && !(sk[e] >= 7.888609052210118e-31f);     // 2^-100, also catches NaN
+    }
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
         const int jl = pass * 32 + (threadIdx.x >> 3);
@@ -104,15 +130,29 @@ weight_quant_kernel(const uint16_t* __restrict__ W, int I, int O, const float* _
                 for (int e = 0; e < 8; ++e) h[e] = (k0 + e < O) ? row[k0 + e] : 0u;
             }
         }
+        float w[8], m[8];
+        float score = 0.0f, big = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float w = half_bits_to_float(h[e]);
-            if (fold) w = f * w;
-            float r = (sk[e] == 0.0f) ? 0.0f : w / sk[e];
-            r = __builtin_rintf(r);
-            r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
-            tile[c8 * 8 + e][jl] = (int8_t)(int)r;
+            w[e] = half_bits_to_float(h[e]);
+            if (fold) w[e] = f * w[e];
+            m[e] = __builtin_fmaf(w[e], rs[e], kRound);
+            const float q = m[e] - kRound;
+            const float d = __builtin_fmaf(w[e], rs[e], -q);
+            score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(q), kTol, __builtin_fabsf(d)));
+            big = __builtin_fmaxf(big, __builtin_fabsf(q));
         }
+        if (__any(score >= 0.5f - kTol || !(big <= qmax) || odd_step)) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float r = (sk[e] == 0.0f) ? 0.0f : w[e] / sk[e];
+                r = __builtin_rintf(r);
+                r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+                m[e] = r + kRound;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[c8 * 8 + e][jl] = (int8_t)(__float_as_uint(m[e]) & 0xFFu);   // low byte = code
     }
     __syncthreads();
     // 64 rows (k) of 128 bytes (j): thread -> (k local, 32-byte piece) = two 16-byte stores
