@@ -2,19 +2,19 @@
 // zero-shot accuracy figures): one pass over X that writes X with its kernel elements zeroed and
 // counts the kernel size and the two indicators of the kernel-size analysis,
 //   case II:  c_j >= t_i          and          B~_ij < B_ij  (zero bound of CrossQuant below per-token's).
-// Analysis tooling rather than the serving path, so it is written for clarity: the code of every
-// element comes from the correctly rounded division itself (about 25 VALU operations per
-// element, which still keeps pace with the 4 bytes per element it moves).
-#include "cq_kernels.h"
+// Only "is the code zero" is needed, and q = rne(fl32(x / fl32(a b))) is 0 exactly when the quotient
+// is at most 1/2, so the sign of one fma, |x| (1/b) - a/2, decides; a wave in which any lane has
+// the two sides within 2^-20 of each other (the approximation is within 2^-22) takes the correctly
+// rounded division for its row piece instead.  The three counts are population counts of compare
+// masks.  About 9 vector instructions per element; with the division everywhere it was 35 and the
+// kernel was bound by them, not by the 4 bytes per element it moves.
+#include "cq_device.h"
 
 namespace cq {
 namespace {
 
-constexpr int kLanes = 64;
 constexpr int kWaves = 8;
 constexpr int kU = 4;
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Block: 8 waves share 512 columns; each wave takes nb batches of 4 consecutive rows.
 template <bool VEC>
@@ -28,15 +28,20 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const int wave = threadIdx.x / kLanes;
     const int col_chunk = blockIdx.x % n_col_chunks;
     const int row_chunk = blockIdx.x / n_col_chunks;
-    const int j0 = col_chunk * 512 + lane * 8;
+    const int j0 = col_chunk * kColsPerWave + lane * 8;
     const int rows_per_wave = nb * kU;
     const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
 
-    float b[8], c[8];
+    float b[8], rb[8], c[8];
+    unsigned long long valid[8];                            // lanes whose column e exists
+    bool odd = false;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
         c[e] = (j0 + e < I) ? c_vec[j0 + e] : 0.0f;
+        rb[e] = safe_rcp(b[e]);
+        odd |= tiny_factor(b[e]);
+        valid[e] = __ballot(j0 + e < I);
     }
     int nvalid = I - j0;
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
@@ -46,28 +51,14 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const float t_lane = has_row ? t_vec[row0 + lane] : 0.0f;
     const float pt_lane = (float)((double)t_lane / (double)qmax);
 
-    uint32_t zeros = 0, col_ge = 0, smaller = 0;
+    uint32_t zeros = 0, col_ge = 0, smaller = 0;            // wave totals (uniform)
     for (int bi = 0; bi < nb; ++bi) {
         const int rbase = row0 + bi * kU;
         if (rbase >= T) break;                              // wave-uniform
         uint4 v[kU];
 #pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            v[u] = make_uint4(0u, 0u, 0u, 0u);
-            const int r = rbase + u;
-            if (r < T) {
-                const uint16_t* row = X + (int64_t)r * ldx;
-                if (VEC && j0 + 8 <= I) {
-                    v[u] = *reinterpret_cast<const uint4*>(row + j0);
-                } else if (j0 < I) {
-                    uint32_t h[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) h[e] = (j0 + e < I) ? row[j0 + e] : 0u;
-                    v[u] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
-                                      h[6] | (h[7] << 16));
-                }
-            }
-        }
+        for (int u = 0; u < kU; ++u)
+            v[u] = (rbase + u < T) ? load8<VEC>(X + (int64_t)(rbase + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int r = rbase + u;
@@ -76,27 +67,41 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), ri));
             const float ti = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t_lane), ri));
             const float pt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pt_lane), ri));
+            const float ha = 0.5f * a, tol = ha * kTieTol;
             const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            _Float16 h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = __builtin_bit_cast(_Float16, (unsigned short)(w[e >> 1] >> (16 * (e & 1))));
+            bool nonzero[8];                                // element e has a non-zero code
+            bool close = false;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float d = __builtin_fmaf(__builtin_fabsf((float)h[e]), rb[e], -ha);
+                nonzero[e] = d > 0.0f;
+                close |= __builtin_fabsf(d) <= tol;
+            }
+            // a == 0: D = 0 and every code of the row is 0 by definition (left to the exact path)
+            if (__any(close || odd || tiny_factor(a) || a == 0.0f)) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float D = a * b[e];
+                    float q = (D == 0.0f) ? 0.0f : __builtin_rintf((float)h[e] / D);
+                    q = __builtin_amdgcn_fmed3f(q, -qmax, qmax);
+                    nonzero[e] = q != 0.0f;
+                }
+            }
             uint32_t out[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                uint32_t keep = 0u;
-#pragma unroll
-                for (int hlf = 0; hlf < 2; ++hlf) {
-                    const int e = 2 * p + hlf;
-                    const uint32_t hbits = hlf ? (w[p] >> 16) : (w[p] & 0xFFFFu);
-                    const float x = h2f(hbits);
-                    const float D = a * b[e];
-                    float q = (D == 0.0f) ? 0.0f : __builtin_rintf(x / D);
-                    q = __builtin_amdgcn_fmed3f(q, -qmax, qmax);
-                    const bool valid = e < nvalid;
-                    const bool is_zero = (q == 0.0f);
-                    zeros += (valid && is_zero) ? 1u : 0u;
-                    col_ge += (valid && c[e] >= ti) ? 1u : 0u;
-                    smaller += (valid && D < pt) ? 1u : 0u;          // 0.5 * D < 0.5 * pt, exactly
-                    keep |= is_zero ? 0u : (hlf ? 0xFFFF0000u : 0x0000FFFFu);
-                }
+                const uint32_t keep = (nonzero[2 * p] ? 0x0000FFFFu : 0u) | (nonzero[2 * p + 1] ? 0xFFFF0000u : 0u);
                 out[p] = w[p] & keep;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float D = a * b[e];
+                zeros += (uint32_t)__builtin_popcountll(valid[e] & ~__ballot(nonzero[e]));
+                col_ge += (uint32_t)__builtin_popcountll(valid[e] & __ballot(c[e] >= ti));
+                smaller += (uint32_t)__builtin_popcountll(valid[e] & __ballot(D < pt));      // 0.5 * D < 0.5 * pt, exactly
             }
             if (xrk) {
                 uint16_t* dst = xrk + (int64_t)r * I + j0;
@@ -111,12 +116,6 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
         }
     }
 
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        zeros += (uint32_t)__shfl_xor((int)zeros, off, kLanes);
-        col_ge += (uint32_t)__shfl_xor((int)col_ge, off, kLanes);
-        smaller += (uint32_t)__shfl_xor((int)smaller, off, kLanes);
-    }
     if (lane == 0) {
         lds_cnt[wave][0] = zeros;
         lds_cnt[wave][1] = col_ge;
