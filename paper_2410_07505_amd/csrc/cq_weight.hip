@@ -184,7 +184,7 @@ weight_group_kernel(const uint16_t* __restrict__ W, int I, int O, const float* _
                     int n_k_tiles, bool in_vec, bool out_vec) {
     __shared__ float lmax[32][64 + 1];
     __shared__ float lstep[64];
-    __shared__ __align__(16) int8_t tile[64][32 + 8];          // [k][j within the 32-row pass]
+    __shared__ __align__(16) int8_t tile[64][128 + 16];        // [k][j within the 128-row chunk]
     const int kt = blockIdx.x % n_k_tiles, G = blockIdx.x / n_k_tiles;
     const int ng = I / g;
     const int c8 = threadIdx.x & 7, jr = threadIdx.x >> 3;
@@ -231,48 +231,83 @@ weight_group_kernel(const uint16_t* __restrict__ W, int I, int O, const float* _
         if (k < O) s[(int64_t)k * ng + G] = step;
     }
     __syncthreads();
-    float sk[8];
+    // the division is taken only near a rounding tie, as in weight_quant_kernel
+    constexpr float kRound = 12582912.0f;             // 1.5 * 2^23
+    constexpr float kTol = 1.9073486328125e-06f;      // 2^-19
+    float sk[8], rs[8];
+    bool odd_step = false;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sk[e] = lstep[c8 * 8 + e];
+    for (int e = 0; e < 8; ++e) {
+        sk[e] = lstep[c8 * 8 + e];
+        rs[e] = (sk[e] == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(sk[e]);
+        odd_step |= sk[e] != 0.0f && !(sk[e] >= 7.888609052210118e-31f);     // 2^-100, also catches NaN
+    }
 
-    for (int jb = j_begin; jb < j_end; jb += 32) {
-        const int j = jb + jr;
-        if (j < j_end) {
-            float w[8];
-            load_row(j, w);
-            uint32_t hq[8];
+    // up to 128 input channels of the group at a time (4 passes of 32 rows), so that the codes leave
+    // in whole 128-byte row pieces where the group is that long
+    for (int jc = j_begin; jc < j_end; jc += 128) {
+        const int jc_end = min(jc + 128, j_end);
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) {
+            const int j = jc + sub * 32 + jr;
+            const bool live = j < jc_end;
+            float w[8], q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w[e] = 0.0f;
+            if (live) load_row(j, w);
+            float score = 0.0f, big = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                float r = (sk[e] == 0.0f) ? 0.0f : w[e] / sk[e];
-                r = __builtin_rintf(r);
-                r = __builtin_amdgcn_fmed3f(r, -qmax, qmax);
-                tile[c8 * 8 + e][jr] = (int8_t)(int)r;
-                hq[e] = f2h(rounded_f32((float)(int)r * sk[e]));
+                const float mm = __builtin_fmaf(w[e], rs[e], kRound);
+                q[e] = mm - kRound;
+                const float d = __builtin_fmaf(w[e], rs[e], -q[e]);
+                score = __builtin_fmaxf(score, __builtin_fmaf(__builtin_fabsf(q[e]), kTol, __builtin_fabsf(d)));
+                big = __builtin_fmaxf(big, __builtin_fabsf(q[e]));
             }
-            if (wdq) {
-                uint16_t* dst = wdq + (int64_t)j * O + k0;
-                if (in_vec && k0 + 8 <= O && (reinterpret_cast<uintptr_t>(wdq) % 16 == 0)) {
-                    *reinterpret_cast<uint4*>(dst) = make_uint4(hq[0] | (hq[1] << 16), hq[2] | (hq[3] << 16),
-                                                                hq[4] | (hq[5] << 16), hq[6] | (hq[7] << 16));
-                } else {
+            if (__any(score >= 0.5f - kTol || !(big <= qmax) || odd_step)) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (k0 + e < O) dst[e] = (uint16_t)hq[e];
+                for (int e = 0; e < 8; ++e) {
+                    float r = (sk[e] == 0.0f) ? 0.0f : w[e] / sk[e];
+                    r = __builtin_rintf(r);
+                    q[e] = __builtin_amdgcn_fmed3f(r, -qmax, qmax) + 0.0f;      // -0 (from rounding e.g. -0.3) -> +0
+                }
+            }
+            if (live) {
+                uint32_t hq[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    tile[c8 * 8 + e][sub * 32 + jr] = (int8_t)(int)q[e];
+                    hq[e] = f2h(rounded_f32(q[e] * sk[e]));
+                }
+                if (wdq) {
+                    uint16_t* dst = wdq + (int64_t)j * O + k0;
+                    if (in_vec && k0 + 8 <= O && (reinterpret_cast<uintptr_t>(wdq) % 16 == 0)) {
+                        *reinterpret_cast<uint4*>(dst) = make_uint4(hq[0] | (hq[1] << 16), hq[2] | (hq[3] << 16),
+                                                                    hq[4] | (hq[5] << 16), hq[6] | (hq[7] << 16));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (k0 + e < O) dst[e] = (uint16_t)hq[e];
+                    }
                 }
             }
         }
         __syncthreads();
-        {   // 64 rows (k) of up to 32 bytes (j): thread -> (k local, 8-byte piece)
+        {   // 64 rows (k) of up to 128 bytes (j): thread -> (k local, 32-byte piece) = two 16-byte stores
             const int kl = threadIdx.x >> 2, piece = threadIdx.x & 3;
             const int k = kt * 64 + kl;
-            const int jo = jb + piece * 8;
-            if (k < O && jo < j_end) {
-                int8_t* dst = qw + (int64_t)k * I + jo;
-                if (out_vec && jo + 8 <= j_end) {
-                    *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(&tile[kl][piece * 8]);
-                } else {
-                    for (int e = 0; e < 8; ++e)
-                        if (jo + e < j_end) dst[e] = tile[kl][piece * 8 + e];
+            if (k < O) {
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int jl = piece * 32 + half * 16;
+                    const int jo = jc + jl;
+                    int8_t* dst = qw + (int64_t)k * I + jo;
+                    if (out_vec && jo + 16 <= jc_end) {
+                        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(&tile[kl][jl]);
+                    } else {
+                        for (int e = 0; e < 16; ++e)
+                            if (jo + e < jc_end) dst[e] = tile[kl][jl + e];
+                    }
                 }
             }
         }
@@ -306,7 +341,7 @@ hipError_t launch_weight_quantize_grouped(const uint16_t* W, int I, int O, const
                                           int8_t* qw, float* w_scale, uint16_t* wdq, hipStream_t stream) {
     const int nkt = (O + 63) / 64, ng = I / group;
     const bool in_vec = (reinterpret_cast<uintptr_t>(W) % 16 == 0) && (O % 8 == 0);
-    const bool out_vec = (reinterpret_cast<uintptr_t>(qw) % 8 == 0) && (I % 8 == 0) && (group % 8 == 0);
+    const bool out_vec = (reinterpret_cast<uintptr_t>(qw) % 16 == 0) && (I % 16 == 0) && (group % 16 == 0);
     weight_group_kernel<<<dim3((unsigned)(nkt * ng)), dim3(256), 0, stream>>>(W, I, O, fold, group, (float)qmax, qw,
                                                                              w_scale, wdq, nkt, in_vec, out_vec);
     return hipGetLastError();
