@@ -46,6 +46,9 @@ typedef enum {
 /* Upper limits on sizes (keeps every index in 32 bits inside the kernels). */
 #define CQ_MAX_DIM ((int64_t)1 << 24)        /* T, I, O, leading dimensions */
 #define CQ_MAX_ELEMS ((int64_t)1 << 40)      /* T*I, I*O, T*O */
+/* A launch is also limited to fewer than 2^32 threads, which only inputs made of millions of tiny
+ * pieces reach (e.g. a batch of 2^23 or more one-token sequences: a sequence takes at least one
+ * block of 512 threads); such a call returns CQ_ERR_SHAPE with nothing enqueued. */
 
 /*
  * Row and column absolute maxima in one pass over X.

@@ -92,17 +92,18 @@ absmax_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, uint32_
 
 hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, float* t,
                          float* c, hipStream_t stream) {
-    {
-        const int n = B * (T + I);                        // t is [B*T], c is [B*I]
-        zero_fill_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(
-            reinterpret_cast<uint32_t*>(t), B * T, reinterpret_cast<uint32_t*>(c), B * I);
-    }
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
     // rows per block = 32 * nb: as many as keep at least 512 blocks in flight (fewer, larger
     // blocks mean fewer atomics; too few blocks leave CUs idle)
     int nb = 8;
     while (nb > 1 && (int64_t)B * ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
+    if (!grid_fits((int64_t)B * ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;
+    {
+        const int n = B * (T + I);                        // t is [B*T], c is [B*I]
+        zero_fill_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(
+            reinterpret_cast<uint32_t*>(t), B * T, reinterpret_cast<uint32_t*>(c), B * I);
+    }
     const dim3 grid((unsigned)(B * ncc * nrc)), block(kWaves * kLanes);
     const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0) && (B == 1 || matrix_stride % 8 == 0);
     if (vec)

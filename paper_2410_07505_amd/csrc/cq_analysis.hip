@@ -139,6 +139,7 @@ hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, 
     int nb = 16;
     while (nb > 1 && (int64_t)ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
+    if (!grid_fits((int64_t)ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(ncc * nrc)), block(kWaves * kLanes);
     const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0);
     const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(xrk) % 16 == 0);

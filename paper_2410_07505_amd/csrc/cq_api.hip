@@ -38,7 +38,11 @@ int check_quant_params(float alpha, int bits, int64_t I) {
 // do two float vectors share any element?
 inline bool overlap(const float* p, int64_t n, const float* q, int64_t m) { return p < q + m && q < p + n; }
 
-inline int from_hip(hipError_t e) { return e == hipSuccess ? CQ_OK : CQ_ERR_HIP; }
+// hipErrorInvalidValue is what the launchers return, before enqueuing anything, for a grid whose total
+// thread count would not fit in 32 bits
+inline int from_hip(hipError_t e) {
+    return e == hipSuccess ? CQ_OK : (e == hipErrorInvalidValue ? CQ_ERR_SHAPE : CQ_ERR_HIP);
+}
 
 }  // namespace
 

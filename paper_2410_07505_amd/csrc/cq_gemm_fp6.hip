@@ -336,6 +336,7 @@ int64_t fp6_packed_bytes(int64_t R, int64_t K) { return ((R + 31) / 32) * (K / 6
 
 hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void* packed, hipStream_t stream) {
     const int64_t n_slots = ((int64_t)(R + 31) / 32) * (K / 64) * 64;
+    if (!grid_fits((n_slots + 255) / 256, 256)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((n_slots + 255) / 256)), block(256);
     if (src_format == 8)
         pack_fp6_kernel<8><<<grid, block, 0, stream>>>(static_cast<const uint8_t*>(codes), R, K,

@@ -25,6 +25,13 @@ __device__ __forceinline__ float rounded_f32(float v) {
 // Library-owned device state comes in kStateSlots pieces; a stream keeps the slot it is given on
 // first use (-1: none left, or a handle that stands for several streams -- the caller then takes
 // the path that clears its accumulators with a kernel of its own first).
+// A launch's total thread count has to stay below 2^32: the runtime forms it in 32 bits, and a larger
+// grid silently runs only as many blocks as the low 32 bits give.  Launchers check this first and
+// return hipErrorInvalidValue with nothing enqueued (reported as a size over the limit).
+inline bool grid_fits(int64_t blocks, int threads) {
+    return blocks >= 1 && blocks * threads < ((int64_t)1 << 32);
+}
+
 constexpr int kStateSlots = 16;
 int stream_slot(hipStream_t stream);
 

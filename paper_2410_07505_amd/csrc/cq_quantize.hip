@@ -40,11 +40,11 @@ constexpr int kU = 4;       // rows a wave has in flight (8 and 16 measured slow
 
 // Zero-count accumulators of the quantize kernel: library-owned (one array per device, one word
 // per stream slot), zero between launches.  Bits 0..40 hold the running count (at most 2^40
-// elements), bits 41..63 the number of blocks that have added theirs.  The block whose add
+// elements), bits 41..63 the number of blocks that have added theirs (a launch of 512-thread blocks
+// has fewer than 2^23 of them).  The block whose add
 // brings the second field to the grid size knows the total, stores it to the caller's counter
 // and clears the accumulator again, so no kernel has to run beforehand to clear anything.
 constexpr int kTicketShift = 41;
-constexpr unsigned kMaxTicketBlocks = 1u << (64 - kTicketShift);
 __device__ unsigned long long g_zero_state[kStateSlots];
 
 __global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
@@ -207,14 +207,15 @@ hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int6
     int nb = 16;
     while (nb > 1 && (int64_t)B * ncc * ((T + 32 * nb - 1) / (32 * nb)) < 512) nb >>= 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
+    if (!grid_fits((int64_t)B * ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;    // hence < 2^23 blocks
     const unsigned n_blocks = (unsigned)(B * ncc * nrc);
     const dim3 grid(n_blocks), block(kWaves * kLanes);
     const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0) && (B == 1 || matrix_stride % 8 == 0);
     // vector stores need every lane's piece aligned: I % 8 == 0 and aligned bases
     const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 8 == 0) &&
                          (reinterpret_cast<uintptr_t>(xhat) % 16 == 0);
-    // no slot, or more blocks than the block field counts: clear the caller's counter and add to it directly
-    const int state = (zc && n_blocks < kMaxTicketBlocks) ? stream_slot(stream) : -1;
+    // no slot: clear the caller's counter and add to it directly
+    const int state = zc ? stream_slot(stream) : -1;
     if (zc && state < 0) zero_u64_kernel<<<dim3(1), dim3(1), 0, stream>>>(zc);
     if (vec)
         quantize_kernel<MODE, XHAT, true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, alpha, qmax, a, b, codes, xhat,
@@ -276,6 +277,7 @@ __global__ void unpack_int4_kernel(const uint8_t* __restrict__ packed, int64_t n
 hipError_t launch_unpack_int4(const uint8_t* packed, int64_t n_bytes, int8_t* codes, hipStream_t stream) {
     const bool vec = (reinterpret_cast<uintptr_t>(packed) % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 16 == 0);
     const int64_t n_threads = (n_bytes + 7) / 8;
+    if (!grid_fits((n_threads + 255) / 256, 256)) return hipErrorInvalidValue;
     unpack_int4_kernel<<<dim3((unsigned)((n_threads + 255) / 256)), dim3(256), 0, stream>>>(packed, n_bytes, codes, vec);
     return hipGetLastError();
 }

@@ -320,6 +320,7 @@ weight_group_kernel(const uint16_t* __restrict__ W, int I, int O, const float* _
 hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* fold, int qmax, int8_t* qw,
                                   float* w_scale, hipStream_t stream) {
     constexpr int RPW = 32;
+    if (!grid_fits((int64_t)((O + 63) / 64) * ((I + 127) / 128), 256)) return hipErrorInvalidValue;   // the larger of the two grids
     zero_u32_kernel<<<dim3((O + 255) / 256), dim3(256), 0, stream>>>(reinterpret_cast<uint32_t*>(w_scale), O);
     const bool in_vec = (reinterpret_cast<uintptr_t>(W) % 16 == 0) && (O % 8 == 0);
     {
@@ -342,6 +343,7 @@ hipError_t launch_weight_quantize_grouped(const uint16_t* W, int I, int O, const
     const int nkt = (O + 63) / 64, ng = I / group;
     const bool in_vec = (reinterpret_cast<uintptr_t>(W) % 16 == 0) && (O % 8 == 0);
     const bool out_vec = (reinterpret_cast<uintptr_t>(qw) % 16 == 0) && (I % 16 == 0) && (group % 16 == 0);
+    if (!grid_fits((int64_t)nkt * ng, 256)) return hipErrorInvalidValue;
     weight_group_kernel<<<dim3((unsigned)(nkt * ng)), dim3(256), 0, stream>>>(W, I, O, fold, group, (float)qmax, qw,
                                                                              w_scale, wdq, nkt, in_vec, out_vec);
     return hipGetLastError();

@@ -118,6 +118,10 @@ def test_batched_argument_errors(cq):
     assert call(B=0) == -2 and call(bs=8) == -2
     assert call(bits=7) == -3 and call(bits=4, I=7, ldx=8) == -3 and call(alpha=-0.5) == -4
     assert call(zc=P + 4) == -5
+    # a launch has to stay below 2^32 threads: one-token sequences take a block each
+    far = dict(t=P, c=P + (1 << 27), rs=P + (2 << 27), cs=P + (3 << 27))
+    assert call(B=1 << 23, S=1, I=1, ldx=1, bs=1, **far) == -2          # 512-thread blocks
+    assert f(P, 1 << 24, 1, 1, 1, 1, P, P, None) == -2                  # 256-thread blocks
     assert call(t=P, c=P + 0x1000, rs=P + 28, cs=P + 0x3000) == -8     # B*S = 8 row factors
     assert call(t=P, c=P + 0x1000, rs=P + 0x2000, cs=P + 0x1000 + 60) == -8   # B*I = 16 column factors
 

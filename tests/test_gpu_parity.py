@@ -522,6 +522,42 @@ def test_batched_small_and_ragged(cq, B, S, I, bits):
     check_batched(cq, X3, 0.15, bits)
 
 
+def test_batched_launch_at_the_grid_size_limit(cq):
+    """2^23 - 5 one-token sequences, one block each: the largest grid a launch of 512-thread blocks
+    can have (its thread count has to stay below 2^32), and nearly the most the zero-count word's
+    block field counts.  The oracle takes minutes for that many sequences, so it checks a sample of
+    them (first, last and random ones: sequences are independent); the count is checked against
+    the zero codes of the whole output.  Eight sequences more and the call is refused."""
+    import torch
+    B = (1 << 23) - 5
+    say("batched, %d sequences of 1 x 1" % B)
+    rng = np.random.default_rng(23)
+    X3 = rng.standard_normal((B + 8, 1, 1)).astype(np.float16)
+    X3[::7, 0, 0] = 0
+    Xbig = gpu(X3)
+    Xg = Xbig[:B]
+    t, c = cq.crossquant_absmax_batched(Xg)
+    codes, xhat, a, b, zc = cq.crossquant_quantize_batched(Xg, t, c, 0.15, 8)
+    _, _, _, _, zc2 = cq.crossquant_quantize_batched(Xg, t, c, 0.15, 8, want_codes=False)
+    n_zero = int((codes == 0).sum().item())
+    assert int(host(zc)[0]) == n_zero == int(host(zc2)[0]) == int((X3[:B] == 0).sum())
+    idx = np.unique(np.concatenate([np.arange(1500), np.arange(B - 1500, B), rng.integers(0, B, 1000)]))
+    Xs = np.ascontiguousarray(X3[idx])
+    t_ref, c_ref = oracle.absmax_batched(Xs)
+    ref = oracle.quantize_batched(Xs, t_ref, c_ref, 0.15, 8)
+    ti = torch.from_numpy(idx).cuda()
+    assert np.array_equal(bits32(host(t.view(B, 1)[ti]).ravel()), bits32(t_ref.ravel()))
+    assert np.array_equal(bits32(host(c.view(B, 1)[ti]).ravel()), bits32(c_ref.ravel()))
+    assert np.array_equal(host(codes.view(B, 1)[ti]).ravel(), ref["codes"].ravel())
+    assert np.array_equal(bits16(host(xhat.view(B, 1)[ti]).ravel()), bits16(ref["xhat"].ravel()))
+    # 2^23 + 3 sequences: the maxima still fit (256-thread blocks), the quantize launch does not
+    t2, c2 = cq.crossquant_absmax_batched(Xbig)
+    assert np.array_equal(bits32(host(t2[:B])), bits32(host(t)))
+    with pytest.raises(cq.CrossQuantError) as err:
+        cq.crossquant_quantize_batched(Xbig, t2, c2, 0.15, 8)
+    assert err.value.status == -2
+
+
 def test_batched_views_with_padding_between_sequences(cq):
     base = batch_tensor(3, 40, 304, seed=9)
     g = gpu(base)
