@@ -370,6 +370,60 @@ def test_calls_overlapping_on_many_streams(cq):
         assert int(host(zc)[0]) == oracle.kernel_count(Xs[k], t_ref, c_ref, 1.0, 8), k
 
 
+def test_more_than_2_to_31_elements(cq):
+    """70 000 x 65 544 = 4.59e9 elements (9.2 GB of binary16): every element offset past row 32 767
+    needs more than 32 bits.  The oracle computes the maxima of the whole matrix; codes and
+    dequantized values are checked on sampled rows from the beginning, the middle and the very end;
+    the zero count against the zero codes of the whole output."""
+    import torch
+    T, I = 70000, 65544
+    say("quantizer on %d x %d (%.1f GB)" % (T, I, T * I * 2 / 1e9))
+    gen = torch.Generator(device="cuda").manual_seed(4591)
+    Xg = torch.empty((T, I), dtype=torch.float16, device="cuda")
+    for r0 in range(0, T, 5000):                                   # in slabs: no large temporary
+        Xg[r0:r0 + 5000].normal_(generator=gen)
+    Xg[:, 1000::9973] *= 60.0                                      # a few outlier channels
+    X = host(Xg)
+    t_ref, c_ref = oracle.absmax(X)
+    t, c = cq.crossquant_absmax(Xg)
+    assert np.array_equal(bits32(host(t)), bits32(t_ref)) and np.array_equal(bits32(host(c)), bits32(c_ref))
+    codes, xhat, a, b, zc = cq.crossquant_quantize(Xg, t, c, 0.15, 8)
+    zc2 = cq.crossquant_kernel_count(Xg, t, c, 0.15, 8)
+    n_zero = sum(int((codes[r0:r0 + 5000] == 0).sum().item()) for r0 in range(0, T, 5000))
+    assert int(host(zc)[0]) == n_zero == int(host(zc2)[0])
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([np.arange(40), np.arange(32760, 32776), np.arange(T - 40, T), rng.integers(0, T, 60)]))
+    ref = oracle.quantize(np.ascontiguousarray(X[rows]), t_ref[rows], c_ref, 0.15, 8)
+    ri = torch.from_numpy(rows).cuda()
+    assert np.array_equal(bits32(host(a[ri])), bits32(ref["a"])) and np.array_equal(bits32(host(b)), bits32(ref["b"]))
+    assert np.array_equal(host(codes[ri]), ref["codes"])
+    assert np.array_equal(bits16(host(xhat[ri])), bits16(ref["xhat"]))
+
+
+def test_linear_output_with_more_than_2_to_31_elements(cq):
+    """32 768 x 65 544 outputs (4.3 GB of binary16) from a short contraction: output offsets past
+    2^31.  Sampled rows against the oracle; an integer checksum over every output against the exact
+    value sum_k (sum_i qx_i) . qw_k computed on the host."""
+    import torch
+    T, I, O = 32768, 128, 65544
+    say("linear %d x %d x %d" % (T, I, O))
+    qx = workloads.int8_codes(T, I, seed=71)
+    qw = workloads.int8_codes(O, I, seed=72)
+    rng = np.random.default_rng(73)
+    a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+    s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+    Y, acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), want_acc=True)
+    rows = np.unique(np.concatenate([np.arange(8), np.arange(32760 // 2 - 4, 32760 // 2 + 4), np.arange(T - 8, T),
+                                     rng.integers(0, T, 16)]))
+    Y_ref, acc_ref = oracle.w8a8_linear(qx[rows], a[rows], qw, s)
+    ri = torch.from_numpy(rows).cuda()
+    assert np.array_equal(host(acc[ri]), acc_ref)
+    assert np.array_equal(bits16(host(Y[ri])), bits16(Y_ref))
+    total = int(acc.sum(dtype=torch.int64).item())
+    expect = int(qx.astype(np.int64).sum(axis=0) @ qw.astype(np.int64).sum(axis=0))
+    assert total == expect
+
+
 def test_wide_leading_dimension(cq):
     """A narrow window of a very wide matrix: rows 64 KiB apart."""
     import torch
