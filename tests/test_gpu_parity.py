@@ -398,6 +398,70 @@ def test_more_than_2_to_31_elements(cq):
     assert np.array_equal(bits32(host(a[ri])), bits32(ref["a"])) and np.array_equal(bits32(host(b)), bits32(ref["b"]))
     assert np.array_equal(host(codes[ri]), ref["codes"])
     assert np.array_equal(bits16(host(xhat[ri])), bits16(ref["xhat"]))
+    del codes
+    # the analysis call on the same matrix: the kept elements on the sampled rows against the oracle, the
+    # kernel size against the count above, the two indicators against their definitions evaluated with
+    # library routines on the device (same binary32 operations)
+    xrk, counters = cq.crossquant_kernel_analysis(Xg, t, c, 0.15, 8, xrk=xhat)
+    ref_a = oracle.kernel_analysis(np.ascontiguousarray(X[rows]), t_ref[rows], c_ref, 0.15, 8)
+    assert np.array_equal(bits16(host(xrk[ri])), bits16(ref_a["xrk"]))
+    got = [int(v) for v in host(counters)]
+    assert got[0] == n_zero
+    c_sorted = torch.sort(c).values
+    assert got[1] == int((I - torch.searchsorted(c_sorted, t.contiguous(), right=False)).sum().item())   # #{c_j >= t_i}
+    pt = t / 127.0
+    n_smaller = 0
+    for r0 in range(0, T, 2000):
+        n_smaller += int(((a[r0:r0 + 2000, None] * b[None, :]) < pt[r0:r0 + 2000, None]).sum().item())
+    assert got[2] == n_smaller
+
+
+def test_batched_tensor_with_more_than_2_to_31_elements(cq):
+    """64 sequences of 8192 x 8200 (4.3e9 elements): sequence offsets past 2^31.  The first, one from the
+    middle and the last sequence against the oracle; the zero count against the zero codes of the whole output."""
+    import torch
+    B, S, I = 64, 8192, 8200
+    say("batched %d x %d x %d" % (B, S, I))
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    Xg = torch.empty((B, S, I), dtype=torch.float16, device="cuda")
+    for b0 in range(B):
+        Xg[b0].normal_(generator=gen)
+        Xg[b0, :, 17 * (b0 + 1)] *= 40.0 + b0                       # a different outlier channel per sequence
+    t, c = cq.crossquant_absmax_batched(Xg)
+    codes, xhat, a, b, zc = cq.crossquant_quantize_batched(Xg, t, c, 0.15, 8)
+    n_zero = sum(int((codes.view(B, S, I)[b0] == 0).sum().item()) for b0 in range(B))
+    assert int(host(zc)[0]) == n_zero
+    for b0 in (0, 31, B - 1):
+        Xs = host(Xg[b0])
+        t_ref, c_ref = oracle.absmax(Xs)
+        ref = oracle.quantize(Xs, t_ref, c_ref, 0.15, 8)
+        assert np.array_equal(bits32(host(t.view(B, S)[b0])), bits32(t_ref)), b0
+        assert np.array_equal(bits32(host(c.view(B, I)[b0])), bits32(c_ref)), b0
+        assert np.array_equal(host(codes.view(B, S, I)[b0]), ref["codes"]), b0
+        assert np.array_equal(bits16(host(xhat.view(B, S, I)[b0])), bits16(ref["xhat"])), b0
+
+
+def test_weights_with_more_than_2_to_31_elements(cq):
+    """8200 x 270 000 weights (2.2e9 elements): output-channel offsets past 2^31 in the transposed codes.
+    Output channels are independent, so the oracle checks a sample of them (first, last, random)."""
+    import torch
+    I, O = 8200, 270000
+    say("weights %d x %d" % (I, O))
+    gen = torch.Generator(device="cuda").manual_seed(78)
+    Wg = torch.empty((I, O), dtype=torch.float16, device="cuda")
+    for j0 in range(0, I, 1025):
+        Wg[j0:j0 + 1025].normal_(std=0.02, generator=gen)
+    rng = np.random.default_rng(79)
+    fold = rng.uniform(0.5, 4.0, I).astype(np.float32)
+    qw, ws = cq.crossquant_weight_quantize(Wg, gpu(fold), 8)
+    cols = np.unique(np.concatenate([np.arange(70), np.arange(O - 70, O), rng.integers(0, O, 120)]))
+    ci = torch.from_numpy(cols).cuda()
+    qw_ref, s_ref = oracle.weight_quantize(host(Wg[:, ci]), fold, 8)
+    assert np.array_equal(bits32(host(ws[ci])), bits32(s_ref))
+    assert np.array_equal(host(qw[ci]), qw_ref)
+    # every channel's largest code is +-127 (the channel's own maximum), wherever it lies
+    peak = qw.view(O, I).abs().amax(dim=1)
+    assert bool((peak == 127).all())
 
 
 def test_linear_output_with_more_than_2_to_31_elements(cq):
