@@ -379,6 +379,7 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                               int T, int I, int O, uint16_t* Y, int64_t ldy, int32_t* acc_debug,
                               hipStream_t stream) {
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (O + BN - 1) / BN;
+    if (!grid_fits((int64_t)tiles_m * tiles_n + kXcds, 512)) return hipErrorInvalidValue;
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + kXcds - 1) / kXcds;
     const dim3 grid((unsigned)(per_xcd * kXcds)), block(kThreads);

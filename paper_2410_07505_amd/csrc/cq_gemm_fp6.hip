@@ -350,6 +350,7 @@ hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void
 hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const void* qw6, const float* w_scale, int T,
                               int I, int O, uint16_t* Y, int64_t ldy, int32_t* acc_debug, hipStream_t stream) {
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (O + BN - 1) / BN;
+    if (!grid_fits((int64_t)tiles_m * tiles_n + kXcds, 512)) return hipErrorInvalidValue;
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + kXcds - 1) / kXcds;
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f6_ring_kernel),
