@@ -239,6 +239,21 @@ def test_quotients_just_off_a_rounding_tie(cq):
         assert int(host(zc2)[0]) == ref["Z"] == oracle.kernel_count(X, tt, cc, alpha, 8)
 
 
+def test_quantize_subnormal_binary16_data(cq):
+    """Every element a subnormal binary16 value (multiples of 2^-24 below 2^-14), and a mix of subnormal
+    and ordinary rows: conversions, reciprocals and the mixed-precision fmas must treat them exactly."""
+    rng = np.random.default_rng(17)
+    sub = (rng.integers(-1023, 1024, (70, 600)).astype(np.float64) * 2.0 ** -24).astype(np.float16)
+    assert np.all(np.abs(sub.astype(np.float64)) < 2.0 ** -14)
+    for alpha in (0.0, 0.15, 1.0):
+        check_quantize(cq, sub, alpha, 8, label="subnormal")
+    mixed = sub.copy()
+    mixed[::3] = outliers(24, 600, seed=18)
+    check_quantize(cq, mixed, 0.15, 8, label="subnormal + ordinary rows")
+    check_quantize(cq, mixed, 0.5, 4, label="subnormal + ordinary rows")
+    check_analysis(cq, mixed, 0.15, 8, label="subnormal + ordinary rows")
+
+
 def test_quantize_golden_cases(cq):
     from test_oracle_pins import read_golden
     for case in read_golden():
