@@ -95,7 +95,7 @@ __global__ void pack_fp6_kernel(const uint8_t* __restrict__ src, int R, int K, u
 // kernel orders reads and in-flight writes itself (slot discipline, explicit vmcnt waits, barriers).
 __device__ __forceinline__ void dma_1k(const uint8_t* src, const int8_t* dst) {
     const uint32_t lds_off = (uint32_t)(uintptr_t)((lptr_t)dst);     // wave-uniform
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off sc0"
                  :
                  : "v"(src), "s"(lds_off)
                  : "m0");
