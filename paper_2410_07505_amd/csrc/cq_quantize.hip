@@ -4,21 +4,18 @@
 // The element-wise step is D_ij = fl32(a_i * b_j) with a_i = t_i^alpha / q_max and
 // b_j = c_j^(1-alpha); the code is q_ij = clamp(rne(fl32(x_ij / D_ij)), +-q_max).
 //
-// HBM-bound kernel (2 B read + 1 or 0.5 B codes + optionally 2 B dequantized per element), so
-// the per-element instruction count has to stay small.  A correctly rounded binary32 division
-// costs more than the rest of the element's work together, so it is taken only where it can
-// matter: the quotient is first approximated as x * (1/a_i) * (1/b_j) (reciprocals formed once
-// per row / per lane, each within 1 ulp), which lies within 2^-21 relative of the correctly
-// rounded quotient (two reciprocals at 2^-23, three roundings at 2^-24, and the quotient's own;
-// 2^-20.7 even if each reciprocal were a further half ulp off);
-// the rounded integer can differ from the one the exact quotient gives only if the approximation
-// lies within that distance of a rounding tie k + 1/2.  Lanes test |frac| + |r| * 2^-19 >= 1/2
-// (a 3x to 4x margin over the bound) and a wave in which any lane trips recomputes its eight elements
-// with the exact division.  The result is therefore identical, bit for bit, to dividing every
-// element.
-//
-// Rounding to nearest-even integer and conversion to two's complement are one add of the
-// constant 1.5 * 2^23: the sum's low mantissa bits are the code.
+// The kernel moves 2 B read + 1 or 0.5 B codes + optionally 2 B dequantized per element, and on this
+// part it is the vector-instruction count per element that decides whether it keeps up with that
+// (packed binary32 arithmetic is not used), so the per-element work is kept small.  A correctly
+// rounded binary32 division costs more than the rest of the element's work together, so it is taken
+// only where it can matter: the quotient is approximated as x * (1/a_i) * (1/b_j) (reciprocals
+// formed once per row / per lane, each within 1 ulp), which lies within 2^-21 relative of the
+// correctly rounded quotient; the product is rounded straight to an integer by one fma against
+// 1.5 * 2^23 (the sum's low mantissa bits are the two's-complement code), a second fma gives its
+// distance from that integer, and the integer can differ from the one the exact quotient gives only
+// if that distance is within the bound of 1/2.  Lanes test for that with a 3x to 4x margin, and a
+// wave in which any lane trips recomputes its eight elements with the exact division (quantize8 in
+// cq_device.h).  The result is therefore identical, bit for bit, to dividing every element.
 #include "cq_device.h"
 
 namespace cq {
