@@ -369,10 +369,12 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
         k_step(kt, no{}, yes{});
         ++kt;
     }
+    EpilogueScales<NI> scales;
+    epilogue_load_scales<NI>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{});
 
-    epilogue_store<v16i, WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
-                            lane, wave);
+    epilogue_store<v16i, WTN, NI>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane, wave);
 }
 
 }  // namespace

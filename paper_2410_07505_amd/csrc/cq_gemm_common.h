@@ -45,26 +45,47 @@ __device__ __forceinline__ bool tile_of_block(int block, int tiles_m, int tiles_
 // each 32-channel block.  Scaled binary16 results go through LDS (free once the K loop has ended
 // on a barrier with no reads outstanding) so that every global store is a full 16 bytes per lane
 // and a wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
+// The scale factors one lane's outputs need: a_i of its 4 rows, s_k of its 4 * NI groups of 4 channels.
+// Requested before the last step of the contraction so that they have arrived when it ends.
+template <int NI>
+struct EpilogueScales {
+    float a_t[4];
+    float4 s4[NI][4];
+};
+template <int NI>
+__device__ __forceinline__ void epilogue_load_scales(EpilogueScales<NI>& sc, const float* __restrict__ row_scale,
+                                                     const float* __restrict__ w_scale, int T, int O, int row0,
+                                                     int col0, int lane) {
+    const int frag_half = lane >> 5, t_lane = lane & 31;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) sc.a_t[mi] = row_scale[min(row0 + mi * 32 + t_lane, T - 1)];   // rows >= T are never stored
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
+            // O % 8 == 0 on this path: a group of 4 channels exists or not as a whole
+            sc.s4[ni][rg] = (col0 + o_loc < O) ? *reinterpret_cast<const float4*>(w_scale + col0 + o_loc)
+                                               : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+}
+
 template <typename ACC, int WTN, int NI>
-__device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, const float* __restrict__ row_scale,
-                                               const float* __restrict__ w_scale, uint16_t* __restrict__ Y,
-                                               int64_t ldy, int32_t* __restrict__ acc_debug, int T, int O, int row0,
-                                               int col0, int lane, int wave) {
+__device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, const EpilogueScales<NI>& sc,
+                                               uint16_t* __restrict__ Y, int64_t ldy,
+                                               int32_t* __restrict__ acc_debug, int T, int O, int row0, int col0,
+                                               int lane, int wave) {
     const int frag_half = lane >> 5;
     constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
     int8_t* stage = lds + wave * (128 * kRowPitch);      // this wave's 128 x WTN staging area
     const int t_lane = lane & 31;
-    float a_t[4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) a_t[mi] = row_scale[min(row0 + mi * 32 + t_lane, T - 1)];   // rows >= T are never stored
+    const float (&a_t)[4] = sc.a_t;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
             const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
-            // O % 8 == 0 on this path: a group of 4 channels exists or not as a whole
-            const float4 s4 = (col0 + o_loc < O) ? *reinterpret_cast<const float4*>(w_scale + col0 + o_loc)
-                                                 : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            const float4 s4 = sc.s4[ni][rg];
             const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi) {

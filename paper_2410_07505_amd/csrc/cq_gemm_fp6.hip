@@ -322,12 +322,14 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         k_step(kt, no{}, no{}, yes{});
         ++kt;
     }
+    EpilogueScales<NI> scales;
+    epilogue_load_scales<NI>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{}, no{});
 
     // every wave's fragments are in registers and all loads have landed: the ring can be reused
     __syncthreads();
-    epilogue_store<v16f, WTN, NI>(acc, lds, row_scale, w_scale, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
-                                  lane, wave);
+    epilogue_store<v16f, WTN, NI>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane, wave);
 }
 
 }  // namespace
