@@ -347,6 +347,16 @@ def test_extreme_aspect_ratios(cq, T, I):
     check_analysis(cq, X, 0.15, 8, label="aspect")
 
 
+@pytest.mark.parametrize("T,I", [(4010, 8200), (6010, 8200), (2500, 16390)])
+def test_row_counts_per_block_that_are_not_powers_of_two(cq, T, I):
+    """The launchers pick the rows per block from the block count: these shapes give 5, 7 and 6 batches per
+    wave (the layer-shaped configurations give 2, 3 and 4), each with a partly filled last row chunk and a
+    column chunk of 8 columns."""
+    X = outliers(T, I, seed=T % 89 + I % 97)
+    check_quantize(cq, X, 0.15, 8, label="rows per block")
+    check_analysis(cq, X, 0.15, 8, label="rows per block")
+
+
 @pytest.mark.parametrize("T,I", [(270000, 8), (4, 262200)])
 def test_very_long_maxima_vectors(cq, T, I):
     """More than 2^18 rows, or columns: thousands of row chunks / column chunks in one launch."""
