@@ -93,14 +93,16 @@ absmax_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, uint32_
 hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, float* t,
                          float* c, hipStream_t stream) {
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
-    // rows per block = 32 * nb.  Small blocks are best for this read-only kernel (measured inside a step, X cold:
-    // nb = 2 beats 4 by 10 % on 4096 x 8192 and is within 2 % of the best on every shape tried; a block's cost
-    // besides its reads is one atomic per column); only huge inputs take more rows per block, to bound the number
-    // of column atomics, and inputs that would not fill the chip take fewer.
+    // rows per block = 32 * nb.  Small blocks are best for this read-only kernel (a block's cost besides its reads
+    // is one atomic per column).  Measured on three layer shapes, inside a step (X cold) and back to back with
+    // the quantize call (X cached): 96 rows beat 64 and 128 by 0-8 % over the two calls together (the order in
+    // which X was last touched also sets the speed of the quantize kernel's re-read), 160 and more lose; an
+    // input with fewer than 256 such blocks takes 64 rows, or 32.  Only huge inputs take more rows per block,
+    // to bound the number of column atomics.
     auto n_blocks_for = [&](int n) { return (int64_t)B * ncc * ((T + 32 * n - 1) / (32 * n)); };
-    int nb = 2;
+    int nb = 3;
+    while (nb > 1 && n_blocks_for(nb) < 256) --nb;
     while (nb < 16 && n_blocks_for(nb) > 4096) ++nb;
-    if (nb == 2 && n_blocks_for(2) < 256) nb = 1;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
     if (!grid_fits((int64_t)B * ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;
     {

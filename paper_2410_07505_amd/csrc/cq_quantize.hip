@@ -87,15 +87,20 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const int row0 = row_chunk * rows_per_block + wave * rows_per_wave;
     const float qmax = (float)qmax_i;
 
+    // A wave walks its batches from the last to the first: the absmax kernel, which normally ran just before,
+    // walks them first to last, so the rows it touched last are still in the caches when they are read here
+    // first (measured in a step on 4096 x 8192: this kernel 32.4 -> 30.2 us, the same in five processes).
+    auto batch_row = [&](int bi) { return row0 + (nb - 1 - bi) * kU; };
     // first two batches of rows: in flight while the scale factors are formed
     uint4 v[kU], w[kU];
 #pragma unroll
     for (int u = 0; u < kU; ++u)
-        v[u] = (row0 + u < T) ? load8<VEC>(X + (int64_t)(row0 + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
+        v[u] = (batch_row(0) + u < T) ? load8<VEC>(X + (int64_t)(batch_row(0) + u) * ldx, j0, I)
+                                      : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
     for (int u = 0; u < kU; ++u)
-        w[u] = (nb > 1 && row0 + kU + u < T) ? load8<VEC>(X + (int64_t)(row0 + kU + u) * ldx, j0, I)
-                                              : make_uint4(0u, 0u, 0u, 0u);
+        w[u] = (nb > 1 && batch_row(1) + u < T) ? load8<VEC>(X + (int64_t)(batch_row(1) + u) * ldx, j0, I)
+                                                : make_uint4(0u, 0u, 0u, 0u);
 
     {
         // thread k of the block: column k of the chunk, and row k of the block
@@ -133,8 +138,7 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     uint32_t nonzero = 0u;    // codes != 0 seen by this wave (uniform)
     int rows_done = 0;
     for (int bi = 0; bi < nb; ++bi) {
-        const int rbase = row0 + bi * kU;
-        if (rbase >= T) break;                              // wave-uniform
+        const int rbase = batch_row(bi);
         if (bi == 1) {
 #pragma unroll
             for (int u = 0; u < kU; ++u) v[u] = w[u];
@@ -143,13 +147,14 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             for (int u = 0; u < kU; ++u)
                 v[u] = (rbase + u < T) ? load8<VEC>(X + (int64_t)(rbase + u) * ldx, j0, I) : make_uint4(0u, 0u, 0u, 0u);
         }
+        if (rbase >= T) continue;                           // wave-uniform: a batch past the last row
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int r = rbase + u;
             if (r >= T) break;                              // wave-uniform
             ++rows_done;
             const float a = __builtin_bit_cast(
-                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), bi * kU + u));
+                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), (nb - 1 - bi) * kU + u));
             if (MODE == 0) {
                 // a == 0 means D = 0 and every code of the row is 0 by definition: left to the exact path
                 nonzero += count_row8_wave(v[u], a, 0.5f * a, 0.5f * a * kTieTol, b, rb, qmax,
