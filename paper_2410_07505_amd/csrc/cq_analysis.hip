@@ -5,9 +5,11 @@
 // Only "is the code zero" is needed, and q = rne(fl32(x / fl32(a b))) is 0 exactly when the quotient
 // is at most 1/2, so the sign of one fma, |x| (1/b) - a/2, decides; a wave in which any lane has
 // the two sides within 2^-20 of each other (the approximation is within 2^-22) takes the correctly
-// rounded division for its row piece instead.  The three counts are population counts of compare
-// masks.  About 9 vector instructions per element; with the division everywhere it was 35 and the
-// kernel was bound by them, not by the 4 bytes per element it moves.
+// rounded division for its row piece instead.  The three counts are kept per lane (one compare and
+// one add-with-carry each) and summed once per wave at the end: as population counts of compare masks
+// they cost three scalar instructions per wave-wide compare, 72 per row piece (4096 x 8192: the call
+// took 41 us that way, 38.5 us now).  With the division everywhere the kernel was bound by the vector
+// unit (35 instructions per element).
 #include "cq_device.h"
 
 namespace cq {
@@ -32,16 +34,18 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const int rows_per_wave = nb * kU;
     const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
 
-    float b[8], rb[8], c[8];
-    unsigned long long valid[8];                            // lanes whose column e exists
+    // Columns past the end: x reads as 0 there, so the code is 0 (not counted as non-zero); c = -1 is never
+    // >= t_i, and a step of +infinity (NaN for a_i = 0) is never below the per-token step.
+    float b[8], rb[8], c[8], b_cmp[8];
     bool odd = false;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        b[e] = (j0 + e < I) ? b_vec[j0 + e] : 0.0f;
-        c[e] = (j0 + e < I) ? c_vec[j0 + e] : 0.0f;
+        const bool exists = j0 + e < I;
+        b[e] = exists ? b_vec[j0 + e] : 0.0f;
+        c[e] = exists ? c_vec[j0 + e] : -1.0f;
+        b_cmp[e] = exists ? b[e] : __builtin_inff();
         rb[e] = safe_rcp(b[e]);
         odd |= tiny_factor(b[e]);
-        valid[e] = __ballot(j0 + e < I);
     }
     int nvalid = I - j0;
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
@@ -51,7 +55,8 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const float t_lane = has_row ? t_vec[row0 + lane] : 0.0f;
     const float pt_lane = (float)((double)t_lane / (double)qmax);
 
-    uint32_t zeros = 0, col_ge = 0, smaller = 0;            // wave totals (uniform)
+    uint32_t nz_lane = 0, ge_lane = 0, sm_lane = 0;         // this lane's counts: codes != 0, c_j >= t_i, B~ < B
+    int rows_done = 0;
     for (int bi = 0; bi < nb; ++bi) {
         const int rbase = row0 + bi * kU;
         if (rbase >= T) break;                              // wave-uniform
@@ -63,6 +68,7 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
         for (int u = 0; u < kU; ++u) {
             const int r = rbase + u;
             if (r >= T) break;                              // wave-uniform
+            ++rows_done;
             const int ri = bi * kU + u;
             const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), ri));
             const float ti = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t_lane), ri));
@@ -73,15 +79,15 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 #pragma unroll
             for (int e = 0; e < 8; ++e) h[e] = __builtin_bit_cast(_Float16, (unsigned short)(w[e >> 1] >> (16 * (e & 1))));
             bool nonzero[8];                                // element e has a non-zero code
-            bool close = false;
+            float nearest = __builtin_inff();               // min over the 8 elements of | |x|/b - a/2 |
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float d = __builtin_fmaf(__builtin_fabsf((float)h[e]), rb[e], -ha);
                 nonzero[e] = d > 0.0f;
-                close |= __builtin_fabsf(d) <= tol;
+                nearest = __builtin_fminf(nearest, __builtin_fabsf(d));
             }
             // a == 0: D = 0 and every code of the row is 0 by definition (left to the exact path)
-            if (__any(close || odd || tiny_factor(a) || a == 0.0f)) {
+            if (__any(nearest <= tol || odd || tiny_factor(a) || a == 0.0f)) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float D = a * b[e];
@@ -98,10 +104,9 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float D = a * b[e];
-                zeros += (uint32_t)__builtin_popcountll(valid[e] & ~__ballot(nonzero[e]));
-                col_ge += (uint32_t)__builtin_popcountll(valid[e] & __ballot(c[e] >= ti));
-                smaller += (uint32_t)__builtin_popcountll(valid[e] & __ballot(D < pt));      // 0.5 * D < 0.5 * pt, exactly
+                nz_lane += nonzero[e] ? 1u : 0u;
+                ge_lane += (c[e] >= ti) ? 1u : 0u;
+                sm_lane += (a * b_cmp[e] < pt) ? 1u : 0u;                // 0.5 * D < 0.5 * pt, exactly
             }
             if (xrk) {
                 uint16_t* dst = xrk + (int64_t)r * I + j0;
@@ -116,10 +121,19 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
         }
     }
 
+    // wave totals
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        nz_lane += (uint32_t)__shfl_xor((int)nz_lane, off, kLanes);
+        ge_lane += (uint32_t)__shfl_xor((int)ge_lane, off, kLanes);
+        sm_lane += (uint32_t)__shfl_xor((int)sm_lane, off, kLanes);
+    }
     if (lane == 0) {
-        lds_cnt[wave][0] = zeros;
-        lds_cnt[wave][1] = col_ge;
-        lds_cnt[wave][2] = smaller;
+        int wave_cols = I - col_chunk * kColsPerWave;        // columns of this wave that exist
+        wave_cols = wave_cols > kColsPerWave ? kColsPerWave : wave_cols;
+        lds_cnt[wave][0] = (uint32_t)(rows_done * wave_cols) - nz_lane;
+        lds_cnt[wave][1] = ge_lane;
+        lds_cnt[wave][2] = sm_lane;
     }
     __syncthreads();
     if (threadIdx.x < 3) {
