@@ -93,15 +93,17 @@ absmax_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, uint32_
 hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, float* t,
                          float* c, hipStream_t stream) {
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
-    // rows per block = 32 * nb.  Small blocks are best for this read-only kernel (a block's cost besides its reads
-    // is one atomic per column).  Measured on three layer shapes, inside a step (X cold) and back to back with
-    // the quantize call (X cached): 96 rows beat 64 and 128 by 0-8 % over the two calls together (the order in
-    // which X was last touched also sets the speed of the quantize kernel's re-read), 160 and more lose; an
-    // input with fewer than 256 such blocks takes 64 rows, or 32.  Only huge inputs take more rows per block,
-    // to bound the number of column atomics.
+    // rows per block = 32 * nb (4 waves x nb batches of 8 rows).  Small blocks are best for this read-only kernel
+    // (a block's cost besides its reads is one atomic per column), and the quantize kernel that normally follows
+    // walks each wave's rows from the last to the first: it finds them in the caches when a wave's rows here end
+    // where a wave's rows there end, i.e. when 8 nb is a multiple of the 4 nbq rows of a quantize wave -- equal
+    // to it if nbq is even.  Measured in a step, K1 + K3 stages: 4096 x 8192 (nbq 4) 50.4 us with nb 2, 52.2 with
+    // nb 3, 53.2 with nb 4; 4096 x 5120 (nbq 3) 37.1 us with nb 3, 39.5 with nb 2 or 4.  Large odd nbq would make
+    // blocks too big for this kernel's own good: nb 3 then.  Huge inputs take more rows per block, to bound the
+    // number of column atomics.
     auto n_blocks_for = [&](int n) { return (int64_t)B * ncc * ((T + 32 * n - 1) / (32 * n)); };
-    int nb = 3;
-    while (nb > 1 && n_blocks_for(nb) < 256) --nb;
+    const int nbq = quantize_batches_per_wave((int64_t)B * ncc, T);
+    int nb = nbq % 2 == 0 ? nbq / 2 : (nbq <= 3 ? nbq : 3);
     while (nb < 16 && n_blocks_for(nb) > 4096) ++nb;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
     if (!grid_fits((int64_t)B * ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;

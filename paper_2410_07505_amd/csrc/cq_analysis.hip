@@ -150,12 +150,7 @@ hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, 
                                   const float* a, const float* b, int qmax, uint16_t* xrk,
                                   unsigned long long* counters, hipStream_t stream) {
     const int ncc = (I + 511) / 512;
-    // rows per block = 32 * nb: the smallest nb >= 2 with at most 512 blocks, as for the quantize kernel
-    auto n_blocks_for = [&](int n) { return (int64_t)ncc * ((T + 32 * n - 1) / (32 * n)); };
-    const int nb_max = T >= 512 ? 16 : (T + 31) / 32;
-    int nb = nb_max < 2 ? nb_max : 2;
-    while (nb < nb_max && n_blocks_for(nb) > 512) ++nb;
-    if (nb == 2 && n_blocks_for(2) < 200) nb = 1;
+    const int nb = quantize_batches_per_wave(ncc, T);                      // rows per block = 32 * nb
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
     if (!grid_fits((int64_t)ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(ncc * nrc)), block(kWaves * kLanes);

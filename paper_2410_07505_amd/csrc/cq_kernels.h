@@ -32,6 +32,22 @@ inline bool grid_fits(int64_t blocks, int threads) {
     return blocks >= 1 && blocks * threads < ((int64_t)1 << 32);
 }
 
+// Rows per block of the quantize / count / analysis kernels = 32 * nb (8 waves x nb batches of 4 rows, nb <= 16).
+// Two of these blocks fit a CU, and a launch is fastest when all its blocks are resident at once, with as little
+// work each as that allows: the smallest nb >= 2 that gives at most 512 blocks (measured over a dozen shapes, for
+// the count-only form too, whose blocks all end with an atomic on one word: within 2 % of the best nb everywhere;
+// "at least 512 blocks, nb a power of two" lost up to 20 % on shapes whose chunk count is not a power of two).
+// One-batch blocks spend most of their time forming scale factors and are left to problems that would otherwise
+// fill less than the chip.  n_chunks = column chunks of 512, times matrices in a batch.
+inline int quantize_batches_per_wave(int64_t n_chunks, int T) {
+    auto n_blocks_for = [&](int n) { return n_chunks * ((T + 32 * n - 1) / (32 * n)); };
+    const int nb_max = T >= 512 ? 16 : (T + 31) / 32;
+    int nb = nb_max < 2 ? nb_max : 2;
+    while (nb < nb_max && n_blocks_for(nb) > 512) ++nb;
+    if (nb == 2 && n_blocks_for(2) < 200) nb = 1;
+    return nb;
+}
+
 constexpr int kStateSlots = 16;
 int stream_slot(hipStream_t stream);
 

@@ -207,17 +207,7 @@ hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int6
                        const float* c, double alpha, int qmax, float* a, float* b, uint8_t* codes, uint16_t* xhat,
                        unsigned long long* zc, hipStream_t stream) {
     const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
-    // rows per block = 32 * nb (nb <= 16).  Two of these blocks fit a CU, and the launch is fastest when all its
-    // blocks are resident at once, with as little work each as that allows: the smallest nb >= 2 that gives at
-    // most 512 blocks (measured over a dozen shapes, for the count-only form too, whose blocks all end with an
-    // atomic on one word: within 2 % of the best nb everywhere; "at least 512 blocks, nb a power of two" lost
-    // up to 20 % on shapes whose chunk count is not a power of two).  One-batch blocks (nb = 1) spend most of
-    // their time forming scale factors and are left to problems that would otherwise fill less than the chip.
-    auto n_blocks_for = [&](int n) { return (int64_t)B * ncc * ((T + 32 * n - 1) / (32 * n)); };
-    const int nb_max = T >= 512 ? 16 : (T + 31) / 32;
-    int nb = nb_max < 2 ? nb_max : 2;
-    while (nb < nb_max && n_blocks_for(nb) > 512) ++nb;
-    if (nb == 2 && n_blocks_for(2) < 200) nb = 1;
+    const int nb = quantize_batches_per_wave((int64_t)B * ncc, T);        // rows per block = 32 * nb
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
     if (!grid_fits((int64_t)B * ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;    // hence < 2^23 blocks
     const unsigned n_blocks = (unsigned)(B * ncc * nrc);
