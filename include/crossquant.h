@@ -14,8 +14,10 @@
  *     void* (NULL = the default stream).  All work is enqueued on that stream, in order.
  *   - X and W are IEEE binary16, row-major.  Outputs are fully overwritten; vectors that the
  *     kernels accumulate into (t, c, zero_count) are cleared on the stream inside the call.
- *   - Return value: CQ_OK (0) or a negative cq_status.  Argument errors are found on the host
- *     before anything is enqueued, so an error return means nothing was launched.
+ *   - Return value: CQ_OK (0) or a negative cq_status.  Argument errors, sizes over a limit and
+ *     unsupported requests are found on the host before anything is enqueued: such a return means
+ *     nothing was launched.  Only CQ_ERR_HIP (the runtime refused a launch) can follow earlier
+ *     launches of the same call.
  *   - Preconditions not checked: X and W finite; buffers at least as large as stated.
  *   - Arithmetic is fixed so results are reproducible bit for bit: scale factors use binary64
  *     pow rounded once to binary32; every per-element result equals a single correctly rounded
@@ -99,22 +101,14 @@ int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const 
  * I % 8 == 0): the caller then uses the two calls.
  * The barrier needs all blocks resident at once (one block per CU).  Other kernels running on the
  * device only delay it; if part of the device stays unavailable for seconds the kernel gives up
- * (it always terminates) and writes NaN into row_scale and col_scale.  The barrier's arrival
- * counter is one word of library-owned device memory per device: calls on the same device must
- * not overlap (use one stream, or order them with events).
- * Faster than the two calls when X is already in the memory-side cache, slower when it is not.
+ * (it always terminates) and writes NaN into row_scale and col_scale.  The barrier's counters are
+ * library-owned device memory, one pair per stream handle (16 per process, shared with the zero
+ * counters of crossquant_quantize): calls on different streams may overlap; a stream without a
+ * pair of its own (the 17th, or the per-thread default stream) gets CQ_ERR_UNSUPPORTED.
  */
 int crossquant_absmax_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits,
                                float *t, float *c, void *codes, void *xhat, float *row_scale,
                                float *col_scale, unsigned long long *zero_count, void *stream);
-
-/*
- * Test hook for crossquant_absmax_quantize: the number of polls a block makes at the grid barrier
- * before it gives up (default 2^22, seconds).  0 makes every block give up at once, so the failure
- * path (NaN in row_scale / col_scale, codes not written) can be exercised without a GPU ever
- * waiting.  Process-wide, not thread-safe; pass 1u << 22 to restore the default.
- */
-void crossquant_debug_set_barrier_polls(unsigned polls);
 
 /*
  * Batched forms for a [B][S][I] activation tensor (the shape the appendix fake-quant listing is
@@ -140,7 +134,8 @@ int crossquant_quantize_batched(const void *X, int64_t B, int64_t S, int64_t I, 
  * Size of the quantization kernel K(CQ) = {X_ij : CQ(X_ij) = 0} (Definition 1) without writing
  * codes; the kernel proportion of the paper is zero_count / (T*I).  alpha = 1 gives the
  * per-token baseline K(Q) of Eq. 1.
- * row_scale / col_scale: float[T] / float[I] work vectors, overwritten with a and b.
+ * row_scale / col_scale: nullable (both or neither): float[T] / float[I], receive a and b when given.
+ *        The kernel keeps the factors it needs on chip, so NULL, NULL costs nothing and is the usual form.
  */
 int crossquant_kernel_count(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
                             const float *c, float alpha, int bits, float *row_scale,
@@ -155,7 +150,10 @@ int crossquant_kernel_count(const void *X, int64_t T, int64_t I, int64_t ldx, co
  *   counters[1] = #{(i,j): c_j >= t_i}     case II
  *   counters[2] = #{(i,j): B~_ij < B_ij}   B~ = 0.5 fl32(a_i b_j), B = 0.5 fl32(t_i / q_max) (Eq. 1's step)
  * xrk: out, nullable, binary16 [T][I].  counters: out, three unsigned 64-bit values, 8-byte aligned.
- * row_scale / col_scale: float[T] / float[I] work vectors, overwritten with a and b.
+ * row_scale / col_scale: nullable (both or neither): float[T] / float[I] work vectors, overwritten with a and
+ *        b (must not overlap t or c: CQ_ERR_ALIAS).  With them the factors are formed once, by a small kernel
+ *        of their own; with NULL, NULL every block forms the factors of its own rows and columns, which makes
+ *        the call about a tenth slower on a 4096 x 8192 matrix.
  */
 int crossquant_kernel_analysis(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
                                const float *c, float alpha, int bits, void *xrk, float *row_scale,
@@ -240,21 +238,6 @@ int crossquant_quantize_fp6(const void *X, int64_t T, int64_t I, int64_t ldx, co
 int crossquant_w4a4_linear(const void *qx_fp6, const float *row_scale, const void *qw_fp6,
                            const float *w_scale, int64_t T, int64_t I, int64_t O, void *Y, int64_t ldy,
                            int32_t *acc_debug, void *stream);
-
-/*
- * Roofline calibration, not part of the method: kernels that do nothing but stream, so that a
- * benchmark can state what this device sustains next to the published peaks: a plain
- * 16-byte-per-lane read, a copy, and an MFMA-only loop.
- * crossquant_calib_read: reads `bytes` (multiple of 16, src 16-byte aligned); sink (nullable,
- *   device, 8-byte aligned) is only there to keep the loads alive and is normally left untouched.
- * crossquant_calib_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, non-overlapping.
- * crossquant_calib_mfma_i8: every SIMD issues iters * 16 independent v_mfma_i32_32x32x32_i8 on
- *   operands held in registers; data_mode 0 = all-zero operands, 1 = bell-shaped int8 codes.
- *   *ops (HOST pointer, nullable) receives the number of integer operations of the launch.
- */
-int crossquant_calib_read(const void *src, int64_t bytes, unsigned long long *sink, void *stream);
-int crossquant_calib_copy(const void *src, void *dst, int64_t bytes, void *stream);
-int crossquant_calib_mfma_i8(int iters, int data_mode, int *sink, double *ops, void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *crossquant_status_string(int status);

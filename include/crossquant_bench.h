@@ -1,0 +1,41 @@
+/*
+ * crossquant_bench.h -- calls of libcrossquant.so that are not part of the method: roofline
+ * calibration kernels for a benchmark, and a test hook.  A program that only quantizes needs
+ * crossquant.h alone.  Conventions (device pointers, stream, return codes) as in crossquant.h.
+ */
+#ifndef CROSSQUANT_BENCH_H
+#define CROSSQUANT_BENCH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Roofline calibration, not part of the method: kernels that do nothing but stream, so that a
+ * benchmark can state what this device sustains next to the published peaks: a plain
+ * 16-byte-per-lane read, a copy, and an MFMA-only loop.
+ * crossquant_calib_read: reads `bytes` (multiple of 16, src 16-byte aligned); sink (nullable,
+ *   device, 8-byte aligned) is only there to keep the loads alive and is normally left untouched.
+ * crossquant_calib_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, non-overlapping.
+ * crossquant_calib_mfma_i8: every SIMD issues iters * 16 independent v_mfma_i32_32x32x32_i8 on
+ *   operands held in registers; data_mode 0 = all-zero operands, 1 = bell-shaped int8 codes.
+ *   *ops (HOST pointer, nullable) receives the number of integer operations of the launch.
+ */
+int crossquant_calib_read(const void *src, int64_t bytes, unsigned long long *sink, void *stream);
+int crossquant_calib_copy(const void *src, void *dst, int64_t bytes, void *stream);
+int crossquant_calib_mfma_i8(int iters, int data_mode, int *sink, double *ops, void *stream);
+
+/*
+ * Test hook for crossquant_absmax_quantize: the number of polls a block makes at the grid barrier
+ * before it gives up (default 2^22, seconds).  0 makes every block give up at once, so the failure
+ * path (NaN in row_scale / col_scale, codes not written) can be exercised without a GPU ever
+ * waiting.  Process-wide, not thread-safe; pass 1u << 22 to restore the default.
+ */
+void crossquant_debug_set_barrier_polls(unsigned polls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CROSSQUANT_BENCH_H */

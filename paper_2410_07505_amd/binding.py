@@ -98,18 +98,71 @@ def _req(t: torch.Tensor, dtype, name: str, ndim: int) -> None:
         raise ValueError("%s must be contiguous" % name)
 
 
+def _buf(ten: torch.Tensor, dtype, shape, name: str, like: torch.Tensor) -> None:
+    """A caller-supplied buffer: exact dtype and shape, contiguous, on the same device as `like`.  The C ABI
+    sees only pointers, so a buffer that is too short would be overrun on the device; it is refused here."""
+    if not isinstance(ten, torch.Tensor):
+        raise TypeError("%s must be a torch.Tensor" % name)
+    if ten.dtype != dtype:
+        raise TypeError("%s must have dtype %s, not %s" % (name, dtype, ten.dtype))
+    if tuple(ten.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, not %s" % (name, tuple(shape), tuple(ten.shape)))
+    if not ten.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if ten.device != like.device:
+        raise ValueError("%s must be on %s, not %s" % (name, like.device, ten.device))
+
+
+def _matrix(X: torch.Tensor, dtype, name: str) -> None:
+    """A 2-D input with unit stride along its rows; the device check comes after the shape checks of the
+    buffers that go with it, so that those can be exercised without a GPU."""
+    if not isinstance(X, torch.Tensor) or X.dtype != dtype or X.dim() != 2:
+        raise TypeError("%s must be a 2-D tensor of dtype %s" % (name, dtype))
+    if X.stride(1) != 1 and X.shape[1] != 1:
+        raise ValueError("%s must have unit stride along its last axis" % name)
+    if X.shape[0] > 1 and X.stride(0) < X.shape[1]:
+        raise ValueError("%s must not have overlapping rows" % name)
+
+
+def _on_gpu(X: torch.Tensor, name: str) -> None:
+    if not X.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+
+
+def _code_shape(T: int, I: int, bits: int):
+    if bits not in (4, 8):
+        raise CrossQuantError(-3)
+    if bits == 4 and I % 2:
+        raise CrossQuantError(-3)
+    return ((T, I), torch.int8) if bits == 8 else ((T, I // 2), torch.uint8)
+
+
 def crossquant_absmax(X: torch.Tensor, *, t: torch.Tensor = None, c: torch.Tensor = None):
     """Row maxima t (float32 [T]) and column maxima c (float32 [I]) of |X| in one pass."""
-    _req(X, torch.float16, "X", 2)
+    _matrix(X, torch.float16, "X")
     T, I = X.shape
     if t is None:
         t = torch.empty(T, dtype=torch.float32, device=X.device)
     if c is None:
         c = torch.empty(I, dtype=torch.float32, device=X.device)
-    _req(t, torch.float32, "t", 1)
-    _req(c, torch.float32, "c", 1)
+    _buf(t, torch.float32, (T,), "t", X)
+    _buf(c, torch.float32, (I,), "c", X)
+    _on_gpu(X, "X")
     _check(lib.crossquant_absmax(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(), _stream(X)))
     return t, c
+
+
+def _quant_buffers(X, T, I, t, c, codes, code_shape, code_dtype, xhat, row_scale, col_scale, zero_count) -> None:
+    _buf(t, torch.float32, (T,), "t", X)
+    _buf(c, torch.float32, (I,), "c", X)
+    _buf(codes, code_dtype, code_shape, "codes", X)
+    if xhat is not None:
+        _buf(xhat, torch.float16, (T, I), "xhat", X)
+    _buf(row_scale, torch.float32, (T,), "row_scale", X)
+    _buf(col_scale, torch.float32, (I,), "col_scale", X)
+    if zero_count is not None:
+        _buf(zero_count, torch.int64, (1,), "zero_count", X)
+    _on_gpu(X, "X")
 
 
 def crossquant_quantize(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
@@ -120,12 +173,12 @@ def crossquant_quantize(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha
 
     Returns (codes, xhat_or_None, row_scale, col_scale, zero_count_or_None); zero_count is a
     one-element int64 tensor (the library's unsigned 64-bit counter)."""
-    _req(X, torch.float16, "X", 2)
+    _matrix(X, torch.float16, "X")
     T, I = X.shape
     dev = X.device
+    code_shape, code_dtype = _code_shape(T, I, bits)
     if codes is None:
-        codes = (torch.empty((T, I), dtype=torch.int8, device=dev) if bits == 8
-                 else torch.empty((T, max(I // 2, 1)), dtype=torch.uint8, device=dev))
+        codes = torch.empty(code_shape, dtype=code_dtype, device=dev)
     if xhat is None and want_xhat:
         xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
     if row_scale is None:
@@ -134,10 +187,7 @@ def crossquant_quantize(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha
         col_scale = torch.empty(I, dtype=torch.float32, device=dev)
     if zero_count is None and want_count:
         zero_count = torch.empty(1, dtype=torch.int64, device=dev)
-    for ten, name in ((t, "t"), (c, "c"), (row_scale, "row_scale"), (col_scale, "col_scale")):
-        _req(ten, torch.float32, name, 1)
-    if not codes.is_contiguous() or (xhat is not None and not xhat.is_contiguous()):
-        raise ValueError("codes and xhat must be contiguous")
+    _quant_buffers(X, T, I, t, c, codes, code_shape, code_dtype, xhat, row_scale, col_scale, zero_count)
     _check(lib.crossquant_quantize(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(), float(alpha),
                                    int(bits), codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(),
                                    col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
@@ -154,16 +204,16 @@ def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want
     Returns (t, c, codes, xhat_or_None, row_scale, col_scale, zero_count_or_None).  Raises
     CrossQuantError with status -6 when the matrix does not fit on chip or is not in the
     vector layout; the caller then makes the two calls."""
-    _req(X, torch.float16, "X", 2)
+    _matrix(X, torch.float16, "X")
     T, I = X.shape
     dev = X.device
+    code_shape, code_dtype = _code_shape(T, I, bits)
     if t is None:
         t = torch.empty(T, dtype=torch.float32, device=dev)
     if c is None:
         c = torch.empty(I, dtype=torch.float32, device=dev)
     if codes is None:
-        codes = (torch.empty((T, I), dtype=torch.int8, device=dev) if bits == 8
-                 else torch.empty((T, max(I // 2, 1)), dtype=torch.uint8, device=dev))
+        codes = torch.empty(code_shape, dtype=code_dtype, device=dev)
     if xhat is None and want_xhat:
         xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
     if row_scale is None:
@@ -172,10 +222,7 @@ def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want
         col_scale = torch.empty(I, dtype=torch.float32, device=dev)
     if zero_count is None and want_count:
         zero_count = torch.empty(1, dtype=torch.int64, device=dev)
-    for ten, name in ((t, "t"), (c, "c"), (row_scale, "row_scale"), (col_scale, "col_scale")):
-        _req(ten, torch.float32, name, 1)
-    if not codes.is_contiguous() or (xhat is not None and not xhat.is_contiguous()):
-        raise ValueError("codes and xhat must be contiguous")
+    _quant_buffers(X, T, I, t, c, codes, code_shape, code_dtype, xhat, row_scale, col_scale, zero_count)
     _check(lib.crossquant_absmax_quantize(X.data_ptr(), T, I, X.stride(0), float(alpha), int(bits), t.data_ptr(),
                                           c.data_ptr(), codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(),
                                           col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
@@ -185,7 +232,7 @@ def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want
 def _req3(X: torch.Tensor):
     if not isinstance(X, torch.Tensor) or not X.is_cuda:
         raise ValueError("X must be a CUDA/HIP tensor")
-    if X.dtype != torch.float16 or X.dim() != 3 or X.stride(2) != 1:
+    if X.dtype != torch.float16 or X.dim() != 3 or (X.stride(2) != 1 and X.shape[2] != 1):
         raise ValueError("X must be a float16 [B][S][I] tensor with contiguous rows")
 
 
@@ -197,8 +244,8 @@ def crossquant_absmax_batched(X: torch.Tensor, *, t: torch.Tensor = None, c: tor
         t = torch.empty((B, S), dtype=torch.float32, device=X.device)
     if c is None:
         c = torch.empty((B, I), dtype=torch.float32, device=X.device)
-    if not (t.is_contiguous() and c.is_contiguous()):
-        raise ValueError("t and c must be contiguous")
+    _buf(t, torch.float32, (B, S), "t", X)
+    _buf(c, torch.float32, (B, I), "c", X)
     _check(lib.crossquant_absmax_batched(X.data_ptr(), B, S, I, X.stride(1), X.stride(0), t.data_ptr(), c.data_ptr(),
                                          _stream(X)))
     return t, c
@@ -221,8 +268,10 @@ def crossquant_quantize_batched(X: torch.Tensor, t: torch.Tensor, c: torch.Tenso
     row_scale = torch.empty((B, S), dtype=torch.float32, device=dev)
     col_scale = torch.empty((B, I), dtype=torch.float32, device=dev)
     zero_count = torch.empty(1, dtype=torch.int64, device=dev) if (want_count or not want_codes) else None
-    if not (t.is_contiguous() and c.is_contiguous()) or t.numel() != B * S or c.numel() != B * I:
-        raise ValueError("t must hold B*S and c B*I contiguous float32 values")
+    for ten, n, name in ((t, B * S, "t"), (c, B * I, "c")):
+        if (not isinstance(ten, torch.Tensor) or ten.dtype != torch.float32 or ten.numel() != n
+                or not ten.is_contiguous() or ten.device != dev):
+            raise ValueError("%s must hold %d contiguous float32 values on %s" % (name, n, dev))
     _check(lib.crossquant_quantize_batched(X.data_ptr(), B, S, I, X.stride(1), X.stride(0), t.data_ptr(), c.data_ptr(),
                                            float(alpha), int(bits), _ptr(codes), _ptr(xhat), row_scale.data_ptr(),
                                            col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
@@ -258,7 +307,7 @@ def crossquant_quantize_fp6(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, a
     """INT4 CrossQuant codes written directly as FP6 fragments for crossquant_w4a4_linear.
 
     Returns (packed, xhat_or_None, row_scale, col_scale, zero_count_or_None)."""
-    _req(X, torch.float16, "X", 2)
+    _matrix(X, torch.float16, "X")
     T, I = X.shape
     dev = X.device
     n = int(lib.crossquant_fp6_packed_bytes(T, I))
@@ -276,12 +325,30 @@ def crossquant_quantize_fp6(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, a
         col_scale = torch.empty(I, dtype=torch.float32, device=dev)
     if zero_count is None and want_count:
         zero_count = torch.empty(1, dtype=torch.int64, device=dev)
-    for ten, name in ((t, "t"), (c, "c"), (row_scale, "row_scale"), (col_scale, "col_scale")):
-        _req(ten, torch.float32, name, 1)
+    _buf(t, torch.float32, (T,), "t", X)
+    _buf(c, torch.float32, (I,), "c", X)
+    _buf(packed, torch.uint8, (n,), "packed", X)
+    if xhat is not None:
+        _buf(xhat, torch.float16, (T, I), "xhat", X)
+    _buf(row_scale, torch.float32, (T,), "row_scale", X)
+    _buf(col_scale, torch.float32, (I,), "col_scale", X)
+    if zero_count is not None:
+        _buf(zero_count, torch.int64, (1,), "zero_count", X)
+    _on_gpu(X, "X")
     _check(lib.crossquant_quantize_fp6(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(), float(alpha),
                                        packed.data_ptr(), _ptr(xhat), row_scale.data_ptr(), col_scale.data_ptr(),
                                        _ptr(zero_count), _stream(X)))
     return packed, xhat, row_scale, col_scale, zero_count
+
+
+def _linear_outputs(Y, acc_debug, T: int, O: int, like: torch.Tensor) -> None:
+    """Y: float16 [T][O], rows may be padded (unit stride inside a row); acc_debug: int32 [T][O] contiguous."""
+    if not isinstance(Y, torch.Tensor) or Y.dtype != torch.float16 or tuple(Y.shape) != (T, O):
+        raise ValueError("Y must be a float16 tensor of shape (%d, %d)" % (T, O))
+    if (O > 1 and Y.stride(1) != 1) or (T > 1 and Y.stride(0) < O) or Y.device != like.device:
+        raise ValueError("Y must have unit stride inside a row, non-overlapping rows, and be on %s" % like.device)
+    if acc_debug is not None:
+        _buf(acc_debug, torch.int32, (T, O), "acc_debug", like)
 
 
 def crossquant_w4a4_linear(qx_fp6: torch.Tensor, row_scale: torch.Tensor, qw_fp6: torch.Tensor, w_scale: torch.Tensor,
@@ -293,14 +360,15 @@ def crossquant_w4a4_linear(qx_fp6: torch.Tensor, row_scale: torch.Tensor, qw_fp6
             raise ValueError("%s must be a contiguous uint8 GPU tensor from crossquant_pack_fp6" % name)
     if qx_fp6.numel() != lib.crossquant_fp6_packed_bytes(T, I) or qw_fp6.numel() != lib.crossquant_fp6_packed_bytes(O, I):
         raise ValueError("packed operand sizes do not match T, I, O")
-    _req(row_scale, torch.float32, "row_scale", 1)
-    _req(w_scale, torch.float32, "w_scale", 1)
-    if row_scale.numel() != T or w_scale.numel() != O:
-        raise ValueError("shape mismatch")
+    _buf(row_scale, torch.float32, (T,), "row_scale", qx_fp6)
+    _buf(w_scale, torch.float32, (O,), "w_scale", qx_fp6)
+    if qw_fp6.device != qx_fp6.device:
+        raise ValueError("qw_fp6 must be on %s" % qx_fp6.device)
     if Y is None:
         Y = torch.empty((T, O), dtype=torch.float16, device=qx_fp6.device)
     if acc_debug is None and want_acc:
         acc_debug = torch.empty((T, O), dtype=torch.int32, device=qx_fp6.device)
+    _linear_outputs(Y, acc_debug, T, O, qx_fp6)
     _check(lib.crossquant_w4a4_linear(qx_fp6.data_ptr(), row_scale.data_ptr(), qw_fp6.data_ptr(), w_scale.data_ptr(),
                                       T, I, O, Y.data_ptr(), Y.stride(0), _ptr(acc_debug), _stream(qx_fp6)))
     return Y, acc_debug
@@ -329,43 +397,59 @@ def crossquant_calib_mfma_i8(iters: int, data_mode: int) -> float:
 def crossquant_kernel_count(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
                             row_scale: torch.Tensor = None, col_scale: torch.Tensor = None,
                             zero_count: torch.Tensor = None) -> torch.Tensor:
-    """Number of elements whose code is zero (one-element int64 tensor on the GPU)."""
-    _req(X, torch.float16, "X", 2)
+    """Number of elements whose code is zero (one-element int64 tensor on the GPU).  row_scale / col_scale:
+    optional buffers that receive the scale factors; without them the library uses none."""
+    _matrix(X, torch.float16, "X")
     T, I = X.shape
     dev = X.device
-    if row_scale is None:
-        row_scale = torch.empty(T, dtype=torch.float32, device=dev)
-    if col_scale is None:
-        col_scale = torch.empty(I, dtype=torch.float32, device=dev)
     if zero_count is None:
         zero_count = torch.empty(1, dtype=torch.int64, device=dev)
+    _buf(t, torch.float32, (T,), "t", X)
+    _buf(c, torch.float32, (I,), "c", X)
+    if (row_scale is None) != (col_scale is None):
+        raise ValueError("row_scale and col_scale: pass both or neither")
+    if row_scale is not None:
+        _buf(row_scale, torch.float32, (T,), "row_scale", X)
+        _buf(col_scale, torch.float32, (I,), "col_scale", X)
+    _buf(zero_count, torch.int64, (1,), "zero_count", X)
+    _on_gpu(X, "X")
     _check(lib.crossquant_kernel_count(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(),
-                                       float(alpha), int(bits), row_scale.data_ptr(), col_scale.data_ptr(),
+                                       float(alpha), int(bits), _ptr(row_scale), _ptr(col_scale),
                                        zero_count.data_ptr(), _stream(X)))
     return zero_count
 
 
 def crossquant_kernel_analysis(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
                                want_xrk: bool = True, xrk: torch.Tensor = None, row_scale: torch.Tensor = None,
-                               col_scale: torch.Tensor = None, counters: torch.Tensor = None):
+                               col_scale: torch.Tensor = None, counters: torch.Tensor = None,
+                               work_vectors: bool = True):
     """"Remove Kernel" matrix (float16 [T][I] or None) and a three-element int64 tensor
-    {kernel size, #{c_j >= t_i}, #{B~_ij < B_ij}}."""
-    _req(X, torch.float16, "X", 2)
+    {kernel size, #{c_j >= t_i}, #{B~_ij < B_ij}}.  row_scale / col_scale are the call's work vectors
+    (allocated here when not given); work_vectors=False passes NULL for both instead."""
+    _matrix(X, torch.float16, "X")
     T, I = X.shape
     dev = X.device
     if xrk is None and want_xrk:
         xrk = torch.empty((T, I), dtype=torch.float16, device=dev)
-    if row_scale is None:
+    if work_vectors and row_scale is None and col_scale is None:
         row_scale = torch.empty(T, dtype=torch.float32, device=dev)
-    if col_scale is None:
         col_scale = torch.empty(I, dtype=torch.float32, device=dev)
     if counters is None:
         counters = torch.empty(3, dtype=torch.int64, device=dev)
-    if xrk is not None and not xrk.is_contiguous():
-        raise ValueError("xrk must be contiguous")
+    _buf(t, torch.float32, (T,), "t", X)
+    _buf(c, torch.float32, (I,), "c", X)
+    if xrk is not None:
+        _buf(xrk, torch.float16, (T, I), "xrk", X)
+    if (row_scale is None) != (col_scale is None):
+        raise ValueError("row_scale and col_scale: pass both or neither")
+    if row_scale is not None:
+        _buf(row_scale, torch.float32, (T,), "row_scale", X)
+        _buf(col_scale, torch.float32, (I,), "col_scale", X)
+    _buf(counters, torch.int64, (3,), "counters", X)
+    _on_gpu(X, "X")
     _check(lib.crossquant_kernel_analysis(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(),
-                                          float(alpha), int(bits), _ptr(xrk), row_scale.data_ptr(),
-                                          col_scale.data_ptr(), counters.data_ptr(), _stream(X)))
+                                          float(alpha), int(bits), _ptr(xrk), _ptr(row_scale),
+                                          _ptr(col_scale), counters.data_ptr(), _stream(X)))
     return xrk, counters
 
 
@@ -377,6 +461,7 @@ def crossquant_unpack_int4(packed: torch.Tensor, *, codes: torch.Tensor = None) 
     T, half = packed.shape
     if codes is None:
         codes = torch.empty((T, 2 * half), dtype=torch.int8, device=packed.device)
+    _buf(codes, torch.int8, (T, 2 * half), "codes", packed)
     _check(lib.crossquant_unpack_int4(packed.data_ptr(), T, 2 * half, codes.data_ptr(), _stream(packed)))
     return codes
 
@@ -392,10 +477,10 @@ def crossquant_weight_quantize(W: torch.Tensor, fold, bits: int, *, qw: torch.Te
         qw = torch.empty((O, I), dtype=torch.int8, device=W.device)
     if w_scale is None:
         w_scale = torch.empty(O, dtype=torch.float32, device=W.device)
+    _buf(qw, torch.int8, (O, I), "qw", W)
+    _buf(w_scale, torch.float32, (O,), "w_scale", W)
     if fold is not None:
-        _req(fold, torch.float32, "fold", 1)
-        if fold.numel() != I:
-            raise ValueError("fold needs one factor per input channel")
+        _buf(fold, torch.float32, (I,), "fold", W)
     _check(lib.crossquant_weight_quantize(W.data_ptr(), I, O, _ptr(fold), int(bits), qw.data_ptr(),
                                           w_scale.data_ptr(), _stream(W)))
     return qw, w_scale
@@ -418,8 +503,12 @@ def crossquant_weight_quantize_grouped(W: torch.Tensor, fold, group: int, bits: 
         w_scale = torch.empty((O, I // group), dtype=torch.float32, device=W.device)
     if w_dq is None and want_dq:
         w_dq = torch.empty((I, O), dtype=torch.float16, device=W.device)
+    _buf(qw, torch.int8, (O, I), "qw", W)
+    _buf(w_scale, torch.float32, (O, I // group), "w_scale", W)
+    if w_dq is not None:
+        _buf(w_dq, torch.float16, (I, O), "w_dq", W)
     if fold is not None:
-        _req(fold, torch.float32, "fold", 1)
+        _buf(fold, torch.float32, (I,), "fold", W)
     _check(lib.crossquant_weight_quantize_grouped(W.data_ptr(), I, O, _ptr(fold), int(group), int(bits),
                                                   qw.data_ptr(), w_scale.data_ptr(), _ptr(w_dq), _stream(W)))
     return qw, w_scale, w_dq
@@ -428,20 +517,24 @@ def crossquant_weight_quantize_grouped(W: torch.Tensor, fold, group: int, bits: 
 def crossquant_w8a8_linear(qx: torch.Tensor, row_scale: torch.Tensor, qw: torch.Tensor, w_scale: torch.Tensor, *,
                            Y: torch.Tensor = None, acc_debug: torch.Tensor = None, want_acc: bool = False):
     """Y = fl16(acc * row_scale_i * w_scale_k) with acc = qx . qw^T in int32.  Returns (Y, acc_or_None)."""
-    _req(qx, torch.int8, "qx", 2)
-    _req(qw, torch.int8, "qw", 2)
+    _matrix(qx, torch.int8, "qx")
+    _matrix(qw, torch.int8, "qw")
     if not qx.is_contiguous() or not qw.is_contiguous():
         raise ValueError("qx and qw must be contiguous")
     T, I = qx.shape
     O, I2 = qw.shape
-    if I != I2 or row_scale.numel() != T or w_scale.numel() != O:
-        raise ValueError("shape mismatch")
-    _req(row_scale, torch.float32, "row_scale", 1)
-    _req(w_scale, torch.float32, "w_scale", 1)
+    if I != I2:
+        raise ValueError("qx is [T][I] and qw [O][I]: the contraction lengths differ (%d, %d)" % (I, I2))
+    if qw.device != qx.device:
+        raise ValueError("qw must be on %s" % qx.device)
+    _buf(row_scale, torch.float32, (T,), "row_scale", qx)
+    _buf(w_scale, torch.float32, (O,), "w_scale", qx)
     if Y is None:
         Y = torch.empty((T, O), dtype=torch.float16, device=qx.device)
     if acc_debug is None and want_acc:
         acc_debug = torch.empty((T, O), dtype=torch.int32, device=qx.device)
+    _linear_outputs(Y, acc_debug, T, O, qx)
+    _on_gpu(qx, "qx")
     _check(lib.crossquant_w8a8_linear(qx.data_ptr(), row_scale.data_ptr(), qw.data_ptr(), w_scale.data_ptr(),
                                       T, I, O, Y.data_ptr(), Y.stride(0), _ptr(acc_debug), _stream(qx)))
     return Y, acc_debug

@@ -18,14 +18,23 @@ namespace {
 constexpr int kWaves = 8;
 constexpr int kU = 4;
 
+__global__ void zero_counters_kernel(unsigned long long* __restrict__ counters) {
+    if (threadIdx.x < 3) counters[threadIdx.x] = 0ull;
+}
+
 // Block: 8 waves share 512 columns; each wave takes nb batches of 4 consecutive rows.
-template <bool VEC>
+// OWN_FACTORS: a_vec / b_vec are not given; the block forms the factors of its rows and columns itself
+// (as the quantize kernel does) and keeps them in LDS.
+template <bool VEC, bool OWN_FACTORS>
 __global__ void __launch_bounds__(kWaves * kLanes)
 analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ t_vec,
                 const float* __restrict__ c_vec, const float* __restrict__ a_vec, const float* __restrict__ b_vec,
-                float qmax, uint16_t* __restrict__ xrk, unsigned long long* __restrict__ counters,
+                double alpha, int qmax_i, uint16_t* __restrict__ xrk, unsigned long long* __restrict__ counters,
                 int n_col_chunks, int nb, bool out_vec) {
     __shared__ uint32_t lds_cnt[kWaves][3];
+    __shared__ float lds_a[OWN_FACTORS ? kWaves * kLanes : 1];
+    __shared__ float lds_b[OWN_FACTORS ? kColsPerWave : 1];
+    const float qmax = (float)qmax_i;
     const int lane = threadIdx.x & (kLanes - 1);
     const int wave = threadIdx.x / kLanes;
     const int col_chunk = blockIdx.x % n_col_chunks;
@@ -33,6 +42,11 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     const int j0 = col_chunk * kColsPerWave + lane * 8;
     const int rows_per_wave = nb * kU;
     const int row0 = row_chunk * (kWaves * rows_per_wave) + wave * rows_per_wave;
+    if (OWN_FACTORS) {
+        block_scale_factors(t_vec, c_vec, alpha, qmax_i, T, I, col_chunk * kColsPerWave,
+                            row_chunk * (kWaves * rows_per_wave), kWaves * rows_per_wave, lds_a, lds_b, nullptr, nullptr);
+        __syncthreads();
+    }
 
     // Columns past the end: x reads as 0 there, so the code is 0 (not counted as non-zero); c = -1 is never
     // >= t_i, and a step of +infinity (NaN for a_i = 0) is never below the per-token step.
@@ -41,7 +55,7 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const bool exists = j0 + e < I;
-        b[e] = exists ? b_vec[j0 + e] : 0.0f;
+        b[e] = exists ? (OWN_FACTORS ? lds_b[lane * 8 + e] : b_vec[j0 + e]) : 0.0f;
         c[e] = exists ? c_vec[j0 + e] : -1.0f;
         b_cmp[e] = exists ? b[e] : __builtin_inff();
         rb[e] = safe_rcp(b[e]);
@@ -51,7 +65,7 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     nvalid = nvalid < 0 ? 0 : (nvalid > 8 ? 8 : nvalid);
     // per row: a_i, t_i and the per-token step fl32(t_i / q_max), one row per lane
     const bool has_row = lane < rows_per_wave && row0 + lane < T;
-    const float a_lane = has_row ? a_vec[row0 + lane] : 0.0f;
+    const float a_lane = has_row ? (OWN_FACTORS ? lds_a[wave * rows_per_wave + lane] : a_vec[row0 + lane]) : 0.0f;
     const float t_lane = has_row ? t_vec[row0 + lane] : 0.0f;
     const float pt_lane = (float)((double)t_lane / (double)qmax);
 
@@ -146,22 +160,37 @@ analysis_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
 
 }  // namespace
 
+// a, b null: the kernel forms the factors itself (counters cleared by a kernel of their own first);
+// otherwise a, b are work vectors that a scale-finalize kernel fills first (it also clears the counters).
 hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, const float* t, const float* c,
-                                  const float* a, const float* b, int qmax, uint16_t* xrk,
+                                  float* a, float* b, float alpha, int qmax, uint16_t* xrk,
                                   unsigned long long* counters, hipStream_t stream) {
     const int ncc = (I + 511) / 512;
     const int nb = quantize_batches_per_wave(ncc, T);                      // rows per block = 32 * nb
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
-    if (!grid_fits((int64_t)ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;
+    if (!grid_fits((int64_t)ncc * nrc, kWaves * kLanes)) return hipErrorInvalidValue;     // before anything is enqueued
     const dim3 grid((unsigned)(ncc * nrc)), block(kWaves * kLanes);
     const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0);
     const bool out_vec = (I % 8 == 0) && (reinterpret_cast<uintptr_t>(xrk) % 16 == 0);
-    if (vec)
-        analysis_kernel<true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, a, b, (float)qmax, xrk, counters, ncc,
-                                                         nb, out_vec);
-    else
-        analysis_kernel<false><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, a, b, (float)qmax, xrk, counters, ncc,
-                                                          nb, out_vec);
+    const double al = (double)alpha;
+    if (a && b) {
+        const hipError_t e = launch_scale_finalize(t, c, T, I, alpha, qmax, a, b, counters, 3, stream);
+        if (e != hipSuccess) return e;
+        if (vec)
+            analysis_kernel<true, false><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, a, b, al, qmax, xrk, counters,
+                                                                    ncc, nb, out_vec);
+        else
+            analysis_kernel<false, false><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, a, b, al, qmax, xrk, counters,
+                                                                     ncc, nb, out_vec);
+    } else {
+        zero_counters_kernel<<<dim3(1), dim3(64), 0, stream>>>(counters);
+        if (vec)
+            analysis_kernel<true, true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, nullptr, nullptr, al, qmax, xrk,
+                                                                   counters, ncc, nb, out_vec);
+        else
+            analysis_kernel<false, true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, nullptr, nullptr, al, qmax, xrk,
+                                                                    counters, ncc, nb, out_vec);
+    }
     return hipGetLastError();
 }
 

@@ -1,6 +1,11 @@
 // C-ABI entry points: argument validation on the host, then kernel launches on the caller's
-// stream.  No allocation, no host synchronisation, no state.
+// stream.  No allocation and no host synchronisation.  The library does hold a little process-wide
+// state, all of it behind these calls: the table that gives every stream handle a slot of device-side
+// accumulators (cq_slots.hip: the quantize kernel's zero-count words, the single-read call's barrier
+// counters), the single-read call's poll limit (a test hook), and one flag per kernel and device saying
+// that the kernel has been allowed its dynamic LDS size.
 #include "../../include/crossquant.h"
+#include "../../include/crossquant_bench.h"
 
 #include <cmath>
 
@@ -120,14 +125,15 @@ void crossquant_debug_set_barrier_polls(unsigned polls) { cq::set_fused_barrier_
 int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
                             float alpha, int bits, float* row_scale, float* col_scale,
                             unsigned long long* zero_count, void* stream) {
-    if (!t || !c || !row_scale || !col_scale || !zero_count) return CQ_ERR_NULL;
+    if (!t || !c || !zero_count) return CQ_ERR_NULL;
+    if ((row_scale == nullptr) != (col_scale == nullptr)) return CQ_ERR_NULL;     // both or neither
     if (int s = check_matrix(X, T, I, ldx)) return s;
     if (bits != 4 && bits != 8) return CQ_ERR_BITS;
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;
     if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
         !aligned(zero_count, 8))
         return CQ_ERR_ALIGN;
-    if (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I)) return CQ_ERR_ALIAS;
+    if (row_scale && (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I))) return CQ_ERR_ALIAS;
     return from_hip(cq::launch_quantize(static_cast<const uint16_t*>(X), 1, (int)T, (int)I, ldx, 0, t, c, alpha, bits,
                                         row_scale, col_scale, nullptr, nullptr, zero_count,
                                         static_cast<hipStream_t>(stream)));
@@ -136,21 +142,20 @@ int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, co
 int crossquant_kernel_analysis(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
                                float alpha, int bits, void* xrk, float* row_scale, float* col_scale,
                                unsigned long long* counters, void* stream) {
-    if (!t || !c || !row_scale || !col_scale || !counters) return CQ_ERR_NULL;
+    if (!t || !c || !counters) return CQ_ERR_NULL;
+    if ((row_scale == nullptr) != (col_scale == nullptr)) return CQ_ERR_NULL;     // both or neither
     if (int s = check_matrix(X, T, I, ldx)) return s;
     if (bits != 4 && bits != 8) return CQ_ERR_BITS;
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;
     if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
         !aligned(xrk, 2) || !aligned(counters, 8))
         return CQ_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the factors are written by one kernel while the next one still reads t and c
+    if (row_scale && (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I))) return CQ_ERR_ALIAS;
     const int qmax = (1 << (bits - 1)) - 1;
-    if (int s = from_hip(cq::launch_scale_finalize(t, c, (int)T, (int)I, alpha, qmax, row_scale, col_scale,
-                                                   counters, 3, st)))
-        return s;
     return from_hip(cq::launch_kernel_analysis(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, t, c,
-                                               row_scale, col_scale, qmax, static_cast<uint16_t*>(xrk), counters,
-                                               st));
+                                               row_scale, col_scale, alpha, qmax, static_cast<uint16_t*>(xrk),
+                                               counters, static_cast<hipStream_t>(stream)));
 }
 
 int crossquant_unpack_int4(const void* packed, int64_t T, int64_t I, int8_t* codes, void* stream) {

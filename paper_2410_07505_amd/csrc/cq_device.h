@@ -89,6 +89,31 @@ __device__ __forceinline__ float col_factor(float c, double al) {
     return (float)p;
 }
 
+// Scale factors of one block of 512 threads, shared through LDS: thread k forms the factor of column col0 + k
+// (lds_b[k]; 0 past the last column) and, if the block has that many rows, of row row0 + k (lds_a[k]; 0 past
+// the last row).  a_out / b_out (nullable): where the caller wants them written as well.  Every block that
+// needs a factor computes the same bits from the same inputs.  The caller synchronises the block afterwards.
+__device__ __forceinline__ void block_scale_factors(const float* __restrict__ t_vec, const float* __restrict__ c_vec,
+                                                    double alpha, int qmax, int T, int I, int col0, int row0,
+                                                    int rows_per_block, float* lds_a, float* lds_b,
+                                                    float* __restrict__ a_out, float* __restrict__ b_out) {
+    const int k = (int)threadIdx.x;
+    const int j = col0 + k;
+    float bj = 0.0f;
+    if (j < I) {
+        bj = col_factor(c_vec[j], alpha);
+        if (b_out) b_out[j] = bj;
+    }
+    lds_b[k] = bj;
+    const int r = row0 + k;
+    float ar = 0.0f;
+    if (k < rows_per_block && r < T) {
+        ar = row_factor(t_vec[r], alpha, qmax);
+        if (a_out) a_out[r] = ar;
+    }
+    lds_a[k] = ar;
+}
+
 __device__ __forceinline__ float safe_rcp(float v) { return (v == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(v); }
 
 __device__ __forceinline__ float half_lo(uint32_t w) { return h2f(w & 0xFFFFu); }

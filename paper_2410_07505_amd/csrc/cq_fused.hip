@@ -42,17 +42,18 @@ constexpr int kFThreads = kFWaves * kLanes;
 constexpr int kFLdsBytes = kFLdsRows * kFThreads * 16;
 constexpr unsigned kFSpinLimit = 1u << 22;        // default poll limit; a poll takes a microsecond or two
 
-// Arrival counter of the grid barrier.  One per device (each device has its own copy of the
-// variable); cleared on the stream before every launch, so calls that overlap on one device race.
-__device__ unsigned int g_fused_arrivals;
+// Grid barrier state: blocks that have arrived at the barrier and blocks that have left it.  One pair per
+// stream slot (calls on different streams may overlap; calls on one stream are ordered), zero between
+// launches: every block arrives once and leaves once, and the block that leaves last clears the pair.
+struct FusedBarrier {
+    unsigned int arrivals, departures;
+};
+__device__ FusedBarrier g_fused_barrier[kStateSlots];
 
 __global__ void fused_zero_kernel(uint32_t* __restrict__ t, int T, uint32_t* __restrict__ c, int I,
                                   unsigned long long* __restrict__ zc) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) {
-        if (zc) *zc = 0ull;
-        g_fused_arrivals = 0u;
-    }
+    if (i == 0 && zc) *zc = 0ull;
     if (i < T) t[i] = 0u;
     else if (i - T < I) c[i - T] = 0u;
 }
@@ -63,7 +64,7 @@ __global__ void __launch_bounds__(kFThreads)
 fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float alpha, int qmax_i,
              uint32_t* t_bits, uint32_t* c_bits, float* __restrict__ a_out, float* __restrict__ b_out,
              uint8_t* __restrict__ codes, uint16_t* __restrict__ xhat, unsigned long long* __restrict__ zero_count,
-             int n_col_chunks, unsigned spin_limit) {
+             int n_col_chunks, unsigned spin_limit, int slot) {
     __shared__ uint32_t lds_col[kFWaves][4][kLanes];
     __shared__ float lds_a[kFBlockRows];
     __shared__ __align__(16) float lds_b[kColsPerWave];
@@ -144,16 +145,23 @@ fused_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, float al
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(&g_fused_arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        FusedBarrier* bar = &g_fused_barrier[slot];
+        __hip_atomic_fetch_add(&bar->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int open = 0;
         for (unsigned spin = 0; spin < spin_limit; ++spin) {
-            if (__hip_atomic_load(&g_fused_arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= gridDim.x) {
+            if (__hip_atomic_load(&bar->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= gridDim.x) {
                 open = 1;
                 break;
             }
             __builtin_amdgcn_s_sleep(8);
         }
         lds_open = open;
+        // leave (also after giving up): whoever leaves last has seen every block arrive, and nobody polls any more
+        const unsigned left = __hip_atomic_fetch_add(&bar->departures, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left == gridDim.x - 1u) {
+            __hip_atomic_store(&bar->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&bar->departures, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __syncthreads();
     const bool barrier_open = lds_open != 0;          // block-uniform
@@ -247,13 +255,19 @@ unsigned g_spin_limit = kFSpinLimit;
 template <int MODE, bool XHAT>
 hipError_t launch_fused_mode(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int qmax, float* t, float* c,
                              float* a, float* b, uint8_t* codes, uint16_t* xhat, unsigned long long* zc, int ncc,
-                             int nblocks, hipStream_t stream) {
-    const void* fn = reinterpret_cast<const void*>(&fused_kernel<MODE, XHAT>);
-    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kFLdsBytes);
+                             int nblocks, int slot, hipStream_t stream) {
+    // everything that can fail is checked before the first kernel of the call is enqueued
+    static std::atomic<uint64_t> lds_allowed{0};
+    const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&fused_kernel<MODE, XHAT>), kFLdsBytes, lds_allowed);
     if (e != hipSuccess) return e;
+    {
+        const int n = T + I;
+        fused_zero_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(reinterpret_cast<uint32_t*>(t), T,
+                                                                           reinterpret_cast<uint32_t*>(c), I, zc);
+    }
     fused_kernel<MODE, XHAT><<<dim3((unsigned)nblocks), dim3(kFThreads), kFLdsBytes, stream>>>(
         X, T, I, ldx, alpha, qmax, reinterpret_cast<uint32_t*>(t), reinterpret_cast<uint32_t*>(c), a, b, codes, xhat, zc,
-        ncc, g_spin_limit);
+        ncc, g_spin_limit, slot);
     return hipGetLastError();
 }
 
@@ -277,22 +291,20 @@ hipError_t launch_absmax_quantize(const uint16_t* X, int T, int I, int64_t ldx, 
     if (e != hipSuccess) return e;
     // a block fills a CU, and the grid barrier needs all blocks resident together: one block per CU
     if (nblocks > n_cu) return hipErrorNotSupported;
+    // the barrier's counters belong to a stream slot: a stream without one takes the two calls
+    const int slot = stream_slot(stream);
+    if (slot < 0) return hipErrorNotSupported;
     const int qmax = (1 << (bits - 1)) - 1;
-    {
-        const int n = T + I;
-        fused_zero_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(reinterpret_cast<uint32_t*>(t), T,
-                                                                           reinterpret_cast<uint32_t*>(c), I, zero_count);
-    }
     uint8_t* cp = static_cast<uint8_t*>(codes);
     if (bits == 8)
         return xhat ? launch_fused_mode<1, true>(X, T, I, ldx, alpha, qmax, t, c, a, b, cp, xhat, zero_count, ncc,
-                                                 (int)nblocks, stream)
+                                                 (int)nblocks, slot, stream)
                     : launch_fused_mode<1, false>(X, T, I, ldx, alpha, qmax, t, c, a, b, cp, nullptr, zero_count, ncc,
-                                                  (int)nblocks, stream);
+                                                  (int)nblocks, slot, stream);
     return xhat ? launch_fused_mode<2, true>(X, T, I, ldx, alpha, qmax, t, c, a, b, cp, xhat, zero_count, ncc,
-                                             (int)nblocks, stream)
+                                             (int)nblocks, slot, stream)
                 : launch_fused_mode<2, false>(X, T, I, ldx, alpha, qmax, t, c, a, b, cp, nullptr, zero_count, ncc,
-                                              (int)nblocks, stream);
+                                              (int)nblocks, slot, stream);
 }
 
 }  // namespace cq

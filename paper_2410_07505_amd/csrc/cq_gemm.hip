@@ -396,14 +396,14 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                       al16(acc_debug);
     hipError_t e;
     if (full) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_ring_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kRingLds);
+        static std::atomic<uint64_t> lds_allowed{0};
+        e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_i8_ring_kernel), kRingLds, lds_allowed);
         if (e != hipSuccess) return e;
         gemm_i8_ring_kernel<<<grid, dim3(512), kRingLds, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
                                                                    acc_debug, tiles_m, tiles_n);
     } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_i8_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        static std::atomic<uint64_t> lds_allowed{0};
+        e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_i8_kernel<true>), kLdsBytes, lds_allowed);
         if (e != hipSuccess) return e;
         gemm_i8_kernel<true><<<grid, block, kLdsBytes, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
                                                                  acc_debug, tiles_m, tiles_n, vec);

@@ -355,8 +355,8 @@ hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const voi
     if (!grid_fits((int64_t)tiles_m * tiles_n + kXcds, 512)) return hipErrorInvalidValue;
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + kXcds - 1) / kXcds;
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f6_ring_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kF6Lds);
+    static std::atomic<uint64_t> lds_allowed{0};
+    const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_f6_ring_kernel), kF6Lds, lds_allowed);
     if (e != hipSuccess) return e;
     gemm_f6_ring_kernel<<<dim3((unsigned)(per_xcd * kXcds)), dim3(512), kF6Lds, stream>>>(
         static_cast<const uint8_t*>(qx6), row_scale, static_cast<const uint8_t*>(qw6), w_scale, T, I, O, Y, ldy,

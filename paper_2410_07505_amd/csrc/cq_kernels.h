@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace cq {
 
 // binary16 bit pattern <-> binary32 (widening is exact; narrowing rounds to nearest even)
@@ -51,6 +53,20 @@ inline int quantize_batches_per_wave(int64_t n_chunks, int T) {
 constexpr int kStateSlots = 16;
 int stream_slot(hipStream_t stream);
 
+// A kernel that needs more dynamic LDS than the default limit has to be told so once per device.
+// `done` is a bit mask of the devices (ordinal < 64) on which that has happened for this kernel; devices with
+// a larger ordinal are simply told every time.
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 // t[0..T), c[0..I) <- 0 ; then one pass over X accumulating both maxima.
 // B matrices of T rows, matrix_stride elements apart (B = 1: a plain matrix); t is [B*T], c is [B*I].
 hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, float* t,
@@ -62,9 +78,12 @@ hipError_t launch_scale_finalize(const float* t, const float* c, int T, int I, f
                                  hipStream_t stream);
 
 // "Remove Kernel" matrix and the Table 1 indicators; counters = {Z, #{c_j >= t_i}, #{B~ < B}}.
+// a, b: work vectors that receive the scale factors, or both null (the kernel then forms the factors itself).
+// Clears the counters on the stream first.
 hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, const float* t,
-                                  const float* c, const float* a, const float* b, int qmax,
+                                  const float* c, float* a, float* b, float alpha, int qmax,
                                   uint16_t* xrk, unsigned long long* counters, hipStream_t stream);
+
 
 // Scale factors (as launch_scale_finalize: a, b are outputs), then fused quantize / dequantize / zero
 // count, in one kernel.  codes or xhat may be null (count only = both null).

@@ -74,8 +74,8 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     X += (int64_t)matrix * matrix_stride;
     t_vec += (int64_t)matrix * T;
     c_vec += (int64_t)matrix * I;
-    a_out += (int64_t)matrix * T;
-    b_out += (int64_t)matrix * I;
+    if (a_out) a_out += (int64_t)matrix * T;           // null: the caller does not want the factors (count only)
+    if (b_out) b_out += (int64_t)matrix * I;
     if (MODE == 1) codes += (int64_t)matrix * T * I;
     if (MODE == 2) codes += (int64_t)matrix * T * (I / 2);
     if (XHAT) xhat += (int64_t)matrix * T * I;
@@ -105,23 +105,8 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
         w[u] = (nb > 1 && batch_row(1) + u < T) ? load8<VEC>(X + (int64_t)(batch_row(1) + u) * ldx, j0, I)
                                                 : make_uint4(0u, 0u, 0u, 0u);
 
-    {
-        // thread k of the block: column k of the chunk, and row k of the block
-        const int j = col_chunk * kColsPerWave + (int)threadIdx.x;
-        float bj = 0.0f;
-        if (j < I) {
-            bj = col_factor(c_vec[j], alpha);
-            if (row_chunk == 0) b_out[j] = bj;
-        }
-        lds_b[threadIdx.x] = bj;
-        const int r = row_chunk * rows_per_block + (int)threadIdx.x;
-        float ar = 0.0f;
-        if ((int)threadIdx.x < rows_per_block && r < T) {
-            ar = row_factor(t_vec[r], alpha, qmax_i);
-            if (col_chunk == 0) a_out[r] = ar;
-        }
-        lds_a[threadIdx.x] = ar;
-    }
+    block_scale_factors(t_vec, c_vec, alpha, qmax_i, T, I, col_chunk * kColsPerWave, row_chunk * rows_per_block,
+                        rows_per_block, lds_a, lds_b, col_chunk == 0 ? a_out : nullptr, row_chunk == 0 ? b_out : nullptr);
     __syncthreads();
     // the wave's row factors, one per lane, handed out with readlane as the rows come up
     const float a_lane = lds_a[wave * rows_per_wave + (lane < rows_per_wave ? lane : 0)];

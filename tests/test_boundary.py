@@ -10,6 +10,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "crossquant.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
 
 
 @pytest.fixture(scope="module")
@@ -18,16 +19,21 @@ def cq():
     return pkg
 
 
-def declared_functions():
-    src = open(HEADER).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(crossquant_\w+)\s*\(", src)))
+def declared_functions(headers=None):
+    names = set()
+    for h in (HEADERS if headers is None else headers):
+        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names.update(re.findall(r"\b(crossquant_\w+)\s*\(", src))
+    return sorted(names)
 
 
 def test_header_declares_the_four_named_calls():
-    names = declared_functions()
+    names = declared_functions([HEADER])
     for n in ("crossquant_absmax", "crossquant_quantize", "crossquant_kernel_count", "crossquant_w8a8_linear"):
         assert n in names
+    # benchmark calibration and test hooks are not in the method's header
+    assert not [n for n in names if "calib" in n or "debug" in n]
+    assert len(HEADERS) >= 2 and any("calib" in n for n in declared_functions())
 
 
 def test_library_exports_every_declared_symbol(cq):
@@ -132,7 +138,9 @@ def test_kernel_count_argument_errors(cq):
     def call(X=P, T=4, I=8, ldx=8, t=P, c=P, alpha=1.0, bits=8, rs=P, cs=P, zc=P):
         return f(X, T, I, ldx, t, c, alpha, bits, rs, cs, zc, None)
 
-    assert call(zc=0) == -1 and call(X=0) == -1 and call(rs=0) == -1
+    assert call(zc=0) == -1 and call(X=0) == -1
+    assert call(rs=0) == -1 and call(cs=0) == -1            # the two work vectors: both or neither
+    assert call(rs=0, cs=0, T=0) == -2                      # neither is fine: the next check is reached
     assert call(T=0) == -2
     assert call(bits=5) == -3
     assert call(alpha=2.0) == -4
@@ -146,11 +154,14 @@ def test_kernel_analysis_argument_errors(cq):
     def call(X=P, T=4, I=8, ldx=8, t=P, c=P, alpha=0.15, bits=8, xrk=P, rs=P, cs=P, cnt=P):
         return f(X, T, I, ldx, t, c, alpha, bits, xrk, rs, cs, cnt, None)
 
-    assert call(cnt=0) == -1 and call(X=0) == -1 and call(cs=0) == -1
+    assert call(cnt=0) == -1 and call(X=0) == -1 and call(cs=0) == -1 and call(rs=0) == -1
+    assert call(rs=0, cs=0, I=0) == -2                      # no work vectors: allowed
     assert call(I=0) == -2 and call(ldx=7) == -2
     assert call(bits=6) == -3
     assert call(alpha=-1.0) == -4
     assert call(cnt=P + 4) == -5 and call(xrk=P + 1) == -5
+    far = dict(t=P, c=P + 0x1000, rs=P + 0x2000, cs=P + 0x3000)
+    assert call(**{**far, "rs": P + 12}) == -8 and call(**{**far, "cs": P + 0x1000}) == -8
 
 
 def test_weight_quantize_argument_errors(cq):
@@ -231,3 +242,62 @@ def test_python_wrappers_refuse_cpu_tensors(cq):
     X = torch.zeros((4, 8), dtype=torch.float16)
     with pytest.raises(ValueError):
         cq.crossquant_absmax(X)
+
+
+def test_python_wrappers_check_every_buffer_they_are_given(cq):
+    """The C ABI sees pointers only, so the binding refuses buffers of the wrong length, shape, dtype or
+    device before the library is called (CPU tensors reach these checks; a correct set fails later, on
+    "must be a GPU tensor")."""
+    import torch
+    T, I, O = 4, 8, 16
+    X = torch.zeros((T, I), dtype=torch.float16)
+    f32 = lambda n: torch.zeros(n, dtype=torch.float32)
+    t, c = f32(T), f32(I)
+    with pytest.raises(ValueError, match="GPU"):
+        cq.crossquant_absmax(X, t=t, c=c)
+    with pytest.raises(ValueError, match="t must have shape"):
+        cq.crossquant_absmax(X, t=c, c=t)                                  # swapped
+    with pytest.raises(ValueError, match="c must have shape"):
+        cq.crossquant_absmax(X, t=t, c=f32(I - 1))
+    with pytest.raises(TypeError, match="t must have dtype"):
+        cq.crossquant_absmax(X, t=torch.zeros(T, dtype=torch.float64), c=c)
+    with pytest.raises(ValueError, match="contiguous"):
+        cq.crossquant_absmax(X, t=f32(2 * T)[::2], c=c)
+    for fn in (cq.crossquant_quantize, ):
+        with pytest.raises(ValueError, match="t must have shape"):
+            fn(X, c, t, 0.15, 8)
+        with pytest.raises(ValueError, match="codes must have shape"):
+            fn(X, t, c, 0.15, 8, codes=torch.zeros((T, I // 2), dtype=torch.int8))
+        with pytest.raises(TypeError, match="codes must have dtype"):
+            fn(X, t, c, 0.15, 4, codes=torch.zeros((T, I // 2), dtype=torch.int8))
+        with pytest.raises(ValueError, match="xhat must have shape"):
+            fn(X, t, c, 0.15, 8, xhat=torch.zeros((T, I - 1), dtype=torch.float16))
+        with pytest.raises(ValueError, match="row_scale must have shape"):
+            fn(X, t, c, 0.15, 8, row_scale=f32(I), col_scale=f32(I))
+        with pytest.raises(ValueError, match="zero_count must have shape"):
+            fn(X, t, c, 0.15, 8, zero_count=torch.zeros(2, dtype=torch.int64))
+        with pytest.raises(TypeError, match="zero_count must have dtype"):
+            fn(X, t, c, 0.15, 8, zero_count=torch.zeros(1, dtype=torch.int32))
+    with pytest.raises(ValueError, match="c must have shape"):
+        cq.crossquant_absmax_quantize(X, 0.15, 8, c=f32(T))
+    with pytest.raises(ValueError, match="both or neither"):
+        cq.crossquant_kernel_count(X, t, c, 1.0, 8, row_scale=f32(T))
+    with pytest.raises(ValueError, match="t must have shape"):
+        cq.crossquant_kernel_count(X, c, t, 1.0, 8)
+    with pytest.raises(ValueError, match="counters must have shape"):
+        cq.crossquant_kernel_analysis(X, t, c, 1.0, 8, counters=torch.zeros(2, dtype=torch.int64))
+    with pytest.raises(ValueError, match="xrk must have shape"):
+        cq.crossquant_kernel_analysis(X, t, c, 1.0, 8, xrk=torch.zeros((I, T), dtype=torch.float16))
+    qx, qw = torch.zeros((T, I), dtype=torch.int8), torch.zeros((O, I), dtype=torch.int8)
+    with pytest.raises(ValueError, match="row_scale must have shape"):
+        cq.crossquant_w8a8_linear(qx, f32(O), qw, f32(O))
+    with pytest.raises(ValueError, match="w_scale must have shape"):
+        cq.crossquant_w8a8_linear(qx, f32(T), qw, f32(T))
+    with pytest.raises(ValueError, match="Y must be a float16 tensor of shape"):
+        cq.crossquant_w8a8_linear(qx, f32(T), qw, f32(O), Y=torch.zeros((T, O - 1), dtype=torch.float16))
+    with pytest.raises(ValueError, match="Y must be a float16 tensor of shape"):
+        cq.crossquant_w8a8_linear(qx, f32(T), qw, f32(O), Y=torch.zeros((T, O), dtype=torch.float32))
+    with pytest.raises(ValueError, match="acc_debug must have shape"):
+        cq.crossquant_w8a8_linear(qx, f32(T), qw, f32(O), acc_debug=torch.zeros((O, T), dtype=torch.int32))
+    with pytest.raises(ValueError, match="contraction lengths"):
+        cq.crossquant_w8a8_linear(qx, f32(T), torch.zeros((O, I + 1), dtype=torch.int8), f32(O))

@@ -6,7 +6,14 @@ if the approximation stays within 2^-19 (relative) of the correctly rounded quot
 analysis gives 2^-20 (two reciprocals at up to 1.5 * 2^-23 each as modelled here, three roundings
 at 2^-24, and the quotient's own).  Here the bound is measured with numpy binary32 arithmetic, with
 the correctly rounded reciprocals perturbed by +-1 ulp in every combination (the hardware
-reciprocal is within 1 ulp of the true value; its exact rounding is not specified)."""
+reciprocal is within 1 ulp of the true value; its exact rounding is not specified).
+
+This file MODELS the kernel's shortcut in numpy; it does not run the kernel, and the 1-ulp
+reciprocal is an assumption about the hardware, not something measured here.  It says that the
+margin is wide enough if that assumption holds.  What pins the shortcut on the device is the GPU
+parity suite: `test_quotients_just_off_a_rounding_tie` (quotients 2^-24 ... 2^-10 away from a tie,
+every one compared with the oracle's division) and the exact-tie cases of
+`test_quantize_rounding_ties` in tests/test_gpu_parity.py."""
 from __future__ import annotations
 
 import numpy as np

@@ -148,8 +148,12 @@ def check_quantize(cq, X, alpha, bits, Xg=None, label=""):
     # codes-only and count-only variants give the same codes / count
     codes2, none_xhat, _, _, zc2 = cq.crossquant_quantize(Xg, t, c, alpha, bits, want_xhat=False)
     assert none_xhat is None and np.array_equal(host(codes2), ref["codes"]) and int(host(zc2)[0]) == ref["Z"]
-    zc3 = cq.crossquant_kernel_count(Xg, t, c, alpha, bits)
+    zc3 = cq.crossquant_kernel_count(Xg, t, c, alpha, bits)          # no work vectors (NULL, NULL)
     assert int(host(zc3)[0]) == ref["Z"] == oracle.kernel_count(X, t_ref, c_ref, alpha, bits)
+    a4, b4 = torch.full_like(a, -1.0), torch.full_like(b, -1.0)      # with them: they receive the factors
+    zc4 = cq.crossquant_kernel_count(Xg, t, c, alpha, bits, row_scale=a4, col_scale=b4)
+    assert int(host(zc4)[0]) == ref["Z"]
+    assert np.array_equal(bits32(host(a4)), bits32(ref["a"])) and np.array_equal(bits32(host(b4)), bits32(ref["b"]))
     return ref
 
 
@@ -745,6 +749,9 @@ def check_analysis(cq, X, alpha, bits, Xg=None, label=""):
     assert np.array_equal(bits16(host(xrk)), bits16(ref["xrk"]))
     none_xrk, counters2 = cq.crossquant_kernel_analysis(Xg, t, c, alpha, bits, want_xrk=False)
     assert none_xrk is None and np.array_equal(host(counters2), got)
+    # without work vectors (NULL, NULL): the kernel forms the factors itself
+    xrk3, counters3 = cq.crossquant_kernel_analysis(Xg, t, c, alpha, bits, work_vectors=False)
+    assert np.array_equal(host(counters3), got) and np.array_equal(bits16(host(xrk3)), bits16(ref["xrk"]))
     return ref
 
 
@@ -1003,9 +1010,10 @@ def test_end_to_end_full_config_sampled(cq, name):
     torch.cuda.synchronize()
     say("gpu side done")
     rng = np.random.default_rng(11)
-    rows = np.sort(rng.choice(cfg.T, 6, replace=False))
+    # at least 64 whole rows and 256 whole columns, tile edges included
+    rows = np.sort(rng.choice(cfg.T, 64, replace=False))
     rows = np.unique(np.concatenate([rows, [0, cfg.T - 1, 255, 256]]))
-    cols = np.sort(rng.choice(cfg.O, 24, replace=False))
+    cols = np.sort(rng.choice(cfg.O, 256, replace=False))
     cols = np.unique(np.concatenate([cols, [0, cfg.O - 1, 255, 256]]))
     Yr, accr = oracle.w8a8_linear(ref["codes"][rows], ref["a"][rows], qw_ref, s_ref)
     assert np.array_equal(host(acc[torch.from_numpy(rows).cuda()]), accr)
