@@ -3,13 +3,18 @@
 
 A step is one pass of the whole path over one batch of synthetic input, all resident in HBM:
   absmax (row + column maxima)  ->  quantize (codes + dequantized matrix + zero count)
-  ->  kernel count at alpha = 1 (the per-token baseline)  ->  W8A8 linear (INT8 MFMA GEMM).
+  ->  kernel count at alpha = 1 (the per-token baseline)  ->  linear layer on the codes
+      (W8A8 on the INT8 matrix instruction; the INT4 configuration: A4W4 on the FP6 one).
 Weight quantization is weight preparation and happens once, outside the timed region.
 
-Prints one JSON line.  `value` is the quantizer's throughput (absmax + quantize stages:
-algorithmic bytes / summed stage time); the W8A8 linear's TOPS is reported beside it.  The
-`roofline` object describes the dominant kernel (the GEMM); `roofline_quantize` the fused
-quantize kernel.  Stage times come from HIP events recorded on the stream the kernels run on.
+Prints one JSON line.  The headline workload is C5 (the 70B-shaped layer): `value` is its
+quantizer throughput = algorithmic bytes of absmax + quantize / the sum of the two stage times,
+each stage time the MEDIAN over the timed steps of the HIP-event interval around the stage (events
+recorded on the stream the kernels run on).  `roofline` describes the dominant kernel (the GEMM),
+`roofline_quantize` the fused quantize kernel.  `event_free` gives the same step timed by the wall
+clock with no event in it, with and without the two quantizer calls: what the event packets between
+the stages cost can be read off the difference.  `configs` repeats the step loop on the other
+configurations (C1-C4), `cpu_baseline` times the CPU oracle on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -27,12 +32,13 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published (5.0 POP/s)
 FP6_PEAK_TOPS = 10100.0      # MI355X dense FP6 / FP4 MFMA, published (10.1 PFLOP/s): the A4W4 path
 METRIC = "CrossQuant quantize GB/s (% HBM peak) + W8A8 linear TOPS (% INT8 MFMA peak)"
+STAGES = ("absmax", "quantize", "count", "linear")
 
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy of known size (profiles/bench_c5_hbm_traffic_pmc.txt).  Measured
-# once per workload; null for workloads that have not been profiled.
+# counters read for a plain copy of known size (profiles/*_hbm_traffic_pmc.txt).  Measured once per
+# workload with the command given in the profile; null for workloads that have not been profiled.
 MEASURED_TRAFFIC_BYTES = {
-    "C5": {"gemm": (1344.9 + 224.0) * 2 ** 20, "quantize": (64.4 + 96.1) * 2 ** 20},
+    "C5": {"linear": (1344.9 + 224.0) * 2 ** 20, "quantize": (64.4 + 96.1) * 2 ** 20},
 }
 
 
@@ -41,13 +47,15 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C5", help="workload: C2, C3 or C5 (INT8 configurations)")
+    ap.add_argument("--config", default="C5", help="headline workload (C1 ... C5); C5 is the one the metric is quoted on")
     ap.add_argument("--alpha", type=float, default=0.15)
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from a captured HIP graph and report its time per step")
     ap.add_argument("--no-extras", action="store_true",
-                    help="only the timed step loop: no single-read / warm / calibration / A4W4 comparisons "
-                         "(the form the committed profiles are taken with)")
+                    help="only the timed step loop of the headline workload: no other configurations, no "
+                         "event-free / single-read / warm / calibration / A4W4 / vendor comparisons (the form the "
+                         "committed kernel-trace profiles are taken with)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the step loops of the other configurations")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the plain read / copy / MFMA-only calibration kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -59,48 +67,205 @@ def parse():
     return ap.parse_args()
 
 
+def median_time(fn, reps):
+    """Median wall time of fn() over reps calls, and the value of the last call."""
+    import statistics
+    ts, out = [], None
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        out = fn()
+        ts.append(time.perf_counter() - t0)
+    return statistics.median(ts), out
+
+
 def cpu_baseline(cfg, X, W, alpha):
-    """The CPU oracle, as it stands, timed on the host cores on a bounded sample of the same
-    workload: the full activation matrix for absmax / quantize / count, a 2048-row slab of the
-    linear layer (full I x O) scaled to T rows."""
-    import numpy as np
+    """The CPU oracle, as it stands, on the host cores, on a bounded sample of the headline workload: the
+    full activation matrix for absmax / quantize / count, a 512-row slab of the linear layer (full I x O)
+    scaled to T rows.  Every leg is run three times and the median reported."""
     import oracle
     T, I, O = cfg.T, cfg.I, cfg.O
-    t0 = time.perf_counter()
-    t, c = oracle.absmax(X)
-    t1 = time.perf_counter()
-    ref = oracle.quantize(X, t, c, alpha, cfg.bits, want_xhat=True)
-    t2 = time.perf_counter()
-    oracle.kernel_count(X, t, c, 1.0, cfg.bits)
-    t3 = time.perf_counter()
-    slab = min(2048, T)
-    Wslab_cols = O
-    qw, s = oracle.weight_quantize(W[:, :Wslab_cols], ref["b"], cfg.bits)
-    t4 = time.perf_counter()
-    oracle.w8a8_linear(ref["codes"][:slab], ref["a"][:slab], qw, s)
-    t5 = time.perf_counter()
+    reps = 3
+    absmax_s, (t, c) = median_time(lambda: oracle.absmax(X), reps)
+    quant_s, ref = median_time(lambda: oracle.quantize(X, t, c, alpha, cfg.bits, want_xhat=True), reps)
+    count_s, _ = median_time(lambda: oracle.kernel_count(X, t, c, 1.0, cfg.bits), reps)
+    slab = min(512, T)
+    qw, s = oracle.weight_quantize(W, ref["b"], cfg.bits)
+    q_slab = ref["codes"][:slab] if cfg.bits == 8 else oracle.unpack_int4(ref["codes"][:slab])
+    lin_slab_s, _ = median_time(lambda: oracle.w8a8_linear(q_slab, ref["a"][:slab], qw, s), reps)
     n = T * I
     q_bytes = 2 * n + (2 + 1 + 2) * n            # absmax read + quantize read/codes/xhat
-    q_time = (t1 - t0) + (t2 - t1)
-    lin_time = (t5 - t4) * (T / slab)
+    lin_time = lin_slab_s * (T / slab)
     # the same quantizer on one thread (the definition as a scalar loop), on a quarter of the rows
     n_thr = oracle.num_threads()
     oracle.set_num_threads(1)
     Xq = X[: max(T // 4, 1)]
-    s0 = time.perf_counter()
-    t1t, c1t = oracle.absmax(Xq)
-    oracle.quantize(Xq, t1t, c1t, alpha, cfg.bits, want_xhat=True)
-    s1 = time.perf_counter()
+
+    def single():
+        t1, c1 = oracle.absmax(Xq)
+        oracle.quantize(Xq, t1, c1, alpha, cfg.bits, want_xhat=True)
+    single_s, _ = median_time(single, reps)
     oracle.set_num_threads(n_thr)
-    single_gbs = 7 * Xq.size / (s1 - s0) / 1e9
     return {
-        "value": q_bytes / q_time / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": "full %dx%d activation for absmax+quantize+count; linear layer on a %d-row slab "
-                  "(full %dx%d weights), time scaled by T/%d" % (T, I, slab, I, O, slab),
-        "absmax_s": t1 - t0, "quantize_s": t2 - t1, "count_s": t3 - t2,
+        "value": q_bytes / (absmax_s + quant_s) / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "full %dx%d activation for absmax+quantize+count; linear layer on a %d-row slab (full %dx%d "
+                  "weights), time scaled by T/%d; every leg the median of %d runs" % (T, I, slab, I, O, slab, reps),
+        "absmax_s": absmax_s, "quantize_s": quant_s, "count_s": count_s,
         "linear_s_extrapolated": lin_time, "w8a8_linear_tops": 2.0 * T * I * O / lin_time / 1e12,
-        "single_thread_value": single_gbs, "single_thread_sample": "absmax + quantize on the first %d rows" % Xq.shape[0],
+        "single_thread_value": 7 * Xq.size / single_s / 1e9,
+        "single_thread_sample": "absmax + quantize on the first %d rows, median of %d runs" % (Xq.shape[0], reps),
     }
+
+
+class Workload:
+    """Everything one configuration's step touches, allocated once; `step` enqueues one pass."""
+
+    def __init__(self, name, alpha, stages):
+        import torch
+        import paper_2410_07505_amd as cq
+        import workloads
+        self.cq, self.torch = cq, torch
+        self.cfg = cfg = workloads.CONFIGS[name]
+        self.alpha, self.stages = alpha, stages
+        self.bits = bits = cfg.bits     # 8: W8A8 on the INT8 kernel; 4: A4W4 on the FP6 kernel
+        T, I, O = cfg.T, cfg.I, cfg.O
+        dev = torch.device("cuda:0")
+        self.X = workloads.config_activation(name)
+        self.W = workloads.config_weight(name)
+        self.Xg = torch.from_numpy(self.X).to(dev)
+        Wg = torch.from_numpy(self.W).to(dev)
+        f32 = lambda n_: torch.empty(n_, dtype=torch.float32, device=dev)
+        self.t, self.c, self.a, self.b, self.a_pt, self.b_pt = f32(T), f32(I), f32(T), f32(I), f32(T), f32(I)
+        self.codes = (torch.empty((T, I), dtype=torch.int8, device=dev) if bits == 8
+                      else torch.empty((T, I // 2), dtype=torch.uint8, device=dev))
+        self.xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
+        self.zc = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.zc_pt = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.Y = torch.empty((T, O), dtype=torch.float16, device=dev)
+        self.qw = torch.empty((O, I), dtype=torch.int8, device=dev)
+        self.ws = f32(O)
+        # weight preparation (once): needs the column factors of this activation
+        cq.crossquant_absmax(self.Xg, t=self.t, c=self.c)
+        cq.crossquant_quantize(self.Xg, self.t, self.c, alpha, bits, codes=self.codes, xhat=self.xhat, row_scale=self.a,
+                               col_scale=self.b, zero_count=self.zc)
+        cq.crossquant_weight_quantize(Wg, self.b, bits, qw=self.qw, w_scale=self.ws)
+        self.px = self.pw = None
+        if bits == 4:
+            self.pw = cq.crossquant_pack_fp6(self.qw)
+            self.px = cq.crossquant_pack_fp6(self.codes)
+        torch.cuda.synchronize()
+        del Wg
+
+    def quantizer(self):
+        cq = self.cq
+        cq.crossquant_absmax(self.Xg, t=self.t, c=self.c)
+        self.quantize()
+
+    def quantize(self):
+        cq = self.cq
+        if self.bits == 8:
+            cq.crossquant_quantize(self.Xg, self.t, self.c, self.alpha, 8, codes=self.codes, xhat=self.xhat,
+                                   row_scale=self.a, col_scale=self.b, zero_count=self.zc)
+        else:       # INT4 codes leave the quantizer already in the FP6 kernel's operand format
+            cq.crossquant_quantize_fp6(self.Xg, self.t, self.c, self.alpha, packed=self.px, xhat=self.xhat,
+                                       row_scale=self.a, col_scale=self.b, zero_count=self.zc)
+
+    def step(self, ev=None, single_read=False, stages=None):
+        cq, cfg = self.cq, self.cfg
+        stages = self.stages if stages is None else stages
+        if ev is not None:
+            ev[0].record()
+        if single_read:
+            cq.crossquant_absmax_quantize(self.Xg, self.alpha, self.bits, t=self.t, c=self.c, codes=self.codes,
+                                          xhat=self.xhat, row_scale=self.a, col_scale=self.b, zero_count=self.zc)
+        elif "absmax" in stages:
+            cq.crossquant_absmax(self.Xg, t=self.t, c=self.c)
+        if ev is not None:
+            ev[1].record()
+        if "quantize" in stages and not single_read:
+            self.quantize()
+        if ev is not None:
+            ev[2].record()
+        if "count" in stages:
+            cq.crossquant_kernel_count(self.Xg, self.t, self.c, 1.0, self.bits, zero_count=self.zc_pt)
+        if ev is not None:
+            ev[3].record()
+        if "linear" in stages:
+            if self.bits == 8:
+                cq.crossquant_w8a8_linear(self.codes, self.a, self.qw, self.ws, Y=self.Y)
+            else:
+                cq.crossquant_w4a4_linear(self.px, self.a, self.pw, self.ws, cfg.T, cfg.I, cfg.O, Y=self.Y)
+        if ev is not None:
+            ev[4].record()
+
+    def timed_steps(self, steps, warmup, **kw):
+        """Stage times in ms (median and mean over the steps of each HIP-event interval) and the wall time per step."""
+        import numpy as np
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(**kw)
+        torch.cuda.synchronize()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(events[i], **kw)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per = np.array([[ev[s].elapsed_time(ev[s + 1]) for s in range(4)] for ev in events])
+        return np.median(per, axis=0), per.mean(axis=0), wall * 1e3 / steps
+
+    def wall_ms_per_step(self, steps, warmup, stages):
+        """The step with no event in it, timed by the host clock around `steps` of them."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(stages=stages)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(stages=stages)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def figures(self, stage_ms):
+        """Rates of one configuration from its stage times (ms)."""
+        cfg, bits = self.cfg, self.bits
+        T, I, O = cfg.T, cfg.I, cfg.O
+        n = T * I
+        code_bytes = 1.0 if bits == 8 else 0.75     # int8 codes, or 6-bit fields of the FP6 fragments
+        bytes_absmax = 2 * n + 4 * (T + I)
+        bytes_quant = (2 + code_bytes + 2) * n + 4 * (T + I)
+        ran = {name: (name in self.stages) for name in STAGES}
+        ms = {name: (float(stage_ms[i]) if ran[name] else 0.0) for i, name in enumerate(STAGES)}
+        quant_gbs = ((bytes_absmax + bytes_quant) / ((ms["absmax"] + ms["quantize"]) * 1e-3) / 1e9
+                     if (ran["absmax"] and ran["quantize"]) else None)
+        tops = 2.0 * T * I * O / (ms["linear"] * 1e-3) / 1e12 if ran["linear"] else None
+        rate = lambda b_, m_: (b_ / (m_ * 1e-3) / 1e9) if m_ > 0 else None
+        return {"ms": ms, "quant_gbs": quant_gbs, "tops": tops, "bytes_absmax": bytes_absmax, "bytes_quant": bytes_quant,
+                "absmax_gbs": rate(bytes_absmax, ms["absmax"]), "quantize_gbs": rate(bytes_quant, ms["quantize"]),
+                "count_gbs": rate(2 * n, ms["count"]), "peak_tops": INT8_PEAK_TOPS if bits == 8 else FP6_PEAK_TOPS}
+
+    def summary(self, steps, warmup):
+        """The per-configuration object of the `configs` section."""
+        med, _, wall_ms = self.timed_steps(steps, warmup)
+        f = self.figures(med)
+        n = self.cfg.T * self.cfg.I
+        lin = "w8a8_linear" if self.bits == 8 else "a4w4_linear_fp6"
+        return {
+            "workload": "%s: %s" % (self.cfg.name, self.cfg.label), "bits": self.bits, "steps": steps,
+            "ms_per_step": wall_ms,
+            "stage_ms_median": {"absmax": f["ms"]["absmax"], "quantize": f["ms"]["quantize"],
+                                "count_per_token": f["ms"]["count"], lin: f["ms"]["linear"]},
+            "quantizer_GBs": f["quant_gbs"], "quantizer_frac_hbm_peak": f["quant_gbs"] / HBM_PEAK_GBS,
+            "absmax_GBs": f["absmax_gbs"], "quantize_GBs": f["quantize_gbs"], "count_GBs": f["count_gbs"],
+            "linear_TOPs": f["tops"], "linear_peak_TOPs": f["peak_tops"], "linear_frac_peak": f["tops"] / f["peak_tops"],
+            "kernel_proportion": {"crossquant": int(self.zc.item()) / n, "per_token": int(self.zc_pt.item()) / n},
+        }
+
+    def release(self):
+        for k in list(self.__dict__):
+            if k not in ("cfg", "bits", "alpha", "stages", "cq", "torch"):
+                delattr(self, k)
+        self.torch.cuda.empty_cache()
 
 
 def main():
@@ -110,7 +275,6 @@ def main():
               "throughput)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     if args.copy_calibration:
@@ -124,149 +288,27 @@ def main():
         return
 
     import paper_2410_07505_amd as cq     # raises if libcrossquant.so is missing: no fallback
-    import workloads
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU available", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    cfg = workloads.CONFIGS[args.config]
-    bits = cfg.bits                 # 8: W8A8 on the INT8 kernel; 4: A4W4 on the FP6 kernel (codes packed per step)
+    stages = STAGES if args.stages == "all" else tuple(args.stages.split(","))
+    full = args.stages == "all"
+    extras = full and not args.no_extras
+
+    wl = Workload(args.config, args.alpha, stages)
+    cfg, bits, alpha = wl.cfg, wl.bits, args.alpha
     T, I, O = cfg.T, cfg.I, cfg.O
-    alpha = args.alpha
-    stages = ("absmax", "quantize", "count", "linear") if args.stages == "all" else tuple(args.stages.split(","))
-
-    X = workloads.config_activation(args.config)
-    W = workloads.config_weight(args.config)
-    Xg = torch.from_numpy(X).to(dev)
-    Wg = torch.from_numpy(W).to(dev)
-
-    # every buffer the step touches is allocated here, once
-    t = torch.empty(T, dtype=torch.float32, device=dev)
-    c = torch.empty(I, dtype=torch.float32, device=dev)
-    a = torch.empty(T, dtype=torch.float32, device=dev)
-    b = torch.empty(I, dtype=torch.float32, device=dev)
-    a_pt = torch.empty(T, dtype=torch.float32, device=dev)
-    b_pt = torch.empty(I, dtype=torch.float32, device=dev)
-    codes = (torch.empty((T, I), dtype=torch.int8, device=dev) if bits == 8
-             else torch.empty((T, I // 2), dtype=torch.uint8, device=dev))
-    xhat = torch.empty((T, I), dtype=torch.float16, device=dev)
-    zc = torch.zeros(1, dtype=torch.int64, device=dev)
-    zc_pt = torch.zeros(1, dtype=torch.int64, device=dev)
-    Y = torch.empty((T, O), dtype=torch.float16, device=dev)
-    qw = torch.empty((O, I), dtype=torch.int8, device=dev)
-    ws = torch.empty(O, dtype=torch.float32, device=dev)
-
-    # weight preparation (once): needs the column factors of this activation
-    cq.crossquant_absmax(Xg, t=t, c=c)
-    cq.crossquant_quantize(Xg, t, c, alpha, bits, codes=codes, xhat=xhat, row_scale=a, col_scale=b, zero_count=zc)
-    cq.crossquant_weight_quantize(Wg, b, bits, qw=qw, w_scale=ws)
-    px = pw = None
-    if bits == 4:
-        pw = cq.crossquant_pack_fp6(qw)
-        px = cq.crossquant_pack_fp6(codes)
-    torch.cuda.synchronize()
-    del Wg
-
-    def step(ev=None, single_read=False):
-        if ev is not None:
-            ev[0].record()
-        if single_read:
-            cq.crossquant_absmax_quantize(Xg, alpha, bits, t=t, c=c, codes=codes, xhat=xhat, row_scale=a,
-                                          col_scale=b, zero_count=zc)
-        elif "absmax" in stages:
-            cq.crossquant_absmax(Xg, t=t, c=c)
-        if ev is not None:
-            ev[1].record()
-        if "quantize" in stages and not single_read:
-            if bits == 8:
-                cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
-                                       zero_count=zc)
-            else:       # INT4 codes leave the quantizer already in the FP6 kernel's operand format
-                cq.crossquant_quantize_fp6(Xg, t, c, alpha, packed=px, xhat=xhat, row_scale=a, col_scale=b,
-                                           zero_count=zc)
-        if ev is not None:
-            ev[2].record()
-        if "count" in stages:
-            cq.crossquant_kernel_count(Xg, t, c, 1.0, bits, row_scale=a_pt, col_scale=b_pt, zero_count=zc_pt)
-        if ev is not None:
-            ev[3].record()
-        if "linear" in stages:
-            if bits == 8:
-                cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)
-            else:
-                cq.crossquant_w4a4_linear(px, a, pw, ws, T, I, O, Y=Y)
-        if ev is not None:
-            ev[4].record()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    stage_ms = np.zeros(4)
-    for ev in events:
-        for s_ in range(4):
-            stage_ms[s_] += ev[s_].elapsed_time(ev[s_ + 1])
-    stage_ms /= args.steps
-    ms_per_step = wall * 1e3 / args.steps
-
     n = T * I
-    bytes_absmax = 2 * n + 4 * (T + I)
-    code_bytes = 1.0 if bits == 8 else 0.75     # int8 codes, or 6-bit fields of the FP6 fragments
-    bytes_quant = (2 + code_bytes + 2) * n + 4 * (T + I)
-    bytes_count = 2 * n
-    ops_linear = 2.0 * T * I * O
-    # a stage that was switched off (--stages) only measures the gap between two event records
-    ran = {name: (name in stages) for name in ("absmax", "quantize", "count", "linear")}
-    for idx, name in enumerate(("absmax", "quantize", "count", "linear")):
-        if not ran[name]:
-            stage_ms[idx] = 0.0
-    quant_gbs = (bytes_absmax + bytes_quant) / ((stage_ms[0] + stage_ms[1]) * 1e-3) / 1e9 \
-        if (ran["absmax"] and ran["quantize"]) else None
-    tops = ops_linear / (stage_ms[3] * 1e-3) / 1e12 if ran["linear"] else None
-    mfma_peak = INT8_PEAK_TOPS if bits == 8 else FP6_PEAK_TOPS
 
-    z, z_pt = int(zc.item()), int(zc_pt.item())
-
-    # The single-read variant of absmax + quantize (same outputs), timed after the main loop, both
-    # inside the same step (X cold: the linear layer has just swept the caches) and back to back
-    # (X still in the Infinity Cache).  It is not part of `value`, which stays on the two named calls.
-    fused = None
-    if args.stages == "all" and not args.no_extras and bits == 8:
-        try:
-            for _ in range(max(args.warmup, 3)):
-                step(single_read=True)
-            torch.cuda.synchronize()
-            n_f = max(args.steps // 2, 1)
-            ev_f = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(n_f)]
-            for i in range(n_f):
-                step(ev_f[i], single_read=True)
-            torch.cuda.synchronize()
-            in_step_ms = sum(ev[0].elapsed_time(ev[2]) for ev in ev_f) / n_f
-            z_f = int(zc.item())
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(n_f):
-                cq.crossquant_absmax_quantize(Xg, alpha, bits, t=t, c=c, codes=codes, xhat=xhat, row_scale=a,
-                                              col_scale=b, zero_count=zc)
-            e1.record()
-            torch.cuda.synchronize()
-            warm_ms = e0.elapsed_time(e1) / n_f
-            f_bytes = (2 + code_bytes + 2) * n + 8 * (T + I)
-            fused = {"in_step_ms": in_step_ms, "in_step_algorithmic_GBs": f_bytes / (in_step_ms * 1e-3) / 1e9,
-                     "back_to_back_ms": warm_ms, "two_call_in_step_ms": float(stage_ms[0] + stage_ms[1]),
-                     "zero_count_matches": z_f == z}
-        except cq.CrossQuantError as e:
-            fused = {"unsupported": str(e)}
+    # ---- the timed region: exactly `steps` steps after `warmup` untimed ones
+    med, mean, ms_per_step = wl.timed_steps(args.steps, args.warmup)
+    f = wl.figures(med)
+    f_mean = wl.figures(mean)
+    quant_gbs, tops, mfma_peak = f["quant_gbs"], f["tops"], f["peak_tops"]
+    z, z_pt = int(wl.zc.item()), int(wl.zc_pt.item())
 
     def event_ms(fn, reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -277,23 +319,52 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
+    # ---- the same step with no event in it (host clock around the loop), with and without the two
+    # quantizer calls: their difference is what absmax + quantize cost inside the step when nothing
+    # but kernels is on the stream; `value` keeps the event-bracketed definition.
+    event_free = None
+    if extras:
+        w_all = wl.wall_ms_per_step(args.steps, 3, STAGES)
+        w_rest = wl.wall_ms_per_step(args.steps, 3, ("count", "linear"))
+        # the second loop leaves t, c, a, b, codes as the first one wrote them, so the count and the
+        # linear layer see the same operands
+        d_ms = w_all - w_rest
+        event_free = {"ms_per_step_all_stages": w_all, "ms_per_step_without_absmax_quantize": w_rest,
+                      "absmax_plus_quantize_ms": d_ms,
+                      "quantizer_GBs": (f["bytes_absmax"] + f["bytes_quant"]) / (d_ms * 1e-3) / 1e9 if d_ms > 0 else None,
+                      "with_events_ms_per_step": ms_per_step,
+                      "event_bracketed_absmax_plus_quantize_ms": f["ms"]["absmax"] + f["ms"]["quantize"]}
+
+    # ---- the single-call variant of absmax + quantize (same outputs), both inside the same step (X cold:
+    # the linear layer has just swept the caches) and back to back (X still in the memory-side cache).
+    # It is not part of `value`, which stays on the two named calls.
+    fused = None
+    if extras and bits == 8:
+        try:
+            n_f = max(args.steps // 2, 1)
+            med_f, _, _ = wl.timed_steps(n_f, max(args.warmup, 3), single_read=True)
+            z_f = int(wl.zc.item())
+            single = lambda: cq.crossquant_absmax_quantize(wl.Xg, alpha, bits, t=wl.t, c=wl.c, codes=wl.codes, xhat=wl.xhat,
+                                                           row_scale=wl.a, col_scale=wl.b, zero_count=wl.zc)
+            event_ms(single, 3)
+            warm_f = event_ms(single, n_f)
+            in_step_ms = float(med_f[0] + med_f[1])
+            f_bytes = (2 + 1 + 2) * n + 8 * (T + I)
+            fused = {"in_step_ms": in_step_ms, "in_step_algorithmic_GBs": f_bytes / (in_step_ms * 1e-3) / 1e9,
+                     "back_to_back_ms": warm_f, "two_call_in_step_ms": f["ms"]["absmax"] + f["ms"]["quantize"],
+                     "zero_count_matches": z_f == z}
+        except cq.CrossQuantError as e:
+            fused = {"unsupported": str(e)}
+
     # the same two quantizer calls back to back (X stays in the memory-side cache): the warm rate
     warm_ms = None
-    if ran["absmax"] and ran["quantize"] and not args.no_extras:
-        def quantizer():
-            cq.crossquant_absmax(Xg, t=t, c=c)
-            if bits == 8:
-                cq.crossquant_quantize(Xg, t, c, alpha, 8, codes=codes, xhat=xhat, row_scale=a, col_scale=b,
-                                       zero_count=zc)
-            else:
-                cq.crossquant_quantize_fp6(Xg, t, c, alpha, packed=px, xhat=xhat, row_scale=a, col_scale=b,
-                                           zero_count=zc)
-        event_ms(quantizer, 5)
-        warm_ms = event_ms(quantizer, max(args.steps // 2, 1))
+    if extras:
+        event_ms(wl.quantizer, 5)
+        warm_ms = event_ms(wl.quantizer, max(args.steps // 2, 1))
 
     # what the device sustains on a plain read, a plain copy and an MFMA-only loop
     achievable = None
-    if not args.no_ceilings and not args.no_extras:
+    if extras and not args.no_ceilings:
         big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)       # 1 GiB: far beyond the caches
         big.fill_(1)
         half = 512 << 20
@@ -316,35 +387,49 @@ def main():
         }
 
     # The same layer in the paper's W4A4 setting: INT4 codes of the same X and W, multiplied on the
-    # FP6 matrix instruction (exact) and, for comparison, unpacked to int8 on the INT8 kernel.
-    a4w4 = None
-    if args.stages == "all" and not args.no_extras and bits == 8:
-        Wg4 = torch.from_numpy(W).to(dev)
-        nib, _, a4, b4, _ = cq.crossquant_quantize(Xg, t, c, alpha, 4, want_xhat=False)
+    # FP6 matrix instruction (exact) and, for comparison, unpacked to int8 on the INT8 kernel; and the
+    # vendor library's int8 GEMM (torch._int_mm, int32 output, no epilogue) on the same W8A8 codes.
+    a4w4 = vendor = None
+    if extras and bits == 8:
+        ops_linear = 2.0 * T * I * O
+        reps = max(args.steps // 4, 1)
+        try:
+            acc32 = torch.empty((T, O), dtype=torch.int32, device=dev)
+            qwt = wl.qw.t()
+            vend = lambda: torch._int_mm(wl.codes, qwt, out=acc32)
+            event_ms(vend, 3)
+            v_ms = event_ms(vend, reps)
+            vendor = {"what": "torch._int_mm on the same int8 codes (int32 output, no scale epilogue)", "ms": v_ms,
+                      "TOPs": ops_linear / (v_ms * 1e-3) / 1e12, "this_kernel_ms": f["ms"]["linear"]}
+            del acc32
+        except Exception as e:                      # not every build of the vendor library takes this layout
+            vendor = {"unavailable": repr(e)[:200]}
+        Wg4 = torch.from_numpy(wl.W).to(dev)
+        nib, _, a4, b4, _ = cq.crossquant_quantize(wl.Xg, wl.t, wl.c, alpha, 4, want_xhat=False)
         qw4, ws4 = cq.crossquant_weight_quantize(Wg4, b4, 4)
         del Wg4
         px, pw = cq.crossquant_pack_fp6(nib), cq.crossquant_pack_fp6(qw4)
         q8 = cq.crossquant_unpack_int4(nib)
-        event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=Y), 10)
-        fp6_ms = event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=Y), max(args.steps // 4, 1))
-        y6 = Y.clone()
-        event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=Y), 10)
-        i8_ms = event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=Y), max(args.steps // 4, 1))
+        event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=wl.Y), 10)
+        fp6_ms = event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=wl.Y), reps)
+        y6 = wl.Y.clone()
+        event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=wl.Y), 10)
+        i8_ms = event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=wl.Y), reps)
         pack_ms = event_ms(lambda: cq.crossquant_pack_fp6(nib, packed=px), 10)
         a4w4 = {"fp6_ms": fp6_ms, "fp6_TOPs": ops_linear / (fp6_ms * 1e-3) / 1e12, "int8_path_ms": i8_ms,
                 "int8_path_TOPs": ops_linear / (i8_ms * 1e-3) / 1e12, "pack_activations_ms": pack_ms,
-                "identical_outputs": bool(torch.equal(y6.view(torch.int16), Y.view(torch.int16)))}
+                "identical_outputs": bool(torch.equal(y6.view(torch.int16), wl.Y.view(torch.int16)))}
         del px, pw, q8, nib, qw4, y6
-        cq.crossquant_w8a8_linear(codes, a, qw, ws, Y=Y)      # leave Y as the W8A8 result
+        cq.crossquant_w8a8_linear(wl.codes, wl.a, wl.qw, wl.ws, Y=wl.Y)      # leave Y as the W8A8 result
 
     graph_ms = None
-    if args.graph and args.stages == "all":
+    if args.graph and full:
         g = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             with torch.cuda.graph(g, stream=side):
-                step()
+                wl.step()
         torch.cuda.current_stream().wait_stream(side)
         for _ in range(args.warmup):
             g.replay()
@@ -355,6 +440,7 @@ def main():
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - tg) * 1e3 / args.steps
 
+    lin_name = "w8a8_linear" if bits == 8 else "a4w4_linear"
     out = {
         "metric": METRIC,
         "value": quant_gbs, "unit": "GB/s",
@@ -369,34 +455,47 @@ def main():
         "data": "synthetic (seeded N(0,1) activations with outlier channels, N(0,0.02) weights)",
         "config": {"workload": "%s: %s" % (cfg.name, cfg.label), "T": T, "I": I, "O": O, "bits": bits,
                    "alpha": alpha, "stages": list(stages)},
-        "stage_ms": {"absmax": stage_ms[0], "quantize": stage_ms[1], "count_per_token": stage_ms[2],
-                     ("w8a8_linear" if bits == 8 else "a4w4_linear"): stage_ms[3]},
-        "stage_rate": {
-            "absmax_GBs": bytes_absmax / (stage_ms[0] * 1e-3) / 1e9 if stage_ms[0] > 0 else None,
-            "quantize_GBs": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
-            "count_GBs": bytes_count / (stage_ms[2] * 1e-3) / 1e9 if stage_ms[2] > 0 else None,
-        },
+        "stage_time_statistic": "median over the timed steps of each stage's HIP-event interval",
+        "stage_ms": {"absmax": f["ms"]["absmax"], "quantize": f["ms"]["quantize"], "count_per_token": f["ms"]["count"],
+                     lin_name: f["ms"]["linear"]},
+        "stage_ms_mean": {"absmax": f_mean["ms"]["absmax"], "quantize": f_mean["ms"]["quantize"],
+                          "count_per_token": f_mean["ms"]["count"], lin_name: f_mean["ms"]["linear"]},
+        "stage_rate": {"absmax_GBs": f["absmax_gbs"], "quantize_GBs": f["quantize_gbs"], "count_GBs": f["count_gbs"]},
         "kernel_proportion": {"crossquant": z / n, "per_token": z_pt / n},
-        "absmax_quantize_single_read": fused,
+        "event_free": event_free,
+        "absmax_quantize_single_call": fused,
         "graph_replay_ms_per_step": graph_ms,
-        "quantizer_warm": {"ms": warm_ms, "GBs": (bytes_absmax + bytes_quant) / (warm_ms * 1e-3) / 1e9} if warm_ms else None,
+        "quantizer_warm": {"ms": warm_ms, "GBs": (f["bytes_absmax"] + f["bytes_quant"]) / (warm_ms * 1e-3) / 1e9} if warm_ms else None,
         "achievable": achievable,
+        "vendor_int8_gemm": vendor,
         "a4w4_linear": a4w4,
         "roofline": {"kernel": ("gemm_i8_ring_kernel (W8A8 linear)" if bits == 8 else
                                 "gemm_f6_ring_kernel (A4W4 linear)"),
                      "bound": "mfma", "achieved": tops, "peak": mfma_peak, "unit": "TOP/s",
                      "frac": tops / mfma_peak if tops else None,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm")},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("linear")},
         "roofline_quantize": {"kernel": "quantize_kernel (scale factors + codes + xhat + zero count)",
-                              "bound": "hbm",
-                              "achieved": bytes_quant / (stage_ms[1] * 1e-3) / 1e9 if stage_ms[1] > 0 else None,
-                              "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": (bytes_quant / (stage_ms[1] * 1e-3) / 1e9 / HBM_PEAK_GBS)
-                              if stage_ms[1] > 0 else None,
+                              "bound": "hbm", "achieved": f["quantize_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": (f["quantize_gbs"] / HBM_PEAK_GBS) if f["quantize_gbs"] else None,
                               "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("quantize")},
     }
+
+    X_head, W_head = wl.X, wl.W
+    # ---- the other configurations: the same step loop (parity cases for the tests, bench lines here so
+    # that every shape's rates are on record); fewer steps each, the headline stays the long run
+    if extras and not args.no_configs:
+        wl.release()
+        out["configs"] = {}
+        for name in ("C1", "C2", "C3", "C4", "C5"):
+            if name == cfg.name:
+                continue
+            w2 = Workload(name, alpha, STAGES)
+            out["configs"][name] = w2.summary(min(args.steps, 100), min(args.warmup, 10))
+            w2.release()
+            del w2
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, X, W, alpha)
+        out["cpu_baseline"] = cpu_baseline(cfg, X_head, W_head, alpha)
     print(json.dumps(out))
 
 

@@ -150,7 +150,7 @@ def check_quantize(cq, X, alpha, bits, Xg=None, label=""):
     assert none_xhat is None and np.array_equal(host(codes2), ref["codes"]) and int(host(zc2)[0]) == ref["Z"]
     zc3 = cq.crossquant_kernel_count(Xg, t, c, alpha, bits)          # no work vectors (NULL, NULL)
     assert int(host(zc3)[0]) == ref["Z"] == oracle.kernel_count(X, t_ref, c_ref, alpha, bits)
-    a4, b4 = torch.full_like(a, -1.0), torch.full_like(b, -1.0)      # with them: they receive the factors
+    a4, b4 = a.clone().fill_(-1.0), b.clone().fill_(-1.0)            # with them: they receive the factors
     zc4 = cq.crossquant_kernel_count(Xg, t, c, alpha, bits, row_scale=a4, col_scale=b4)
     assert int(host(zc4)[0]) == ref["Z"]
     assert np.array_equal(bits32(host(a4)), bits32(ref["a"])) and np.array_equal(bits32(host(b4)), bits32(ref["b"]))
