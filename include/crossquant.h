@@ -160,6 +160,22 @@ int crossquant_kernel_analysis(const void *X, int64_t T, int64_t I, int64_t ldx,
                                float *col_scale, unsigned long long *counters, void *stream);
 
 /*
+ * crossquant_kernel_analysis for callers that cannot allocate device memory and therefore cannot
+ * supply the two work vectors: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs and arithmetic, but the scale factors are kept in a
+ * static device array of the library (2 x CQ_ANALYSIS_STATIC_MAX floats = 4 MiB, one copy on every
+ * device the library runs on, there until the process ends).  The call allocates nothing.
+ * Limits: T <= CQ_ANALYSIS_STATIC_MAX and I <= CQ_ANALYSIS_STATIC_MAX, else CQ_ERR_SHAPE with
+ * nothing enqueued.  All calls on one device share that device's array: calls that overlap on one
+ * device (different streams, or replays of graphs that contain it) race and must be ordered by the
+ * caller; calls on one stream are ordered anyway.
+ */
+#define CQ_ANALYSIS_STATIC_MAX (1 << 19)
+int crossquant_kernel_analysis_static(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
+                                      const float *c, float alpha, int bits, void *xrk,
+                                      unsigned long long *counters, void *stream);
+
+/*
  * Expand packed INT4 codes (crossquant_quantize with bits == 4) to int8 codes in [-7, 7], so that
  * A4 activations can feed crossquant_w8a8_linear (gfx950 has no INT4 matrix instruction; weight
  * codes from crossquant_weight_quantize with bits == 4 are already stored one per byte).

@@ -40,6 +40,8 @@ lib.crossquant_debug_set_barrier_polls.argtypes = [ctypes.c_uint]
 lib.crossquant_debug_set_barrier_polls.restype = None
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
+lib.crossquant_kernel_analysis_static.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp]
+lib.crossquant_kernel_analysis_static.restype = _int
 lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]
 lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
 lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
@@ -450,6 +452,23 @@ def crossquant_kernel_analysis(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor
     _check(lib.crossquant_kernel_analysis(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(),
                                           float(alpha), int(bits), _ptr(xrk), _ptr(row_scale),
                                           _ptr(col_scale), counters.data_ptr(), _stream(X)))
+    return xrk, counters
+
+
+def crossquant_kernel_analysis_static(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int, *,
+                                      xrk: torch.Tensor = None, counters: torch.Tensor):
+    """crossquant_kernel_analysis with the work vectors in the library's static device array: nothing is
+    allocated here or in the library, so every buffer (xrk optional, counters required) comes from the caller."""
+    _matrix(X, torch.float16, "X")
+    T, I = X.shape
+    _buf(t, torch.float32, (T,), "t", X)
+    _buf(c, torch.float32, (I,), "c", X)
+    if xrk is not None:
+        _buf(xrk, torch.float16, (T, I), "xrk", X)
+    _buf(counters, torch.int64, (3,), "counters", X)
+    _on_gpu(X, "X")
+    _check(lib.crossquant_kernel_analysis_static(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(),
+                                                 float(alpha), int(bits), _ptr(xrk), counters.data_ptr(), _stream(X)))
     return xrk, counters
 
 

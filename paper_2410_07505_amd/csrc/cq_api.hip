@@ -158,6 +158,20 @@ int crossquant_kernel_analysis(const void* X, int64_t T, int64_t I, int64_t ldx,
                                                counters, static_cast<hipStream_t>(stream)));
 }
 
+int crossquant_kernel_analysis_static(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
+                                      float alpha, int bits, void* xrk, unsigned long long* counters, void* stream) {
+    if (!t || !c || !counters) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (T > CQ_ANALYSIS_STATIC_MAX || I > CQ_ANALYSIS_STATIC_MAX) return CQ_ERR_SHAPE;
+    if (bits != 4 && bits != 8) return CQ_ERR_BITS;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(xrk, 2) || !aligned(counters, 8)) return CQ_ERR_ALIGN;
+    const int qmax = (1 << (bits - 1)) - 1;
+    return from_hip(cq::launch_kernel_analysis_static(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, t, c, alpha,
+                                                      qmax, static_cast<uint16_t*>(xrk), counters,
+                                                      static_cast<hipStream_t>(stream)));
+}
+
 int crossquant_unpack_int4(const void* packed, int64_t T, int64_t I, int8_t* codes, void* stream) {
     if (!packed || !codes) return CQ_ERR_NULL;
     if (!dim_ok(T) || !dim_ok(I) || (I & 1) || T * I > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;

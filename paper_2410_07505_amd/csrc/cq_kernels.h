@@ -85,6 +85,12 @@ hipError_t launch_kernel_analysis(const uint16_t* X, int T, int I, int64_t ldx, 
                                   uint16_t* xrk, unsigned long long* counters, hipStream_t stream);
 
 
+// The same with the work vectors in the library's static device array (T, I <= CQ_ANALYSIS_STATIC_MAX, else
+// hipErrorInvalidValue with nothing enqueued).  Calls that overlap on one device race on that array.
+hipError_t launch_kernel_analysis_static(const uint16_t* X, int T, int I, int64_t ldx, const float* t, const float* c,
+                                         float alpha, int qmax, uint16_t* xrk, unsigned long long* counters,
+                                         hipStream_t stream);
+
 // Scale factors (as launch_scale_finalize: a, b are outputs), then fused quantize / dequantize / zero
 // count, in one kernel.  codes or xhat may be null (count only = both null).
 // B matrices as in launch_absmax; t, a are [B*T], c, b are [B*I], codes / xhat are [B*T][...].
