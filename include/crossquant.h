@@ -59,6 +59,12 @@ typedef enum {
  * X: binary16 [T][ldx], ldx >= I (elements), 2-byte aligned (16-byte alignment of X together
  *    with ldx % 8 == 0 selects the vectorised path; any other layout takes a slower one).
  * t: out, float[T].  c: out, float[I].  Both are exact (a maximum of binary16 values).
+ * The maxima are accumulated with atomics, so t and c are cleared first, inside the call.  In the
+ * vectorised layout with I % 8 == 0 that is done by the one launch itself: its first blocks store the
+ * zeros and the others wait for them (a bounded wait on a counter in library-owned device memory, one
+ * per stream handle as for crossquant_quantize's zero count) before their atomics.  Calls captured
+ * into a graph, calls on a stream without a counter of its own, and other layouts clear with a small
+ * kernel of their own before the pass.
  */
 int crossquant_absmax(const void *X, int64_t T, int64_t I, int64_t ldx, float *t, float *c,
                       void *stream);

@@ -168,9 +168,10 @@ constexpr float kTinyFactor = 8.673617379884035e-19f;   // 2^-60: both products 
 
 __device__ __forceinline__ bool tiny_factor(float f) { return f != 0.0f && f < kTinyFactor; }
 
-__device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, const float (&b)[8],
-                                          const float (&rb)[8], float qmax, float (&m)[8], float (&q)[8],
-                                          bool tiny) {
+// The fast part: m, q from the reciprocals; returns whether this wave's row piece has to be redone exactly
+// (wave-uniform).
+__device__ __forceinline__ bool quantize8_fast(const uint4& v, float ra, const float (&rb)[8], float qmax,
+                                               float (&m)[8], float (&q)[8], bool tiny) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
     _Float16 h[8];
 #pragma unroll
@@ -187,16 +188,26 @@ __device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, con
         big = __builtin_fmaxf(big, __builtin_fabsf(q[e]));
     }
     // !(big <= qmax) also catches a NaN from an overflowed product
-    if (__any(score >= 0.5f - kTieTol || !(big <= qmax) || tiny)) {     // rare: exact division for this wave's row piece
+    return __any(score >= 0.5f - kTieTol || !(big <= qmax) || tiny);
+}
+// The exact part: the correctly rounded division and the clamp, for all 8 elements.
+__device__ __forceinline__ void quantize8_exact(const uint4& v, float a, const float (&b)[8], float qmax,
+                                                float (&m)[8], float (&q)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float D = a * b[e];
-            float rt = (D == 0.0f) ? 0.0f : (float)h[e] / D;
-            rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
-            m[e] = rt + kMagic;
-            q[e] = m[e] - kMagic;
-        }
+    for (int e = 0; e < 8; ++e) {
+        const float x = (float)__builtin_bit_cast(_Float16, (unsigned short)(w[e >> 1] >> (16 * (e & 1))));
+        const float D = a * b[e];
+        float rt = (D == 0.0f) ? 0.0f : x / D;
+        rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
+        m[e] = rt + kMagic;
+        q[e] = m[e] - kMagic;
     }
+}
+__device__ __forceinline__ void quantize8(const uint4& v, float a, float ra, const float (&b)[8],
+                                          const float (&rb)[8], float qmax, float (&m)[8], float (&q)[8],
+                                          bool tiny) {
+    if (quantize8_fast(v, ra, rb, qmax, m, q, tiny)) quantize8_exact(v, a, b, qmax, m, q);   // rare
 }
 
 // Count-only form of quantize8: how many of the wave's 8 x 64 elements of one row have a non-zero code.
@@ -251,14 +262,52 @@ __device__ __forceinline__ float count_nonzero8(const float (&m)[8]) {
     return nz;
 }
 
-// INT8 codes: 8 bytes at dst (the low mantissa byte of kMagic + q is q in two's complement)
+// ---- buffer access for the streaming kernels.  A row piece is addressed as a raw buffer: its base and its
+// length in bytes sit in scalar registers, every lane adds its own byte offset, and the hardware's range check
+// does the masking: a load at or past the end returns 0, a store there is dropped.  Only used where a lane's
+// piece lies entirely inside or entirely outside the row (no partial pieces).
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t row_buffer(const void* base, int bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);   // raw, 32-bit data
+}
+constexpr int kWriteThrough = 16;     // cache policy sc1: written through to memory at device scope (see store_through)
+__device__ __forceinline__ uint4 buffer_load16(rsrc_t r, int byte_offset) {
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 0));
+}
+
+// INT8 codes of 8 elements as 8 bytes (the low mantissa byte of kMagic + q is q in two's complement)
+__device__ __forceinline__ u32x2 pack_codes_i8(const float (&m)[8]) {
+    uint32_t u[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) u[e] = __float_as_uint(m[e]);
+    return u32x2{pack_bytes(u[0], u[1], u[2], u[3]), pack_bytes(u[4], u[5], u[6], u[7])};
+}
+// INT4 codes of 8 elements as 4 bytes: two's-complement nibbles, even column in the low nibble
+__device__ __forceinline__ uint32_t pack_codes_i4(const float (&m)[8]) {
+    uint32_t u[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) u[e] = __float_as_uint(m[e]);
+    uint32_t w0 = pack_bytes(u[0], u[1], u[2], u[3]) & 0x0F0F0F0Fu;
+    uint32_t w1 = pack_bytes(u[4], u[5], u[6], u[7]) & 0x0F0F0F0Fu;
+    w0 |= w0 >> 4;                 // bytes 0 and 2 now hold two nibbles each
+    w1 |= w1 >> 4;
+    return __builtin_amdgcn_perm(w1, w0, 0x06040200u);
+}
+// dequantized values fl16(fl32(q * fl32(a * b))) of 8 elements as 16 bytes
+__device__ __forceinline__ u32x4 pack_xhat(const float (&q)[8], float a, const float (&b)[8]) {
+    float y[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y[e] = rounded_f32(q[e] * (a * b[e]));
+    return u32x4{pack_half2(y[0], y[1]), pack_half2(y[2], y[3]), pack_half2(y[4], y[5]), pack_half2(y[6], y[7])};
+}
+
+// INT8 codes: 8 bytes at dst
 __device__ __forceinline__ void store_codes_i8(const float (&m)[8], uint8_t* dst, bool vec_ok, int nvalid) {
     uint32_t u[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) u[e] = __float_as_uint(m[e]);
     if (vec_ok && nvalid == 8) {
-        store_through(u32x2{pack_bytes(u[0], u[1], u[2], u[3]), pack_bytes(u[4], u[5], u[6], u[7])},
-                      reinterpret_cast<u32x2*>(dst));
+        store_through(pack_codes_i8(m), reinterpret_cast<u32x2*>(dst));
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)

@@ -187,6 +187,172 @@ quantize_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const
     }
 }
 
+// The same kernel for the layout every real activation has: X 16-byte aligned with ldx % 8 == 0, I % 8 == 0 and
+// aligned outputs, so that a lane's 8 columns exist or not as a whole.  What differs from quantize_kernel:
+//   - rows are addressed as raw buffers (base and length in scalar registers, range-checked by the hardware), so
+//     the loop body has no per-lane branches and no 64-bit vector address arithmetic;
+//   - the stores are buffer stores with the write-through policy the compiler knows about, so its vmcnt waits for
+//     the next rows' loads do not also wait for this row's stores to be acknowledged by memory;
+//   - the loop is software-pipelined by hand: two register sets of kU rows alternate, the loads of batch bi + 1
+//     are requested before batch bi is worked on.  (The loop is kept a loop: unrolled completely for a known
+//     number of batches, where the compiler's count of outstanding memory operations becomes exact, it ran 4 us
+//     slower on the 4096 x 8192 layer than with the loop's conservative waits.)
+template <int MODE, bool XHAT>
+__global__ void __launch_bounds__(kWaves * kLanes)
+quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx, const float* __restrict__ t_vec,
+                       const float* __restrict__ c_vec, double alpha, int qmax_i, float* __restrict__ a_out,
+                       float* __restrict__ b_out, uint8_t* __restrict__ codes, uint16_t* __restrict__ xhat,
+                       unsigned long long* __restrict__ zero_count, int slot, int n_col_chunks, int nb,
+                       int blocks_per_matrix, int64_t matrix_stride) {
+    __shared__ uint32_t lds_cnt[kWaves];
+    __shared__ float lds_b[kColsPerWave];
+    __shared__ float lds_a[kWaves * kLanes];
+    const int lane = threadIdx.x & (kLanes - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kLanes);     // row indices are scalar values
+    const int matrix = blockIdx.x / blocks_per_matrix;
+    const int blk = blockIdx.x - matrix * blocks_per_matrix;
+    X += (int64_t)matrix * matrix_stride;
+    t_vec += (int64_t)matrix * T;
+    c_vec += (int64_t)matrix * I;
+    if (a_out) a_out += (int64_t)matrix * T;
+    if (b_out) b_out += (int64_t)matrix * I;
+    if (MODE == 1) codes += (int64_t)matrix * T * I;
+    if (MODE == 2) codes += (int64_t)matrix * T * (I / 2);
+    if (XHAT) xhat += (int64_t)matrix * T * I;
+    const int col_chunk = blk % n_col_chunks;
+    const int row_chunk = blk / n_col_chunks;
+    const int col0 = col_chunk * kColsPerWave;
+    const int cols_here = min(kColsPerWave, I - col0);      // columns of this chunk that exist: a multiple of 8
+    const int rows_per_wave = nb * kU;                      // <= 64
+    const int rows_per_block = kWaves * rows_per_wave;      // <= 512 = the block's thread count
+    const int row0 = row_chunk * rows_per_block + wave * rows_per_wave;
+    const float qmax = (float)qmax_i;
+
+    // walk order as in quantize_kernel: last batch first, except for the count-only form
+    auto batch_at = [&](int bi) { return MODE == 0 ? bi : nb - 1 - bi; };
+    // Rows past the last one are read from the last row instead (and never worked on): a register that is
+    // written by nothing but loads lets the compiler count outstanding loads instead of waiting for all of them.
+    auto load_batch = [&](uint4 (&dst)[kU], int bi) {
+        if (bi >= nb) return;                                // scalar condition
+        const int rbase = row0 + batch_at(bi) * kU;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int r = min(rbase + u, T - 1);
+            dst[u] = buffer_load16(row_buffer(X + (int64_t)r * ldx + col0, cols_here * 2), lane * 16);
+        }
+    };
+    uint4 va[kU], vb[kU];
+    load_batch(va, 0);
+    load_batch(vb, 1);
+
+    block_scale_factors(t_vec, c_vec, alpha, qmax_i, T, I, col0, row_chunk * rows_per_block, rows_per_block, lds_a,
+                        lds_b, col_chunk == 0 ? a_out : nullptr, row_chunk == 0 ? b_out : nullptr);
+    __syncthreads();
+    // the wave's row factors and their reciprocals, one row per lane, handed out with readlane as the rows come up
+    const float a_lane = lds_a[wave * rows_per_wave + (lane < rows_per_wave ? lane : 0)];
+    const float ra_lane = safe_rcp(a_lane);
+
+    float b[8], rb[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        b[e] = lds_b[lane * 8 + e];                         // 0 for columns past the end
+        rb[e] = safe_rcp(b[e]);
+    }
+    bool b_tiny = false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b_tiny |= tiny_factor(b[e]);
+
+    uint32_t nonzero = 0u;    // codes != 0 seen by this wave (uniform)
+    int rows_done = 0;
+    // No branch depends on whether a row exists: rows past the last one are worked on like the others (their data
+    // is the last row's, their factor is 0), but their stores go to an empty buffer, which drops them, and their
+    // counts are not added.  The only branch left is the rare exact-division path inside quantize8.
+    auto work = [&](const uint4 (&v)[kU], int bi) {
+        const int rbase = row0 + batch_at(bi) * kU;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int r = rbase + u;
+            const bool row_ok = r < T;                      // scalar
+            const int rr = row_ok ? r : 0;
+            rows_done += row_ok ? 1 : 0;
+            const int ri = batch_at(bi) * kU + u;
+            const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a_lane), ri));
+            const float ra = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, ra_lane), ri));
+            if (MODE == 0) {
+                // a == 0 means D = 0 and every code of the row is 0 by definition: left to the exact path
+                const uint32_t nz = count_row8_wave(v[u], a, 0.5f * a, 0.5f * a * kTieTol, b, rb, qmax,
+                                                    b_tiny || tiny_factor(a) || a == 0.0f);
+                nonzero += row_ok ? nz : 0u;
+                continue;
+            }
+            const int live = row_ok ? cols_here : 0;         // columns of this row that may be stored
+            // count, pack and store one row piece; returns the wave's number of non-zero codes in it
+            auto emit = [&](const float (&m)[8], const float (&q)[8]) -> uint32_t {
+                const uint32_t nz = count_nonzero8_wave(m);
+                if (MODE == 1)
+                    __builtin_amdgcn_raw_buffer_store_b64(pack_codes_i8(m), row_buffer(codes + (int64_t)rr * I + col0, live),
+                                                          lane * 8, 0, kWriteThrough);
+                if (MODE == 2)
+                    __builtin_amdgcn_raw_buffer_store_b32(pack_codes_i4(m),
+                                                          row_buffer(codes + (int64_t)rr * (I / 2) + col0 / 2, live / 2),
+                                                          lane * 4, 0, kWriteThrough);
+                if (MODE == 3) store_codes_fp6(m, codes, rr, col0, lane, I / 64, lane * 8 < live);
+                if (XHAT)
+                    __builtin_amdgcn_raw_buffer_store_b128(pack_xhat(q, a, b), row_buffer(xhat + (int64_t)rr * I + col0, live * 2),
+                                                           lane * 16, 0, kWriteThrough);
+                return nz;
+            };
+            // The exact path packs and stores for itself instead of handing m and q back: values that come out of
+            // either path would need register copies where the paths join, and the compiler puts those copies
+            // (3 per element) on the common path.
+            float m[8], q[8];
+            uint32_t nz;
+            if (__builtin_expect(quantize8_fast(v[u], ra, rb, qmax, m, q, b_tiny || tiny_factor(a)), 0)) {
+                float mx[8], qx[8];
+                quantize8_exact(v[u], a, b, qmax, mx, qx);
+                nz = emit(mx, qx);
+            } else {
+                nz = emit(m, q);
+            }
+            nonzero += row_ok ? nz : 0u;
+            __builtin_amdgcn_sched_barrier(0);               // rows one after the other: keeps scalar register pressure down
+        }
+    };
+    for (int bi = 0; bi < nb; bi += 2) {
+        work(va, bi);
+        load_batch(va, bi + 2);
+        if (bi + 1 < nb) {
+            work(vb, bi + 1);
+            load_batch(vb, bi + 3);
+        }
+    }
+
+    if (zero_count) {
+        // columns past the end read as x = 0 and add nothing to `nonzero`
+        const uint32_t zeros = (uint32_t)(rows_done * cols_here) - nonzero;
+        if (lane == 0) lds_cnt[wave] = zeros;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t s = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += lds_cnt[w];
+            // one atomic per block: same-address atomics serialise, so the grid is kept small
+            if (slot >= 0) {
+                unsigned long long* zero_state = &g_zero_state[slot];
+                const unsigned long long add = (1ull << kTicketShift) | (unsigned long long)s;
+                const unsigned long long old =
+                    __hip_atomic_fetch_add(zero_state, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((unsigned)(old >> kTicketShift) == gridDim.x - 1u) {        // every other block has added
+                    *zero_count = (old + add) & ((1ull << kTicketShift) - 1ull);
+                    __hip_atomic_store(zero_state, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else if (s) {
+                atomicAdd(zero_count, (unsigned long long)s);                    // caller's counter, cleared before
+            }
+        }
+    }
+}
+
 template <int MODE, bool XHAT>
 hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int64_t matrix_stride, const float* t,
                        const float* c, double alpha, int qmax, float* a, float* b, uint8_t* codes, uint16_t* xhat,
@@ -204,7 +370,13 @@ hipError_t launch_mode(const uint16_t* X, int B, int T, int I, int64_t ldx, int6
     // no slot: clear the caller's counter and add to it directly
     const int state = zc ? stream_slot(stream) : -1;
     if (zc && state < 0) zero_u64_kernel<<<dim3(1), dim3(1), 0, stream>>>(zc);
-    if (vec)
+    // the layout every real activation has: the streaming kernel (no partial pieces, no misaligned pointers)
+    const bool stream_ok = vec && (I % 8 == 0) && (reinterpret_cast<uintptr_t>(codes) % 8 == 0) &&
+                           (reinterpret_cast<uintptr_t>(xhat) % 16 == 0);
+    if (stream_ok)
+        quantize_stream_kernel<MODE, XHAT><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, alpha, qmax, a, b, codes, xhat,
+                                                                      zc, state, ncc, nb, ncc * nrc, matrix_stride);
+    else if (vec)
         quantize_kernel<MODE, XHAT, true><<<grid, block, 0, stream>>>(X, T, I, ldx, t, c, alpha, qmax, a, b, codes, xhat,
                                                                      zc, state, ncc, nb, out_vec, ncc * nrc,
                                                                      matrix_stride);

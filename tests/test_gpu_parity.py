@@ -88,6 +88,29 @@ def test_absmax_overwrites_stale_outputs_and_handles_zeros(cq):
     assert np.array_equal(host(t), t_ref) and np.array_equal(host(c), c_ref)
 
 
+def test_absmax_calls_in_a_row_clear_for_themselves(cq):
+    """The vector-layout call clears t and c inside its one launch (the launch's first blocks store the zeros, the
+    others wait for them before their atomics).  Many calls in a row on one stream, into the same output vectors,
+    with data whose maxima shrink from call to call: a maximum left over from an earlier call would survive."""
+    import torch
+    say("absmax: 40 calls in a row, shrinking maxima, two shapes alternating")
+    rng = np.random.default_rng(5)
+    shapes = [(300, 1536), (64, 520 * 8)]
+    t_buf = {s_: torch.empty(s_[0], dtype=torch.float32, device="cuda") for s_ in shapes}
+    c_buf = {s_: torch.empty(s_[1], dtype=torch.float32, device="cuda") for s_ in shapes}
+    pending = []
+    for it in range(40):
+        T, I = shapes[it % 2]
+        X = (rng.standard_normal((T, I)) * (100.0 / (it + 1))).astype(np.float16)
+        Xg = gpu(X)
+        cq.crossquant_absmax(Xg, t=t_buf[(T, I)], c=c_buf[(T, I)])
+        pending.append((X, t_buf[(T, I)].clone(), c_buf[(T, I)].clone()))      # clones are ordered on the stream
+    torch.cuda.synchronize()
+    for X, t, c in pending:
+        t_ref, c_ref = oracle.absmax(X)
+        assert np.array_equal(bits32(host(t)), bits32(t_ref)) and np.array_equal(bits32(host(c)), bits32(c_ref))
+
+
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
 def test_absmax_full_configs(cq, name):
     say("absmax config %s" % name)
