@@ -227,17 +227,16 @@ constexpr int kSlotBytes = BM * BK;               // 32 KiB: one operand's 256 x
 constexpr int kRingSlots = 5;
 constexpr int kRingLds = kRingSlots * kSlotBytes; // 160 KiB: the whole LDS of a gfx950 CU
 
-__global__ void __launch_bounds__(512)
-gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
-                    const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I, int O,
-                    uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
-                    int tiles_n) {
-    constexpr int WN = 4, WTN = 64, NI = 2;
-    extern __shared__ __align__(16) int8_t lds[];
-
-    int tile_m, tile_n;
-    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n)) return;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+// One output tile of 256 tokens x (128 NI) channels starting at (m0, n0).  NI = 2 is the full 256 x 256 tile;
+// NI = 1 the half tile of the last, partly filled round (see launch_w8a8_linear): the same schedule with
+// 128 x 32 wave tiles, half the weight requests and half the matrix instructions per step.
+template <int NI>
+__device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
+                                          const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I,
+                                          int O, uint16_t* __restrict__ Y, int64_t ldy,
+                                          int32_t* __restrict__ acc_debug, int m0, int n0, int8_t* lds) {
+    constexpr int WN = 4, WTN = 32 * NI;
+    constexpr int NLB = 4 * NI;                   // requests a weight-loading wave makes per half tile (8 or 4)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -252,25 +251,33 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     const int lw = wave & 3;
     // Tiles on the bottom / right edge of a ragged problem read a clamped (valid) row instead of
     // the rows past the end; what lands in those LDS rows only feeds outputs the epilogue drops.
+    // (a weight-loading wave of a half tile fills 32 rows with 4 requests)
+    const int rows_per_loader = b_loader ? 8 * NLB : 64;
     const int8_t* gsrc[8];
     {
         const int8_t* base = b_loader ? qw : qx;
         const int first = b_loader ? n0 : m0, last = (b_loader ? O : T) - 1;
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
-            const int R = 64 * lw + 8 * ii + ld_r;
+            const int R = rows_per_loader * lw + 8 * ii + ld_r;
             const int c = ld_p ^ ((R >> 1) & 7);
             gsrc[ii] = base + (int64_t)min(first + R, last) * I + c * 16;
         }
     }
     auto issue_half = [&](int kt, int slot) {
-        int8_t* dst = lds + slot * kSlotBytes + lw * (64 * BK);
+        int8_t* dst = lds + slot * kSlotBytes + lw * (rows_per_loader * BK);
         const int64_t koff = (int64_t)kt * BK;
 #pragma unroll
         // cache policy sc0: the data goes straight to LDS and is never looked up in the vector L1 again, so the
         // requests bypass it (no measurable difference on the 70B-shaped layer; non-temporal requests are 6 % slower)
         for (int ii = 0; ii < 8; ++ii)
-            __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii] + koff), (lptr_t)(dst + ii * 1024), 16, 0, 1);
+            if (ii < NLB || !b_loader)
+                __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii] + koff), (lptr_t)(dst + ii * 1024), 16, 0, 1);
+    };
+    // "all but the requests of the last half tile have landed", for this wave's kind of half tile
+    auto wait_for_previous_half = [&]() {
+        if (NLB == 8 || !b_loader) __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 15));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(NLB, 15));
     };
 
     const int frag_row = lane & 31, frag_half = lane >> 5;
@@ -289,7 +296,7 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     // prologue: A0 A1 (waves 0-3) / B0 B1 (waves 4-7); half tile n -> slot n % 5
     issue_half(0, b_loader ? 1 : 0);
     if (nk > 1) issue_half(1, b_loader ? 3 : 2);
-    if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 15));
+    if (nk > 1) wait_for_previous_half();
     else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
     __syncthreads();
 
@@ -377,6 +384,37 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     epilogue_store<v16i, WTN, NI>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane, wave);
 }
 
+// Work of a block.  Blocks [0, main_blocks) take the first n_main tiles of the walk whole, de-interleaved by XCD
+// as in tile_of_block; the blocks after them take the remaining tiles as half tiles of 128 channels (half tile
+// h = column half h & 1 of tile n_main + h / 2), again de-interleaved by XCD so that the two halves of a tile, which
+// share their activation rows, sit in one L2.  n_main equals the tile count when no tile is split.
+__global__ void __launch_bounds__(512)
+gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
+                    const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I, int O,
+                    uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
+                    int tiles_n, int n_main, int main_blocks) {
+    extern __shared__ __align__(16) int8_t lds[];
+    const int block = blockIdx.x;
+    int tile_m, tile_n;
+    if (block < main_blocks) {
+        const int per_xcd = (n_main + kXcds - 1) / kXcds;
+        const int L = (block % kXcds) * per_xcd + block / kXcds;
+        if (L >= n_main) return;
+        tile_of_index(L, tiles_m, tiles_n, tile_m, tile_n);
+        ring_tile<2>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN, lds);
+    } else {
+        const int n_half = 2 * (tiles_m * tiles_n - n_main);
+        const int h_block = block - main_blocks;
+        const int per_xcd = (n_half + kXcds - 1) / kXcds;
+        const int h = (h_block % kXcds) * per_xcd + h_block / kXcds;
+        if (h >= n_half) return;
+        tile_of_index(n_main + h / 2, tiles_m, tiles_n, tile_m, tile_n);
+        if (tile_n * BN + (h & 1) * (BN / 2) >= O) return;        // the second half of a tile on the ragged edge may be empty
+        ring_tile<1>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN + (h & 1) * (BN / 2),
+                     lds);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_t* qw, const float* w_scale,
@@ -399,8 +437,20 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
         static std::atomic<uint64_t> lds_allowed{0};
         e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_i8_ring_kernel), kRingLds, lds_allowed);
         if (e != hipSuccess) return e;
-        gemm_i8_ring_kernel<<<grid, dim3(512), kRingLds, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
-                                                                   acc_debug, tiles_m, tiles_n);
+        // One block fills a CU, so the tiles run in rounds of n_cu.  A last round that is at most half full is
+        // run as half tiles (256 x 128) instead, which spreads it over twice as many CUs: 2048 x 4096 x 11008
+        // has 344 tiles = 1.34 rounds of 256 and took 2 tile times; the 88 tiles of its last round now take
+        // 176 CUs for about 0.6 of a tile time.
+        int n_cu = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+            n_cu = 256;
+        const int rem = total % n_cu;
+        const int n_main = (rem > 0 && 2 * rem <= n_cu) ? total - rem : total;
+        const int main_blocks = ((n_main + kXcds - 1) / kXcds) * kXcds;
+        const int half_blocks = ((2 * (total - n_main) + kXcds - 1) / kXcds) * kXcds;
+        gemm_i8_ring_kernel<<<dim3((unsigned)(main_blocks + half_blocks)), dim3(512), kRingLds, stream>>>(
+            qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n, n_main, main_blocks);
     } else {
         static std::atomic<uint64_t> lds_allowed{0};
         e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_i8_kernel<true>), kLdsBytes, lds_allowed);

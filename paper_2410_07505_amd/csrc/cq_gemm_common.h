@@ -26,17 +26,21 @@ constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 0xF) | ((vm >> 4) << 
 // de-interleaved by XCD (each XCD gets a contiguous range of tiles, hence its own L2 sees a compact
 // patch), then walked in groups of kGroupM tile-rows so that concurrently resident tiles share A
 // rows and B columns.  Returns false for the padding blocks of the last XCD range.
-__device__ __forceinline__ bool tile_of_block(int block, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
-    const int total = tiles_m * tiles_n;
-    const int per_xcd = (total + kXcds - 1) / kXcds;
-    const int L = (block % kXcds) * per_xcd + block / kXcds;
-    if (L >= total) return false;
+// position L of the walk -> tile
+__device__ __forceinline__ void tile_of_index(int L, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
     const int group_sz = kGroupM * tiles_n;
     const int g = L / group_sz;
     const int gm = min(kGroupM, tiles_m - g * kGroupM);
     const int in_g = L - g * group_sz;
     tile_m = g * kGroupM + in_g % gm;
     tile_n = in_g / gm;
+}
+__device__ __forceinline__ bool tile_of_block(int block, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    const int L = (block % kXcds) * per_xcd + block / kXcds;
+    if (L >= total) return false;
+    tile_of_index(L, tiles_m, tiles_n, tile_m, tile_n);
     return true;
 }
 

@@ -898,6 +898,26 @@ def test_linear_small_and_ragged(cq, T, I, O):
     assert none_acc is None and np.array_equal(bits16(host(Y2)), bits16(Y_ref))
 
 
+@pytest.mark.parametrize("T,I,O", [(2304, 256, 10240),     # 9 x 40 = 360 tiles = 1.41 rounds of 256: 104 tiles run as halves
+                                   (2250, 256, 10248),     # 9 x 41 = 369 tiles, ragged: the last tile column is 8 wide
+                                   (1280, 384, 5120),      # 100 tiles, less than half a round: every tile runs as two halves
+                                   (300, 128, 392),        # 4 tiles; the last one's second half is empty
+                                   (256, 128, 128)])       # one tile that is a single half
+def test_linear_with_a_partly_filled_last_round_of_tiles(cq, T, I, O):
+    """One block fills a CU, so output tiles run in rounds of 256; a last round that is at most half full is run as
+    256 x 128 half tiles.  Every accumulator and output against the oracle."""
+    say("linear, half-tile round: T=%d I=%d O=%d" % (T, I, O))
+    qx = workloads.int8_codes(T, I, seed=T + 1)
+    qw = workloads.int8_codes(O, I, seed=O + 11)
+    rng = np.random.default_rng(T + O)
+    a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+    s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    Y, acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), want_acc=True)
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+
+
 def test_linear_extreme_accumulators(cq):
     say("linear extremes")
     T, I, O = 256, 8192, 256
