@@ -244,6 +244,40 @@ class Workload:
                 "absmax_gbs": rate(bytes_absmax, ms["absmax"]), "quantize_gbs": rate(bytes_quant, ms["quantize"]),
                 "count_gbs": rate(2 * n, ms["count"]), "peak_tops": INT8_PEAK_TOPS if bits == 8 else FP6_PEAK_TOPS}
 
+    def inside_gemm(self, reps=3):
+        """The quantize step inside the GEMM's activation load (one call: X -> Y) against the two calls it replaces
+        (quantize without the dequantized matrix, then the linear layer), each timed back to back."""
+        cq, torch, cfg = self.cq, self.torch, self.cfg
+        qw8 = self.qw                       # int8 codes; for the INT4 configuration the codes are in [-7, 7]
+
+        def timed(fn):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        fused_ms = timed(lambda: cq.crossquant_quantize_linear_fused(self.Xg, self.t, self.c, self.alpha, self.bits, qw8,
+                                                                     self.ws, Y=self.Y, row_scale=self.a, col_scale=self.b))
+        y_fused = self.Y.clone()
+
+        def two_calls():
+            if self.bits == 8:
+                cq.crossquant_quantize(self.Xg, self.t, self.c, self.alpha, 8, codes=self.codes, want_xhat=False,
+                                       row_scale=self.a, col_scale=self.b, want_count=False)
+                cq.crossquant_w8a8_linear(self.codes, self.a, qw8, self.ws, Y=self.Y)
+            else:
+                cq.crossquant_quantize_fp6(self.Xg, self.t, self.c, self.alpha, packed=self.px, row_scale=self.a,
+                                           col_scale=self.b, want_count=False)
+                cq.crossquant_w4a4_linear(self.px, self.a, self.pw, self.ws, cfg.T, cfg.I, cfg.O, Y=self.Y)
+        two_ms = timed(two_calls)
+        same = bool(torch.equal(y_fused.view(torch.int16), self.Y.view(torch.int16)))
+        return {"one_call_ms": fused_ms, "two_calls_ms": two_ms, "column_tiles": (cfg.O + 255) // 256,
+                "slowdown": fused_ms / two_ms, "identical_outputs": same}
+
     def summary(self, steps, warmup):
         """The per-configuration object of the `configs` section."""
         med, _, wall_ms = self.timed_steps(steps, warmup)
@@ -259,6 +293,7 @@ class Workload:
             "absmax_GBs": f["absmax_gbs"], "quantize_GBs": f["quantize_gbs"], "count_GBs": f["count_gbs"],
             "linear_TOPs": f["tops"], "linear_peak_TOPs": f["peak_tops"], "linear_frac_peak": f["tops"] / f["peak_tops"],
             "kernel_proportion": {"crossquant": int(self.zc.item()) / n, "per_token": int(self.zc_pt.item()) / n},
+            "quantize_inside_gemm": self.inside_gemm(),
         }
 
     def release(self):
@@ -422,6 +457,10 @@ def main():
         del px, pw, q8, nib, qw4, y6
         cq.crossquant_w8a8_linear(wl.codes, wl.a, wl.qw, wl.ws, Y=wl.Y)      # leave Y as the W8A8 result
 
+    inside = wl.inside_gemm() if extras else None
+    if extras:
+        wl.step()                            # leave every buffer as the step writes it
+
     graph_ms = None
     if args.graph and full:
         g = torch.cuda.CUDAGraph()
@@ -468,6 +507,7 @@ def main():
         "quantizer_warm": {"ms": warm_ms, "GBs": (f["bytes_absmax"] + f["bytes_quant"]) / (warm_ms * 1e-3) / 1e9} if warm_ms else None,
         "achievable": achievable,
         "vendor_int8_gemm": vendor,
+        "quantize_inside_gemm": inside,
         "a4w4_linear": a4w4,
         "roofline": {"kernel": ("gemm_i8_ring_kernel (W8A8 linear)" if bits == 8 else
                                 "gemm_f6_ring_kernel (A4W4 linear)"),

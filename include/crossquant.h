@@ -227,6 +227,24 @@ int crossquant_w8a8_linear(const int8_t *qx, const float *row_scale, const int8_
                            int64_t ldy, int32_t *acc_debug, void *stream);
 
 /*
+ * crossquant_quantize followed by crossquant_w8a8_linear with the quantize step inside the GEMM's
+ * activation load (the W8A8 / W4A4 layers of the paper's tables computed from X directly): X goes in,
+ * Y comes out, the codes never exist in memory.  Results equal the two calls bit for bit (bits = 4:
+ * codes in [-7, 7] on the INT8 matrix instruction, qw as crossquant_weight_quantize(bits = 4) stores
+ * them).  t, c, alpha, bits, row_scale, col_scale as in crossquant_quantize (the factors are written
+ * first, by a small kernel); qw, w_scale, Y, ldy, acc_debug as in crossquant_w8a8_linear.
+ * Every activation element is quantized once per 256 output channels, so this call is SLOWER than the
+ * two calls on any layer with more than a few hundred output channels (measured: bench.py's
+ * `quantize_inside_gemm`); it exists to put a number on that trade, and for callers that cannot afford
+ * the T x I bytes of codes.  Requires I % 128 == 0, ldx % 8 == 0 and 16-byte aligned X, qw, col_scale,
+ * else CQ_ERR_UNSUPPORTED.
+ */
+int crossquant_quantize_linear_fused(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
+                                     const float *c, float alpha, int bits, const int8_t *qw,
+                                     const float *w_scale, int64_t O, void *Y, int64_t ldy, float *row_scale,
+                                     float *col_scale, int32_t *acc_debug, void *stream);
+
+/*
  * A4W4 linear layer on the FP6 matrix instruction (the W4A4 setting of the paper's accuracy
  * tables).  gfx950 multiplies 6-bit floats at twice the INT8 rate and every INT4 code in [-7, 7] is
  * exact in FP6 E2M3; with binary32 accumulation the dot product is exact for I <= 2^18, so

@@ -46,6 +46,9 @@ lib.crossquant_unpack_int4.argtypes = [_vp, _i64, _i64, _vp, _vp]
 lib.crossquant_weight_quantize.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp]
 lib.crossquant_weight_quantize_grouped.argtypes = [_vp, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_w8a8_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
+lib.crossquant_quantize_linear_fused.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _i64, _vp, _i64, _vp,
+                                                 _vp, _vp, _vp]
+lib.crossquant_quantize_linear_fused.restype = _int
 for _n in ("crossquant_absmax", "crossquant_quantize", "crossquant_absmax_quantize", "crossquant_absmax_batched",
            "crossquant_quantize_batched", "crossquant_calib_read", "crossquant_calib_copy", "crossquant_calib_mfma_i8", "crossquant_pack_fp6",
            "crossquant_w4a4_linear", "crossquant_quantize_fp6", "crossquant_kernel_count", "crossquant_kernel_analysis", "crossquant_unpack_int4",
@@ -557,3 +560,39 @@ def crossquant_w8a8_linear(qx: torch.Tensor, row_scale: torch.Tensor, qw: torch.
     _check(lib.crossquant_w8a8_linear(qx.data_ptr(), row_scale.data_ptr(), qw.data_ptr(), w_scale.data_ptr(),
                                       T, I, O, Y.data_ptr(), Y.stride(0), _ptr(acc_debug), _stream(qx)))
     return Y, acc_debug
+
+
+def crossquant_quantize_linear_fused(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, bits: int,
+                                     qw: torch.Tensor, w_scale: torch.Tensor, *, Y: torch.Tensor = None,
+                                     row_scale: torch.Tensor = None, col_scale: torch.Tensor = None,
+                                     acc_debug: torch.Tensor = None, want_acc: bool = False):
+    """Quantize inside the GEMM's activation load: Y from X directly.  Returns (Y, row_scale, col_scale, acc_or_None)."""
+    _matrix(X, torch.float16, "X")
+    _matrix(qw, torch.int8, "qw")
+    T, I = X.shape
+    O, I2 = qw.shape
+    if I != I2 or not qw.is_contiguous():
+        raise ValueError("qw must be a contiguous [O][I] tensor with I = %d" % I)
+    dev = X.device
+    if row_scale is None:
+        row_scale = torch.empty(T, dtype=torch.float32, device=dev)
+    if col_scale is None:
+        col_scale = torch.empty(I, dtype=torch.float32, device=dev)
+    if Y is None:
+        Y = torch.empty((T, O), dtype=torch.float16, device=dev)
+    if acc_debug is None and want_acc:
+        acc_debug = torch.empty((T, O), dtype=torch.int32, device=dev)
+    _buf(t, torch.float32, (T,), "t", X)
+    _buf(c, torch.float32, (I,), "c", X)
+    _buf(row_scale, torch.float32, (T,), "row_scale", X)
+    _buf(col_scale, torch.float32, (I,), "col_scale", X)
+    _buf(w_scale, torch.float32, (O,), "w_scale", X)
+    _linear_outputs(Y, acc_debug, T, O, X)
+    if qw.device != dev:
+        raise ValueError("qw must be on %s" % dev)
+    _on_gpu(X, "X")
+    _check(lib.crossquant_quantize_linear_fused(X.data_ptr(), T, I, X.stride(0), t.data_ptr(), c.data_ptr(), float(alpha),
+                                                int(bits), qw.data_ptr(), w_scale.data_ptr(), O, Y.data_ptr(),
+                                                Y.stride(0), row_scale.data_ptr(), col_scale.data_ptr(),
+                                                _ptr(acc_debug), _stream(X)))
+    return Y, row_scale, col_scale, acc_debug

@@ -217,6 +217,27 @@ int crossquant_w8a8_linear(const int8_t* qx, const float* row_scale, const int8_
                                            static_cast<hipStream_t>(stream)));
 }
 
+int crossquant_quantize_linear_fused(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
+                                     float alpha, int bits, const int8_t* qw, const float* w_scale, int64_t O, void* Y,
+                                     int64_t ldy, float* row_scale, float* col_scale, int32_t* acc_debug, void* stream) {
+    if (!t || !c || !qw || !w_scale || !Y || !row_scale || !col_scale) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (!dim_ok(O) || ldy < O || ldy > CQ_MAX_DIM) return CQ_ERR_SHAPE;
+    if (I * O > CQ_MAX_ELEMS || T * ldy > CQ_MAX_ELEMS || I > 133000) return CQ_ERR_SHAPE;
+    if (bits != 4 && bits != 8) return CQ_ERR_BITS;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return CQ_ERR_ALPHA;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) || !aligned(w_scale, 4) ||
+        !aligned(Y, 2) || !aligned(acc_debug, 4))
+        return CQ_ERR_ALIGN;
+    if (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I)) return CQ_ERR_ALIAS;
+    // only the layout of a real layer: whole K steps, vector loads
+    if (I % 128 != 0 || ldx % 8 != 0 || !aligned(X, 16) || !aligned(qw, 16) || !aligned(col_scale, 16))
+        return CQ_ERR_UNSUPPORTED;
+    return from_hip(cq::launch_quantize_linear(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, t, c, alpha, bits,
+                                               row_scale, col_scale, qw, w_scale, (int)O, static_cast<uint16_t*>(Y),
+                                               ldy, acc_debug, static_cast<hipStream_t>(stream)));
+}
+
 int64_t crossquant_fp6_packed_bytes(int64_t R, int64_t K) {
     if (!dim_ok(R) || !dim_ok(K) || K % 128 != 0) return -1;
     return cq::fp6_packed_bytes(R, K);

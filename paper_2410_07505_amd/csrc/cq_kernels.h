@@ -118,6 +118,11 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
                               const float* w_scale, int T, int I, int O, uint16_t* Y, int64_t ldy,
                               int32_t* acc_debug, hipStream_t stream);
 
+// CrossQuant step inside the GEMM's activation load (X binary16 -> Y, no codes in memory); a, b receive the factors.
+hipError_t launch_quantize_linear(const uint16_t* X, int T, int I, int64_t ldx, const float* t, const float* c,
+                                  float alpha, int bits, float* a, float* b, const int8_t* qw, const float* w_scale,
+                                  int O, uint16_t* Y, int64_t ldy, int32_t* acc_debug, hipStream_t stream);
+
 // INT4 codes as FP6 fragments (32 rows x 64 columns per 1536-byte fragment) and the A4W4 linear layer on them.
 hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, const float* t, const float* c, float alpha,
                                float* a, float* b, void* packed, uint16_t* xhat, unsigned long long* zero_count,

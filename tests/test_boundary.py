@@ -237,6 +237,21 @@ def test_linear_argument_errors(cq):
     assert call(Y=P + 1) == -5 and call(acc=P + 2) == -5
 
 
+def test_quantize_linear_fused_argument_errors(cq):
+    f = cq.raw.crossquant_quantize_linear_fused
+
+    def call(X=P, T=4, I=128, ldx=128, t=P, c=P + 0x1000, alpha=0.15, bits=8, qw=P, ws=P, O=8, Y=P, ldy=8,
+             rs=P + 0x2000, cs=P + 0x3000, acc=None):
+        return f(X, T, I, ldx, t, c, alpha, bits, qw, ws, O, Y, ldy, rs, cs, acc, None)
+
+    assert call(X=0) == -1 and call(t=0) == -1 and call(qw=0) == -1 and call(Y=0) == -1 and call(rs=0) == -1
+    assert call(T=0) == -2 and call(O=0) == -2 and call(ldy=4) == -2 and call(ldx=64) == -2
+    assert call(bits=6) == -3 and call(alpha=1.5) == -4
+    assert call(Y=P + 1) == -5 and call(acc=P + 2) == -5
+    assert call(rs=P) == -8 and call(cs=P + 0x1000) == -8
+    assert call(I=64, ldx=64) == -6 and call(ldx=132) == -6 and call(X=P + 2) == -6 and call(cs=P + 0x3004) == -6
+
+
 def test_python_wrappers_refuse_cpu_tensors(cq):
     import torch
     X = torch.zeros((4, 8), dtype=torch.float16)

@@ -1076,6 +1076,59 @@ def test_end_to_end_full_config_sampled(cq, name):
     assert torch.equal(y_from_acc.view(torch.int16), Y.view(torch.int16))
 
 
+# ----------------------------------------------------------------------------- quantize inside the GEMM's activation load
+@pytest.mark.parametrize("T,I,O,bits,alpha", [(1, 128, 8, 8, 0.15), (37, 128, 70, 8, 0.0), (300, 256, 520, 8, 0.15),
+                                              (257, 384, 264, 4, 0.15), (513, 1024, 1000, 8, 1.0), (64, 256, 256, 4, 0.5)])
+def test_quantize_inside_the_gemm_equals_the_two_calls_and_the_oracle(cq, T, I, O, bits, alpha):
+    say("fused quantize + linear T=%d I=%d O=%d bits=%d alpha=%g" % (T, I, O, bits, alpha))
+    X = outliers(T, I, seed=T + I + O)
+    if T > 2:
+        X[1, :] = 0                      # a zero row: a_i = 0
+        X[:, 5] = 0                      # a zero column: b_j = 0 (alpha < 1)
+    W = workloads.weight(I, O, seed=O)
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, alpha, bits, want_xhat=False)
+    codes_ref = ref["codes"] if bits == 8 else oracle.unpack_int4(ref["codes"])
+    qw_ref, s_ref = oracle.weight_quantize(W, ref["b"], bits)
+    Y_ref, acc_ref = oracle.w8a8_linear(codes_ref, ref["a"], qw_ref, s_ref)
+    Xg = gpu(X)
+    t, c = cq.crossquant_absmax(Xg)
+    Y, a, b, acc = cq.crossquant_quantize_linear_fused(Xg, t, c, alpha, bits, gpu(qw_ref), gpu(s_ref), want_acc=True)
+    assert np.array_equal(bits32(host(a)), bits32(ref["a"])) and np.array_equal(bits32(host(b)), bits32(ref["b"]))
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+
+
+def test_quantize_inside_the_gemm_rounding_ties_and_layer_scale(cq):
+    """Exact ties (the fast quotient must hand over to the division inside the GEMM's loader too) and a
+    full-size layer, against the two calls."""
+    import torch
+    say("fused quantize + linear: ties, then C4 against the two calls")
+    T, I, O = 128, 128, 64
+    X = np.zeros((T, I), dtype=np.float16)
+    X[:, 0] = 127.0                              # every row and column maximum 127 -> D = 1 at any alpha
+    X[0, :] = 127.0
+    X[1:, 1:] = (np.arange((T - 1) * (I - 1)).reshape(T - 1, I - 1) % 253 - 126 + 0.5).astype(np.float16)   # k + 1/2
+    t_ref, c_ref = oracle.absmax(X)
+    ref = oracle.quantize(X, t_ref, c_ref, 0.5, 8, want_xhat=False)
+    qw = workloads.int8_codes(O, I, seed=3)
+    s = np.full(O, 1e-3, np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(ref["codes"], ref["a"], qw, s)
+    Xg = gpu(X)
+    t, c = cq.crossquant_absmax(Xg)
+    Y, a, b, acc = cq.crossquant_quantize_linear_fused(Xg, t, c, 0.5, 8, gpu(qw), gpu(s), want_acc=True)
+    assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    cfg = workloads.CONFIGS["C4"]
+    Xg, Wg = gpu(workloads.config_activation("C4")), gpu(workloads.config_weight("C4"))
+    t, c = cq.crossquant_absmax(Xg)
+    nib, _, a2, b2, _ = cq.crossquant_quantize(Xg, t, c, 0.15, 4, want_xhat=False)
+    qw4, ws4 = cq.crossquant_weight_quantize(Wg, b2, 4)
+    Y2, acc2 = cq.crossquant_w8a8_linear(cq.crossquant_unpack_int4(nib), a2, qw4, ws4, want_acc=True)
+    Y, a, b, acc = cq.crossquant_quantize_linear_fused(Xg, t, c, 0.15, 4, qw4, ws4, want_acc=True)
+    assert torch.equal(acc, acc2) and torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
+    assert torch.equal(a, a2) and torch.equal(b, b2)
+
+
 # ----------------------------------------------------------------------------- HIP graph replay
 def test_whole_path_replays_from_a_hip_graph(cq):
     """The calls allocate nothing, never synchronise and clear their accumulators with kernels, so
