@@ -98,19 +98,11 @@ int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const 
                         void *stream);
 
 /*
- * crossquant_absmax followed by crossquant_quantize, fused: X is read from HBM once and held in
- * the chip's registers and LDS across a grid-wide barrier, which is possible when the matrix fits:
- * ceil(T/256) * ceil(I/512) <= number of CUs (256 on MI355X, i.e. up to 4096 x 8192).  Outputs and
- * arithmetic are exactly those of the two calls (t, c included).
- * Returns CQ_ERR_UNSUPPORTED, with nothing enqueued, if the matrix is too large or if the layout
- * is not the vector one (X and xhat 16-byte aligned, codes 8-byte aligned, ldx % 8 == 0,
- * I % 8 == 0): the caller then uses the two calls.
- * The barrier needs all blocks resident at once (one block per CU).  Other kernels running on the
- * device only delay it; if part of the device stays unavailable for seconds the kernel gives up
- * (it always terminates) and writes NaN into row_scale and col_scale.  The barrier's counters are
- * library-owned device memory, one pair per stream handle (16 per process, shared with the zero
- * counters of crossquant_quantize): calls on different streams may overlap; a stream without a
- * pair of its own (the 17th, or the per-thread default stream) gets CQ_ERR_UNSUPPORTED.
+ * crossquant_absmax followed by crossquant_quantize as one call: same arguments, outputs and arithmetic
+ * as the two (t and c included; row_scale / col_scale must not overlap them), any layout and size.
+ * It enqueues the same two kernels the two calls do, so it costs what they cost; one-launch forms (a grid
+ * barrier between the maxima and the quantize phase, with X kept on chip or re-read from the caches) were
+ * built and measured, and were slower on this device than the boundary between two kernels.
  */
 int crossquant_absmax_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits,
                                float *t, float *c, void *codes, void *xhat, float *row_scale,

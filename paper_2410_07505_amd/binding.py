@@ -36,8 +36,6 @@ lib.crossquant_fp6_packed_bytes.restype = ctypes.c_int64
 lib.crossquant_pack_fp6.argtypes = [_vp, _int, _i64, _i64, _vp, _vp]
 lib.crossquant_quantize_fp6.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_w4a4_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
-lib.crossquant_debug_set_barrier_polls.argtypes = [ctypes.c_uint]
-lib.crossquant_debug_set_barrier_polls.restype = None
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_kernel_analysis_static.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp]
@@ -204,11 +202,9 @@ def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want
                                codes: torch.Tensor = None, xhat: torch.Tensor = None,
                                row_scale: torch.Tensor = None, col_scale: torch.Tensor = None,
                                zero_count: torch.Tensor = None):
-    """crossquant_absmax + crossquant_quantize in one single-read kernel.
+    """crossquant_absmax + crossquant_quantize as one call.
 
-    Returns (t, c, codes, xhat_or_None, row_scale, col_scale, zero_count_or_None).  Raises
-    CrossQuantError with status -6 when the matrix does not fit on chip or is not in the
-    vector layout; the caller then makes the two calls."""
+    Returns (t, c, codes, xhat_or_None, row_scale, col_scale, zero_count_or_None)."""
     _matrix(X, torch.float16, "X")
     T, I = X.shape
     dev = X.device

@@ -1,9 +1,10 @@
 // C-ABI entry points: argument validation on the host, then kernel launches on the caller's
 // stream.  No allocation and no host synchronisation.  The library does hold a little process-wide
 // state, all of it behind these calls: the table that gives every stream handle a slot of device-side
-// accumulators (cq_slots.hip: the quantize kernel's zero-count words, the single-read call's barrier
-// counters), the single-read call's poll limit (a test hook), and one flag per kernel and device saying
-// that the kernel has been allowed its dynamic LDS size.
+// accumulators (cq_slots.hip: the quantize kernel's zero-count words, the counters of the absmax launch
+// that clears for itself, with the values they reach kept on the host), the device addresses of those
+// and of the static work array of crossquant_kernel_analysis_static, and one flag per kernel and device
+// saying that the kernel has been allowed its dynamic LDS size.
 #include "../../include/crossquant.h"
 #include "../../include/crossquant_bench.h"
 
@@ -110,17 +111,11 @@ int crossquant_absmax_quantize(const void* X, int64_t T, int64_t I, int64_t ldx,
     if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
         !aligned(xhat, 2) || !aligned(zero_count, 8))
         return CQ_ERR_ALIGN;
-    // the register-resident path only takes the vector layout; anything else: use the two calls
-    if (!aligned(X, 16) || ldx % 8 != 0 || I % 8 != 0 || !aligned(codes, 8) || !aligned(xhat, 16))
-        return CQ_ERR_UNSUPPORTED;
-    const hipError_t e = cq::launch_absmax_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, alpha, bits,
-                                                    t, c, row_scale, col_scale, codes, static_cast<uint16_t*>(xhat),
-                                                    zero_count, static_cast<hipStream_t>(stream));
-    if (e == hipErrorNotSupported) return CQ_ERR_UNSUPPORTED;
-    return from_hip(e);
+    if (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I)) return CQ_ERR_ALIAS;
+    return from_hip(cq::launch_absmax_quantize(static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, alpha, bits, t, c,
+                                               row_scale, col_scale, codes, static_cast<uint16_t*>(xhat), zero_count,
+                                               static_cast<hipStream_t>(stream)));
 }
-
-void crossquant_debug_set_barrier_polls(unsigned polls) { cq::set_fused_barrier_polls(polls); }
 
 int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
                             float alpha, int bits, float* row_scale, float* col_scale,

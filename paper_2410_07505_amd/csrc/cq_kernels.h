@@ -101,9 +101,7 @@ hipError_t launch_quantize(const uint16_t* X, int B, int T, int I, int64_t ldx, 
 // packed nibbles [n_bytes] -> int8 codes [2 * n_bytes]
 hipError_t launch_unpack_int4(const uint8_t* packed, int64_t n_bytes, int8_t* codes, hipStream_t stream);
 
-// Single-read fused maxima + quantize (one block per CU, own grid barrier).  hipErrorNotSupported, with nothing
-// enqueued, if the matrix does not fit in the chip's registers.
-void set_fused_barrier_polls(unsigned polls);
+// Maxima, then scale factors + quantize / dequantize / zero count: launch_absmax followed by launch_quantize.
 hipError_t launch_absmax_quantize(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int bits, float* t,
                                   float* c, float* a, float* b, void* codes, uint16_t* xhat,
                                   unsigned long long* zero_count, hipStream_t stream);

@@ -478,4 +478,23 @@ hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, con
                 : launch_mode<3, false>(X, 1, T, I, ldx, 0, t, c, al, 7, a, b, cp, nullptr, zero_count, stream);
 }
 
+
+// crossquant_absmax_quantize: the two kernels one after the other on the stream.  Two one-launch forms were built
+// and measured on the 4096 x 8192 layer, and both lost to this: keeping the tile in registers and LDS across a grid
+// barrier (X read once: 79 us in a step against 56 us), and re-reading the tile from the caches after a grid barrier
+// (70 us against 39 us back to back; 41 us with the barrier's waits compiled out, i.e. no gain even from a free
+// barrier).  A barrier through memory costs two to three round trips to the device's coherence point plus the
+// slowest block's lag; the boundary between two kernels costs about 3 us.
+hipError_t launch_absmax_quantize(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int bits, float* t,
+                                  float* c, float* a, float* b, void* codes, uint16_t* xhat,
+                                  unsigned long long* zero_count, hipStream_t stream) {
+    // both grids are checked before the first kernel is enqueued
+    const int ncc = (I + kColsPerWave - 1) / kColsPerWave;
+    const int nb = quantize_batches_per_wave(ncc, T);
+    if (!grid_fits((int64_t)ncc * ((T + 32 * nb - 1) / (32 * nb)), kWaves * kLanes)) return hipErrorInvalidValue;
+    const hipError_t e = launch_absmax(X, 1, T, I, ldx, 0, t, c, stream);
+    if (e != hipSuccess) return e;
+    return launch_quantize(X, 1, T, I, ldx, 0, t, c, alpha, bits, a, b, codes, xhat, zero_count, stream);
+}
+
 }  // namespace cq

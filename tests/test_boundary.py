@@ -103,8 +103,7 @@ def test_absmax_quantize_argument_errors(cq):
     assert call(T=0) == -2 and call(ldx=4) == -2
     assert call(bits=5) == -3 and call(alpha=1.5) == -4
     assert call(zc=P + 4) == -5 and call(xhat=P + 1) == -5
-    # valid requests outside the vector layout are "unsupported", found on the host
-    assert call(X=P + 2) == -6 and call(I=12, ldx=12) == -6 and call(ldx=12) == -6 and call(codes=P + 4) == -6
+    assert call(rs=P) == -8 and call(c=P + 0x100, cs=P + 0x100) == -8
 
 
 def test_batched_argument_errors(cq):
