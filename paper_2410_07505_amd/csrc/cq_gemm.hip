@@ -186,25 +186,29 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
 
 // a_off / b_off: byte offset of this lane's row and swizzled chunk for slab 0; slab ks flips the
 // chunk's bits 1-2, i.e. XORs the byte offset with ks * 32
+// (weight fragment ni of a wave holds the rows NI fr + ni of the wave's 32 NI rows, fr = the lane's fragment row:
+// fragments are one LDS row apart, and a lane ends up with NI consecutive output channels)
 template <int NI>
 __device__ __forceinline__ void load_frags(v4i (&af)[4], v4i (&bf)[NI], const int8_t* As, const int8_t* Bs,
                                            int a_off, int b_off, int ks) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) af[mi] = *reinterpret_cast<const v4i*>(As + mi * 32 * BK + (a_off ^ (ks * 32)));
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bf[ni] = *reinterpret_cast<const v4i*>(Bs + ni * 32 * BK + (b_off ^ (ks * 32)));
+    for (int ni = 0; ni < NI; ++ni) bf[ni] = *reinterpret_cast<const v4i*>(Bs + ni * BK + (b_off ^ (ks * 32)));
 }
 
-// The weight fragment is passed as the first MFMA operand, so the accumulator tile is laid out
-// transposed: lane l holds token (l & 31) and, per group of 4 registers, 4 consecutive output
-// channels 8*(r/4) + 4*(l/32) + (r%4) -- which is what lets the epilogue write 8-byte pieces.
+// The activation fragment is the first MFMA operand.  With the weight fragment first the accumulator tile comes
+// out transposed (a lane holds 4 consecutive channels of one token per register group, which makes for a simpler
+// epilogue), but the kernel runs 4.6 % slower on the 70B-shaped layer (720 -> 687 us, 4 % on the 7B-shaped one, 1 %
+// on the heavy-tailed 13B-shaped one): which operand the smaller codes travel on changes what the matrix
+// instruction draws, and this kernel is limited by power.
 template <int NI>
 __device__ __forceinline__ void mfma_slab(v16i (&acc)[4][NI], const v4i (&af)[4], const v4i (&bf)[NI]) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[ni], af[mi], acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -283,7 +287,9 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     const int frag_row = lane & 31, frag_half = lane >> 5;
     const int sw = (frag_row >> 1) & 7;
     const int a_off = (wm * 128 + frag_row) * BK + ((frag_half ^ sw) * 16);
-    const int b_off = (wn * WTN + frag_row) * BK + ((frag_half ^ sw) * 16);
+    // weight row of fragment 0: wn * WTN + NI * frag_row (its swizzle term is that row's, and the same for row + 1)
+    const int sw_b = ((NI * frag_row) >> 1) & 7;
+    const int b_off = (wn * WTN + NI * frag_row) * BK + ((frag_half ^ sw_b) * 16);
 
     v16i acc[4][NI];
 #pragma unroll
@@ -376,13 +382,15 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         k_step(kt, no{}, yes{});
         ++kt;
     }
-    EpilogueScales<NI> scales;
-    epilogue_load_scales<NI>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    EpilogueScalesRows<NI> scales;
+    epilogue_rows_load_scales<NI>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
     __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{});
 
-    epilogue_store<v16i, WTN, NI>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane, wave);
+    epilogue_rows_store<v16i, WTN, NI, 8>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane,
+                                          wave);
 }
+static_assert(epilogue_rows_lds(8, 64) <= kRingLds, "the epilogue's staging areas reuse the ring's LDS");
 
 // Work of a block.  Blocks [0, main_blocks) take the first n_main tiles of the walk whole, de-interleaved by XCD
 // as in tile_of_block; the blocks after them take the remaining tiles as half tiles of 128 channels (half tile

@@ -136,5 +136,95 @@ __device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, c
     }
 }
 
+// ---- The same for accumulators in the instruction's natural orientation (activation fragment as the first
+// operand): lane l holds one output channel per 32 x 32 tile and, in register r of the tile, token
+// 8 (r / 4) + 4 (l >> 5) + (r & 3).  The kernel assigns the rows of its NI weight fragments so that lane l's
+// channels are NI consecutive ones, NI (l & 31) + ni: with NI = 2 a lane packs two binary16 results of one token
+// into a word without any exchange between lanes.  A lane needs 64 different row factors; they go through a small
+// wave-private piece of LDS behind the staging areas (each lane requests two of its wave's 128 before the last step
+// of the contraction, stores them when the loop is over and reads them back four at a time).  Results are staged
+// token row by token row (a half wave writes 128 or 64 contiguous bytes of one token) and leave as whole 128-byte
+// pieces exactly as above.
+template <int NI>
+struct EpilogueScalesRows {
+    float a_own[2];        // row factors of tokens row0 + lane and row0 + 64 + lane
+    float s[NI];           // column steps of channels col0 + NI (lane & 31) + ni
+};
+template <int NI>
+__device__ __forceinline__ void epilogue_rows_load_scales(EpilogueScalesRows<NI>& sc, const float* __restrict__ row_scale,
+                                                          const float* __restrict__ w_scale, int T, int O, int row0,
+                                                          int col0, int lane) {
+    sc.a_own[0] = row_scale[min(row0 + lane, T - 1)];                 // rows >= T are never stored
+    sc.a_own[1] = row_scale[min(row0 + 64 + lane, T - 1)];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) sc.s[ni] = w_scale[min(col0 + NI * (lane & 31) + ni, O - 1)];
+}
+
+constexpr int epilogue_rows_pitch(int wtn) { return wtn * 2 + 16; }   // bytes per staged token row
+// LDS the epilogue needs for n_waves waves of 128 x wtn outputs: staging areas, then 512 bytes of row factors per wave
+constexpr int epilogue_rows_lds(int n_waves, int wtn) { return n_waves * (128 * epilogue_rows_pitch(wtn) + 512); }
+
+template <typename ACC, int WTN, int NI, int NWAVES>
+__device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* lds, const EpilogueScalesRows<NI>& sc,
+                                                    uint16_t* __restrict__ Y, int64_t ldy,
+                                                    int32_t* __restrict__ acc_debug, int T, int O, int row0, int col0,
+                                                    int lane, int wave) {
+    static_assert(NI == 1 || NI == 2, "one or two consecutive channels per lane");
+    constexpr int kRowPitch = epilogue_rows_pitch(WTN);
+    int8_t* stage = lds + wave * (128 * kRowPitch);
+    float* a_lds = reinterpret_cast<float*>(lds + NWAVES * (128 * kRowPitch) + wave * 512);
+    const int frag_half = lane >> 5, ch = lane & 31;
+    a_lds[lane] = sc.a_own[0];
+    a_lds[64 + lane] = sc.a_own[1];
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));      // wave-private: the writes above are done
+    const int o_loc = NI * ch;                           // first of this lane's NI channels
+    const bool o_ok = col0 + o_loc < O;                  // O % 8 == 0 on this path: both channels exist or neither
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        float4 a4[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) a4[g] = *reinterpret_cast<const float4*>(a_lds + mi * 32 + 8 * g + 4 * frag_half);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float av[4] = {a4[g].x, a4[g].y, a4[g].z, a4[g].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int t_loc = mi * 32 + 8 * g + 4 * frag_half + j;
+                uint32_t h[NI];
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    float y = (float)acc[mi][ni][4 * g + j] * av[j];
+                    y = rounded_f32(y * sc.s[ni]);
+                    h[ni] = f2h(y);
+                }
+                int8_t* dst = stage + t_loc * kRowPitch + o_loc * 2;
+                if (NI == 2) *reinterpret_cast<uint32_t*>(dst) = h[0] | (h[NI - 1] << 16);
+                else *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h[0];
+                if (acc_debug && row0 + t_loc < T && o_ok) {
+                    int32_t* d = acc_debug + (int64_t)(row0 + t_loc) * O + col0 + o_loc;
+                    if (NI == 2) *reinterpret_cast<int2*>(d) = make_int2((int)acc[mi][0][4 * g + j], (int)acc[mi][NI - 1][4 * g + j]);
+                    else *d = (int)acc[mi][0][4 * g + j];
+                }
+            }
+        }
+    }
+    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 4)
+    constexpr int kRowsPerInst = 64 / kLanesPerRow;
+    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+#pragma unroll
+    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
+        const int trow = i * kRowsPerInst + rsub;
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
+        if (row0 + trow < T && col0 + piece * 8 < O) {
+            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
+            // written through to memory as a stream (sc1 nt), as in epilogue_store
+            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(u32x4v{v.x, v.y, v.z, v.w})
+                         : "memory");
+        }
+    }
+}
+
 }  // namespace
 }  // namespace cq
