@@ -150,26 +150,30 @@ struct EpilogueScalesRows {
     float a_own[2];        // row factors of tokens row0 + lane and row0 + 64 + lane
     float s[NI];           // column steps of channels col0 + NI (lane & 31) + ni
 };
-template <int NI>
+// SPLIT (NI = 2): the lane's two channels are (lane & 31) and 32 + (lane & 31) -- weight fragments of 32
+// consecutive rows, as the FP6 operand format has them -- instead of two adjacent ones.
+template <int NI, bool SPLIT = false>
 __device__ __forceinline__ void epilogue_rows_load_scales(EpilogueScalesRows<NI>& sc, const float* __restrict__ row_scale,
                                                           const float* __restrict__ w_scale, int T, int O, int row0,
                                                           int col0, int lane) {
     sc.a_own[0] = row_scale[min(row0 + lane, T - 1)];                 // rows >= T are never stored
     sc.a_own[1] = row_scale[min(row0 + 64 + lane, T - 1)];
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) sc.s[ni] = w_scale[min(col0 + NI * (lane & 31) + ni, O - 1)];
+    for (int ni = 0; ni < NI; ++ni)
+        sc.s[ni] = w_scale[min(col0 + (SPLIT ? (lane & 31) + 32 * ni : NI * (lane & 31) + ni), O - 1)];
 }
 
 constexpr int epilogue_rows_pitch(int wtn) { return wtn * 2 + 16; }   // bytes per staged token row
 // LDS the epilogue needs for n_waves waves of 128 x wtn outputs: staging areas, then 512 bytes of row factors per wave
 constexpr int epilogue_rows_lds(int n_waves, int wtn) { return n_waves * (128 * epilogue_rows_pitch(wtn) + 512); }
 
-template <typename ACC, int WTN, int NI, int NWAVES>
+template <typename ACC, int WTN, int NI, int NWAVES, bool SPLIT = false>
 __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* lds, const EpilogueScalesRows<NI>& sc,
                                                     uint16_t* __restrict__ Y, int64_t ldy,
                                                     int32_t* __restrict__ acc_debug, int T, int O, int row0, int col0,
                                                     int lane, int wave) {
-    static_assert(NI == 1 || NI == 2, "one or two consecutive channels per lane");
+    static_assert(NI == 1 || NI == 2, "one or two channels per lane");
+    static_assert(!SPLIT || (NI == 2 && WTN == 64), "the split form is the 128 x 64 wave tile");
     constexpr int kRowPitch = epilogue_rows_pitch(WTN);
     int8_t* stage = lds + wave * (128 * kRowPitch);
     float* a_lds = reinterpret_cast<float*>(lds + NWAVES * (128 * kRowPitch) + wave * 512);
@@ -177,8 +181,9 @@ __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* l
     a_lds[lane] = sc.a_own[0];
     a_lds[64 + lane] = sc.a_own[1];
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));      // wave-private: the writes above are done
-    const int o_loc = NI * ch;                           // first of this lane's NI channels
-    const bool o_ok = col0 + o_loc < O;                  // O % 8 == 0 on this path: both channels exist or neither
+    // SPLIT: word ch of a staged row holds channels ch and 32 + ch; they are taken apart again on the way out
+    const int o_loc = SPLIT ? ch : NI * ch;              // first of this lane's NI channels
+    const bool o_ok = col0 + o_loc < O;                  // O % 8 == 0 on this path: adjacent channels exist or not together
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
         float4 a4[4];
@@ -197,31 +202,55 @@ __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* l
                     y = rounded_f32(y * sc.s[ni]);
                     h[ni] = f2h(y);
                 }
-                int8_t* dst = stage + t_loc * kRowPitch + o_loc * 2;
+                int8_t* dst = stage + t_loc * kRowPitch + (SPLIT ? ch * 4 : o_loc * 2);
                 if (NI == 2) *reinterpret_cast<uint32_t*>(dst) = h[0] | (h[NI - 1] << 16);
                 else *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h[0];
                 if (acc_debug && row0 + t_loc < T && o_ok) {
                     int32_t* d = acc_debug + (int64_t)(row0 + t_loc) * O + col0 + o_loc;
-                    if (NI == 2) *reinterpret_cast<int2*>(d) = make_int2((int)acc[mi][0][4 * g + j], (int)acc[mi][NI - 1][4 * g + j]);
-                    else *d = (int)acc[mi][0][4 * g + j];
+                    if (SPLIT) {
+                        d[0] = (int)acc[mi][0][4 * g + j];
+                        if (col0 + o_loc + 32 < O) d[32] = (int)acc[mi][NI - 1][4 * g + j];
+                    } else if (NI == 2) {
+                        *reinterpret_cast<int2*>(d) = make_int2((int)acc[mi][0][4 * g + j], (int)acc[mi][NI - 1][4 * g + j]);
+                    } else {
+                        *d = (int)acc[mi][0][4 * g + j];
+                    }
                 }
             }
         }
     }
     // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
-    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 4)
-    constexpr int kRowsPerInst = 64 / kLanesPerRow;
-    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
-#pragma unroll
-    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
-        const int trow = i * kRowsPerInst + rsub;
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
-        if (row0 + trow < T && col0 + piece * 8 < O) {
-            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
+    auto store16 = [&](int trow, int col, u32x4v v) {
+        if (row0 + trow < T && col0 + col < O) {
+            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + col;
             // written through to memory as a stream (sc1 nt), as in epilogue_store
-            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(u32x4v{v.x, v.y, v.z, v.w})
-                         : "memory");
+            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(v) : "memory");
+        }
+    };
+    if (SPLIT) {
+        // a lane takes 8 words of a row (channels 8 p .. 8 p + 7 in the low halves, 32 + 8 p .. in the high halves)
+        // and stores them as two 16-byte pieces
+        const int p = lane & 3, rsub = lane >> 2;
+#pragma unroll
+        for (int i = 0; i < 128 / 16; ++i) {
+            const int trow = i * 16 + rsub;
+            const uint4 w0 = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + p * 32);
+            const uint4 w1 = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + p * 32 + 16);
+            auto lows = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); };
+            auto highs = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); };
+            store16(trow, 8 * p, u32x4v{lows(w0.x, w0.y), lows(w0.z, w0.w), lows(w1.x, w1.y), lows(w1.z, w1.w)});
+            store16(trow, 32 + 8 * p, u32x4v{highs(w0.x, w0.y), highs(w0.z, w0.w), highs(w1.x, w1.y), highs(w1.z, w1.w)});
+        }
+    } else {
+        constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 4)
+        constexpr int kRowsPerInst = 64 / kLanesPerRow;
+        const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+#pragma unroll
+        for (int i = 0; i < 128 / kRowsPerInst; ++i) {
+            const int trow = i * kRowsPerInst + rsub;
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
+            store16(trow, piece * 8, u32x4v{v.x, v.y, v.z, v.w});
         }
     }
 }

@@ -34,9 +34,11 @@ constexpr int kFragBytes = 1536;                     // 32 rows x 64 elements x 
 constexpr int kFragLo = 1024;                        // first plane: 64 lanes x 16 bytes
 constexpr int kF6Slot = 8 * 2 * kFragBytes;          // 24 KiB: 256 rows x 128 elements
 constexpr int kF6Slots = 6;
-// the ring takes 144 KiB; the epilogue's staging area (8 waves x 128 rows x 136 bytes = 136 KiB) reuses it
-constexpr int kF6Lds = kF6Slots * kF6Slot;
-static_assert(kF6Lds >= 8 * 128 * (64 * 2 + 8) && kF6Lds <= 160 * 1024, "LDS budget of a gfx950 CU");
+// the ring takes 144 KiB
+constexpr int kF6Ring = kF6Slots * kF6Slot;
+// ... or a little more: the epilogue's staging areas and row factors (148 KiB) reuse the ring's LDS
+constexpr int kF6Lds = kF6Ring > epilogue_rows_lds(8, 64) ? kF6Ring : epilogue_rows_lds(8, 64);
+static_assert(kF6Lds <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 // ---- packing ---------------------------------------------------------------------------------
 // One thread builds one lane's 24 bytes of one fragment.  SRC 8: int8 codes [R][K]; SRC 4: packed
@@ -152,8 +154,9 @@ __device__ __forceinline__ void load_frags6(frag6 (&af)[4], frag6 (&bf)[NI], con
     for (int ni = 0; ni < NI; ++ni) bf[ni] = read_frag(Bs, b_rb + ni, kf, lane);
 }
 
-// Weight fragment first, as in the INT8 kernel: the accumulator tile comes out transposed (lane =
-// token, 4 consecutive channels per register group), which is what the shared epilogue expects.
+// Activation fragment first, as in the INT8 kernel (weights first runs 3 to 4 % slower): the accumulator tile has the
+// instruction's natural orientation, a lane holds channels l & 31 and 32 + (l & 31) of its wave's 64 (the operand
+// format keeps 32 consecutive rows in a fragment), and the shared row-oriented epilogue takes them apart again.
 // Format 2 = FP6 E2M3 for both operands; scale operands 0 select the unscaled instruction.
 template <int NI>
 __device__ __forceinline__ void mfma_slab6(v16f (&acc)[4][NI], const frag6 (&af)[4], const frag6 (&bf)[NI]) {
@@ -161,7 +164,7 @@ __device__ __forceinline__ void mfma_slab6(v16f (&acc)[4][NI], const frag6 (&af)
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(bf[ni]), as_operand(af[mi]),
+            acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(af[mi]), as_operand(bf[ni]),
                                                                           acc[mi][ni], 2, 2, 0, 0, 0, 0);
 }
 
@@ -322,14 +325,15 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         k_step(kt, no{}, no{}, yes{});
         ++kt;
     }
-    EpilogueScales<NI> scales;
-    epilogue_load_scales<NI>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    EpilogueScalesRows<NI> scales;
+    epilogue_rows_load_scales<NI, true>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
     __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{}, no{});
 
     // every wave's fragments are in registers and all loads have landed: the ring can be reused
     __syncthreads();
-    epilogue_store<v16f, WTN, NI>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane, wave);
+    epilogue_rows_store<v16f, WTN, NI, 8, true>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
+                                                lane, wave);
 }
 
 }  // namespace
