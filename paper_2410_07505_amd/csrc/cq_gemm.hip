@@ -261,10 +261,13 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     {
         const int8_t* base = b_loader ? qw : qx;
         const int first = b_loader ? n0 : m0, last = (b_loader ? O : T) - 1;
+        // the row term of the swizzle: (R >> 1) & 7 for activation rows; (R >> NI) & 7 for weight rows, which the
+        // fragments take NI apart (see b_off), so that a lane's chunk again only depends on (fragment row >> 1)
+        const int sw_shift = b_loader ? NI : 1;
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
             const int R = rows_per_loader * lw + 8 * ii + ld_r;
-            const int c = ld_p ^ ((R >> 1) & 7);
+            const int c = ld_p ^ ((R >> sw_shift) & 7);
             gsrc[ii] = base + (int64_t)min(first + R, last) * I + c * 16;
         }
     }
@@ -287,9 +290,9 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     const int frag_row = lane & 31, frag_half = lane >> 5;
     const int sw = (frag_row >> 1) & 7;
     const int a_off = (wm * 128 + frag_row) * BK + ((frag_half ^ sw) * 16);
-    // weight row of fragment 0: wn * WTN + NI * frag_row (its swizzle term is that row's, and the same for row + 1)
-    const int sw_b = ((NI * frag_row) >> 1) & 7;
-    const int b_off = (wn * WTN + NI * frag_row) * BK + ((frag_half ^ sw_b) * 16);
+    // weight row of fragment ni: wn * WTN + NI * frag_row + ni; its swizzle term (row >> NI) & 7 is (frag_row >> 1) & 7
+    // again, so the weight reads hit the banks exactly as the activation reads do (no conflicts)
+    const int b_off = (wn * WTN + NI * frag_row) * BK + ((frag_half ^ sw) * 16);
 
     v16i acc[4][NI];
 #pragma unroll
