@@ -100,13 +100,36 @@ int crossquant_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, const 
 /*
  * crossquant_absmax followed by crossquant_quantize as one call: same arguments, outputs and arithmetic
  * as the two (t and c included; row_scale / col_scale must not overlap them), any layout and size.
- * It enqueues the same two kernels the two calls do, so it costs what they cost; one-launch forms (a grid
+ * It enqueues the same two kernels the two calls do, so it costs what they cost: one-launch forms (a grid
  * barrier between the maxima and the quantize phase, with X kept on chip or re-read from the caches) were
- * built and measured, and were slower on this device than the boundary between two kernels.
+ * measured slower on this device than the boundary between two kernels (see the next call).
  */
 int crossquant_absmax_quantize(const void *X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits,
                                float *t, float *c, void *codes, void *xhat, float *row_scale,
                                float *col_scale, unsigned long long *zero_count, void *stream);
+
+/*
+ * The same call as ONE kernel that reads X from HBM once and holds it in the chip's registers and LDS
+ * across a grid-wide barrier (3 bytes of traffic per element instead of 5; 5 instead of 7 with xhat):
+ * possible when the matrix fits, ceil(T/256) * ceil(I/512) <= number of CUs (256 on MI355X, i.e. up to
+ * 4096 x 8192).  Arguments, outputs and arithmetic are exactly those of crossquant_absmax_quantize.
+ * On this device it is SLOWER than crossquant_absmax_quantize although it moves fewer bytes (the barrier
+ * keeps reads and writes apart in time and costs more than a kernel boundary): it is for input that is
+ * expensive to read twice, and for measuring that trade.
+ * Returns CQ_ERR_UNSUPPORTED, with nothing enqueued, if the matrix is too large or if the layout
+ * is not the vector one (X and xhat 16-byte aligned, codes 8-byte aligned, ldx % 8 == 0, I % 8 == 0).
+ * The barrier needs all blocks resident at once (one block per CU).  Other kernels running on the
+ * device only delay it; if part of the device stays unavailable for seconds the kernel gives up
+ * (it always terminates) and writes NaN into row_scale and col_scale.  The barrier's counters are
+ * library-owned device memory, one pair per stream handle (16 per process, shared with the zero
+ * counters of crossquant_quantize): calls on different streams may overlap; a stream without a
+ * pair of its own (the 17th, or the per-thread default stream) gets CQ_ERR_UNSUPPORTED; calls captured
+ * into a graph keep the pair of the stream they were captured on, so replays must not overlap.
+ */
+int crossquant_absmax_quantize_single_read(const void *X, int64_t T, int64_t I, int64_t ldx, float alpha,
+                                           int bits, float *t, float *c, void *codes, void *xhat,
+                                           float *row_scale, float *col_scale,
+                                           unsigned long long *zero_count, void *stream);
 
 /*
  * Batched forms for a [B][S][I] activation tensor (the shape the appendix fake-quant listing is

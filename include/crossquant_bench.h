@@ -1,6 +1,6 @@
 /*
  * crossquant_bench.h -- calls of libcrossquant.so that are not part of the method: roofline
- * calibration kernels for a benchmark.  A program that only quantizes needs
+ * calibration kernels for a benchmark, and a test hook.  A program that only quantizes needs
  * crossquant.h alone.  Conventions (device pointers, stream, return codes) as in crossquant.h.
  */
 #ifndef CROSSQUANT_BENCH_H
@@ -26,6 +26,14 @@ extern "C" {
 int crossquant_calib_read(const void *src, int64_t bytes, unsigned long long *sink, void *stream);
 int crossquant_calib_copy(const void *src, void *dst, int64_t bytes, void *stream);
 int crossquant_calib_mfma_i8(int iters, int data_mode, int *sink, double *ops, void *stream);
+
+/*
+ * Test hook for crossquant_absmax_quantize_single_read: the number of polls a block makes at the grid
+ * barrier before it gives up (default 2^22, seconds).  0 makes every block give up at once, so the failure
+ * path (NaN in row_scale / col_scale, codes not written) can be exercised without a GPU ever
+ * waiting.  Process-wide, not thread-safe; pass 1u << 22 to restore the default.
+ */
+void crossquant_debug_set_barrier_polls(unsigned polls);
 
 #ifdef __cplusplus
 }

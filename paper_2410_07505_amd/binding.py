@@ -26,6 +26,10 @@ _vp, _i64, _int, _f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_
 lib.crossquant_absmax.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp]
 lib.crossquant_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_absmax_quantize.argtypes = [_vp, _i64, _i64, _i64, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.crossquant_absmax_quantize_single_read.argtypes = lib.crossquant_absmax_quantize.argtypes
+lib.crossquant_absmax_quantize_single_read.restype = _int
+lib.crossquant_debug_set_barrier_polls.argtypes = [ctypes.c_uint]
+lib.crossquant_debug_set_barrier_polls.restype = None
 lib.crossquant_absmax_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp]
 lib.crossquant_quantize_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_calib_read.argtypes = [_vp, _i64, _vp, _vp]
@@ -197,14 +201,17 @@ def crossquant_quantize(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha
     return codes, xhat, row_scale, col_scale, zero_count
 
 
-def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want_xhat: bool = True,
-                               want_count: bool = True, t: torch.Tensor = None, c: torch.Tensor = None,
+def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, single_read: bool = False,
+                               want_xhat: bool = True, want_count: bool = True, t: torch.Tensor = None, c: torch.Tensor = None,
                                codes: torch.Tensor = None, xhat: torch.Tensor = None,
                                row_scale: torch.Tensor = None, col_scale: torch.Tensor = None,
                                zero_count: torch.Tensor = None):
     """crossquant_absmax + crossquant_quantize as one call.
 
-    Returns (t, c, codes, xhat_or_None, row_scale, col_scale, zero_count_or_None)."""
+    Returns (t, c, codes, xhat_or_None, row_scale, col_scale, zero_count_or_None).
+    single_read=True calls crossquant_absmax_quantize_single_read instead (one kernel that keeps X on
+    chip): same results; raises CrossQuantError with status -6 when the matrix does not fit on chip or
+    is not in the vector layout."""
     _matrix(X, torch.float16, "X")
     T, I = X.shape
     dev = X.device
@@ -224,10 +231,15 @@ def crossquant_absmax_quantize(X: torch.Tensor, alpha: float, bits: int, *, want
     if zero_count is None and want_count:
         zero_count = torch.empty(1, dtype=torch.int64, device=dev)
     _quant_buffers(X, T, I, t, c, codes, code_shape, code_dtype, xhat, row_scale, col_scale, zero_count)
-    _check(lib.crossquant_absmax_quantize(X.data_ptr(), T, I, X.stride(0), float(alpha), int(bits), t.data_ptr(),
-                                          c.data_ptr(), codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(),
-                                          col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
+    call = lib.crossquant_absmax_quantize_single_read if single_read else lib.crossquant_absmax_quantize
+    _check(call(X.data_ptr(), T, I, X.stride(0), float(alpha), int(bits), t.data_ptr(), c.data_ptr(),
+                codes.data_ptr(), _ptr(xhat), row_scale.data_ptr(), col_scale.data_ptr(), _ptr(zero_count), _stream(X)))
     return t, c, codes, xhat, row_scale, col_scale, zero_count
+
+
+def crossquant_absmax_quantize_single_read(X: torch.Tensor, alpha: float, bits: int, **kw):
+    """crossquant_absmax_quantize(..., single_read=True)."""
+    return crossquant_absmax_quantize(X, alpha, bits, single_read=True, **kw)
 
 
 def _req3(X: torch.Tensor):

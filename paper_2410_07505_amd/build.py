@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcrossquant.so")
-SOURCES = ["cq_api.hip", "cq_slots.hip", "cq_absmax.hip", "cq_quantize.hip", "cq_analysis.hip", "cq_static.hip", "cq_weight.hip", "cq_gemm.hip", "cq_gemm_fusedq.hip", "cq_gemm_fp6.hip", "cq_ceilings.hip"]
+SOURCES = ["cq_api.hip", "cq_slots.hip", "cq_absmax.hip", "cq_quantize.hip", "cq_analysis.hip", "cq_static.hip", "cq_fused.hip", "cq_weight.hip", "cq_gemm.hip", "cq_gemm_fusedq.hip", "cq_gemm_fp6.hip", "cq_ceilings.hip"]
 
 # -ffp-contract=off: every binary32 operation rounds on its own (results are specified bit for
 # bit).  -packed-fp32-ops off: packed FP32 VALU forms are not used on the test machines.

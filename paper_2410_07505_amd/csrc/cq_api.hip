@@ -117,6 +117,28 @@ int crossquant_absmax_quantize(const void* X, int64_t T, int64_t I, int64_t ldx,
                                                static_cast<hipStream_t>(stream)));
 }
 
+int crossquant_absmax_quantize_single_read(const void* X, int64_t T, int64_t I, int64_t ldx, float alpha, int bits,
+                                           float* t, float* c, void* codes, void* xhat, float* row_scale,
+                                           float* col_scale, unsigned long long* zero_count, void* stream) {
+    if (!t || !c || !codes || !row_scale || !col_scale) return CQ_ERR_NULL;
+    if (int s = check_matrix(X, T, I, ldx)) return s;
+    if (int s = check_quant_params(alpha, bits, I)) return s;
+    if (!aligned(t, 4) || !aligned(c, 4) || !aligned(row_scale, 4) || !aligned(col_scale, 4) ||
+        !aligned(xhat, 2) || !aligned(zero_count, 8))
+        return CQ_ERR_ALIGN;
+    if (overlap(t, T, row_scale, T) || overlap(c, I, col_scale, I)) return CQ_ERR_ALIAS;
+    // the register-resident kernel only takes the vector layout
+    if (!aligned(X, 16) || ldx % 8 != 0 || I % 8 != 0 || !aligned(codes, 8) || !aligned(xhat, 16))
+        return CQ_ERR_UNSUPPORTED;
+    const hipError_t e = cq::launch_absmax_quantize_single_read(
+        static_cast<const uint16_t*>(X), (int)T, (int)I, ldx, alpha, bits, t, c, row_scale, col_scale, codes,
+        static_cast<uint16_t*>(xhat), zero_count, static_cast<hipStream_t>(stream));
+    if (e == hipErrorNotSupported) return CQ_ERR_UNSUPPORTED;
+    return from_hip(e);
+}
+
+void crossquant_debug_set_barrier_polls(unsigned polls) { cq::set_fused_barrier_polls(polls); }
+
 int crossquant_kernel_count(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,
                             float alpha, int bits, float* row_scale, float* col_scale,
                             unsigned long long* zero_count, void* stream) {

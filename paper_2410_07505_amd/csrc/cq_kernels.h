@@ -106,6 +106,15 @@ hipError_t launch_absmax_quantize(const uint16_t* X, int T, int I, int64_t ldx, 
                                   float* c, float* a, float* b, void* codes, uint16_t* xhat,
                                   unsigned long long* zero_count, hipStream_t stream);
 
+// The same result from one kernel that reads X once and holds it in registers and LDS across a grid barrier
+// (vector layout only).  hipErrorNotSupported, with nothing enqueued, when the matrix does not fit on chip or the
+// stream has no barrier state of its own.
+hipError_t launch_absmax_quantize_single_read(const uint16_t* X, int T, int I, int64_t ldx, float alpha, int bits, float* t,
+                                  float* c, float* a, float* b, void* codes, uint16_t* xhat,
+                                  unsigned long long* zero_count, hipStream_t stream);
+// polls a block of the single-read kernel makes at its grid barrier before it gives up (test hook)
+void set_fused_barrier_polls(unsigned polls);
+
 hipError_t launch_weight_quantize(const uint16_t* W, int I, int O, const float* fold, int qmax,
                                   int8_t* qw, float* w_scale, hipStream_t stream);
 

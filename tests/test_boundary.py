@@ -93,8 +93,9 @@ def test_quantize_argument_errors(cq):
     assert call(**{**far, "cs": P + 0x1000 - 28}) == -8  # cs's last element is c's first
 
 
-def test_absmax_quantize_argument_errors(cq):
-    f = cq.raw.crossquant_absmax_quantize
+@pytest.mark.parametrize("entry", ["crossquant_absmax_quantize", "crossquant_absmax_quantize_single_read"])
+def test_absmax_quantize_argument_errors(cq, entry):
+    f = getattr(cq.raw, entry)
 
     def call(X=P, T=4, I=8, ldx=8, alpha=0.15, bits=8, t=P, c=P, codes=P, xhat=P, rs=P, cs=P, zc=P):
         return f(X, T, I, ldx, alpha, bits, t, c, codes, xhat, rs, cs, zc, None)

@@ -550,8 +550,9 @@ def test_wide_leading_dimension(cq):
 
 
 # ----------------------------------------------------------------------------- single-read fused call
-def check_fused(cq, X, alpha, bits, Xg=None, label="", want_xhat=True):
-    say("absmax_quantize %s shape=%s alpha=%g bits=%d xhat=%s" % (label, X.shape, alpha, bits, want_xhat))
+def check_fused(cq, X, alpha, bits, Xg=None, label="", want_xhat=True, single_read=False):
+    say("absmax_quantize%s %s shape=%s alpha=%g bits=%d xhat=%s" % ("_single_read" if single_read else "", label, X.shape,
+                                                                  alpha, bits, want_xhat))
     import torch
     Xg = gpu(X) if Xg is None else Xg
     T, I = X.shape
@@ -560,7 +561,8 @@ def check_fused(cq, X, alpha, bits, Xg=None, label="", want_xhat=True):
     # stale contents everywhere: the call must overwrite all of it
     stale = dict(t=torch.full((T,), 7.0, device="cuda"), c=torch.full((I,), 9.0, device="cuda"),
                  zero_count=torch.full((1,), 12345, dtype=torch.int64, device="cuda"))
-    t, c, codes, xhat, a, b, zc = cq.crossquant_absmax_quantize(Xg, alpha, bits, want_xhat=want_xhat, **stale)
+    t, c, codes, xhat, a, b, zc = cq.crossquant_absmax_quantize(Xg, alpha, bits, want_xhat=want_xhat,
+                                                                single_read=single_read, **stale)
     assert np.array_equal(bits32(host(t)), bits32(t_ref)) and np.array_equal(bits32(host(c)), bits32(c_ref))
     assert np.array_equal(bits32(host(a)), bits32(ref["a"])), "row scale factors differ"
     assert np.array_equal(bits32(host(b)), bits32(ref["b"])), "column scale factors differ"
@@ -583,26 +585,66 @@ FUSED_SHAPES = [(1, 8), (3, 16), (37, 56), (64, 256), (130, 1000), (129, 520), (
 
 @pytest.mark.parametrize("T,I", FUSED_SHAPES)
 @pytest.mark.parametrize("bits", [8, 4])
-def test_fused_small_and_ragged(cq, T, I, bits):
+@pytest.mark.parametrize("single_read", [False, True])
+def test_fused_small_and_ragged(cq, T, I, bits, single_read):
     X = outliers(T, I, seed=T + I)
-    check_fused(cq, X, 0.15, bits)
-    check_fused(cq, X, 1.0, bits, want_xhat=False)
+    check_fused(cq, X, 0.15, bits, single_read=single_read)
+    check_fused(cq, X, 1.0, bits, want_xhat=False, single_read=single_read)
 
 
-def test_fused_zero_rows_columns_ties_and_strided(cq):
+@pytest.mark.parametrize("single_read", [False, True])
+def test_fused_zero_rows_columns_ties_and_strided(cq, single_read):
     X = outliers(40, 96, seed=3)
     X[5, :] = 0
     X[:, 17] = 0
     for alpha in (0.0, 0.15, 1.0):
-        check_fused(cq, X, alpha, 8, label="zero row/col")
-    check_fused(cq, np.zeros((20, 64), np.float16), 0.15, 8, label="all zero")
+        check_fused(cq, X, alpha, 8, label="zero row/col", single_read=single_read)
+    check_fused(cq, np.zeros((20, 64), np.float16), 0.15, 8, label="all zero", single_read=single_read)
     rng = np.random.default_rng(5)
     Xt = (rng.integers(-250, 251, (96, 512)) / 2.0).astype(np.float16)
     Xt[:, 0] = 127.0
-    check_fused(cq, Xt, 1.0, 8, label="ties")
+    check_fused(cq, Xt, 1.0, 8, label="ties", single_read=single_read)
     base = outliers(50, 304, seed=77)
     g = gpu(base)
-    check_fused(cq, base[:, 8:264], 0.15, 8, Xg=g[:, 8:264], label="view[8:264]")
+    check_fused(cq, base[:, 8:264], 0.15, 8, Xg=g[:, 8:264], label="view[8:264]", single_read=single_read)
+
+
+def test_single_read_reports_unsupported_requests(cq):
+    """Layouts the register-resident kernel does not take, and matrices that do not fit on the
+    chip, come back as CQ_ERR_UNSUPPORTED with nothing enqueued; crossquant_absmax_quantize serves them."""
+    import torch
+    base = outliers(50, 304, seed=78)
+    g = gpu(base)
+    for view in (g[:, 1:257], g[:, 0:54]):                     # misaligned rows; I % 8 != 0
+        with pytest.raises(cq.CrossQuantError) as e:
+            cq.crossquant_absmax_quantize_single_read(view, 0.15, 8)
+        assert e.value.status == -6
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    rows = 256 * (n_cu // 16) + 1                              # one row block too many at I = 8192
+    big = torch.zeros((rows, 8192), dtype=torch.float16, device="cuda")
+    with pytest.raises(cq.CrossQuantError) as e:
+        cq.crossquant_absmax_quantize_single_read(big, 0.15, 8)
+    assert e.value.status == -6
+    torch.cuda.synchronize()
+
+
+def test_single_read_barrier_gives_up_cleanly(cq):
+    """The grid barrier's bounded wait, forced from the host: with a poll limit of 0 every block
+    gives up at once, the kernel ends normally, flags the failure with NaN scale factors and
+    writes no codes; with the default limit the same call is correct again."""
+    import torch
+    X = outliers(300, 1024, seed=55)
+    Xg = gpu(X)
+    codes = torch.full((300, 1024), 99, dtype=torch.int8, device="cuda")
+    try:
+        cq.raw.crossquant_debug_set_barrier_polls(0)
+        _, _, codes_out, _, a, b, _ = cq.crossquant_absmax_quantize_single_read(Xg, 0.15, 8, codes=codes)
+        torch.cuda.synchronize()
+    finally:
+        cq.raw.crossquant_debug_set_barrier_polls(1 << 22)
+    assert bool(torch.isnan(a).all()) and bool(torch.isnan(b).all())
+    assert bool((codes_out == 99).all())
+    check_fused(cq, X, 0.15, 8, Xg=Xg, label="after the forced failure", single_read=True)
 
 
 def test_fused_call_takes_every_layout_and_size(cq):
@@ -670,6 +712,12 @@ def test_fused_full_configs(cq, name):
     r1 = cq.crossquant_absmax_quantize(Xg, 0.15, 8)
     r2 = cq.crossquant_absmax_quantize(Xg, 0.15, 8)
     assert all(torch.equal(x, y) for x, y in zip(r1, r2))
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    if ((T + 255) // 256) * ((I + 511) // 512) <= n_cu:        # fits on chip: the single-read kernel as well
+        check_fused(cq, X, 0.15, 8, Xg=Xg, label=name, single_read=True)
+        check_fused(cq, X, 0.15, 4, Xg=Xg, label=name, want_xhat=False, single_read=True)
+        r3 = cq.crossquant_absmax_quantize_single_read(Xg, 0.15, 8)
+        assert all(torch.equal(x, y) for x, y in zip(r1, r3))
 
 
 # ----------------------------------------------------------------------------- batched [B][S][I]
