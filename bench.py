@@ -35,10 +35,14 @@ METRIC = "CrossQuant quantize GB/s (% HBM peak) + W8A8 linear TOPS (% INT8 MFMA 
 STAGES = ("absmax", "quantize", "count", "linear")
 
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy of known size (profiles/*_hbm_traffic_pmc.txt).  Measured once per
-# workload with the command given in the profile; null for workloads that have not been profiled.
+# counters read for a plain copy of known size (profiles/bench_hbm_traffic_pmc.txt).  Measured once per
+# workload with the commands given in that profile ("linear": the matrix kernel of the workload's linear
+# layer; "quantize": its quantize kernel); null for workloads that have not been profiled (C1).
 MEASURED_TRAFFIC_BYTES = {
-    "C5": {"linear": (1344.9 + 224.0) * 2 ** 20, "quantize": (64.4 + 96.1) * 2 ** 20},
+    "C2": {"quantize": (16.4 + 24.0) * 2 ** 20, "linear": (160.6 + 43.0) * 2 ** 20},
+    "C3": {"quantize": (40.6 + 60.0) * 2 ** 20, "linear": (600.7 + 160.0) * 2 ** 20},
+    "C4": {"quantize": (36.6 + 44.1) * 2 ** 20, "linear": (72.4 + 32.0) * 2 ** 20},
+    "C5": {"quantize": (64.5 + 96.1) * 2 ** 20, "linear": (1344.8 + 224.0) * 2 ** 20},
 }
 
 
@@ -294,6 +298,7 @@ class Workload:
             "quantizer_GBs": f["quant_gbs"], "quantizer_frac_hbm_peak": f["quant_gbs"] / HBM_PEAK_GBS,
             "absmax_GBs": f["absmax_gbs"], "quantize_GBs": f["quantize_gbs"], "count_GBs": f["count_gbs"],
             "linear_TOPs": f["tops"], "linear_peak_TOPs": f["peak_tops"], "linear_frac_peak": f["tops"] / f["peak_tops"],
+            "traffic_bytes": MEASURED_TRAFFIC_BYTES.get(self.cfg.name),
             "kernel_proportion": {"crossquant": int(self.zc.item()) / n, "per_token": int(self.zc_pt.item()) / n},
             "quantize_inside_gemm": self.inside_gemm(),
         }

@@ -190,11 +190,11 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
 // fragments are one LDS row apart, and a lane ends up with NI consecutive output channels)
 template <int NI>
 __device__ __forceinline__ void load_frags(v4i (&af)[4], v4i (&bf)[NI], const int8_t* As, const int8_t* Bs,
-                                           int a_off, int b_off, int ks) {
+                                           int a_off, int b_off, int b_flip, int ks) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) af[mi] = *reinterpret_cast<const v4i*>(As + mi * 32 * BK + (a_off ^ (ks * 32)));
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bf[ni] = *reinterpret_cast<const v4i*>(Bs + ni * BK + (b_off ^ (ks * 32)));
+    for (int ni = 0; ni < NI; ++ni) bf[ni] = *reinterpret_cast<const v4i*>(Bs + ni * b_flip + (b_off ^ (ks * 32)));
 }
 
 // The activation fragment is the first MFMA operand.  With the weight fragment first the accumulator tile comes
@@ -261,14 +261,19 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     {
         const int8_t* base = b_loader ? qw : qx;
         const int first = b_loader ? n0 : m0, last = (b_loader ? O : T) - 1;
-        // the row term of the swizzle: (R >> 1) & 7 for activation rows; (R >> NI) & 7 for weight rows, which the
-        // fragments take NI apart (see b_off), so that a lane's chunk again only depends on (fragment row >> 1)
+        // LDS row R of an operand tile holds, for activations, tile row R with chunk c at c ^ ((R >> 1) & 7): a
+        // fragment's 16 lanes per LDS cycle read 16 consecutive rows, whose parity picks the half of the 64 banks
+        // and whose (R >> 1) & 7 picks the 16-byte group.  Weight fragment ni takes the tile rows NI fr + ni (see
+        // b_off); for NI = 2 those are all even or all odd, so LDS row R holds tile row R ^ ((R >> 1) & 1) (the two
+        // rows of a pair change places in every other pair) and the swizzle term comes from R >> 2: a lane then
+        // reads LDS row 2 fr + (ni ^ (fr & 1)), parity and group exactly as for the activation fragment.
         const int sw_shift = b_loader ? NI : 1;
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
             const int R = rows_per_loader * lw + 8 * ii + ld_r;
             const int c = ld_p ^ ((R >> sw_shift) & 7);
-            gsrc[ii] = base + (int64_t)min(first + R, last) * I + c * 16;
+            const int tile_row = (b_loader && NI == 2) ? (R ^ ((R >> 1) & 1)) : R;
+            gsrc[ii] = base + (int64_t)min(first + tile_row, last) * I + c * 16;
         }
     }
     auto issue_half = [&](int kt, int slot) {
@@ -290,9 +295,11 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     const int frag_row = lane & 31, frag_half = lane >> 5;
     const int sw = (frag_row >> 1) & 7;
     const int a_off = (wm * 128 + frag_row) * BK + ((frag_half ^ sw) * 16);
-    // weight row of fragment ni: wn * WTN + NI * frag_row + ni; its swizzle term (row >> NI) & 7 is (frag_row >> 1) & 7
-    // again, so the weight reads hit the banks exactly as the activation reads do (no conflicts)
-    const int b_off = (wn * WTN + NI * frag_row) * BK + ((frag_half ^ sw) * 16);
+    // weight fragment ni: tile row wn * WTN + NI * frag_row + ni, which for NI = 2 sits in LDS row
+    // wn * WTN + 2 frag_row + (ni ^ (frag_row & 1)); b_off is fragment 0's offset, b_flip the step to fragment 1
+    const int b_par = (NI == 2) ? (frag_row & 1) : 0;
+    const int b_off = (wn * WTN + NI * frag_row + b_par) * BK + ((frag_half ^ sw) * 16);
+    const int b_flip = b_par ? -BK : BK;
 
     v16i acc[4][NI];
 #pragma unroll
@@ -314,7 +321,7 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     auto adv = [](int v) { v += 2; return v >= kRingSlots ? v - kRingSlots : v; };
 
     v4i af0[4], bf0[NI], af1[4], bf1[NI];
-    load_frags<NI>(af0, bf0, lds + sa * kSlotBytes, lds + sb * kSlotBytes, a_off, b_off, 0);
+    load_frags<NI>(af0, bf0, lds + sa * kSlotBytes, lds + sb * kSlotBytes, a_off, b_off, b_flip, 0);
 
     constexpr int NMF = 4 * NI, NRD = 4 + NI;
     auto interleave_reads = [&]() {
@@ -334,13 +341,13 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         const int8_t* As = lds + sa * kSlotBytes;
         const int8_t* Bs = lds + sb * kSlotBytes;
         const int na = adv(sa), nb = adv(sb);                   // slots of tile kt+1
-        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 1);
+        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, b_flip, 1);
         mfma_slab<NI>(acc, af0, bf0);
         interleave_reads();
-        load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, 2);
+        load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, b_flip, 2);
         mfma_slab<NI>(acc, af1, bf1);
         interleave_reads();
-        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, 3);
+        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, b_flip, 3);
         mfma_slab<NI>(acc, af0, bf0);
         interleave_reads();
         // A loaders: A(kt+2) = half tile 2kt+4 -> slot (2kt+4) % 5 = adv(na); its previous tenant
@@ -366,7 +373,7 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         // nobody reads any more (slab 3's fragments are in registers)
         if (b_loader && ISSUE) issue_half(kt + 2, sa);
         __builtin_amdgcn_sched_barrier(0);
-        if (PREFETCH) load_frags<NI>(af0, bf0, lds + na * kSlotBytes, lds + nb * kSlotBytes, a_off, b_off, 0);
+        if (PREFETCH) load_frags<NI>(af0, bf0, lds + na * kSlotBytes, lds + nb * kSlotBytes, a_off, b_off, b_flip, 0);
         mfma_slab<NI>(acc, af1, bf1);
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
