@@ -2,9 +2,10 @@
 // stream.  No allocation and no host synchronisation.  The library does hold a little process-wide
 // state, all of it behind these calls: the table that gives every stream handle a slot of device-side
 // accumulators (cq_slots.hip: the quantize kernel's zero-count words, the counters of the absmax launch
-// that clears for itself, with the values they reach kept on the host), the device addresses of those
-// and of the static work array of crossquant_kernel_analysis_static, and one flag per kernel and device
-// saying that the kernel has been allowed its dynamic LDS size.
+// that clears for itself, with the values they reach kept on the host, the barrier words of the
+// single-read kernel and its poll limit), the device addresses of those and of the static work array of
+// crossquant_kernel_analysis_static, and one flag per kernel and device saying that the kernel has been
+// allowed its dynamic LDS size.
 #include "../../include/crossquant.h"
 #include "../../include/crossquant_bench.h"
 
