@@ -222,11 +222,12 @@ hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, in
     // where a wave's rows there end, i.e. when 8 nb is a multiple of the 4 nbq rows of a quantize wave -- equal
     // to it if nbq is even.  Measured in a step, K1 + K3 stages: 4096 x 8192 (nbq 4) 50.4 us with nb 2, 52.2 with
     // nb 3, 53.2 with nb 4; 4096 x 5120 (nbq 3) 37.1 us with nb 3, 39.5 with nb 2 or 4.  Large odd nbq would make
-    // blocks too big for this kernel's own good: nb 3 then.  Huge inputs take more rows per block, to bound the
+    // blocks too big for this kernel's own good: nb 3 then.  A wave wants at least two batches to have loads in
+    // flight while it reduces (4096 x 4096, nbq 2: this kernel 12.6 us with nb 1, 10.8 with nb 2).  Huge inputs take more rows per block, to bound the
     // number of column atomics.
     auto n_blocks_for = [&](int n) { return (int64_t)B * ncc * ((T + 32 * n - 1) / (32 * n)); };
     const int nbq = quantize_batches_per_wave((int64_t)B * ncc, T);
-    int nb = nbq % 2 == 0 ? nbq / 2 : (nbq <= 3 ? nbq : 3);
+    int nb = nbq % 2 == 0 ? (nbq >= 4 ? nbq / 2 : 2) : (nbq <= 3 ? nbq : 3);
     while (nb < 16 && n_blocks_for(nb) > 4096) ++nb;
     const int nrc = (T + 32 * nb - 1) / (32 * nb);
     const bool vec = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 8 == 0) && (B == 1 || matrix_stride % 8 == 0);

@@ -5,10 +5,11 @@
 // the layout v_mfma_i32_32x32x32_i8 wants: every lane supplies 16 consecutive bytes of one row.
 //
 // Two kernels, same results (integer accumulation is exact, so tiling and order cannot matter):
-//   - gemm_i8_ring_kernel, the fast path: whole 256 x 256 tiles, 16-byte aligned operands, K a
-//     multiple of 128.  512 threads = 8 waves in a 2 x 4 arrangement, each wave owning 128 x 64 =
-//     4 x 2 MFMA tiles of 32 x 32 (128 accumulator registers); operands go from global memory
-//     straight into a five-slot LDS ring (described at the kernel);
+//   - gemm_i8_ring_kernel, the fast path: 16-byte aligned operands, K a multiple of 128, any T (edge tiles
+//     read clamped rows and drop the surplus outputs).  512 threads = 8 waves in a 2 x 4 arrangement, each
+//     wave owning 128 x 64 = 4 x 2 MFMA tiles of 32 x 32 (128 accumulator registers); operands go from
+//     global memory straight into a five-slot LDS ring (described at the kernel); a last round of tiles
+//     that is at most half full runs as 256 x 128 half tiles;
 //   - gemm_i8_kernel<true>, any shape and alignment: 256 threads = 4 waves in a 2 x 2 arrangement
 //     (128 x 128 per wave), two LDS stages of (256 + 256) rows x 128 B = 128 KiB; the next K step
 //     is fetched into registers (bounds-checked) while the current one is multiplied, then stored
@@ -16,7 +17,8 @@
 // Common to both:
 //   - block tile 256 x 256, K step 128 bytes;
 //   - LDS rows are 128 B = 8 chunks of 16 B, stored at chunk ^ ((row >> 1) & 7) so that the 16
-//     rows a quarter-wave reads (and the row pairs it writes) fall in 16 distinct bank groups;
+//     rows a quarter-wave reads (and the row pairs it writes) fall in 16 distinct bank groups of the
+//     64-bank LDS (the ring kernel's weight tile differs in one detail, see its loader);
 //   - block -> tile mapping: consecutive block ids land on different XCDs, so ids are first
 //     de-interleaved by XCD (each XCD gets a contiguous range of tiles, hence its own L2 sees a
 //     compact patch), then walked in groups of 4 tile-rows so that concurrently resident tiles

@@ -44,99 +44,10 @@ __device__ __forceinline__ bool tile_of_block(int block, int tiles_m, int tiles_
     return true;
 }
 
-// Epilogue shared by the fast-path kernels.  Lane l holds token t = l & 31 of each 32-token block
-// and, for register group rg = r / 4, the 4 consecutive channels 8*rg + 4*(l >> 5) + {0..3} of
-// each 32-channel block.  Scaled binary16 results go through LDS (free once the K loop has ended
-// on a barrier with no reads outstanding) so that every global store is a full 16 bytes per lane
-// and a wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
-// The scale factors one lane's outputs need: a_i of its 4 rows, s_k of its 4 * NI groups of 4 channels.
-// Requested before the last step of the contraction so that they have arrived when it ends.
-template <int NI>
-struct EpilogueScales {
-    float a_t[4];
-    float4 s4[NI][4];
-};
-template <int NI>
-__device__ __forceinline__ void epilogue_load_scales(EpilogueScales<NI>& sc, const float* __restrict__ row_scale,
-                                                     const float* __restrict__ w_scale, int T, int O, int row0,
-                                                     int col0, int lane) {
-    const int frag_half = lane >> 5, t_lane = lane & 31;
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) sc.a_t[mi] = row_scale[min(row0 + mi * 32 + t_lane, T - 1)];   // rows >= T are never stored
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
-            // O % 8 == 0 on this path: a group of 4 channels exists or not as a whole
-            sc.s4[ni][rg] = (col0 + o_loc < O) ? *reinterpret_cast<const float4*>(w_scale + col0 + o_loc)
-                                               : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        }
-}
-
-template <typename ACC, int WTN, int NI>
-__device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, const EpilogueScales<NI>& sc,
-                                               uint16_t* __restrict__ Y, int64_t ldy,
-                                               int32_t* __restrict__ acc_debug, int T, int O, int row0, int col0,
-                                               int lane, int wave) {
-    const int frag_half = lane >> 5;
-    constexpr int kRowPitch = WTN * 2 + 8;              // bytes per staged row (+8: spreads LDS banks)
-    int8_t* stage = lds + wave * (128 * kRowPitch);      // this wave's 128 x WTN staging area
-    const int t_lane = lane & 31;
-    const float (&a_t)[4] = sc.a_t;
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-            const int o_loc = ni * 32 + 8 * rg + 4 * frag_half;          // first of 4 channels
-            const float4 s4 = sc.s4[ni][rg];
-            const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                uint32_t h[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float y = (float)acc[mi][ni][rg * 4 + j] * a_t[mi];
-                    y = rounded_f32(y * sv[j]);
-                    h[j] = f2h(y);
-                }
-                *reinterpret_cast<uint2*>(stage + (mi * 32 + t_lane) * kRowPitch + o_loc * 2) =
-                    make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                const int row = row0 + mi * 32 + t_lane;
-                if (acc_debug && row < T && col0 + o_loc < O) {
-                    int4 v = make_int4((int)acc[mi][ni][rg * 4 + 0], (int)acc[mi][ni][rg * 4 + 1],
-                                       (int)acc[mi][ni][rg * 4 + 2], (int)acc[mi][ni][rg * 4 + 3]);
-                    *reinterpret_cast<int4*>(acc_debug + (int64_t)row * O + col0 + o_loc) = v;
-                }
-            }
-        }
-    }
-    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
-    constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 16)
-    constexpr int kRowsPerInst = 64 / kLanesPerRow;
-    const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
-#pragma unroll
-    for (int i = 0; i < 128 / kRowsPerInst; ++i) {
-        const int trow = i * kRowsPerInst + rsub;
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
-        if (row0 + trow < T && col0 + piece * 8 < O) {
-            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + piece * 8;
-            // Y is not read again here and whole 128-byte pieces leave at once: written through to memory
-            // as a stream (sc1 nt).  The GEMM itself does not care, but the memory-side cache is left
-            // without 224 MiB of dirty lines, so the kernel that runs next reads its cold input faster
-            // (64 MiB: 4 us less; of the policies tried -- plain, nt, sc1, sc1 nt, sc0 nt, sc0 sc1 nt --
-            // this one gave the shortest following absmax + quantize calls).
-            // (The compiler offers no way to ask for this policy, hence the assembly; it cannot see a
-            // store in it, so the two wait states the hardware needs before the data registers of a
-            // 16-byte store may be overwritten are added by hand.)
-            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(u32x4v{v.x, v.y, v.z, v.w})
-                         : "memory");
-        }
-    }
-}
-
-// ---- The same for accumulators in the instruction's natural orientation (activation fragment as the first
+// Epilogue shared by the fast-path kernels.  Scaled binary16 results go through LDS (free once the K loop has
+// ended on a barrier with no reads outstanding) so that every global store is a full 16 bytes per lane and a
+// wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
+// The accumulators are in the instruction's natural orientation (activation fragment as the first
 // operand): lane l holds one output channel per 32 x 32 tile and, in register r of the tile, token
 // 8 (r / 4) + 4 (l >> 5) + (r & 3).  The kernel assigns the rows of its NI weight fragments so that lane l's
 // channels are NI consecutive ones, NI (l & 31) + ni: with NI = 2 a lane packs two binary16 results of one token
@@ -144,7 +55,7 @@ __device__ __forceinline__ void epilogue_store(ACC (&acc)[4][NI], int8_t* lds, c
 // wave-private piece of LDS behind the staging areas (each lane requests two of its wave's 128 before the last step
 // of the contraction, stores them when the loop is over and reads them back four at a time).  Results are staged
 // token row by token row (a half wave writes 128 or 64 contiguous bytes of one token) and leave as whole 128-byte
-// pieces exactly as above.
+// pieces.
 template <int NI>
 struct EpilogueScalesRows {
     float a_own[2];        // row factors of tokens row0 + lane and row0 + 64 + lane
@@ -224,7 +135,14 @@ __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* l
     auto store16 = [&](int trow, int col, u32x4v v) {
         if (row0 + trow < T && col0 + col < O) {
             uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + col;
-            // written through to memory as a stream (sc1 nt), as in epilogue_store
+            // Y is not read again here and whole 128-byte pieces leave at once: written through to memory
+            // as a stream (sc1 nt).  The GEMM itself does not care, but the memory-side cache is left
+            // without 224 MiB of dirty lines, so the kernel that runs next reads its cold input faster
+            // (64 MiB: 4 us less; of the policies tried -- plain, nt, sc1, sc1 nt, sc0 nt, sc0 sc1 nt --
+            // this one gave the shortest following absmax + quantize calls).
+            // (The compiler offers no way to ask for this policy, hence the assembly; it cannot see a
+            // store in it, so the two wait states the hardware needs before the data registers of a
+            // 16-byte store may be overwritten are added by hand.)
             asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(v) : "memory");
         }
     };
