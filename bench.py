@@ -420,9 +420,12 @@ def main():
         copy_ms = event_ms(lambda: cq.crossquant_calib_copy(big[:half], big[half:]), 10)
         del big
         mf = {}
-        for mode, name in ((0, "zero_operands"), (1, "code_like_operands")):
-            ops_ = cq.crossquant_calib_mfma_i8(2000, mode)
-            ms_ = event_ms(lambda: cq.crossquant_calib_mfma_i8(2000, mode), 5)
+        # mode 2: the code-like operands re-read from LDS every step at the linear kernel's 0.75 KiB per
+        # matrix instruction, two waves per SIMD -- its inner loop without global loads, barriers and epilogue
+        for mode, name, it_ in ((0, "zero_operands", 2000), (1, "code_like_operands", 2000),
+                                (2, "code_like_operands_fed_from_lds", 4000)):
+            ops_ = cq.crossquant_calib_mfma_i8(it_, mode)
+            ms_ = event_ms(lambda: cq.crossquant_calib_mfma_i8(it_, mode), 5)
             mf[name] = ops_ / (ms_ * 1e-3) / 1e12
         achievable = {
             "hbm_read_GBs": (1 << 30) / (read_ms * 1e-3) / 1e9,
@@ -430,6 +433,7 @@ def main():
             "mfma_i8_TOPs": mf,
             "quantizer_frac_of_copy": (quant_gbs / (2 * half / (copy_ms * 1e-3) / 1e9)) if quant_gbs else None,
             "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands"]) if (tops and bits == 8) else None,
+            "w8a8_linear_frac_of_lds_fed_mfma_loop": (tops / mf["code_like_operands_fed_from_lds"]) if (tops and bits == 8) else None,
         }
 
     # The same layer in the paper's W4A4 setting: INT4 codes of the same X and W, multiplied on the

@@ -21,6 +21,10 @@ extern "C" {
  * crossquant_calib_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, non-overlapping.
  * crossquant_calib_mfma_i8: every SIMD issues iters * 16 independent v_mfma_i32_32x32x32_i8 on
  *   operands held in registers; data_mode 0 = all-zero operands, 1 = bell-shaped int8 codes.
+ *   data_mode 2 = the same codes re-read from LDS every step the way the linear layer's inner loop reads
+ *   them (two waves per SIMD, 6 fragment reads per 8 instructions = 0.75 KiB per instruction; iters * 8
+ *   instructions per wave): the ceiling of a kernel with that wave tile, which no global load, barrier
+ *   or epilogue burdens.
  *   *ops (HOST pointer, nullable) receives the number of integer operations of the launch.
  */
 int crossquant_calib_read(const void *src, int64_t bytes, unsigned long long *sink, void *stream);

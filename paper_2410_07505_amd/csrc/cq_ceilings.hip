@@ -90,6 +90,57 @@ calib_mfma_kernel(int iters, int data_mode, int* __restrict__ sink) {
     if (s == 0x7fffffff && sink) sink[0] = s;
 }
 
+// The same, fed the way the GEMM's inner loop is: 8 waves per CU (two per SIMD), every step reads 4 + 2 operand
+// fragments (1 KiB each per wave) from LDS and issues the 8 matrix instructions of a 128 x 64 wave tile, i.e.
+// 0.75 KiB of LDS reads per instruction; no global loads, no barriers, no epilogue.  LDS holds the bell-shaped
+// codes of data_mode 1.  What this loop sustains is the ceiling of any kernel with that wave tile on such data.
+__global__ void __launch_bounds__(512)
+calib_mfma_lds_kernel(int iters, int* __restrict__ sink) {
+    __shared__ __align__(16) int8_t lds[32768];
+    for (int i = threadIdx.x; i < 32768 / 4; i += 512) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t r = calib_hash((uint32_t)i * 4u + c + blockIdx.x * 7919u);
+            const int q = (int)((r & 63) + ((r >> 6) & 63) + ((r >> 12) & 63) + ((r >> 18) & 63)) - 126;
+            w |= (uint32_t)(uint8_t)(int8_t)(q / 3) << (8 * c);
+        }
+        reinterpret_cast<uint32_t*>(lds)[i] = w;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // a fragment = 64 lanes x 16 consecutive bytes (conflict-free); the six fragments of a step are 1 KiB apart
+    const int8_t* p = lds + lane * 16;
+    v16i acc[4][2];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+        const int base = ((it * 5 + wave * 3) & 15) * 1024;        // walks the 32 KiB, stays 6 KiB clear of the end
+        v4i a[4], b[2];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) a[mi] = *reinterpret_cast<const v4i*>(p + base + mi * 1024);
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) b[ni] = *reinterpret_cast<const v4i*>(p + base + (4 + ni) * 1024);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
+    if (s == 0x7fffffff && sink) sink[0] = s;
+}
+
 int calib_blocks() {
     int dev = 0, n_cu = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
@@ -113,6 +164,11 @@ hipError_t launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStrea
 // returns the number of integer operations (2 per multiply-add) the launch performs through *ops
 hipError_t launch_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops, hipStream_t stream) {
     const int blocks = calib_blocks();
+    if (data_mode == 2) {
+        calib_mfma_lds_kernel<<<dim3((unsigned)blocks), dim3(512), 0, stream>>>(iters, sink);
+        if (ops) *ops = (double)blocks * 8.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 32);
+        return hipGetLastError();
+    }
     calib_mfma_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(iters, data_mode, sink);
     if (ops) *ops = (double)blocks * 4.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 32);
     return hipGetLastError();
