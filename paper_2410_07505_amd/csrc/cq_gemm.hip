@@ -240,7 +240,7 @@ template <int NI>
 __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
                                           const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I,
                                           int O, uint16_t* __restrict__ Y, int64_t ldy,
-                                          int32_t* __restrict__ acc_debug, int m0, int n0, int8_t* lds) {
+                                          int32_t* __restrict__ acc_debug, int m0, int n0, int8_t* lds, bool y_cached) {
     constexpr int WN = 4, WTN = 32 * NI;
     constexpr int NLB = 4 * NI;                   // requests a weight-loading wave makes per half tile (8 or 4)
 
@@ -400,7 +400,7 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     k_step(kt, no{}, no{});
 
     epilogue_rows_store<v16i, WTN, NI, 8>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane,
-                                          wave);
+                                          wave, y_cached);
 }
 static_assert(epilogue_rows_lds(8, 64) <= kRingLds, "the epilogue's staging areas reuse the ring's LDS");
 
@@ -412,7 +412,7 @@ __global__ void __launch_bounds__(512)
 gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
                     const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I, int O,
                     uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
-                    int tiles_n, int n_main, int main_blocks) {
+                    int tiles_n, int n_main, int main_blocks, int y_cached) {
     extern __shared__ __align__(16) int8_t lds[];
     const int block = blockIdx.x;
     int tile_m, tile_n;
@@ -421,7 +421,7 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
         const int L = (block % kXcds) * per_xcd + block / kXcds;
         if (L >= n_main) return;
         tile_of_index(L, tiles_m, tiles_n, tile_m, tile_n);
-        ring_tile<2>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN, lds);
+        ring_tile<2>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN, lds, y_cached != 0);
     } else {
         const int n_half = 2 * (tiles_m * tiles_n - n_main);
         const int h_block = block - main_blocks;
@@ -431,7 +431,7 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
         tile_of_index(n_main + h / 2, tiles_m, tiles_n, tile_m, tile_n);
         if (tile_n * BN + (h & 1) * (BN / 2) >= O) return;        // the second half of a tile on the ragged edge may be empty
         ring_tile<1>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN + (h & 1) * (BN / 2),
-                     lds);
+                     lds, y_cached != 0);
     }
 }
 
@@ -470,7 +470,8 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
         const int main_blocks = ((n_main + kXcds - 1) / kXcds) * kXcds;
         const int half_blocks = ((2 * (total - n_main) + kXcds - 1) / kXcds) * kXcds;
         gemm_i8_ring_kernel<<<dim3((unsigned)(main_blocks + half_blocks)), dim3(512), kRingLds, stream>>>(
-            qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n, n_main, main_blocks);
+            qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n, n_main, main_blocks,
+            y_stays_cached(T, O) ? 1 : 0);
     } else {
         static std::atomic<uint64_t> lds_allowed{0};
         e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_i8_kernel<true>), kLdsBytes, lds_allowed);

@@ -172,7 +172,7 @@ __global__ void __launch_bounds__(512)
 gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ row_scale,
                     const uint8_t* __restrict__ qw6, const float* __restrict__ w_scale, int T, int I, int O,
                     uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
-                    int tiles_n) {
+                    int tiles_n, int y_cached) {
     constexpr int WN = 4, WTN = 64, NI = 2;
     extern __shared__ __align__(16) int8_t lds[];
 
@@ -333,7 +333,7 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     // every wave's fragments are in registers and all loads have landed: the ring can be reused
     __syncthreads();
     epilogue_rows_store<v16f, WTN, NI, 8, true>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
-                                                lane, wave);
+                                                lane, wave, y_cached != 0);
 }
 
 }  // namespace
@@ -364,7 +364,7 @@ hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const voi
     if (e != hipSuccess) return e;
     gemm_f6_ring_kernel<<<dim3((unsigned)(per_xcd * kXcds)), dim3(512), kF6Lds, stream>>>(
         static_cast<const uint8_t*>(qx6), row_scale, static_cast<const uint8_t*>(qw6), w_scale, T, I, O, Y, ldy,
-        acc_debug, tiles_m, tiles_n);
+        acc_debug, tiles_m, tiles_n, y_stays_cached(T, O) ? 1 : 0);
     return hipGetLastError();
 }
 
