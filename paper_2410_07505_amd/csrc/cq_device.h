@@ -368,6 +368,66 @@ __device__ __forceinline__ void store_codes_fp6(const float (&m)[8], uint8_t* pa
         *reinterpret_cast<u32x2*>(f + 1024 + flane * 8) = u32x2{hi | (lo1 << 16), (lo1 >> 16) | (hi1 << 16)};
 }
 
+// The same fragments written four rows at a time (rows 4 k .. 4 k + 3 of one matrix, as the streaming kernel
+// works on them): every lane of a quad gets the quad's whole 24-byte record of a row through quad broadcasts
+// (register moves, no LDS), lane 4 g + u keeps the record of row u, and after the four rows each lane stores
+// one 16-byte and one 8-byte piece: a quad writes 64 and 32 contiguous bytes where the row-by-row form writes
+// four scattered 16-byte and 8-byte pieces.
+struct Fp6Batch {
+    uint32_t d[6];      // this lane's row (row & 3 == lane & 3) of the quad's group: 4 + 2 words
+};
+template <int K>
+__device__ __forceinline__ uint32_t quad_lane(uint32_t x) {      // lane K of every quad, in all four lanes
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, K * 0x55, 0xF, 0xF, true);
+}
+// Four INT4 codes (two's-complement bytes, -7 .. 7) -> their four E2M3 patterns packed into 24 bits.  Byte-wise:
+// |q| = (q ^ mask) + sign bit with mask = 0xFF in negative bytes (no carry can cross a byte: |q| <= 7); the E2M3
+// pattern of 0 .. 7 is one lookup in an 8-byte table (v_perm_b32 takes its selector bytes 0 .. 7 from the codes
+// themselves); bit 5 is the sign.  Then the four 6-bit fields are squeezed together in two steps.
+__device__ __forceinline__ uint32_t fp6_fields4(uint32_t w) {
+    const uint32_t s = w & 0x80808080u;
+    const uint32_t ones = s >> 7;
+    const uint32_t mask = s | (s - ones);                               // 0xFF where negative
+    const uint32_t mag = (w ^ mask) + ones;
+    uint32_t e = __builtin_amdgcn_perm(0x1E1C1A18u, 0x14100800u, mag);  // 0 8 16 20 | 24 26 28 30
+    e |= ones << 5;
+    const uint32_t y = (e & 0x003F003Fu) | ((e & 0x3F003F00u) >> 2);    // two 12-bit fields in the half words
+    return (y & 0xFFFu) | ((y >> 4) & 0xFFF000u);
+}
+// row u (0..3) of the batch: the lane's 8 codes as rounding-step values m
+__device__ __forceinline__ void fp6_batch_row(Fp6Batch& out, const float (&m)[8], int u, int lane) {
+    const u32x2 w = pack_codes_i8(m);
+    const uint32_t f0 = fp6_fields4(w.x), f1 = fp6_fields4(w.y);        // 24 bits each
+    const uint32_t lo = f0 | (f1 << 24);
+    const uint32_t hi = f1 >> 8;                                        // 16 bits
+    const uint32_t lo0 = quad_lane<0>(lo), lo1 = quad_lane<1>(lo), lo2 = quad_lane<2>(lo), lo3 = quad_lane<3>(lo);
+    const uint32_t hi0 = quad_lane<0>(hi), hi1 = quad_lane<1>(hi), hi2 = quad_lane<2>(hi), hi3 = quad_lane<3>(hi);
+    const uint32_t d[6] = {lo0, hi0 | (lo1 << 16), (lo1 >> 16) | (hi1 << 16), lo2,
+                           hi2 | (lo3 << 16), (lo3 >> 16) | (hi3 << 16)};
+    const bool mine = (lane & 3) == u;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) out.d[k] = mine ? d[k] : out.d[k];
+}
+// rows row4 .. row4 + 3 (row4 % 4 == 0); rows_ok: bit u set if row row4 + u exists; group_ok: the lane's columns exist.
+// The four rows lie in one row of fragments, which is addressed as a raw buffer (frags_per_row * 1536 bytes).
+__device__ __forceinline__ void fp6_batch_store(const Fp6Batch& out, uint8_t* packed, int row4, int first_col, int lane,
+                                                int frags_per_row, uint32_t rows_ok, bool group_ok) {
+    const int u = lane & 3, g = lane >> 2;
+    const int col = first_col + 32 * g;
+    const int flane = ((row4 + u) & 31) + 32 * ((col >> 5) & 1);
+    const bool ok = group_ok && ((rows_ok >> u) & 1u);
+    const rsrc_t frow = row_buffer(packed + (int64_t)(row4 >> 5) * frags_per_row * 1536, frags_per_row * 1536);
+    // a lane that must not store points past the buffer's end: the hardware's range check drops its stores
+    const int off = ok ? (col >> 6) * 1536 : 0x7FFF0000;
+#ifdef CQ_F6_PLAIN
+    constexpr int policy = 0;
+#else
+    constexpr int policy = kWriteThrough;
+#endif
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4{out.d[0], out.d[1], out.d[2], out.d[3]}, frow, off + flane * 16, 0, policy);
+    __builtin_amdgcn_raw_buffer_store_b64(u32x2{out.d[4], out.d[5]}, frow, off + 1024 + flane * 8, 0, policy);
+}
+
 // dequantized values fl16(fl32(q * fl32(a * b))): 16 bytes at dst
 __device__ __forceinline__ void store_xhat(const float (&q)[8], float a, const float (&b)[8], uint16_t* dst,
                                            bool vec_ok, int nvalid) {

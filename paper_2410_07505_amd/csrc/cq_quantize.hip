@@ -271,6 +271,11 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
     // counts are not added.  The only branch left is the rare exact-division path inside quantize8.
     auto work = [&](const uint4 (&v)[kU], int bi) {
         const int rbase = row0 + batch_at(bi) * kU;
+        Fp6Batch f6;                                        // MODE 3: the batch's four rows leave together
+        if (MODE == 3) {
+#pragma unroll
+            for (int k = 0; k < 6; ++k) f6.d[k] = 0u;
+        }
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int r = rbase + u;
@@ -298,7 +303,7 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
                     __builtin_amdgcn_raw_buffer_store_b32(pack_codes_i4(m),
                                                           row_buffer(codes + (int64_t)rr * (I / 2) + col0 / 2, live / 2),
                                                           lane * 4, 0, kWriteThrough);
-                if (MODE == 3) store_codes_fp6(m, codes, rr, col0, lane, I / 64, lane * 8 < live);
+                if (MODE == 3) fp6_batch_row(f6, m, u, lane);
                 if (XHAT)
                     __builtin_amdgcn_raw_buffer_store_b128(pack_xhat(q, a, b), row_buffer(xhat + (int64_t)rr * I + col0, live * 2),
                                                            lane * 16, 0, kWriteThrough);
@@ -318,6 +323,12 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
             }
             nonzero += row_ok ? nz : 0u;
             __builtin_amdgcn_sched_barrier(0);               // rows one after the other: keeps scalar register pressure down
+        }
+        if (MODE == 3) {
+            static_assert(kU == 4, "a batch is the four rows a quad of lanes shares out");
+            const int left = T - rbase;                      // rows of the batch that exist
+            const uint32_t rows_ok = left >= 4 ? 0xFu : (left > 0 ? (1u << left) - 1u : 0u);
+            fp6_batch_store(f6, codes, rbase, col0, lane, I / 64, rows_ok, lane * 8 < cols_here);
         }
     };
     for (int bi = 0; bi < nb; bi += 2) {
