@@ -251,7 +251,7 @@ hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, in
                                   cap == hipStreamCaptureStatusNone;
         if (plain_stream) {
             static std::mutex mu;
-            static unsigned int reached[kStateSlots];          // what g_cleared[slot] reaches once all launches so far have cleared
+            static unsigned int reached[64][kStateSlots];      // what a device's g_cleared[slot] reaches once all launches so far have cleared
             static unsigned int* counters[64];                 // device address of g_cleared on each device, once known
             int dev = 0;
             hipError_t e = hipGetDevice(&dev);
@@ -263,12 +263,12 @@ hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, in
                 if (e != hipSuccess) return e;
             }
             unsigned int* counter = counters[dev];
-            const unsigned int target = reached[slot] + (unsigned)n_clear;
+            const unsigned int target = reached[dev][slot] + (unsigned)n_clear;
             absmax_stream_kernel<true><<<dim3((unsigned)(n_work + n_clear)), block, 0, stream>>>(
                 X, T, I, ldx, tb, cb, ncc, nb, ncc * nrc, matrix_stride, n_clear, B * T, B * I, counter + slot, target,
                 1u << 22);
             e = hipGetLastError();
-            if (e == hipSuccess) reached[slot] = target;
+            if (e == hipSuccess) reached[dev][slot] = target;
             return e;
         }
         zero_fill_kernel<<<dim3((n_words + 255) / 256), dim3(256), 0, stream>>>(tb, B * T, cb, B * I);
