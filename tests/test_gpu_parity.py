@@ -1257,6 +1257,9 @@ def test_calibration_kernels_run_and_copy_is_exact(cq):
     assert torch.equal(src, dst)
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     assert ops == n_cu * 4 * 10 * 16 * 65536.0
+    ops_lds = cq.crossquant_calib_mfma_i8(10, 2)            # the loop fed from LDS: 8 waves x 8 instructions a step
+    torch.cuda.synchronize()
+    assert ops_lds == n_cu * 8 * 10 * 8 * 65536.0
 
 
 # ----------------------------------------------------------------------------- seeded random shapes
