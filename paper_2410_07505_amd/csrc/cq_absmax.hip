@@ -223,7 +223,9 @@ hipError_t launch_absmax(const uint16_t* X, int B, int T, int I, int64_t ldx, in
     // to it if nbq is even.  Measured in a step, K1 + K3 stages: 4096 x 8192 (nbq 4) 50.4 us with nb 2, 52.2 with
     // nb 3, 53.2 with nb 4; 4096 x 5120 (nbq 3) 37.1 us with nb 3, 39.5 with nb 2 or 4.  Large odd nbq would make
     // blocks too big for this kernel's own good: nb 3 then.  A wave wants at least two batches to have loads in
-    // flight while it reduces (4096 x 4096, nbq 2: this kernel 12.6 us with nb 1, 10.8 with nb 2).  Huge inputs take more rows per block, to bound the
+    // flight while it reduces (4096 x 4096, nbq 2: this kernel 12.6 us with nb 1, 10.8 with nb 2).  Four waves
+    // per block is the optimum as well: 4096 x 8192 takes 23.6, 17.3, 15.8, 18.3 and 18.5 us as a stage with 1, 2,
+    // 4, 8 and 16 waves (more blocks mean more column atomics, larger blocks turn over too slowly).  Huge inputs take more rows per block, to bound the
     // number of column atomics.
     auto n_blocks_for = [&](int n) { return (int64_t)B * ncc * ((T + 32 * n - 1) / (32 * n)); };
     const int nbq = quantize_batches_per_wave((int64_t)B * ncc, T);
