@@ -473,6 +473,51 @@ def main():
         cq.crossquant_w8a8_linear(wl.codes, wl.a, wl.qw, wl.ws, Y=wl.Y)      # leave Y as the W8A8 result
 
     inside = wl.inside_gemm() if extras else None
+
+    # ---- the calls built beyond the four named ones, on the headline shapes (medians of event intervals, the
+    # calls back to back): the kernel-size analysis, weight preparation per channel and per group of 128, and the
+    # batched form on 32 sequences of 128 tokens.  GB/s are algorithmic bytes over the call's time.
+    next_rows = None
+    if extras and bits == 8:
+        reps = max(args.steps // 4, 3)
+        xrk = torch.empty_like(wl.xhat)
+        cnt3 = torch.empty(3, dtype=torch.int64, device=dev)
+        an = lambda: cq.crossquant_kernel_analysis(wl.Xg, wl.t, wl.c, alpha, bits, xrk=xrk, counters=cnt3,
+                                                   work_vectors=False)
+        event_ms(an, 3)
+        an_ms = event_ms(an, reps)
+        del xrk
+        Wg = torch.from_numpy(wl.W).to(dev)
+        wq = lambda: cq.crossquant_weight_quantize(Wg, wl.b, bits, qw=wl.qw, w_scale=wl.ws)
+        event_ms(wq, 2)
+        wq_ms = event_ms(wq, max(reps // 4, 3))
+        gs = torch.empty((O, I // 128), dtype=torch.float32, device=dev)
+        qg = torch.empty_like(wl.qw)
+        wg = lambda: cq.crossquant_weight_quantize_grouped(Wg, wl.b, 128, 4, qw=qg, w_scale=gs)
+        event_ms(wg, 2)
+        wg_ms = event_ms(wg, max(reps // 4, 3))
+        del qg, gs
+        wq()                                                    # wl.qw / wl.ws as the step expects them
+        del Wg
+        Bq, Sq = 32, 128
+        X3 = wl.Xg[:Bq * Sq].view(Bq, Sq, I)
+        def batched():
+            t3, c3 = cq.crossquant_absmax_batched(X3)
+            return cq.crossquant_quantize_batched(X3, t3, c3, alpha, bits)
+        event_ms(batched, 3)
+        b_ms = event_ms(batched, reps)
+        nb3 = Bq * Sq * I
+        next_rows = {
+            "kernel_analysis": {"what": "Remove-Kernel matrix + the three indicator counts, one call", "ms": an_ms,
+                                "GBs": 4 * n / (an_ms * 1e-3) / 1e9},
+            "weight_quantize": {"what": "per-output-channel INT8 codes of diag(b) W (%d x %d)" % (I, O), "ms": wq_ms,
+                                "GBs_3_bytes_per_weight": 3.0 * I * O / (wq_ms * 1e-3) / 1e9},
+            "weight_quantize_grouped": {"what": "INT4 codes with one step per group of 128 input channels", "ms": wg_ms,
+                                        "GBs_3_bytes_per_weight": 3.0 * I * O / (wg_ms * 1e-3) / 1e9},
+            "batched_absmax_quantize": {"what": "[%d][%d][%d] tensor, per-sequence column maxima, two calls incl. their "
+                                                "output allocation" % (Bq, Sq, I), "ms": b_ms,
+                                        "GBs": 7.0 * nb3 / (b_ms * 1e-3) / 1e9},
+        }
     if extras:
         wl.step()                            # leave every buffer as the step writes it
 
@@ -524,6 +569,7 @@ def main():
         "achievable": achievable,
         "vendor_int8_gemm": vendor,
         "quantize_inside_gemm": inside,
+        "next_rows": next_rows,
         "a4w4_linear": a4w4,
         "roofline": {"kernel": ("gemm_i8_ring_kernel (W8A8 linear)" if bits == 8 else
                                 "gemm_f6_ring_kernel (A4W4 linear)"),
