@@ -366,12 +366,28 @@ def main():
     # but kernels is on the stream; `value` keeps the event-bracketed definition.
     event_free = None
     if extras:
-        w_all = wl.wall_ms_per_step(args.steps, 3, STAGES)
-        w_rest = wl.wall_ms_per_step(args.steps, 3, ("count", "linear"))
-        # the second loop leaves t, c, a, b, codes as the first one wrote them, so the count and the
-        # linear layer see the same operands
-        d_ms = w_all - w_rest
+        # The linear layer's time drifts by a per cent or two over seconds (it is limited by power), which is as
+        # much as the two quantizer calls take: the two loops therefore alternate in short runs, and the figure
+        # is the median of the per-round differences.  (The second loop leaves t, c, a, b, codes as the first
+        # one wrote them, so the count and the linear layer see the same operands.)
+        # Three loops: all stages; without quantize (the count still follows absmax and reads X from the
+        # memory-side cache, as in the full step, so the difference is the quantize call alone); without absmax and
+        # quantize (here the count reads X cold, which lengthens this loop by a few microseconds: the difference to
+        # the full step understates the two calls by that much).
+        import statistics
+        rounds = 8
+        per_round = max(args.steps // rounds, 5)
+        alls, no_q, rests = [], [], []
+        for _ in range(rounds):
+            alls.append(wl.wall_ms_per_step(per_round, 2, STAGES))
+            no_q.append(wl.wall_ms_per_step(per_round, 2, ("absmax", "count", "linear")))
+            rests.append(wl.wall_ms_per_step(per_round, 2, ("count", "linear")))
+        w_all, w_rest = statistics.median(alls), statistics.median(rests)
+        d_ms = statistics.median([x - y for x, y in zip(alls, rests)])
+        q_ms = statistics.median([x - y for x, y in zip(alls, no_q)])
         event_free = {"ms_per_step_all_stages": w_all, "ms_per_step_without_absmax_quantize": w_rest,
+                      "rounds": rounds, "steps_per_round": per_round,
+                      "quantize_ms": q_ms,
                       "absmax_plus_quantize_ms": d_ms,
                       "quantizer_GBs": (f["bytes_absmax"] + f["bytes_quant"]) / (d_ms * 1e-3) / 1e9 if d_ms > 0 else None,
                       "with_events_ms_per_step": ms_per_step,
