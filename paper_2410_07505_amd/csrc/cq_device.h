@@ -369,16 +369,32 @@ __device__ __forceinline__ void store_codes_fp6(const float (&m)[8], uint8_t* pa
 }
 
 // The same fragments written four rows at a time (rows 4 k .. 4 k + 3 of one matrix, as the streaming kernel
-// works on them): every lane of a quad gets the quad's whole 24-byte record of a row through quad broadcasts
-// (register moves, no LDS), lane 4 g + u keeps the record of row u, and after the four rows each lane stores
-// one 16-byte and one 8-byte piece: a quad writes 64 and 32 contiguous bytes where the row-by-row form writes
-// four scattered 16-byte and 8-byte pieces.
+// works on them): a lane keeps its 48 bits of each of the four rows, then the quad transposes them (two
+// exchange steps of quad-permute register moves, no LDS) so that lane 4 g + u holds the whole 24-byte record of
+// row u, and each lane stores one 16-byte and one 8-byte piece: a quad writes 64 and 32 contiguous bytes where
+// the row-by-row form writes four scattered 16-byte and 8-byte pieces.
 struct Fp6Batch {
-    uint32_t d[6];      // this lane's row (row & 3 == lane & 3) of the quad's group: 4 + 2 words
+    uint32_t lo[4], hi[4];      // this lane's fields of rows 0 .. 3: 32 + 16 bits each
 };
-template <int K>
-__device__ __forceinline__ uint32_t quad_lane(uint32_t x) {      // lane K of every quad, in all four lanes
-    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, K * 0x55, 0xF, 0xF, true);
+template <int CTRL>
+__device__ __forceinline__ uint32_t quad_permute(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, CTRL, 0xF, 0xF, true);
+}
+// r[k] = this lane's value of row k  ->  r[k] = the value lane k of the quad had for row (lane & 3)
+__device__ __forceinline__ void quad_transpose(uint32_t (&r)[4], int lane) {
+    const bool odd = lane & 1, up = lane & 2;
+    // neighbours exchange: an even lane ends up with rows 0 and 2 of both lanes, an odd lane with rows 1 and 3
+    const uint32_t g01 = quad_permute<0xB1>(odd ? r[0] : r[1]);         // lanes 1 0 3 2
+    const uint32_t g23 = quad_permute<0xB1>(odd ? r[2] : r[3]);
+    const uint32_t a01 = odd ? g01 : r[0], b01 = odd ? r[1] : g01;
+    const uint32_t a23 = odd ? g23 : r[2], b23 = odd ? r[3] : g23;
+    // pairs exchange: lanes 0, 1 give away their rows 2, 3 and lanes 2, 3 their rows 0, 1
+    const uint32_t ga = quad_permute<0x4E>(up ? a01 : a23);             // lanes 2 3 0 1
+    const uint32_t gb = quad_permute<0x4E>(up ? b01 : b23);
+    r[0] = up ? ga : a01;
+    r[1] = up ? gb : b01;
+    r[2] = up ? a23 : ga;
+    r[3] = up ? b23 : gb;
 }
 // Four INT4 codes (two's-complement bytes, -7 .. 7) -> their four E2M3 patterns packed into 24 bits.  Byte-wise:
 // |q| = (q ^ mask) + sign bit with mask = 0xFF in negative bytes (no carry can cross a byte: |q| <= 7); the E2M3
@@ -395,23 +411,22 @@ __device__ __forceinline__ uint32_t fp6_fields4(uint32_t w) {
     return (y & 0xFFFu) | ((y >> 4) & 0xFFF000u);
 }
 // row u (0..3) of the batch: the lane's 8 codes as rounding-step values m
-__device__ __forceinline__ void fp6_batch_row(Fp6Batch& out, const float (&m)[8], int u, int lane) {
+__device__ __forceinline__ void fp6_batch_row(Fp6Batch& out, const float (&m)[8], int u) {
     const u32x2 w = pack_codes_i8(m);
     const uint32_t f0 = fp6_fields4(w.x), f1 = fp6_fields4(w.y);        // 24 bits each
-    const uint32_t lo = f0 | (f1 << 24);
-    const uint32_t hi = f1 >> 8;                                        // 16 bits
-    const uint32_t lo0 = quad_lane<0>(lo), lo1 = quad_lane<1>(lo), lo2 = quad_lane<2>(lo), lo3 = quad_lane<3>(lo);
-    const uint32_t hi0 = quad_lane<0>(hi), hi1 = quad_lane<1>(hi), hi2 = quad_lane<2>(hi), hi3 = quad_lane<3>(hi);
-    const uint32_t d[6] = {lo0, hi0 | (lo1 << 16), (lo1 >> 16) | (hi1 << 16), lo2,
-                           hi2 | (lo3 << 16), (lo3 >> 16) | (hi3 << 16)};
-    const bool mine = (lane & 3) == u;
-#pragma unroll
-    for (int k = 0; k < 6; ++k) out.d[k] = mine ? d[k] : out.d[k];
+    out.lo[u] = f0 | (f1 << 24);
+    out.hi[u] = f1 >> 8;                                                // 16 bits
 }
 // rows row4 .. row4 + 3 (row4 % 4 == 0); rows_ok: bit u set if row row4 + u exists; group_ok: the lane's columns exist.
 // The four rows lie in one row of fragments, which is addressed as a raw buffer (frags_per_row * 1536 bytes).
-__device__ __forceinline__ void fp6_batch_store(const Fp6Batch& out, uint8_t* packed, int row4, int first_col, int lane,
+// Must be called by the whole wave (the transposition exchanges registers between lanes).
+__device__ __forceinline__ void fp6_batch_store(Fp6Batch& out, uint8_t* packed, int row4, int first_col, int lane,
                                                 int frags_per_row, uint32_t rows_ok, bool group_ok) {
+    quad_transpose(out.lo, lane);
+    quad_transpose(out.hi, lane);
+    // the group's 192-bit record of this lane's row: four lanes' 32 + 16 bits one after the other
+    const uint32_t d1 = out.hi[0] | (out.lo[1] << 16), d2 = (out.lo[1] >> 16) | (out.hi[1] << 16);
+    const uint32_t d4 = out.hi[2] | (out.lo[3] << 16), d5 = (out.lo[3] >> 16) | (out.hi[3] << 16);
     const int u = lane & 3, g = lane >> 2;
     const int col = first_col + 32 * g;
     const int flane = ((row4 + u) & 31) + 32 * ((col >> 5) & 1);
@@ -419,13 +434,8 @@ __device__ __forceinline__ void fp6_batch_store(const Fp6Batch& out, uint8_t* pa
     const rsrc_t frow = row_buffer(packed + (int64_t)(row4 >> 5) * frags_per_row * 1536, frags_per_row * 1536);
     // a lane that must not store points past the buffer's end: the hardware's range check drops its stores
     const int off = ok ? (col >> 6) * 1536 : 0x7FFF0000;
-#ifdef CQ_F6_PLAIN
-    constexpr int policy = 0;
-#else
-    constexpr int policy = kWriteThrough;
-#endif
-    __builtin_amdgcn_raw_buffer_store_b128(u32x4{out.d[0], out.d[1], out.d[2], out.d[3]}, frow, off + flane * 16, 0, policy);
-    __builtin_amdgcn_raw_buffer_store_b64(u32x2{out.d[4], out.d[5]}, frow, off + 1024 + flane * 8, 0, policy);
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4{out.lo[0], d1, d2, out.lo[2]}, frow, off + flane * 16, 0, kWriteThrough);
+    __builtin_amdgcn_raw_buffer_store_b64(u32x2{d4, d5}, frow, off + 1024 + flane * 8, 0, kWriteThrough);
 }
 
 // dequantized values fl16(fl32(q * fl32(a * b))): 16 bytes at dst

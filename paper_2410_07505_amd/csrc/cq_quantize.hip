@@ -313,7 +313,7 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
         Fp6Batch f6;                                        // MODE 3: the batch's four rows leave together
         if (MODE == 3) {
 #pragma unroll
-            for (int k = 0; k < 6; ++k) f6.d[k] = 0u;
+            for (int k = 0; k < 4; ++k) f6.lo[k] = f6.hi[k] = 0u;
         }
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
@@ -342,7 +342,7 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
                     __builtin_amdgcn_raw_buffer_store_b32(pack_codes_i4(m),
                                                           row_buffer(codes + (int64_t)rr * (I / 2) + col0 / 2, live / 2),
                                                           lane * 4, 0, kWriteThrough);
-                if (MODE == 3) fp6_batch_row(f6, m, u, lane);
+                if (MODE == 3) fp6_batch_row(f6, m, u);
                 if (XHAT)
                     __builtin_amdgcn_raw_buffer_store_b128(pack_xhat(q, a, b), row_buffer(xhat + (int64_t)rr * I + col0, live * 2),
                                                            lane * 16, 0, kWriteThrough);
