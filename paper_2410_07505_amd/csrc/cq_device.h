@@ -118,12 +118,6 @@ __device__ __forceinline__ float safe_rcp(float v) { return (v == 0.0f) ? 0.0f :
 
 __device__ __forceinline__ float half_lo(uint32_t w) { return h2f(w & 0xFFFFu); }
 __device__ __forceinline__ float half_hi(uint32_t w) { return h2f(w >> 16); }
-// two binary32 values -> packed binary16 pair, each rounded to nearest even (one v_cvt_pk_f16_f32)
-__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
-}
 
 // Output stores of the streaming kernels: written through to memory at device scope (sc1) instead
 // of being left dirty in the caches.  Measured on the 4096 x 8192 layer against plain and

@@ -112,16 +112,15 @@ __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* l
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int t_loc = mi * 32 + 8 * g + 4 * frag_half + j;
-                uint32_t h[NI];
+                float y[NI];
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
-                    float y = (float)acc[mi][ni][4 * g + j] * av[j];
-                    y = rounded_f32(y * sc.s[ni]);
-                    h[ni] = f2h(y);
+                    y[ni] = (float)acc[mi][ni][4 * g + j] * av[j];
+                    y[ni] = rounded_f32(y[ni] * sc.s[ni]);
                 }
                 int8_t* dst = stage + t_loc * kRowPitch + (SPLIT ? ch * 4 : o_loc * 2);
-                if (NI == 2) *reinterpret_cast<uint32_t*>(dst) = h[0] | (h[NI - 1] << 16);
-                else *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h[0];
+                if (NI == 2) *reinterpret_cast<uint32_t*>(dst) = pack_half2(y[0], y[NI - 1]);   // one conversion for the pair
+                else *reinterpret_cast<uint16_t*>(dst) = (uint16_t)f2h(y[0]);
                 if (acc_debug && row0 + t_loc < T && o_ok) {
                     int32_t* d = acc_debug + (int64_t)(row0 + t_loc) * O + col0 + o_loc;
                     if (SPLIT) {

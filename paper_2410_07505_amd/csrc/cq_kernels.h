@@ -16,6 +16,13 @@ __device__ __forceinline__ uint32_t f2h(float f) {
     return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);
 }
 
+// two binary32 values -> packed binary16 pair, each rounded to nearest even (one v_cvt_pk_f16_f32)
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
+}
+
 // A binary32 value that must be rounded on its own before it is converted to binary16: passing
 // it through an empty asm keeps the compiler from folding the multiply that produced it into a
 // mixed-precision multiply-convert, which would round once where the specification rounds twice.
