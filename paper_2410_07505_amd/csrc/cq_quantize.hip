@@ -4,6 +4,9 @@
 // The element-wise step is D_ij = fl32(a_i * b_j) with a_i = t_i^alpha / q_max and
 // b_j = c_j^(1-alpha); the code is q_ij = clamp(rne(fl32(x_ij / D_ij)), +-q_max).
 //
+// Two kernels: quantize_stream_kernel for the layout every real activation has (aligned, I % 8 == 0), and
+// quantize_kernel, its older form with per-lane bounds handling, for everything else.
+//
 // The kernel moves 2 B read + 1 or 0.5 B codes + optionally 2 B dequantized per element, and on this
 // part it is the vector-instruction count per element that decides whether it keeps up with that
 // (packed binary32 arithmetic is not used), so the per-element work is kept small.  A correctly
