@@ -186,31 +186,40 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
 //   wait for the next tile, barrier ; read slab0 of the next tile | mfma slab3.
 // ---------------------------------------------------------------------------------------------
 
-// a_off / b_off: byte offset of this lane's row and swizzled chunk for slab 0; slab ks flips the
-// chunk's bits 1-2, i.e. XORs the byte offset with ks * 32
-// (weight fragment ni of a wave holds the rows NI fr + ni of the wave's 32 NI rows, fr = the lane's fragment row:
-// fragments are one LDS row apart, and a lane ends up with NI consecutive output channels)
-template <int NI>
-__device__ __forceinline__ void load_frags(v4i (&af)[4], v4i (&bf)[NI], const int8_t* As, const int8_t* Bs,
-                                           int a_off, int b_off, int b_flip, int ks) {
+// Fragments of the 16 x 16 x 64 instruction: a lane supplies 16 consecutive bytes of row (lane & 15), K chunk
+// lane >> 4 of the 64-byte slab (which K positions those are inside the instruction does not matter for an integer
+// dot product, as long as both operands are read the same way).  A K step of 128 bytes is two slabs; a slab is
+// worked on in two phases of 4 activation tiles each, so that only 4 + G fragments have to be held ahead.
+// a_off / b_off: byte offset of this lane's row and swizzled chunk for slab 0; slab 1 flips bit 2 of the chunk,
+// i.e. XORs the byte offset with 64.  Activation tile mi is 16 LDS rows further on.  Weight tile ni of a wave holds
+// the channels G fr + ni (fr = lane & 15), so that a lane ends up with G consecutive output channels; in LDS those
+// rows sit at G fr + (ni ^ (fr & 1)) (see the loader): b_off is tile 0's offset, b_flip the step to tile 1, and
+// tiles 2, 3 are two rows further on.
+__device__ __forceinline__ void load_a4(v4i (&af)[4], const int8_t* As, int a_off, int half, int slab) {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) af[mi] = *reinterpret_cast<const v4i*>(As + mi * 32 * BK + (a_off ^ (ks * 32)));
+    for (int mi = 0; mi < 4; ++mi)
+        af[mi] = *reinterpret_cast<const v4i*>(As + (4 * half + mi) * 16 * BK + (a_off ^ (slab * 64)));
+}
+template <int G>
+__device__ __forceinline__ void load_b(v4i (&bf)[G], const int8_t* Bs, int b_off, int b_flip, int slab) {
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bf[ni] = *reinterpret_cast<const v4i*>(Bs + ni * b_flip + (b_off ^ (ks * 32)));
+    for (int ni = 0; ni < G; ++ni)
+        bf[ni] = *reinterpret_cast<const v4i*>(Bs + (ni >> 1) * 2 * BK + (ni & 1) * b_flip + (b_off ^ (slab * 64)));
 }
 
 // The activation fragment is the first MFMA operand.  With the weight fragment first the accumulator tile comes
-// out transposed (a lane holds 4 consecutive channels of one token per register group, which makes for a simpler
-// epilogue), but the kernel runs 4.6 % slower on the 70B-shaped layer (720 -> 687 us, 4 % on the 7B-shaped one, 1 %
-// on the heavy-tailed 13B-shaped one): which operand the smaller codes travel on changes what the matrix
-// instruction draws, and this kernel is limited by power.
-template <int NI>
-__device__ __forceinline__ void mfma_slab(v16i (&acc)[4][NI], const v4i (&af)[4], const v4i (&bf)[NI]) {
+// out transposed, but the kernel runs 4.6 % slower on the 70B-shaped layer (720 -> 687 us, 4 % on the 7B-shaped one,
+// 1 % on the heavy-tailed 13B-shaped one): which operand the smaller codes travel on changes what the matrix
+// instruction draws, and this kernel is limited by power.  For the same reason the instruction is the 16 x 16 x 64
+// one: it reads and writes half as many accumulator registers per multiply-add as 32 x 32 x 32, and a loop fed
+// from LDS at this kernel's ratio sustains 9 % more with it on code-like operands (3.13-3.22 against 2.87-2.95 POP/s).
+template <int G>
+__device__ __forceinline__ void mfma_phase(v4i (&acc)[8][G], int half, const v4i (&af)[4], const v4i (&bf)[G]) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < G; ++ni)
+            acc[4 * half + mi][ni] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[mi], bf[ni], acc[4 * half + mi][ni], 0, 0, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -242,6 +251,7 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
                                           int O, uint16_t* __restrict__ Y, int64_t ldy,
                                           int32_t* __restrict__ acc_debug, int m0, int n0, int8_t* lds, bool y_cached) {
     constexpr int WN = 4, WTN = 32 * NI;
+    constexpr int G = 2 * NI, LOG2G = NI;         // weight tiles of 16 channels per wave (4 or 2)
     constexpr int NLB = 4 * NI;                   // requests a weight-loading wave makes per half tile (8 or 4)
 
     const int tid = threadIdx.x;
@@ -265,16 +275,16 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         const int first = b_loader ? n0 : m0, last = (b_loader ? O : T) - 1;
         // LDS row R of an operand tile holds, for activations, tile row R with chunk c at c ^ ((R >> 1) & 7): a
         // fragment's 16 lanes per LDS cycle read 16 consecutive rows, whose parity picks the half of the 64 banks
-        // and whose (R >> 1) & 7 picks the 16-byte group.  Weight fragment ni takes the tile rows NI fr + ni (see
-        // b_off); for NI = 2 those are all even or all odd, so LDS row R holds tile row R ^ ((R >> 1) & 1) (the two
-        // rows of a pair change places in every other pair) and the swizzle term comes from R >> 2: a lane then
-        // reads LDS row 2 fr + (ni ^ (fr & 1)), parity and group exactly as for the activation fragment.
-        const int sw_shift = b_loader ? NI : 1;
+        // and whose (R >> 1) & 7 picks the 16-byte group.  Weight tile ni takes the tile rows G fr + ni (see
+        // b_off), which for one ni all have the same parity; so LDS row R holds tile row R ^ ((R / G) & 1) (the
+        // rows of a pair change places in every other group of G) and the swizzle term comes from R / (2 G): a lane
+        // then reads LDS row G fr + (ni ^ (fr & 1)), parity and group exactly as for the activation fragment.
+        const int sw_shift = b_loader ? LOG2G + 1 : 1;
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
             const int R = rows_per_loader * lw + 8 * ii + ld_r;
             const int c = ld_p ^ ((R >> sw_shift) & 7);
-            const int tile_row = (b_loader && NI == 2) ? (R ^ ((R >> 1) & 1)) : R;
+            const int tile_row = b_loader ? (R ^ ((R >> LOG2G) & 1)) : R;
             gsrc[ii] = base + (int64_t)min(first + tile_row, last) * I + c * 16;
         }
     }
@@ -294,22 +304,22 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         else __builtin_amdgcn_s_waitcnt(waitcnt_imm(NLB, 15));
     };
 
-    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int frag_row = lane & 15, frag_chunk = lane >> 4;
     const int sw = (frag_row >> 1) & 7;
-    const int a_off = (wm * 128 + frag_row) * BK + ((frag_half ^ sw) * 16);
-    // weight fragment ni: tile row wn * WTN + NI * frag_row + ni, which for NI = 2 sits in LDS row
-    // wn * WTN + 2 frag_row + (ni ^ (frag_row & 1)); b_off is fragment 0's offset, b_flip the step to fragment 1
-    const int b_par = (NI == 2) ? (frag_row & 1) : 0;
-    const int b_off = (wn * WTN + NI * frag_row + b_par) * BK + ((frag_half ^ sw) * 16);
+    const int a_off = (wm * 128 + frag_row) * BK + ((frag_chunk ^ sw) * 16);
+    // weight tile ni: channel wn * WTN + G * frag_row + ni, which sits in LDS row
+    // wn * WTN + G * frag_row + (ni ^ (frag_row & 1)); b_off is tile 0's offset, b_flip the step to tile 1
+    const int b_par = frag_row & 1;
+    const int b_off = (wn * WTN + G * frag_row + b_par) * BK + ((frag_chunk ^ sw) * 16);
     const int b_flip = b_par ? -BK : BK;
 
-    v16i acc[4][NI];
+    v4i acc[8][G];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int ni = 0; ni < G; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0;
+            for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0;
 
     // prologue: A0 A1 (waves 0-3) / B0 B1 (waves 4-7); half tile n -> slot n % 5
     issue_half(0, b_loader ? 1 : 0);
@@ -322,36 +332,45 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     int sa = 0, sb = 1;
     auto adv = [](int v) { v += 2; return v >= kRingSlots ? v - kRingSlots : v; };
 
-    v4i af0[4], bf0[NI], af1[4], bf1[NI];
-    load_frags<NI>(af0, bf0, lds + sa * kSlotBytes, lds + sb * kSlotBytes, a_off, b_off, b_flip, 0);
+    // fragment registers: two sets of 4 activation tiles (the two halves of a slab alternate), two sets of G weight tiles
+    v4i a_lo[4], a_hi[4], b0[G], b1[G];
+    load_a4(a_lo, lds + sa * kSlotBytes, a_off, 0, 0);
+    load_b<G>(b0, lds + sb * kSlotBytes, b_off, b_flip, 0);
 
-    constexpr int NMF = 4 * NI, NRD = 4 + NI;
-    auto interleave_reads = [&]() {
+    constexpr int NMF = 4 * G;                     // matrix instructions of a phase
+    auto interleave_reads = [&](auto n_reads) {
+        constexpr int NRD = decltype(n_reads)::value;
 #pragma unroll
         for (int i = 0; i < NRD; ++i) {
-            // an MFMA first (its operands were read a slab ago), then one read of the next slab:
-            // the reads are all out before the slab's last MFMAs, which cover their latency
+            // an MFMA first (its operands were read a phase ago), then one read for the next phase:
+            // the reads are all out before the phase's last MFMAs, which cover their latency
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
+    using rd_a = std::integral_constant<int, 4>;
+    using rd_ab = std::integral_constant<int, 4 + G>;
+    using rd_none = std::integral_constant<int, 0>;
     auto k_step = [&](int kt, auto issue_c, auto prefetch_c) {
         constexpr bool ISSUE = decltype(issue_c)::value;        // kt + 2 < nk
         constexpr bool PREFETCH = decltype(prefetch_c)::value;  // kt + 1 < nk
         const int8_t* As = lds + sa * kSlotBytes;
         const int8_t* Bs = lds + sb * kSlotBytes;
         const int na = adv(sa), nb = adv(sb);                   // slots of tile kt+1
-        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, b_flip, 1);
-        mfma_slab<NI>(acc, af0, bf0);
-        interleave_reads();
-        load_frags<NI>(af0, bf0, As, Bs, a_off, b_off, b_flip, 2);
-        mfma_slab<NI>(acc, af1, bf1);
-        interleave_reads();
-        load_frags<NI>(af1, bf1, As, Bs, a_off, b_off, b_flip, 3);
-        mfma_slab<NI>(acc, af0, bf0);
-        interleave_reads();
+        // slab 0: activation tiles 0-3, then 4-7
+        load_a4(a_hi, As, a_off, 1, 0);
+        mfma_phase<G>(acc, 0, a_lo, b0);
+        interleave_reads(rd_a{});
+        load_a4(a_lo, As, a_off, 0, 1);
+        load_b<G>(b1, Bs, b_off, b_flip, 1);
+        mfma_phase<G>(acc, 1, a_hi, b0);
+        interleave_reads(rd_ab{});
+        // slab 1
+        load_a4(a_hi, As, a_off, 1, 1);
+        mfma_phase<G>(acc, 0, a_lo, b1);
+        interleave_reads(rd_a{});
         // A loaders: A(kt+2) = half tile 2kt+4 -> slot (2kt+4) % 5 = adv(na); its previous tenant
         // B(kt-1) was released at the previous barrier.  Then tile kt+1's A (requested a step ago)
         // must have landed: at most the 8 requests just made may still be in flight.
@@ -372,17 +391,16 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         // B loaders: B(kt+2) = half tile 2kt+5 -> slot (2kt+5) % 5 = sa, tile kt's A slot, which
-        // nobody reads any more (slab 3's fragments are in registers)
+        // nobody reads any more (the last phase's fragments are in registers)
         if (b_loader && ISSUE) issue_half(kt + 2, sa);
         __builtin_amdgcn_sched_barrier(0);
-        if (PREFETCH) load_frags<NI>(af0, bf0, lds + na * kSlotBytes, lds + nb * kSlotBytes, a_off, b_off, b_flip, 0);
-        mfma_slab<NI>(acc, af1, bf1);
-#pragma unroll
-        for (int i = 0; i < NMF; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (PREFETCH && i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (PREFETCH) {
+            load_a4(a_lo, lds + na * kSlotBytes, a_off, 0, 0);
+            load_b<G>(b0, lds + nb * kSlotBytes, b_off, b_flip, 0);
         }
-        __builtin_amdgcn_sched_barrier(0);
+        mfma_phase<G>(acc, 1, a_hi, b1);
+        if (PREFETCH) interleave_reads(rd_ab{});
+        else interleave_reads(rd_none{});
         sa = na;
         sb = nb;
     };
@@ -394,13 +412,13 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         k_step(kt, no{}, yes{});
         ++kt;
     }
-    EpilogueScalesRows<NI> scales;
-    epilogue_rows_load_scales<NI>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    EpilogueScales16<G> scales;
+    epilogue16_load_scales<G>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
     __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{});
 
-    epilogue_rows_store<v16i, WTN, NI, 8>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane,
-                                          wave, y_cached);
+    epilogue16_store<WTN, G, 8>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane, wave,
+                                y_cached);
 }
 static_assert(epilogue_rows_lds(8, 64) <= kRingLds, "the epilogue's staging areas reuse the ring's LDS");
 

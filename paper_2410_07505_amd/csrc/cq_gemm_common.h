@@ -84,6 +84,57 @@ constexpr int epilogue_rows_pitch(int wtn) { return wtn * 2 + 16; }   // bytes p
 // LDS the epilogue needs for n_waves waves of 128 x wtn outputs: staging areas, then 512 bytes of row factors per wave
 constexpr int epilogue_rows_lds(int n_waves, int wtn) { return n_waves * (128 * epilogue_rows_pitch(wtn) + 512); }
 
+// Second half of the epilogue: a wave reads its staged rows back and stores them as whole 16-byte pieces.
+template <int WTN, bool SPLIT>
+__device__ __forceinline__ void epilogue_rows_flush(const int8_t* stage, uint16_t* __restrict__ Y, int64_t ldy, int T, int O,
+                                                    int row0, int col0, int lane, bool y_cached) {
+    constexpr int kRowPitch = epilogue_rows_pitch(WTN);
+    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+    auto store16 = [&](int trow, int col, u32x4v v) {
+        if (row0 + trow < T && col0 + col < O) {
+            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + col;
+            // Y is not read again here and whole 128-byte pieces leave at once: written through to memory
+            // as a stream (sc1 nt).  The GEMM itself does not care, but the memory-side cache is left
+            // without 224 MiB of dirty lines, so the kernel that runs next reads its cold input faster
+            // (64 MiB: 4 us less; of the policies tried -- plain, nt, sc1, sc1 nt, sc0 nt, sc0 sc1 nt --
+            // this one gave the shortest following absmax + quantize calls).
+            // (The compiler offers no way to ask for this policy, hence the assembly; it cannot see a
+            // store in it, so the two wait states the hardware needs before the data registers of a
+            // 16-byte store may be overwritten are added by hand.)
+            // A small Y (see y_stays_cached) fits the memory-side cache next to everything else of its layer: plain
+            // stores then, which make the kernel itself 2-3 % faster on such layers and change nothing after it.
+            if (y_cached) *reinterpret_cast<u32x4v*>(dst) = v;
+            else asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(v) : "memory");
+        }
+    };
+    if (SPLIT) {
+        // a lane takes 8 words of a row (channels 8 p .. 8 p + 7 in the low halves, 32 + 8 p .. in the high halves)
+        // and stores them as two 16-byte pieces
+        const int p = lane & 3, rsub = lane >> 2;
+#pragma unroll
+        for (int i = 0; i < 128 / 16; ++i) {
+            const int trow = i * 16 + rsub;
+            const uint4 w0 = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + p * 32);
+            const uint4 w1 = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + p * 32 + 16);
+            auto lows = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); };
+            auto highs = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); };
+            store16(trow, 8 * p, u32x4v{lows(w0.x, w0.y), lows(w0.z, w0.w), lows(w1.x, w1.y), lows(w1.z, w1.w)});
+            store16(trow, 32 + 8 * p, u32x4v{highs(w0.x, w0.y), highs(w0.z, w0.w), highs(w1.x, w1.y), highs(w1.z, w1.w)});
+        }
+    } else {
+        constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 4)
+        constexpr int kRowsPerInst = 64 / kLanesPerRow;
+        const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+#pragma unroll
+        for (int i = 0; i < 128 / kRowsPerInst; ++i) {
+            const int trow = i * kRowsPerInst + rsub;
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
+            store16(trow, piece * 8, u32x4v{v.x, v.y, v.z, v.w});
+        }
+    }
+}
+
 template <typename ACC, int WTN, int NI, int NWAVES, bool SPLIT = false>
 __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* lds, const EpilogueScalesRows<NI>& sc,
                                                     uint16_t* __restrict__ Y, int64_t ldy,
@@ -135,50 +186,69 @@ __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* l
             }
         }
     }
-    // each wave reads back only what it wrote itself: no barrier, just its own LDS writes done
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
-    auto store16 = [&](int trow, int col, u32x4v v) {
-        if (row0 + trow < T && col0 + col < O) {
-            uint16_t* dst = Y + (int64_t)(row0 + trow) * ldy + col0 + col;
-            // Y is not read again here and whole 128-byte pieces leave at once: written through to memory
-            // as a stream (sc1 nt).  The GEMM itself does not care, but the memory-side cache is left
-            // without 224 MiB of dirty lines, so the kernel that runs next reads its cold input faster
-            // (64 MiB: 4 us less; of the policies tried -- plain, nt, sc1, sc1 nt, sc0 nt, sc0 sc1 nt --
-            // this one gave the shortest following absmax + quantize calls).
-            // (The compiler offers no way to ask for this policy, hence the assembly; it cannot see a
-            // store in it, so the two wait states the hardware needs before the data registers of a
-            // 16-byte store may be overwritten are added by hand.)
-            // A small Y (see y_stays_cached) fits the memory-side cache next to everything else of its layer: plain
-            // stores then, which make the kernel itself 2-3 % faster on such layers and change nothing after it.
-            if (y_cached) *reinterpret_cast<u32x4v*>(dst) = v;
-            else asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(v) : "memory");
-        }
-    };
-    if (SPLIT) {
-        // a lane takes 8 words of a row (channels 8 p .. 8 p + 7 in the low halves, 32 + 8 p .. in the high halves)
-        // and stores them as two 16-byte pieces
-        const int p = lane & 3, rsub = lane >> 2;
+    epilogue_rows_flush<WTN, SPLIT>(stage, Y, ldy, T, O, row0, col0, lane, y_cached);
+}
+
+// ---- The same for the 16 x 16 x 64 instruction (INT8 kernel): lane l holds channel l & 15 of each 16 x 16 tile and,
+// in register r, token 4 (l >> 4) + r.  The kernel assigns the rows of its G weight tiles so that lane l's channels
+// are the G consecutive ones G (l & 15) + ni: a lane packs G binary16 results of one token into one 4 G / 2 byte
+// LDS write, and needs the row factors of 4 consecutive tokens at a time.
+template <int G>
+struct EpilogueScales16 {
+    float a_own[2];        // row factors of tokens row0 + lane and row0 + 64 + lane
+    float s[G];            // column steps of channels col0 + G (lane & 15) + ni
+};
+template <int G>
+__device__ __forceinline__ void epilogue16_load_scales(EpilogueScales16<G>& sc, const float* __restrict__ row_scale,
+                                                       const float* __restrict__ w_scale, int T, int O, int row0, int col0,
+                                                       int lane) {
+    sc.a_own[0] = row_scale[min(row0 + lane, T - 1)];                 // rows >= T are never stored
+    sc.a_own[1] = row_scale[min(row0 + 64 + lane, T - 1)];
 #pragma unroll
-        for (int i = 0; i < 128 / 16; ++i) {
-            const int trow = i * 16 + rsub;
-            const uint4 w0 = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + p * 32);
-            const uint4 w1 = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + p * 32 + 16);
-            auto lows = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); };
-            auto highs = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); };
-            store16(trow, 8 * p, u32x4v{lows(w0.x, w0.y), lows(w0.z, w0.w), lows(w1.x, w1.y), lows(w1.z, w1.w)});
-            store16(trow, 32 + 8 * p, u32x4v{highs(w0.x, w0.y), highs(w0.z, w0.w), highs(w1.x, w1.y), highs(w1.z, w1.w)});
-        }
-    } else {
-        constexpr int kLanesPerRow = WTN * 2 / 16;           // 16-byte pieces per staged row (8 or 4)
-        constexpr int kRowsPerInst = 64 / kLanesPerRow;
-        const int piece = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+    for (int ni = 0; ni < G; ++ni) sc.s[ni] = w_scale[min(col0 + G * (lane & 15) + ni, O - 1)];
+}
+
+template <int WTN, int G, int NWAVES>
+__device__ __forceinline__ void epilogue16_store(v4i (&acc)[8][G], int8_t* lds, const EpilogueScales16<G>& sc,
+                                                 uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug,
+                                                 int T, int O, int row0, int col0, int lane, int wave, bool y_cached) {
+    static_assert(G == 2 || G == 4, "two or four channels per lane");
+    static_assert(WTN == 16 * G, "G tiles of 16 channels");
+    constexpr int kRowPitch = epilogue_rows_pitch(WTN);
+    int8_t* stage = lds + wave * (128 * kRowPitch);
+    float* a_lds = reinterpret_cast<float*>(lds + NWAVES * (128 * kRowPitch) + wave * 512);
+    const int fr = lane & 15, grp = lane >> 4;
+    a_lds[lane] = sc.a_own[0];
+    a_lds[64 + lane] = sc.a_own[1];
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));      // wave-private: the writes above are done
+    const int o_loc = G * fr;                            // first of this lane's G channels
+    const bool o_ok = col0 + o_loc < O;                  // O % 8 == 0 on this path: the G channels exist or not together
 #pragma unroll
-        for (int i = 0; i < 128 / kRowsPerInst; ++i) {
-            const int trow = i * kRowsPerInst + rsub;
-            const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * kRowPitch + piece * 16);
-            store16(trow, piece * 8, u32x4v{v.x, v.y, v.z, v.w});
+    for (int mi = 0; mi < 8; ++mi) {
+        const float4 a4 = *reinterpret_cast<const float4*>(a_lds + 16 * mi + 4 * grp);
+        const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int t_loc = 16 * mi + 4 * grp + r;
+            float y[G];
+#pragma unroll
+            for (int ni = 0; ni < G; ++ni) {
+                y[ni] = (float)acc[mi][ni][r] * av[r];
+                y[ni] = rounded_f32(y[ni] * sc.s[ni]);
+            }
+            int8_t* dst = stage + t_loc * kRowPitch + o_loc * 2;
+            if (G == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_half2(y[0], y[1]), pack_half2(y[G - 2], y[G - 1]));
+            else *reinterpret_cast<uint32_t*>(dst) = pack_half2(y[0], y[1]);
+            if (acc_debug && row0 + t_loc < T && o_ok) {
+                int32_t* d = acc_debug + (int64_t)(row0 + t_loc) * O + col0 + o_loc;
+                if (G == 4)
+                    *reinterpret_cast<int4*>(d) = make_int4(acc[mi][0][r], acc[mi][1][r], acc[mi][G - 2][r], acc[mi][G - 1][r]);
+                else
+                    *reinterpret_cast<int2*>(d) = make_int2(acc[mi][0][r], acc[mi][1][r]);
+            }
         }
     }
+    epilogue_rows_flush<WTN, false>(stage, Y, ldy, T, O, row0, col0, lane, y_cached);
 }
 
 }  // namespace
