@@ -436,10 +436,11 @@ def main():
         copy_ms = event_ms(lambda: cq.crossquant_calib_copy(big[:half], big[half:]), 10)
         del big
         mf = {}
-        # mode 2: the code-like operands re-read from LDS every step at the linear kernel's 0.75 KiB per
-        # matrix instruction, two waves per SIMD -- its inner loop without global loads, barriers and epilogue
+        # modes 0, 1: v_mfma_i32_32x32x32_i8 on operands in registers; mode 3: the 16 x 16 x 64 instruction the linear
+        # kernel uses; mode 2: that instruction with the code-like operands re-read from LDS every step at the
+        # kernel's own ratio, two waves per SIMD -- its inner loop without global loads, barriers and epilogue
         for mode, name, it_ in ((0, "zero_operands", 2000), (1, "code_like_operands", 2000),
-                                (2, "code_like_operands_fed_from_lds", 4000)):
+                                (3, "code_like_operands_16x16x64", 1000), (2, "code_like_operands_fed_from_lds", 1000)):
             ops_ = cq.crossquant_calib_mfma_i8(it_, mode)
             ms_ = event_ms(lambda: cq.crossquant_calib_mfma_i8(it_, mode), 5)
             mf[name] = ops_ / (ms_ * 1e-3) / 1e12
@@ -448,7 +449,7 @@ def main():
             "hbm_copy_GBs_read_plus_write": 2 * half / (copy_ms * 1e-3) / 1e9,
             "mfma_i8_TOPs": mf,
             "quantizer_frac_of_copy": (quant_gbs / (2 * half / (copy_ms * 1e-3) / 1e9)) if quant_gbs else None,
-            "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands"]) if (tops and bits == 8) else None,
+            "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands_16x16x64"]) if (tops and bits == 8) else None,
             "w8a8_linear_frac_of_lds_fed_mfma_loop": (tops / mf["code_like_operands_fed_from_lds"]) if (tops and bits == 8) else None,
         }
 

@@ -21,10 +21,11 @@ extern "C" {
  * crossquant_calib_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, non-overlapping.
  * crossquant_calib_mfma_i8: every SIMD issues iters * 16 independent v_mfma_i32_32x32x32_i8 on
  *   operands held in registers; data_mode 0 = all-zero operands, 1 = bell-shaped int8 codes.
- *   data_mode 2 = the same codes re-read from LDS every step the way the linear layer's inner loop reads
- *   them (two waves per SIMD, 6 fragment reads per 8 instructions = 0.75 KiB per instruction; iters * 8
- *   instructions per wave): the ceiling of a kernel with that wave tile, which no global load, barrier
- *   or epilogue burdens.
+ *   data_mode 3 = the bell-shaped codes on v_mfma_i32_16x16x64_i8, the instruction the linear kernel uses
+ *   (iters * 32 instructions per wave, two waves per SIMD).  data_mode 2 = the same, with the operands re-read from LDS every step
+ *   the way the linear kernel's inner loop reads them (two waves per SIMD, 8 + 4 fragment reads per 32
+ *   instructions = 0.75 KiB per 32 x 32 x 32 worth of multiply-adds; iters * 32 instructions per wave): the ceiling
+ *   of a kernel with that wave tile, which no global load, barrier or epilogue burdens.
  *   *ops (HOST pointer, nullable) receives the number of integer operations of the launch.
  */
 int crossquant_calib_read(const void *src, int64_t bytes, unsigned long long *sink, void *stream);

@@ -318,7 +318,7 @@ int crossquant_calib_copy(const void* src, void* dst, int64_t bytes, void* strea
 
 int crossquant_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops, void* stream) {
     if (iters < 1 || iters > (1 << 20)) return CQ_ERR_SHAPE;
-    if (data_mode < 0 || data_mode > 2) return CQ_ERR_UNSUPPORTED;
+    if (data_mode < 0 || data_mode > 3) return CQ_ERR_UNSUPPORTED;
     if (!aligned(sink, 4)) return CQ_ERR_ALIGN;
     return from_hip(cq::launch_calib_mfma_i8(iters, data_mode, sink, ops, static_cast<hipStream_t>(stream)));
 }

@@ -90,10 +90,57 @@ calib_mfma_kernel(int iters, int data_mode, int* __restrict__ sink) {
     if (s == 0x7fffffff && sink) sink[0] = s;
 }
 
-// The same, fed the way the GEMM's inner loop is: 8 waves per CU (two per SIMD), every step reads 4 + 2 operand
-// fragments (1 KiB each per wave) from LDS and issues the 8 matrix instructions of a 128 x 64 wave tile, i.e.
-// 0.75 KiB of LDS reads per instruction; no global loads, no barriers, no epilogue.  LDS holds the bell-shaped
-// codes of data_mode 1.  What this loop sustains is the ceiling of any kernel with that wave tile on such data.
+// The same loop on the 16 x 16 x 64 instruction, the one the linear kernel uses (half the accumulator registers read
+// and written per multiply-add): 32 independent 16 x 16 accumulators, operands fixed in registers, code-like data.
+// Two waves per SIMD: one wave alone cannot keep the pipe full with an instruction this short.
+__global__ void __launch_bounds__(512)
+calib_mfma16_kernel(int iters, int* __restrict__ sink) {
+    v4i a[8], b[4];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t wa = 0, wb = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t ra = calib_hash(threadIdx.x * 977u + k * 131u + e * 17u + c + blockIdx.x * 7919u);
+                const uint32_t rb = calib_hash(threadIdx.x * 613u + k * 37u + e * 11u + c + 99991u + blockIdx.x * 104729u);
+                const int qa = (int)((ra & 63) + ((ra >> 6) & 63) + ((ra >> 12) & 63) + ((ra >> 18) & 63)) - 126;
+                const int qb = (int)((rb & 63) + ((rb >> 6) & 63) + ((rb >> 12) & 63) + ((rb >> 18) & 63)) - 126;
+                wa |= (uint32_t)(uint8_t)(int8_t)(qa / 3) << (8 * c);
+                wb |= (uint32_t)(uint8_t)(int8_t)(qb / 3) << (8 * c);
+            }
+            a[k][e] = (int)wa;
+            if (k < 4) b[k][e] = (int)wb;
+        }
+    v4i acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s += acc[i][j][r];
+    if (s == 0x7fffffff && sink) sink[0] = s;
+}
+
+// Fed the way the linear kernel's inner loop is: 8 waves per CU (two per SIMD), every step reads 8 + 4 operand
+// fragments (1 KiB each per wave) from LDS and issues the 32 matrix instructions (16 x 16 x 64) of a 128 x 64 wave
+// tile over 64 bytes of the contraction, i.e. 0.75 KiB of LDS reads per 32 x 32 x 32 worth of multiply-adds; no
+// global loads, no barriers, no epilogue.  LDS holds the bell-shaped codes of data_mode 1.  What this loop sustains
+// is the ceiling of any kernel with that wave tile and instruction on such data.
 __global__ void __launch_bounds__(512)
 calib_mfma_lds_kernel(int iters, int* __restrict__ sink) {
     __shared__ __align__(16) int8_t lds[32768];
@@ -109,35 +156,35 @@ calib_mfma_lds_kernel(int iters, int* __restrict__ sink) {
     }
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // a fragment = 64 lanes x 16 consecutive bytes (conflict-free); the six fragments of a step are 1 KiB apart
+    // a fragment = 64 lanes x 16 consecutive bytes (conflict-free); the twelve fragments of a step are 1 KiB apart
     const int8_t* p = lds + lane * 16;
-    v16i acc[4][2];
+    v4i acc[8][4];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0;
+            for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0;
     for (int it = 0; it < iters; ++it) {
-        const int base = ((it * 5 + wave * 3) & 15) * 1024;        // walks the 32 KiB, stays 6 KiB clear of the end
-        v4i a[4], b[2];
+        const int base = ((it * 5 + wave * 3) & 15) * 1024;        // walks the 32 KiB, stays 12 KiB clear of the end
+        v4i a[8], b[4];
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) a[mi] = *reinterpret_cast<const v4i*>(p + base + mi * 1024);
+        for (int mi = 0; mi < 8; ++mi) a[mi] = *reinterpret_cast<const v4i*>(p + ((base + mi * 1024) & 16383));
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) b[ni] = *reinterpret_cast<const v4i*>(p + base + (4 + ni) * 1024);
+        for (int ni = 0; ni < 4; ++ni) b[ni] = *reinterpret_cast<const v4i*>(p + 16384 + ((base + ni * 1024) & 16383));
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+        for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+            for (int ni = 0; ni < 4; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
     }
     int s = 0;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
+            for (int r = 0; r < 4; ++r) s += acc[mi][ni][r];
     if (s == 0x7fffffff && sink) sink[0] = s;
 }
 
@@ -166,7 +213,12 @@ hipError_t launch_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops
     const int blocks = calib_blocks();
     if (data_mode == 2) {
         calib_mfma_lds_kernel<<<dim3((unsigned)blocks), dim3(512), 0, stream>>>(iters, sink);
-        if (ops) *ops = (double)blocks * 8.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 32);
+        if (ops) *ops = (double)blocks * 8.0 * (double)iters * 32.0 * (2.0 * 16 * 16 * 64);
+        return hipGetLastError();
+    }
+    if (data_mode == 3) {
+        calib_mfma16_kernel<<<dim3((unsigned)blocks), dim3(512), 0, stream>>>(iters, sink);
+        if (ops) *ops = (double)blocks * 8.0 * (double)iters * 32.0 * (2.0 * 16 * 16 * 64);
         return hipGetLastError();
     }
     calib_mfma_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(iters, data_mode, sink);

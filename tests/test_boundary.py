@@ -221,7 +221,7 @@ def test_calibration_argument_errors(cq):
     assert r(0, 1024, None, None) == -1 and r(P, 0, None, None) == -2 and r(P, 1000, None, None) == -2
     assert r(P + 8, 1024, None, None) == -5
     assert c(P, 0, 1024, None) == -1 and c(P, P + 4096, 24, None) == -2 and c(P, P + 4, 1024, None) == -5
-    assert m(0, 0, None, None, None) == -2 and m(10, 3, None, None, None) == -6
+    assert m(0, 0, None, None, None) == -2 and m(10, 4, None, None, None) == -6
 
 
 def test_linear_argument_errors(cq):

@@ -1257,9 +1257,10 @@ def test_calibration_kernels_run_and_copy_is_exact(cq):
     assert torch.equal(src, dst)
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     assert ops == n_cu * 4 * 10 * 16 * 65536.0
-    ops_lds = cq.crossquant_calib_mfma_i8(10, 2)            # the loop fed from LDS: 8 waves x 8 instructions a step
+    ops_lds = cq.crossquant_calib_mfma_i8(10, 2)            # the loop fed from LDS: 8 waves x 32 instructions (16 x 16 x 64) a step
+    ops_16 = cq.crossquant_calib_mfma_i8(10, 3)             # the same instruction on operands in registers: 8 waves
     torch.cuda.synchronize()
-    assert ops_lds == n_cu * 8 * 10 * 8 * 65536.0
+    assert ops_lds == n_cu * 8 * 10 * 32 * 32768.0 and ops_16 == n_cu * 8 * 10 * 32 * 32768.0
 
 
 # ----------------------------------------------------------------------------- seeded random shapes
