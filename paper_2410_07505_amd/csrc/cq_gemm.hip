@@ -2,12 +2,12 @@
 // accumulation and the scale epilogue  Y_ik = fl16(fl32(fl32(float(acc_ik) * a_i) * s_k)).
 //
 // Both operands are stored with the contraction axis contiguous (qx [T][I], qw [O][I]), which is
-// the layout v_mfma_i32_32x32x32_i8 wants: every lane supplies 16 consecutive bytes of one row.
+// the layout the INT8 matrix instructions want: every lane supplies 16 consecutive bytes of one row.
 //
 // Two kernels, same results (integer accumulation is exact, so tiling and order cannot matter):
 //   - gemm_i8_ring_kernel, the fast path: 16-byte aligned operands, K a multiple of 128, any T (edge tiles
 //     read clamped rows and drop the surplus outputs).  512 threads = 8 waves in a 2 x 4 arrangement, each
-//     wave owning 128 x 64 = 4 x 2 MFMA tiles of 32 x 32 (128 accumulator registers); operands go from
+//     wave owning 128 x 64 = 8 x 4 MFMA tiles of 16 x 16 (128 accumulator registers); operands go from
 //     global memory straight into a five-slot LDS ring (described at the kernel); a last round of tiles
 //     that is at most half full runs as 256 x 128 half tiles;
 //   - gemm_i8_kernel<true>, any shape and alignment: 256 threads = 4 waves in a 2 x 2 arrangement
@@ -181,9 +181,10 @@ gemm_i8_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scal
 // instruction fills 8 consecutive 128-byte LDS rows.  The XOR swizzle is therefore applied on
 // the global side: the lane that will land in physical chunk p of row R fetches logical chunk
 // p ^ ((R >> 1) & 7) of that row (still the same 128 contiguous bytes per 8 lanes).
-// Software pipeline per K step (4 slabs of 32 bytes, fragment registers F0/F1 alternate):
-//   read slab1 | mfma slab0 ; read slab2 | mfma slab1 ; read slab3 | mfma slab2 ;
-//   wait for the next tile, barrier ; read slab0 of the next tile | mfma slab3.
+// Software pipeline per K step (2 slabs of 64 bytes, each worked on as activation tiles 0-3 then 4-7; two sets of
+// 4 activation fragments and two sets of weight fragments alternate):
+//   read s0 hi | mfma s0 lo ; read s1 lo + weights s1 | mfma s0 hi ; read s1 hi | mfma s1 lo ;
+//   wait for the next tile, barrier ; read s0 lo + weights s0 of the next tile | mfma s1 hi.
 // ---------------------------------------------------------------------------------------------
 
 // Fragments of the 16 x 16 x 64 instruction: a lane supplies 16 consecutive bytes of row (lane & 15), K chunk
