@@ -8,8 +8,10 @@
 //   - gemm_i8_ring_kernel, the fast path: 16-byte aligned operands, K a multiple of 128, any T (edge tiles
 //     read clamped rows and drop the surplus outputs).  512 threads = 8 waves in a 2 x 4 arrangement, each
 //     wave owning 128 x 64 = 8 x 4 MFMA tiles of 16 x 16 (128 accumulator registers); operands go from
-//     global memory straight into a five-slot LDS ring (described at the kernel); a last round of tiles
-//     that is at most half full runs as 256 x 128 half tiles;
+//     global memory straight into a five-slot LDS ring (described at the kernel); one block per CU walks over
+//     several tiles, requesting the next tile's first operands before it scales and stores the current one, and
+//     the results leave straight from the accumulator registers (8 bytes per lane, whole 128-byte lines per
+//     16 lanes); a last round of tiles that is at most half full runs as 256 x 128 half tiles;
 //   - gemm_i8_kernel<true>, any shape and alignment: 256 threads = 4 waves in a 2 x 2 arrangement
 //     (128 x 128 per wave), two LDS stages of (256 + 256) rows x 128 B = 128 KiB; the next K step
 //     is fetched into registers (bounds-checked) while the current one is multiplied, then stored
@@ -23,6 +25,7 @@
 //     de-interleaved by XCD (each XCD gets a contiguous range of tiles, hence its own L2 sees a
 //     compact patch), then walked in groups of 4 tile-rows so that concurrently resident tiles
 //     share A rows and B columns.
+#include <algorithm>
 #include <type_traits>
 
 #include "cq_gemm_common.h"
@@ -246,16 +249,20 @@ constexpr int kRingLds = kRingSlots * kSlotBytes; // 160 KiB: the whole LDS of a
 // One output tile of 256 tokens x (128 NI) channels starting at (m0, n0).  NI = 2 is the full 256 x 256 tile;
 // NI = 1 the half tile of the last, partly filled round (see launch_w8a8_linear): the same schedule with
 // 128 x 32 wave tiles, half the weight requests and half the matrix instructions per step.
-template <int NI>
+template <int NI, bool DEBUG, bool STREAM>
 __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
                                           const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I,
                                           int O, uint16_t* __restrict__ Y, int64_t ldy,
-                                          int32_t* __restrict__ acc_debug, int m0, int n0, int8_t* lds, bool y_cached) {
+                                          int32_t* __restrict__ acc_debug, int m0, int n0, int8_t* lds,
+                                          bool prefetched, int next_m0, int next_n0) {
     constexpr int WN = 4, WTN = 32 * NI;
     constexpr int G = 2 * NI, LOG2G = NI;         // weight tiles of 16 channels per wave (4 or 2)
     constexpr int NLB = 4 * NI;                   // requests a weight-loading wave makes per half tile (8 or 4)
 
-    const int tid = threadIdx.x;
+    // (the thread id goes through an empty asm: the lane-dependent offsets below are then worked out again for every
+    // tile of the block's walk instead of being kept, and spilled, across the whole loop over tiles)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int nk = I / BK;
@@ -264,16 +271,19 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     // ---- loader: loader wave lw = wave & 3 fills rows [64 lw, 64 lw + 64) of its operand's half
     // tile with 8 instructions; instruction ii covers rows 64 lw + 8 ii + (lane >> 3), physical
     // chunk lane & 7 (the swizzle is applied to the global column).
-    const int ld_r = lane >> 3, ld_p = lane & 7;
     const int lw = wave & 3;
     // Tiles on the bottom / right edge of a ragged problem read a clamped (valid) row instead of
     // the rows past the end; what lands in those LDS rows only feeds outputs the epilogue drops.
     // (a weight-loading wave of a half tile fills 32 rows with 4 requests)
     const int rows_per_loader = b_loader ? 8 * NLB : 64;
     const int8_t* gsrc[8];
-    {
+    auto set_sources = [&](int tile_m0, int tile_n0) {
+        // (worked out from scratch at each of the two calls rather than kept in registers in between)
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        const int ld_r = l >> 3, ld_p = l & 7;
         const int8_t* base = b_loader ? qw : qx;
-        const int first = b_loader ? n0 : m0, last = (b_loader ? O : T) - 1;
+        const int first = b_loader ? tile_n0 : tile_m0, last = (b_loader ? O : T) - 1;
         // LDS row R of an operand tile holds, for activations, tile row R with chunk c at c ^ ((R >> 1) & 7): a
         // fragment's 16 lanes per LDS cycle read 16 consecutive rows, whose parity picks the half of the 64 banks
         // and whose (R >> 1) & 7 picks the 16-byte group.  Weight tile ni takes the tile rows G fr + ni (see
@@ -288,7 +298,8 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
             const int tile_row = b_loader ? (R ^ ((R >> LOG2G) & 1)) : R;
             gsrc[ii] = base + (int64_t)min(first + tile_row, last) * I + c * 16;
         }
-    }
+    };
+    set_sources(m0, n0);
     auto issue_half = [&](int kt, int slot) {
         int8_t* dst = lds + slot * kSlotBytes + lw * (rows_per_loader * BK);
         const int64_t koff = (int64_t)kt * BK;
@@ -322,12 +333,22 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0;
 
-    // prologue: A0 A1 (waves 0-3) / B0 B1 (waves 4-7); half tile n -> slot n % 5
-    issue_half(0, b_loader ? 1 : 0);
-    if (nk > 1) issue_half(1, b_loader ? 3 : 2);
-    if (nk > 1) wait_for_previous_half();
-    else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
-    __syncthreads();
+    // prologue: A0 A1 (waves 0-3) / B0 B1 (waves 4-7); half tile n -> slot n % 5.  The block's previous tile may
+    // have requested them already (see the end of this function): then its 32 stores are the newest requests of
+    // this wave, after A1 / B1, and "A0 / B0 has landed" is "at most 8 + 32 requests in flight" (the counter is
+    // decremented in the order of issue).
+    if (!prefetched) {
+        issue_half(0, b_loader ? 1 : 0);
+        if (nk > 1) issue_half(1, b_loader ? 3 : 2);
+        if (nk > 1) wait_for_previous_half();
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    } else {
+        if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(8 + kEpilogue16Stores, 15));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(kEpilogue16Stores, 15));
+    }
+    // (a bare barrier, as in the loop below: the second half tile's requests stay in flight across it)
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
 
     // slots of the current tile (sa, sb) and of the next one (na, nb), advanced by 2 mod 5 per step
     int sa = 0, sb = 1;
@@ -418,39 +439,61 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{});
 
-    epilogue16_store<WTN, G, 8>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane, wave,
-                                y_cached);
+    // Every wave is past the last step's barrier: nothing in the ring is read any more.  The first two half tiles
+    // of the block's next tile are requested now, into their slots 0-3, and travel while this tile's results are
+    // scaled and stored; the epilogue keeps its row factors in slot 4, which the next tile's loop does not write
+    // before its first barrier.  (Not with DEBUG: the number of stores in flight is not fixed then.)
+    if (!DEBUG && NI == 2 && next_m0 >= 0) {
+        set_sources(next_m0, next_n0);
+        issue_half(0, b_loader ? 1 : 0);
+        if (nk > 1) issue_half(1, b_loader ? 3 : 2);
+    }
+    float* a_lds = reinterpret_cast<float*>(lds + 4 * kSlotBytes + wave * 512);
+    epilogue16_store<WTN, G, DEBUG, STREAM>(acc, a_lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    __builtin_amdgcn_sched_barrier(0);
 }
-static_assert(epilogue_rows_lds(8, 64) <= kRingLds, "the epilogue's staging areas reuse the ring's LDS");
 
-// Work of a block.  Blocks [0, main_blocks) take the first n_main tiles of the walk whole, de-interleaved by XCD
-// as in tile_of_block; the blocks after them take the remaining tiles as half tiles of 128 channels (half tile
-// h = column half h & 1 of tile n_main + h / 2), again de-interleaved by XCD so that the two halves of a tile, which
-// share their activation rows, sit in one L2.  n_main equals the tile count when no tile is split.
+// Work of a block.  The grid is one block per CU (a block fills a CU's LDS) and every block walks over several
+// tiles: block b belongs to XCD b % 8 (block ids are dealt round-robin) and takes positions i, i + per, i + 2 per, ...
+// of that XCD's contiguous range of the tile walk, i = b / 8, per = gridDim.x / 8, so that the blocks running
+// together in one XCD work on neighbouring tiles as in tile_of_block.  Staying in the kernel between tiles means
+// that the stores of one tile drain while the next tile's first operands are on their way, and no wave has to be
+// launched in between.  The first n_main tiles of the walk are taken whole; the remaining ones as half tiles of
+// 128 channels (half tile h = column half h & 1 of tile n_main + h / 2), dealt the same way so that the two
+// halves of a tile, which share their activation rows, sit in one L2.  n_main equals the tile count when no tile
+// is split.
+template <bool DEBUG, bool STREAM>
 __global__ void __launch_bounds__(512)
 gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
                     const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I, int O,
                     uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
-                    int tiles_n, int n_main, int main_blocks, int y_cached) {
+                    int tiles_n, int n_main) {
     extern __shared__ __align__(16) int8_t lds[];
-    const int block = blockIdx.x;
+    const int xcd = blockIdx.x % kXcds, first = blockIdx.x / kXcds, per = gridDim.x / kXcds;
     int tile_m, tile_n;
-    if (block < main_blocks) {
-        const int per_xcd = (n_main + kXcds - 1) / kXcds;
-        const int L = (block % kXcds) * per_xcd + block / kXcds;
-        if (L >= n_main) return;
+    const int main_per_xcd = (n_main + kXcds - 1) / kXcds;
+    bool prefetched = false;
+    for (int i = first; i < main_per_xcd; i += per) {
+        const int L = xcd * main_per_xcd + i;
+        if (L >= n_main) break;
         tile_of_index(L, tiles_m, tiles_n, tile_m, tile_n);
-        ring_tile<2>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN, lds, y_cached != 0);
-    } else {
-        const int n_half = 2 * (tiles_m * tiles_n - n_main);
-        const int h_block = block - main_blocks;
-        const int per_xcd = (n_half + kXcds - 1) / kXcds;
-        const int h = (h_block % kXcds) * per_xcd + h_block / kXcds;
-        if (h >= n_half) return;
+        // the tile after this one, whose first operands this one requests before its epilogue
+        int next_m = -1, next_n = -1;
+        const bool has_next = i + per < main_per_xcd && L + per < n_main;
+        if (has_next) tile_of_index(L + per, tiles_m, tiles_n, next_m, next_n);
+        ring_tile<2, DEBUG, STREAM>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN, lds,
+                                    prefetched, has_next ? next_m * BM : -1, next_n * BN);
+        prefetched = has_next && !DEBUG;
+    }
+    const int n_half = 2 * (tiles_m * tiles_n - n_main);
+    const int half_per_xcd = (n_half + kXcds - 1) / kXcds;
+    for (int i = first; i < half_per_xcd; i += per) {
+        const int h = xcd * half_per_xcd + i;
+        if (h >= n_half) break;
         tile_of_index(n_main + h / 2, tiles_m, tiles_n, tile_m, tile_n);
-        if (tile_n * BN + (h & 1) * (BN / 2) >= O) return;        // the second half of a tile on the ragged edge may be empty
-        ring_tile<1>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN + (h & 1) * (BN / 2),
-                     lds, y_cached != 0);
+        if (tile_n * BN + (h & 1) * (BN / 2) >= O) continue;      // the second half of a tile on the ragged edge may be empty
+        ring_tile<1, DEBUG, STREAM>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM,
+                                    tile_n * BN + (h & 1) * (BN / 2), lds, false, -1, -1);
     }
 }
 
@@ -469,12 +512,20 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
     auto al16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
     // fast path: K a multiple of the K step and everything the vector loads/stores touch aligned to 16
     // bytes (any T; O a multiple of 8)
+    // (the fast path's epilogue addresses a wave's 128 output rows with 32-bit byte offsets)
     const bool full = vec && (I % BK == 0) && (O % 8 == 0) && al16(Y) && (ldy % 8 == 0) && al16(w_scale) &&
-                      al16(acc_debug);
+                      al16(acc_debug) && ldy < ((int64_t)1 << 22);
     hipError_t e;
     if (full) {
-        static std::atomic<uint64_t> lds_allowed{0};
-        e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_i8_ring_kernel), kRingLds, lds_allowed);
+        // four instances: with or without the raw accumulators, Y streamed to memory or left in the caches
+        using kernel_t = void (*)(const int8_t*, const float*, const int8_t*, const float*, int, int, int, uint16_t*,
+                                  int64_t, int32_t*, int, int, int);
+        static const kernel_t kernels[4] = {&gemm_i8_ring_kernel<false, false>, &gemm_i8_ring_kernel<false, true>,
+                                            &gemm_i8_ring_kernel<true, false>, &gemm_i8_ring_kernel<true, true>};
+        static std::atomic<uint64_t> lds_allowed[4];
+        const int which = (acc_debug ? 2 : 0) + (y_stays_cached(T, O) ? 0 : 1);
+        const kernel_t kernel = kernels[which];
+        e = allow_dynamic_lds(reinterpret_cast<const void*>(kernel), kRingLds, lds_allowed[which]);
         if (e != hipSuccess) return e;
         // One block fills a CU, so the tiles run in rounds of n_cu.  A last round that is at most half full is
         // run as half tiles (256 x 128) instead, which spreads it over twice as many CUs: 2048 x 4096 x 11008
@@ -488,9 +539,11 @@ hipError_t launch_w8a8_linear(const int8_t* qx, const float* row_scale, const in
         const int n_main = (rem > 0 && 2 * rem <= n_cu) ? total - rem : total;
         const int main_blocks = ((n_main + kXcds - 1) / kXcds) * kXcds;
         const int half_blocks = ((2 * (total - n_main) + kXcds - 1) / kXcds) * kXcds;
-        gemm_i8_ring_kernel<<<dim3((unsigned)(main_blocks + half_blocks)), dim3(512), kRingLds, stream>>>(
-            qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tiles_m, tiles_n, n_main, main_blocks,
-            y_stays_cached(T, O) ? 1 : 0);
+        // one block per CU (a multiple of the XCD count), fewer when there are fewer tiles than that
+        const int cu_blocks = n_cu >= kXcds ? n_cu / kXcds * kXcds : kXcds;
+        const int blocks = std::min(cu_blocks, std::max(main_blocks, half_blocks));
+        kernel<<<dim3((unsigned)blocks), dim3(512), kRingLds, stream>>>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy,
+                                                                        acc_debug, tiles_m, tiles_n, n_main);
     } else {
         static std::atomic<uint64_t> lds_allowed{0};
         e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_i8_kernel<true>), kLdsBytes, lds_allowed);

@@ -50,9 +50,9 @@ __device__ __forceinline__ bool tile_of_block(int block, int tiles_m, int tiles_
 // absmax call that follows 1.5 and 6 us slower with plain stores.
 inline bool y_stays_cached(int T, int O) { return (int64_t)T * O * 2 <= (int64_t)64 << 20; }
 
-// Epilogue shared by the fast-path kernels.  Scaled binary16 results go through LDS (free once the K loop has
-// ended on a barrier with no reads outstanding) so that every global store is a full 16 bytes per lane and a
-// wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
+// Epilogue of the A4W4 kernel, which is on the 32 x 32 FP6 instruction.  Scaled binary16 results go through LDS
+// (free once the K loop has ended on a barrier with no reads outstanding) so that every global store is a full
+// 16 bytes per lane and a wave writes whole 128-byte row pieces.  row0 / col0: first token / channel of this wave.
 // The accumulators are in the instruction's natural orientation (activation fragment as the first
 // operand): lane l holds one output channel per 32 x 32 tile and, in register r of the tile, token
 // 8 (r / 4) + 4 (l >> 5) + (r & 3).  The kernel assigns the rows of its NI weight fragments so that lane l's
@@ -189,10 +189,16 @@ __device__ __forceinline__ void epilogue_rows_store(ACC (&acc)[4][NI], int8_t* l
     epilogue_rows_flush<WTN, SPLIT>(stage, Y, ldy, T, O, row0, col0, lane, y_cached);
 }
 
-// ---- The same for the 16 x 16 x 64 instruction (INT8 kernel): lane l holds channel l & 15 of each 16 x 16 tile and,
+// ---- Epilogue for the 16 x 16 x 64 instruction (INT8 kernel): lane l holds channel l & 15 of each 16 x 16 tile and,
 // in register r, token 4 (l >> 4) + r.  The kernel assigns the rows of its G weight tiles so that lane l's channels
-// are the G consecutive ones G (l & 15) + ni: a lane packs G binary16 results of one token into one 4 G / 2 byte
-// LDS write, and needs the row factors of 4 consecutive tokens at a time.
+// are the G consecutive ones G (l & 15) + ni: the G binary16 results of one token are 2 G adjacent bytes of Y, the
+// 16 lanes of a group cover 32 G contiguous bytes of a token row (whole 128-byte lines for G = 4), and they are
+// stored straight from registers, with no pass through LDS.  The wave's outputs are addressed as one raw buffer that
+// ends with the last valid element, so the hardware's range check drops the rows past T; a lane whose channels lie
+// past O gets an offset beyond any buffer.  No store is predicated: a wave always issues exactly 32 of them, which
+// the kernel's hand-counted waits rely on.
+// A lane needs the row factors of 4 consecutive tokens at a time; they go through 512 bytes of wave-private LDS
+// (each lane requests two of its wave's 128 before the last step of the contraction).
 template <int G>
 struct EpilogueScales16 {
     float a_own[2];        // row factors of tokens row0 + lane and row0 + 64 + lane
@@ -208,47 +214,67 @@ __device__ __forceinline__ void epilogue16_load_scales(EpilogueScales16<G>& sc, 
     for (int ni = 0; ni < G; ++ni) sc.s[ni] = w_scale[min(col0 + G * (lane & 15) + ni, O - 1)];
 }
 
-template <int WTN, int G, int NWAVES>
-__device__ __forceinline__ void epilogue16_store(v4i (&acc)[8][G], int8_t* lds, const EpilogueScales16<G>& sc,
+constexpr int kEpilogue16Stores = 32;     // buffer stores per wave and tile (8 accumulator tiles x 4 registers)
+
+// STREAM: Y is written through to memory as a stream (sc1 nt).  It is not read again here, and the memory-side cache
+// is left without hundreds of MiB of dirty lines, so the kernel that runs next reads its cold input faster (64 MiB:
+// 4 us less; of the policies tried -- plain, nt, sc1, sc1 nt, sc0 nt, sc0 sc1 nt -- this one gave the shortest
+// following absmax + quantize calls).  A small Y (see y_stays_cached) fits the memory-side cache next to everything
+// else of its layer: plain stores then, which make the kernel itself 2-3 % faster on such layers and change nothing
+// after it.  DEBUG: the raw accumulators are stored as well (predicated stores; no fixed count then).
+template <int WTN, int G, bool DEBUG, bool STREAM>
+__device__ __forceinline__ void epilogue16_store(v4i (&acc)[8][G], float* a_lds, const EpilogueScales16<G>& sc,
                                                  uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug,
-                                                 int T, int O, int row0, int col0, int lane, int wave, bool y_cached) {
+                                                 int T, int O, int row0, int col0, int lane) {
     static_assert(G == 2 || G == 4, "two or four channels per lane");
     static_assert(WTN == 16 * G, "G tiles of 16 channels");
-    constexpr int kRowPitch = epilogue_rows_pitch(WTN);
-    int8_t* stage = lds + wave * (128 * kRowPitch);
-    float* a_lds = reinterpret_cast<float*>(lds + NWAVES * (128 * kRowPitch) + wave * 512);
+    constexpr int kPolicy = STREAM ? 18 : 0;             // sc1 (16) | nt (2)
     const int fr = lane & 15, grp = lane >> 4;
     a_lds[lane] = sc.a_own[0];
     a_lds[64 + lane] = sc.a_own[1];
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));      // wave-private: the writes above are done
     const int o_loc = G * fr;                            // first of this lane's G channels
-    const bool o_ok = col0 + o_loc < O;                  // O % 8 == 0 on this path: the G channels exist or not together
+    // the wave's 128 x WTN outputs as a buffer: rows [row0, T) and channels [col0, O) of them exist
+    const int n_rows = min(128, T - row0), n_cols = min(WTN, O - col0);
+    const int pitch = (int)ldy * 2;                      // bytes; 128 rows of it stay below 2^31 (checked by the launcher)
+    const int bytes = (n_rows > 0 && n_cols > 0) ? (n_rows - 1) * pitch + n_cols * 2 : 0;
+    const __amdgpu_buffer_rsrc_t yb =
+        __builtin_amdgcn_make_buffer_rsrc(Y + (int64_t)row0 * ldy + col0, 0, bytes, 0x00020000);   // raw, 32-bit data
+    // O % 8 == 0 on this path: a lane's G channels exist or not together
+    const bool o_ok = o_loc < n_cols;
+    const uint32_t lane_off = o_ok ? (uint32_t)(4 * grp * pitch + o_loc * 2) : 0x80000000u;
 #pragma unroll
     for (int mi = 0; mi < 8; ++mi) {
         const float4 a4 = *reinterpret_cast<const float4*>(a_lds + 16 * mi + 4 * grp);
         const float av[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int t_loc = 16 * mi + 4 * grp + r;
             float y[G];
 #pragma unroll
             for (int ni = 0; ni < G; ++ni) {
                 y[ni] = (float)acc[mi][ni][r] * av[r];
                 y[ni] = rounded_f32(y[ni] * sc.s[ni]);
             }
-            int8_t* dst = stage + t_loc * kRowPitch + o_loc * 2;
-            if (G == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(pack_half2(y[0], y[1]), pack_half2(y[G - 2], y[G - 1]));
-            else *reinterpret_cast<uint32_t*>(dst) = pack_half2(y[0], y[1]);
-            if (acc_debug && row0 + t_loc < T && o_ok) {
-                int32_t* d = acc_debug + (int64_t)(row0 + t_loc) * O + col0 + o_loc;
-                if (G == 4)
-                    *reinterpret_cast<int4*>(d) = make_int4(acc[mi][0][r], acc[mi][1][r], acc[mi][G - 2][r], acc[mi][G - 1][r]);
-                else
-                    *reinterpret_cast<int2*>(d) = make_int2(acc[mi][0][r], acc[mi][1][r]);
+            const int off = (int)(lane_off + (uint32_t)((16 * mi + r) * pitch));
+            if (G == 4) {
+                typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+                __builtin_amdgcn_raw_buffer_store_b64(u32x2v{pack_half2(y[0], y[1]), pack_half2(y[G - 2], y[G - 1])}, yb, off, 0,
+                                                      kPolicy);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(y[0], y[1]), yb, off, 0, kPolicy);
+            }
+            if (DEBUG) {
+                const int t_loc = 16 * mi + 4 * grp + r;
+                if (row0 + t_loc < T && o_ok) {
+                    int32_t* d = acc_debug + (int64_t)(row0 + t_loc) * O + col0 + o_loc;
+                    if (G == 4)
+                        *reinterpret_cast<int4*>(d) = make_int4(acc[mi][0][r], acc[mi][1][r], acc[mi][G - 2][r], acc[mi][G - 1][r]);
+                    else
+                        *reinterpret_cast<int2*>(d) = make_int2(acc[mi][0][r], acc[mi][1][r]);
+                }
             }
         }
     }
-    epilogue_rows_flush<WTN, false>(stage, Y, ldy, T, O, row0, col0, lane, y_cached);
 }
 
 }  // namespace
