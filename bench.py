@@ -10,7 +10,10 @@ Weight quantization is weight preparation and happens once, outside the timed re
 Prints one JSON line.  The headline workload is C5 (the 70B-shaped layer): `value` is its
 quantizer throughput = algorithmic bytes of absmax + quantize / the sum of the two stage times,
 each stage time the MEDIAN over the timed steps of the HIP-event interval around the stage (events
-recorded on the stream the kernels run on).  `roofline` describes the dominant kernel (the GEMM),
+recorded on the stream the kernels run on; they are timing-only events, created with
+hipEventDisableSystemFence, so that recording one does not add a system-scope cache release to the
+stage it closes -- `with_default_events` repeats the loop with torch.cuda.Event, which does, and shows
+the difference).  `roofline` describes the dominant kernel (the GEMM),
 `roofline_quantize` the fused quantize kernel.  `event_free` gives the same step timed by the wall
 clock with no event in it, with and without the two quantizer calls: what the event packets between
 the stages cost can be read off the difference.  `configs` repeats the step loop on the other
@@ -44,6 +47,69 @@ MEASURED_TRAFFIC_BYTES = {
     "C4": {"quantize": (32.5 + 44.0) * 2 ** 20, "linear": (72.4 + 32.0) * 2 ** 20},
     "C5": {"quantize": (64.5 + 96.1) * 2 ** 20, "linear": (1344.8 + 224.0) * 2 ** 20},
 }
+
+
+class _TimingEvent:
+    """A HIP event for timing only, created with hipEventDisableSystemFence: recording it does not make the stream
+    perform a system-scope release (a write-back of the caches for the host's benefit), which a default event --
+    torch.cuda.Event is one -- adds to whatever it brackets.  Recorded on torch's current stream, the stream the
+    library's calls are enqueued on."""
+    DISABLE_SYSTEM_FENCE = 0x20000000
+    _hip = None
+
+    @classmethod
+    def library(cls):
+        if cls._hip is None:
+            import ctypes
+            hip = ctypes.CDLL("libamdhip64.so")          # the runtime torch has loaded already
+            vp = ctypes.c_void_p
+            hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(vp), ctypes.c_uint]
+            hip.hipEventRecord.argtypes = [vp, vp]
+            hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), vp, vp]
+            hip.hipEventDestroy.argtypes = [vp]
+            cls._hip = hip
+        return cls._hip
+
+    def __init__(self, torch):
+        import ctypes
+        self._h = self.library()
+        self._e = ctypes.c_void_p()
+        self._stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        if self._h.hipEventCreateWithFlags(ctypes.byref(self._e), self.DISABLE_SYSTEM_FENCE) != 0:
+            raise RuntimeError("hipEventCreateWithFlags failed")
+
+    def record(self):
+        if self._h.hipEventRecord(self._e, self._stream) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def elapsed_time(self, other):
+        import ctypes
+        ms = ctypes.c_float()
+        if self._h.hipEventElapsedTime(ctypes.byref(ms), self._e, other._e) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value
+
+    def __del__(self):
+        if getattr(self, "_e", None) is not None and self._e.value:
+            self._h.hipEventDestroy(self._e)
+            self._e = None
+
+
+EVENT_KINDS = set()     # what make_events handed out in this run, for the JSON line
+
+
+def make_events(torch, n, timing_only=True):
+    """n events for bracketing stages: timing-only HIP events, or torch's default ones (also when the HIP runtime
+    cannot be reached through ctypes; the JSON line says which kind was used)."""
+    if timing_only:
+        try:
+            ev = [_TimingEvent(torch) for _ in range(n)]
+            EVENT_KINDS.add("hipEventDisableSystemFence")
+            return ev
+        except (OSError, AttributeError, RuntimeError):
+            pass
+        EVENT_KINDS.add("torch.cuda.Event (fallback)")
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
 def parse():
@@ -203,14 +269,14 @@ class Workload:
         if ev is not None:
             ev[4].record()
 
-    def timed_steps(self, steps, warmup, **kw):
+    def timed_steps(self, steps, warmup, timing_only_events=True, **kw):
         """Stage times in ms (median and mean over the steps of each HIP-event interval) and the wall time per step."""
         import numpy as np
         torch = self.torch
         for _ in range(warmup):
             self.step(**kw)
         torch.cuda.synchronize()
-        events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+        events = [make_events(torch, 5, timing_only_events) for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
@@ -349,6 +415,14 @@ def main():
     med, mean, ms_per_step = wl.timed_steps(args.steps, args.warmup)
     f = wl.figures(med)
     f_mean = wl.figures(mean)
+    # The same loop with default events (torch.cuda.Event), which make the stream release to system scope at every
+    # record: about 1.5 us on each stage that the stage's kernels do not spend.  Reported beside the headline.
+    med_d, _, ms_per_step_d = wl.timed_steps(args.steps, min(args.warmup, 3), timing_only_events=False)
+    f_d = wl.figures(med_d)
+    default_events = {"stage_ms": dict(zip(("absmax", "quantize", "count_per_token", "w8a8_linear"), map(float, med_d))),
+                      "ms_per_step": ms_per_step_d, "quantizer_GBs": f_d["quant_gbs"],
+                      "quantizer_frac_hbm_peak": (f_d["quant_gbs"] / HBM_PEAK_GBS) if f_d["quant_gbs"] else None,
+                      "w8a8_linear_TOPs": f_d["tops"]}
     quant_gbs, tops, mfma_peak = f["quant_gbs"], f["tops"], f["peak_tops"]
     z, z_pt = int(wl.zc.item()), int(wl.zc_pt.item())
 
@@ -572,6 +646,9 @@ def main():
         "config": {"workload": "%s: %s" % (cfg.name, cfg.label), "T": T, "I": I, "O": O, "bits": bits,
                    "alpha": alpha, "stages": list(stages)},
         "stage_time_statistic": "median over the timed steps of each stage's HIP-event interval",
+        "stage_events": ("timing-only HIP events (hipEventDisableSystemFence) on the launch stream; the same loop with "
+                         "default events is under with_default_events"),
+        "with_default_events": default_events,
         "stage_ms": {"absmax": f["ms"]["absmax"], "quantize": f["ms"]["quantize"], "count_per_token": f["ms"]["count"],
                      lin_name: f["ms"]["linear"]},
         "stage_ms_mean": {"absmax": f_mean["ms"]["absmax"], "quantize": f_mean["ms"]["quantize"],
@@ -615,6 +692,7 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, X_head, W_head, alpha)
+    out["stage_event_kinds"] = sorted(EVENT_KINDS)
     print(json.dumps(out))
 
 
