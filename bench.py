@@ -220,7 +220,7 @@ class Workload:
         cq.crossquant_weight_quantize(Wg, self.b, bits, qw=self.qw, w_scale=self.ws)
         self.px = self.pw = None
         if bits == 4:
-            self.pw = cq.crossquant_pack_fp6(self.qw)
+            self.pw = cq.crossquant_pack_fp6_weights(self.qw)
             self.px = cq.crossquant_pack_fp6(self.codes)
         torch.cuda.synchronize()
         del Wg
@@ -549,7 +549,7 @@ def main():
         nib, _, a4, b4, _ = cq.crossquant_quantize(wl.Xg, wl.t, wl.c, alpha, 4, want_xhat=False)
         qw4, ws4 = cq.crossquant_weight_quantize(Wg4, b4, 4)
         del Wg4
-        px, pw = cq.crossquant_pack_fp6(nib), cq.crossquant_pack_fp6(qw4)
+        px, pw = cq.crossquant_pack_fp6(nib), cq.crossquant_pack_fp6_weights(qw4)
         q8 = cq.crossquant_unpack_int4(nib)
         event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=wl.Y), 10)
         fp6_ms = event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=wl.Y), reps)

@@ -275,18 +275,26 @@ int crossquant_quantize_linear_fused(const void *X, int64_t T, int64_t I, int64_
  *          src_format 4 = packed nibbles [R][K/2] (crossquant_quantize with bits = 4);
  *          values outside [-7, 7] are clamped.  K % 128 == 0 (else CQ_ERR_UNSUPPORTED).
  *   packed: out, crossquant_fp6_packed_bytes(R, K) bytes (-1 for invalid sizes), 16-byte aligned.
+ * crossquant_pack_fp6_weights does the same for the weight operand, codes [O][K], whose rows the kernel wants
+ *   interleaved four ways: inside every group of 64 output channels, row 16 n + f of the packed matrix holds
+ *   channel 4 f + n (n = 0..3, f = 0..15), so that a lane of the matrix kernel ends up with four adjacent
+ *   channels of a token and stores them straight from its registers.  The packed matrix has whole groups:
+ *   crossquant_fp6_packed_weight_bytes(O, K) = crossquant_fp6_packed_bytes(64 ceil(O / 64), K) bytes; channels
+ *   past O are zero rows.  Arguments and errors as for crossquant_pack_fp6.
  * crossquant_quantize_fp6: crossquant_quantize with bits = 4 whose codes leave the kernel already in
  *   this format (no nibble buffer, no packing pass): packed receives crossquant_fp6_packed_bytes(T, I)
  *   bytes; the rows past T of the last row block are left untouched (they only feed outputs that
  *   crossquant_w4a4_linear never stores).  I % 128 == 0 and packed 16-byte aligned, else
  *   CQ_ERR_UNSUPPORTED.  Other arguments as in crossquant_quantize.
- * crossquant_w4a4_linear: qx_fp6 / qw_fp6 are the packed activations (R = T, K = I) and weights
- *   (R = O, K = I).  Y, acc_debug, row_scale, w_scale as in crossquant_w8a8_linear.  Requires
+ * crossquant_w4a4_linear: qx_fp6 are the packed activations (crossquant_pack_fp6 or crossquant_quantize_fp6,
+ *   R = T, K = I), qw_fp6 the packed weights (crossquant_pack_fp6_weights, O channels, K = I).  Y, acc_debug, row_scale, w_scale as in crossquant_w8a8_linear.  Requires
  *   I % 128 == 0, O % 8 == 0, ldy % 8 == 0 and 16-byte aligned pointers, else CQ_ERR_UNSUPPORTED
  *   (the caller then takes the integer path); I <= 2^18.
  */
 int64_t crossquant_fp6_packed_bytes(int64_t R, int64_t K);
+int64_t crossquant_fp6_packed_weight_bytes(int64_t O, int64_t K);
 int crossquant_pack_fp6(const void *codes, int src_format, int64_t R, int64_t K, void *packed, void *stream);
+int crossquant_pack_fp6_weights(const void *codes, int src_format, int64_t O, int64_t K, void *packed, void *stream);
 int crossquant_quantize_fp6(const void *X, int64_t T, int64_t I, int64_t ldx, const float *t,
                             const float *c, float alpha, void *packed, void *xhat, float *row_scale,
                             float *col_scale, unsigned long long *zero_count, void *stream);

@@ -37,7 +37,11 @@ lib.crossquant_calib_copy.argtypes = [_vp, _vp, _i64, _vp]
 lib.crossquant_calib_mfma_i8.argtypes = [_int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
 lib.crossquant_fp6_packed_bytes.argtypes = [_i64, _i64]
 lib.crossquant_fp6_packed_bytes.restype = ctypes.c_int64
+lib.crossquant_fp6_packed_weight_bytes.argtypes = [_i64, _i64]
+lib.crossquant_fp6_packed_weight_bytes.restype = ctypes.c_int64
 lib.crossquant_pack_fp6.argtypes = [_vp, _int, _i64, _i64, _vp, _vp]
+lib.crossquant_pack_fp6_weights.argtypes = [_vp, _int, _i64, _i64, _vp, _vp]
+lib.crossquant_pack_fp6_weights.restype = _int
 lib.crossquant_quantize_fp6.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.crossquant_w4a4_linear.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp]
 lib.crossquant_kernel_count.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _f32, _int, _vp, _vp, _vp, _vp]
@@ -291,9 +295,10 @@ def crossquant_quantize_batched(X: torch.Tensor, t: torch.Tensor, c: torch.Tenso
     return codes, xhat, row_scale, col_scale, zero_count
 
 
-def crossquant_pack_fp6(codes: torch.Tensor, *, packed: torch.Tensor = None) -> torch.Tensor:
+def crossquant_pack_fp6(codes: torch.Tensor, *, packed: torch.Tensor = None, weights: bool = False) -> torch.Tensor:
     """INT4 codes -> FP6 fragments for crossquant_w4a4_linear.  codes: int8 [R][K] (values in
-    [-7, 7]) or uint8 packed nibbles [R][K/2]; returns a uint8 tensor of the packed size."""
+    [-7, 7]) or uint8 packed nibbles [R][K/2]; returns a uint8 tensor of the packed size.
+    weights=True: the weight operand's row order (crossquant_pack_fp6_weights), for codes [O][K]."""
     if not codes.is_cuda or codes.dim() != 2 or not codes.is_contiguous():
         raise ValueError("codes must be a contiguous 2-D GPU tensor")
     if codes.dtype == torch.int8:
@@ -302,15 +307,22 @@ def crossquant_pack_fp6(codes: torch.Tensor, *, packed: torch.Tensor = None) -> 
         fmt, R, K = 4, codes.shape[0], codes.shape[1] * 2
     else:
         raise TypeError("codes must be int8 (one code per byte) or uint8 (packed nibbles)")
-    n = int(lib.crossquant_fp6_packed_bytes(R, K))
+    n = int((lib.crossquant_fp6_packed_weight_bytes if weights else lib.crossquant_fp6_packed_bytes)(R, K))
     if n < 0:
         raise CrossQuantError(-6)
     if packed is None:
         packed = torch.empty(n, dtype=torch.uint8, device=codes.device)
     elif packed.dtype != torch.uint8 or packed.numel() != n or not packed.is_contiguous():
         raise ValueError("packed must be a contiguous uint8 tensor of %d bytes" % n)
-    _check(lib.crossquant_pack_fp6(codes.data_ptr(), fmt, R, K, packed.data_ptr(), _stream(codes)))
+    pack = lib.crossquant_pack_fp6_weights if weights else lib.crossquant_pack_fp6
+    _check(pack(codes.data_ptr(), fmt, R, K, packed.data_ptr(), _stream(codes)))
     return packed
+
+
+def crossquant_pack_fp6_weights(codes: torch.Tensor, *, packed: torch.Tensor = None) -> torch.Tensor:
+    """INT4 weight codes [O][K] -> the weight operand of crossquant_w4a4_linear (FP6 fragments with the rows of
+    every group of 64 output channels interleaved four ways)."""
+    return crossquant_pack_fp6(codes, packed=packed, weights=True)
 
 
 def crossquant_quantize_fp6(X: torch.Tensor, t: torch.Tensor, c: torch.Tensor, alpha: float, *,
@@ -370,8 +382,8 @@ def crossquant_w4a4_linear(qx_fp6: torch.Tensor, row_scale: torch.Tensor, qw_fp6
     """A4W4 linear layer on FP6-packed INT4 codes (exact).  Returns (Y, acc_or_None)."""
     for ten, name in ((qx_fp6, "qx_fp6"), (qw_fp6, "qw_fp6")):
         if not ten.is_cuda or ten.dtype != torch.uint8 or not ten.is_contiguous():
-            raise ValueError("%s must be a contiguous uint8 GPU tensor from crossquant_pack_fp6" % name)
-    if qx_fp6.numel() != lib.crossquant_fp6_packed_bytes(T, I) or qw_fp6.numel() != lib.crossquant_fp6_packed_bytes(O, I):
+            raise ValueError("%s must be a contiguous uint8 GPU tensor from crossquant_pack_fp6 / _weights" % name)
+    if qx_fp6.numel() != lib.crossquant_fp6_packed_bytes(T, I) or qw_fp6.numel() != lib.crossquant_fp6_packed_weight_bytes(O, I):
         raise ValueError("packed operand sizes do not match T, I, O")
     _buf(row_scale, torch.float32, (T,), "row_scale", qx_fp6)
     _buf(w_scale, torch.float32, (O,), "w_scale", qx_fp6)

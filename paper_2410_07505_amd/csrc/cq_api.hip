@@ -261,13 +261,27 @@ int64_t crossquant_fp6_packed_bytes(int64_t R, int64_t K) {
     return cq::fp6_packed_bytes(R, K);
 }
 
-int crossquant_pack_fp6(const void* codes, int src_format, int64_t R, int64_t K, void* packed, void* stream) {
+int64_t crossquant_fp6_packed_weight_bytes(int64_t O, int64_t K) {
+    if (!dim_ok(O) || !dim_ok(K) || K % 128 != 0) return -1;
+    return cq::fp6_packed_weight_bytes(O, K);
+}
+
+static int pack_fp6(const void* codes, int src_format, bool weights, int64_t R, int64_t K, void* packed, void* stream) {
     if (!codes || !packed) return CQ_ERR_NULL;
     if (!dim_ok(R) || !dim_ok(K) || R * K > CQ_MAX_ELEMS) return CQ_ERR_SHAPE;
     if (src_format != 8 && src_format != 4) return CQ_ERR_BITS;
     if (K % 128 != 0) return CQ_ERR_UNSUPPORTED;
     if (!aligned(codes, 16) || !aligned(packed, 16)) return CQ_ERR_ALIGN;
-    return from_hip(cq::launch_pack_fp6(codes, src_format, (int)R, (int)K, packed, static_cast<hipStream_t>(stream)));
+    return from_hip(cq::launch_pack_fp6(codes, src_format, weights, (int)R, (int)K, packed,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int crossquant_pack_fp6(const void* codes, int src_format, int64_t R, int64_t K, void* packed, void* stream) {
+    return pack_fp6(codes, src_format, false, R, K, packed, stream);
+}
+
+int crossquant_pack_fp6_weights(const void* codes, int src_format, int64_t O, int64_t K, void* packed, void* stream) {
+    return pack_fp6(codes, src_format, true, O, K, packed, stream);
 }
 
 int crossquant_quantize_fp6(const void* X, int64_t T, int64_t I, int64_t ldx, const float* t, const float* c,

@@ -1,6 +1,6 @@
 // A4W4 linear layer on the FP6 matrix instruction (the W4A4 rows of the paper's accuracy tables).
 //
-// gfx950 has no INT4 matrix instruction, but v_mfma_f32_32x32x64_f8f6f4 multiplies 6-bit floats at
+// gfx950 has no INT4 matrix instruction, but the f8f6f4 matrix instructions multiply 6-bit floats at
 // twice the INT8 rate, and every INT4 code q in [-7, 7] is exactly representable in FP6 E2M3
 // (1 sign, 2 exponent, 3 mantissa bits, bias 1: 0, 1, 2, 3, 4, 5, 6, 7 are 0b000000, 0b001000,
 // 0b010000, 0b010100, 0b011000, 0b011010, 0b011100, 0b011110).  Products are integers of at most
@@ -8,19 +8,30 @@
 // and is exact: the result equals the integer GEMM bit for bit, and the scale epilogue is the
 // same sequence of binary32 operations as in the INT8 path.
 //
-// Operand format ("FP6 fragments"), produced by pack_fp6_kernel.  The instruction wants, in lane
-// l, the 32 consecutive K elements [32 (l >> 5), +32) of row (l & 31) as one 192-bit little-endian
-// stream (element j in bits [6j, 6j + 6)).  A matrix of R rows and K columns is therefore stored
-// as [ceil(R/32)][K/64] fragments of 1536 bytes, each fragment as a 1024-byte plane (64 lanes x
-// 16 bytes: bits [0, 128) of every lane's stream) followed by a 512-byte plane (64 lanes x 8 bytes:
-// bits [128, 192)); rows past R are zero.  A fragment is copied to LDS verbatim and a wave picks
-// its operand up with one 16-byte and one 8-byte read per lane, each a contiguous run across the
-// wave: no bank conflicts, no swizzle, no register shuffling.
+// Operand format ("FP6 fragments"), produced by pack_fp6_kernel.  A fragment holds 32 rows x 64 K elements: lane
+// slot s (0..63) is the 32 consecutive K elements [32 (s >> 5), +32) of row (s & 31) as one 192-bit little-endian
+// stream (element j in bits [6j, 6j + 6)).  A matrix of R rows and K columns is stored as [ceil(R/32)][K/64]
+// fragments of 1536 bytes, each fragment as a 1024-byte plane (64 slots x 16 bytes: bits [0, 128) of every
+// slot's stream) followed by a 512-byte plane (64 slots x 8 bytes: bits [128, 192)); rows past R are zero.
+// The weight operand uses the same fragments with its rows in a different order (pack_fp6_kernel<.., true>):
+// inside every group of 64 output channels, stored row 16 n + f holds channel 4 f + n, so that the 16 rows of
+// the kernel's weight tile n are the channels 4 f + n and a lane ends up with four adjacent channels.
+//
+// The matrix instruction is v_mfma_f32_16x16x128_f8f6f4: lane l supplies row (l & 15) and the 32 consecutive K
+// elements of chunk l >> 4 of a 128-element K step, i.e. slot 16 p + (l & 15) + 32 (c & 1) of fragment c >> 1
+// of the two fragments along K, for the rows [16 p, 16 p + 16) of a 32-row block: one 16-byte and one 8-byte
+// LDS read per lane and tile.  (Which K positions a lane's elements take inside the instruction does not matter
+// for a dot product, as long as both operands are read the same way.)  The 16-byte reads of 16 lanes are
+// consecutive; for the 8-byte reads, of which the LDS serves 32 lanes per cycle, the two halves of a fragment's
+// second plane would fall on the same banks, so in LDS the two 128-byte pieces of that plane's second half
+// change places (done by the global -> LDS requests, which pick their 16 source bytes per lane).
+// The 16 x 16 x 128 instruction instead of 32 x 32 x 64: half the accumulator register traffic per multiply-add
+// (a loop fed from LDS sustains about 5 % more with it), and the accumulator layout the direct epilogue wants.
 //
 // The kernel follows the INT8 ring kernel's schedule with 6-bit operands: 256 x 256 block tile,
-// 8 waves of 128 x 64, K step 128 elements (two fragments along K, 24 KiB per operand).  The
-// smaller operands leave room for a ring of six LDS slots, i.e. three tiles in flight: requests
-// run two to three steps ahead (described at the kernel).  Per K step a wave issues 16 matrix
+// 8 waves of 128 x 64 (8 x 4 tiles of 16 x 16), K step 128 elements (two fragments along K, 24 KiB per operand).
+// The smaller operands leave room for a ring of six LDS slots, i.e. three tiles in flight: requests
+// run two to three steps ahead (described at the kernel).  Per K step a wave issues 32 matrix
 // instructions (half the cycles of the INT8 kernel for the same K) against 18 KiB of LDS reads,
 // so this kernel is bound by operand movement rather than by the matrix pipe.
 #include <type_traits>
@@ -34,16 +45,15 @@ constexpr int kFragBytes = 1536;                     // 32 rows x 64 elements x 
 constexpr int kFragLo = 1024;                        // first plane: 64 lanes x 16 bytes
 constexpr int kF6Slot = 8 * 2 * kFragBytes;          // 24 KiB: 256 rows x 128 elements
 constexpr int kF6Slots = 6;
-// the ring takes 144 KiB
-constexpr int kF6Ring = kF6Slots * kF6Slot;
-// ... or a little more: the epilogue's staging areas and row factors (148 KiB) reuse the ring's LDS
-constexpr int kF6Lds = kF6Ring > epilogue_rows_lds(8, 64) ? kF6Ring : epilogue_rows_lds(8, 64);
+constexpr int kF6Ring = kF6Slots * kF6Slot;         // 144 KiB; the epilogue's row factors reuse its first 4 KiB
+constexpr int kF6Lds = kF6Ring;
 static_assert(kF6Lds <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 // ---- packing ---------------------------------------------------------------------------------
 // One thread builds one lane's 24 bytes of one fragment.  SRC 8: int8 codes [R][K]; SRC 4: packed
 // two's-complement nibbles [R][K/2], even column in the low nibble.  Codes are clamped to +-7.
-template <int SRC>
+// WEIGHTS: stored row 64 g + 16 n + f holds row 64 g + 4 f + n of the source (see the head of this file).
+template <int SRC, bool WEIGHTS>
 __global__ void pack_fp6_kernel(const uint8_t* __restrict__ src, int R, int K, uint8_t* __restrict__ dst,
                                 int64_t n_slots) {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -52,7 +62,8 @@ __global__ void pack_fp6_kernel(const uint8_t* __restrict__ src, int R, int K, u
     const int64_t frag = idx >> 6;
     const int KB = K / 64;
     const int kb = (int)(frag % KB), rb = (int)(frag / KB);
-    const int row = rb * 32 + (lane & 31);
+    const int stored = rb * 32 + (lane & 31);
+    const int row = WEIGHTS ? (stored & ~63) + 4 * (stored & 15) + ((stored >> 4) & 3) : stored;
     const int k0 = kb * 64 + 32 * (lane >> 5);
     uint32_t w[6] = {0u, 0u, 0u, 0u, 0u, 0u};
     if (row < R) {
@@ -136,44 +147,57 @@ __device__ __forceinline__ v8i as_operand(const frag6& f) {
     return v;
 }
 
-// slot: one operand's 256 rows x 128 elements as [row block 8][k fragment 2] fragments
-__device__ __forceinline__ frag6 read_frag(const int8_t* slot, int row_block, int kf, int lane) {
-    const int8_t* f = slot + (row_block * 2 + kf) * kFragBytes;
+// Where a piece of a fragment sits in LDS: the two 128-byte pieces of the second plane's second half change places
+// (fragment-local byte offsets [1280, 1408) and [1408, 1536)); everything else is where the operand format has it.
+__device__ __forceinline__ int lds_place(int frag_offset) {
+    return frag_offset >= 1280 ? frag_offset ^ 128 : frag_offset;      // 1280 = 10 * 128: the xor swaps the two pieces
+}
+
+// Per-lane read offsets inside a slot, for the 16 x 16 tile made of the rows [16 p, 16 p + 16) of a 32-row block:
+// lane l = row (l & 15), K chunk c = l >> 4 -> fragment c >> 1 along K, slot 16 p + (l & 15) + 32 (c & 1).
+struct FragLane {
+    int lo[2];             // 16-byte piece, p = 0 / 1
+    int hi[2][2];          // 8-byte piece, [p][row block even / odd]
+};
+__device__ __forceinline__ FragLane frag_lane(int lane) {
+    const int r = lane & 15, c = lane >> 4;
+    FragLane f;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int slot = 16 * p + r + 32 * (c & 1);
+        f.lo[p] = (c >> 1) * kFragBytes + slot * 16;
+        f.hi[p][0] = (c >> 1) * kFragBytes + lds_place(kFragLo + slot * 8);
+        // The odd row block's offset goes through an empty asm so that the compiler cannot see that it is the even
+        // one's plus a constant: it would otherwise pair the 8-byte reads of two row blocks into one instruction
+        // and then has to move the halves of its result next to each tile's 16-byte piece, waiting for the read first.
+        f.hi[p][1] = f.hi[p][0] + 2 * kFragBytes;
+        asm volatile("" : "+v"(f.hi[p][1]));
+    }
+    return f;
+}
+// tile `tile` (16 rows) of the operand rows that start at row block rb0 (even) of the slot
+__device__ __forceinline__ frag6 read_tile(const int8_t* slot, int rb0, int tile, const FragLane& fl) {
+    const int8_t* f_even = slot + (rb0 + ((tile >> 1) & ~1)) * (2 * kFragBytes);
     frag6 r;
-    r.lo = *reinterpret_cast<const uint4*>(f + lane * 16);
-    r.hi = *reinterpret_cast<const uint2*>(f + kFragLo + lane * 8);
+    r.lo = *reinterpret_cast<const uint4*>(f_even + ((tile >> 1) & 1) * (2 * kFragBytes) + fl.lo[tile & 1]);
+    r.hi = *reinterpret_cast<const uint2*>(f_even + fl.hi[tile & 1][(tile >> 1) & 1]);
     return r;
 }
 
-template <int NI>
-__device__ __forceinline__ void load_frags6(frag6 (&af)[4], frag6 (&bf)[NI], const int8_t* As, const int8_t* Bs,
-                                            int a_rb, int b_rb, int kf, int lane) {
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) af[mi] = read_frag(As, a_rb + mi, kf, lane);
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bf[ni] = read_frag(Bs, b_rb + ni, kf, lane);
-}
-
 // Activation fragment first, as in the INT8 kernel (weights first runs 3 to 4 % slower): the accumulator tile has the
-// instruction's natural orientation, a lane holds channels l & 31 and 32 + (l & 31) of its wave's 64 (the operand
-// format keeps 32 consecutive rows in a fragment), and the shared row-oriented epilogue takes them apart again.
+// instruction's natural orientation (lane l: channel l & 15 of the weight tile, tokens 4 (l >> 4) + register).
 // Format 2 = FP6 E2M3 for both operands; scale operands 0 select the unscaled instruction.
-template <int NI>
-__device__ __forceinline__ void mfma_slab6(v16f (&acc)[4][NI], const frag6 (&af)[4], const frag6 (&bf)[NI]) {
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(af[mi]), as_operand(bf[ni]),
-                                                                          acc[mi][ni], 2, 2, 0, 0, 0, 0);
+__device__ __forceinline__ v4f mfma6(const frag6& a, const frag6& b, v4f acc) {
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(a), as_operand(b), acc, 2, 2, 0, 0, 0, 0);
 }
 
+template <bool DEBUG, bool STREAM>
 __global__ void __launch_bounds__(512)
 gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ row_scale,
                     const uint8_t* __restrict__ qw6, const float* __restrict__ w_scale, int T, int I, int O,
                     uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
-                    int tiles_n, int y_cached) {
-    constexpr int WN = 4, WTN = 64, NI = 2;
+                    int tiles_n) {
+    constexpr int WN = 4, WTN = 64, G = 4;
     extern __shared__ __align__(16) int8_t lds[];
 
     int tile_m, tile_n;
@@ -196,10 +220,10 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     // One wave of every SIMD multiplies while its mate is held in load issue, as in the INT8 kernel.
     const bool late = wave >= 4;
 
-    // ---- loader: a slot (half tile) is 24 instructions of 1 KiB.  Instruction n copies bytes
-    // [1024 (n % 3), +1024) of the two consecutive fragments (3072 bytes) of row block n / 3.  Row
-    // blocks past the end of a ragged operand are replaced by the last valid one: what lands there
-    // only feeds outputs the epilogue drops.
+    // ---- loader: a slot (half tile) is 24 instructions of 1 KiB.  Instruction n fills bytes
+    // [1024 (n % 3), +1024) of the two consecutive fragments (3072 bytes) of row block n / 3 in LDS; a lane's
+    // 16 bytes come from where lds_place puts them.  Row blocks past the end of a ragged operand are replaced
+    // by the last valid one: what lands there only feeds outputs the epilogue drops.
     //   B(kt+2), before the barrier: early wave lw issues instructions 6 lw .. 6 lw + 5;
     //   A(kt+3), after the barrier:  late wave lw issues kLateA of them, early wave lw the other
     //                                kEarlyA = 6 - kLateA (the late waves are the critical path of a
@@ -208,14 +232,18 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     constexpr int kEarlyA = 2, kLateA = 6 - kEarlyA;   // 0 / 6 measured ~4 % slower, 1..3 alike
     auto src_of = [&](const uint8_t* base, int first_rb, int last_rb, int n) {
         const int rb = min(first_rb + n / 3, last_rb);
-        return base + (int64_t)rb * KB * kFragBytes + (n % 3) * 1024 + lane * 16;
+        const int pair_offset = (n % 3) * 1024 + lane * 16;                  // where the 16 bytes land, in the pair
+        const int frag = pair_offset >= kFragBytes ? 1 : 0;
+        // (lds_place is its own inverse)
+        return base + (int64_t)rb * KB * kFragBytes + frag * kFragBytes + lds_place(pair_offset - frag * kFragBytes);
     };
     const uint8_t* src_b[6];                      // early waves only
     const uint8_t* src_a[kLateA > kEarlyA ? kLateA : kEarlyA];
     const int n_a = late ? kLateA : kEarlyA;      // this wave's share of an A half tile ...
     const int a_first = late ? kLateA * lw : 4 * kLateA + kEarlyA * lw;   // ... starting at this instruction
+    // (the weight operand always has whole groups of 64 channels, i.e. an even number of row blocks)
 #pragma unroll
-    for (int ii = 0; ii < 6; ++ii) src_b[ii] = src_of(qw6, n0 / 32, (O + 31) / 32 - 1, 6 * lw + ii);
+    for (int ii = 0; ii < 6; ++ii) src_b[ii] = src_of(qw6, n0 / 32, 2 * ((O + 63) / 64) - 1, 6 * lw + ii);
 #pragma unroll
     for (int ii = 0; ii < (kLateA > kEarlyA ? kLateA : kEarlyA); ++ii)
         src_a[ii] = src_of(qx6, m0 / 32, (T + 31) / 32 - 1, a_first + min(ii, n_a > 0 ? n_a - 1 : 0));
@@ -241,14 +269,15 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     const int pend_a = n_a;
 
     const int a_rb = wm * 4, b_rb = wn * 2;       // first row block of this wave inside the A / B slot
+    const FragLane fl = frag_lane(lane);
 
-    v16f acc[4][NI];
+    v4f acc[8][G];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int ni = 0; ni < G; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
+            for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0.0f;
 
     // prologue, oldest first: B0 A0 B1 A1 A2 (B by the early waves only); tile 0 must have landed,
     // the rest may still be in flight
@@ -268,30 +297,44 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     int sa = 0, sb = 1;
     auto adv = [](int v) { v += 2; return v >= kF6Slots ? v - kF6Slots : v; };
 
-    frag6 af0[4], bf0[NI], af1[4], bf1[NI];
-    load_frags6<NI>(af0, bf0, lds + sa * kF6Slot, lds + sb * kF6Slot, a_rb, b_rb, 0, lane);
-
-    constexpr int NMF = 4 * NI;                   // matrix instructions per slab
-    constexpr int NRD = 2 * (4 + NI);             // LDS reads per slab (one 16-byte, one 8-byte per fragment)
-    auto interleave_reads = [&]() {
+    // Fragment registers: the activation tiles 0-3 and 4-7 of a step alternate (a_lo, a_hi), the four weight tiles
+    // are replaced one by one as the step's second half finishes with them.  A step is two phases of 16 matrix
+    // instructions, walked weight tile by weight tile:
+    //   phase 1: tokens 0-63   (a_lo x bf) while a_hi of this step is read;
+    //   [requests, waits and the step's barrier]
+    //   phase 2: tokens 64-127 (a_hi x bf) while a_lo and then bf of the next step are read, each weight tile
+    //            after the four instructions that used its predecessor.
+    frag6 a_lo[4], a_hi[4], bf[G];
 #pragma unroll
-        for (int i = 0; i < NMF; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    };
+    for (int mi = 0; mi < 4; ++mi) a_lo[mi] = read_tile(lds + sa * kF6Slot, a_rb, mi, fl);
+#pragma unroll
+    for (int ni = 0; ni < G; ++ni) bf[ni] = read_tile(lds + sb * kF6Slot, b_rb, ni, fl);
 
+    // The arguments that only the epilogue uses are brought into registers here.  Left to the compiler their scalar
+    // loads stay pending into the loop, and while one is pending every wait for an LDS read at the head of the loop has
+    // to be a wait for all of them (scalar loads return out of order, on the same counter): the first matrix
+    // instruction of a step then waits for the last read of the step before.
+    asm volatile("" ::"s"(row_scale), "s"(w_scale), "s"(Y), "s"(ldy), "s"(acc_debug), "s"(T), "s"(O));
     auto k_step = [&](int kt, auto ahead2_c, auto ahead3_c, auto prefetch_c) {
         constexpr bool AHEAD2 = decltype(ahead2_c)::value;      // kt + 2 < nk
         constexpr bool AHEAD3 = decltype(ahead3_c)::value;      // kt + 3 < nk
         constexpr bool PREFETCH = decltype(prefetch_c)::value;  // kt + 1 < nk
         const int8_t* As = lds + sa * kF6Slot;
-        const int8_t* Bs = lds + sb * kF6Slot;
         const int na = adv(sa), nb = adv(sb);                   // slots of tile kt+1
-        load_frags6<NI>(af1, bf1, As, Bs, a_rb, b_rb, 1, lane);
-        mfma_slab6<NI>(acc, af0, bf0);
-        interleave_reads();
+        // phase 1
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) a_hi[mi] = read_tile(As, a_rb, 4 + mi, fl);
+#pragma unroll
+        for (int ni = 0; ni < G; ++ni)
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) acc[mi][ni] = mfma6(a_lo[mi], bf[ni], acc[mi][ni]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {                           // 8 reads, one after each of the first 8 instructions
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
         // Before the barrier every wave makes sure its share of tile kt+1 has landed; requests are
         // served in order, so it is enough that at most the newest ones (its share of A(kt+2) and
         // B(kt+2)) are still in flight.  lgkmcnt(0): this wave's reads of tile kt are done (its slots
@@ -303,13 +346,28 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         __builtin_amdgcn_sched_barrier(0);
         if (AHEAD3) issue_a(kt + 3, sa);                        // A(kt+3) -> slot of A(kt)
         __builtin_amdgcn_sched_barrier(0);
-        if (PREFETCH) load_frags6<NI>(af0, bf0, lds + na * kF6Slot, lds + nb * kF6Slot, a_rb, b_rb, 0, lane);
-        mfma_slab6<NI>(acc, af1, bf1);
+        // phase 2
         if (PREFETCH) {
-            interleave_reads();
-        } else {
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) a_lo[mi] = read_tile(lds + na * kF6Slot, a_rb, mi, fl);
         }
+#pragma unroll
+        for (int ni = 0; ni < G; ++ni) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) acc[4 + mi][ni] = mfma6(a_hi[mi], bf[ni], acc[4 + mi][ni]);
+            if (PREFETCH) bf[ni] = read_tile(lds + nb * kF6Slot, b_rb, ni, fl);
+        }
+        if (PREFETCH) {
+            // reads 1-8 (a_lo) behind instructions 1-8, the weight tiles' behind 9-14, the last tile's after 16
+#pragma unroll
+            for (int i = 0; i < 14; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         sa = na;
         sb = nb;
     };
@@ -325,31 +383,37 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         k_step(kt, no{}, no{}, yes{});
         ++kt;
     }
-    EpilogueScalesRows<NI> scales;
-    epilogue_rows_load_scales<NI, true>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    EpilogueScales16<G> scales;
+    epilogue16_load_scales<G>(scales, row_scale, w_scale, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
     __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{}, no{});
 
-    // every wave's fragments are in registers and all loads have landed: the ring can be reused
-    __syncthreads();
-    epilogue_rows_store<v16f, WTN, NI, 8, true>(acc, lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN,
-                                                lane, wave, y_cached != 0);
+    // Every wave is past the last step's barrier and all requests have landed: the ring is free, and each wave
+    // keeps its row factors in a piece of it.
+    float* a_lds = reinterpret_cast<float*>(lds + wave * 512);
+    epilogue16_store<WTN, G, DEBUG, STREAM>(acc, a_lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
 }
 
 }  // namespace
 
 int64_t fp6_packed_bytes(int64_t R, int64_t K) { return ((R + 31) / 32) * (K / 64) * (int64_t)kFragBytes; }
+int64_t fp6_packed_weight_bytes(int64_t O, int64_t K) { return fp6_packed_bytes(((O + 63) / 64) * 64, K); }
 
-hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void* packed, hipStream_t stream) {
-    const int64_t n_slots = ((int64_t)(R + 31) / 32) * (K / 64) * 64;
+hipError_t launch_pack_fp6(const void* codes, int src_format, bool weights, int R, int K, void* packed,
+                           hipStream_t stream) {
+    const int64_t row_blocks = weights ? 2 * (((int64_t)R + 63) / 64) : ((int64_t)R + 31) / 32;
+    const int64_t n_slots = row_blocks * (K / 64) * 64;
     if (!grid_fits((n_slots + 255) / 256, 256)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((n_slots + 255) / 256)), block(256);
-    if (src_format == 8)
-        pack_fp6_kernel<8><<<grid, block, 0, stream>>>(static_cast<const uint8_t*>(codes), R, K,
-                                                       static_cast<uint8_t*>(packed), n_slots);
-    else
-        pack_fp6_kernel<4><<<grid, block, 0, stream>>>(static_cast<const uint8_t*>(codes), R, K,
-                                                       static_cast<uint8_t*>(packed), n_slots);
+    const uint8_t* src = static_cast<const uint8_t*>(codes);
+    uint8_t* dst = static_cast<uint8_t*>(packed);
+    if (src_format == 8) {
+        if (weights) pack_fp6_kernel<8, true><<<grid, block, 0, stream>>>(src, R, K, dst, n_slots);
+        else pack_fp6_kernel<8, false><<<grid, block, 0, stream>>>(src, R, K, dst, n_slots);
+    } else {
+        if (weights) pack_fp6_kernel<4, true><<<grid, block, 0, stream>>>(src, R, K, dst, n_slots);
+        else pack_fp6_kernel<4, false><<<grid, block, 0, stream>>>(src, R, K, dst, n_slots);
+    }
     return hipGetLastError();
 }
 
@@ -357,14 +421,21 @@ hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const voi
                               int I, int O, uint16_t* Y, int64_t ldy, int32_t* acc_debug, hipStream_t stream) {
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (O + BN - 1) / BN;
     if (!grid_fits((int64_t)tiles_m * tiles_n + kXcds, 512)) return hipErrorInvalidValue;
+    if (ldy >= ((int64_t)1 << 22)) return hipErrorInvalidValue;      // the epilogue's 32-bit byte offsets
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + kXcds - 1) / kXcds;
-    static std::atomic<uint64_t> lds_allowed{0};
-    const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_f6_ring_kernel), kF6Lds, lds_allowed);
+    // four instances: with or without the raw accumulators, Y streamed to memory or left in the caches
+    using kernel_t = void (*)(const uint8_t*, const float*, const uint8_t*, const float*, int, int, int, uint16_t*, int64_t,
+                              int32_t*, int, int);
+    static const kernel_t kernels[4] = {&gemm_f6_ring_kernel<false, false>, &gemm_f6_ring_kernel<false, true>,
+                                        &gemm_f6_ring_kernel<true, false>, &gemm_f6_ring_kernel<true, true>};
+    static std::atomic<uint64_t> lds_allowed[4];
+    const int which = (acc_debug ? 2 : 0) + (y_stays_cached(T, O) ? 0 : 1);
+    const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kernels[which]), kF6Lds, lds_allowed[which]);
     if (e != hipSuccess) return e;
-    gemm_f6_ring_kernel<<<dim3((unsigned)(per_xcd * kXcds)), dim3(512), kF6Lds, stream>>>(
+    kernels[which]<<<dim3((unsigned)(per_xcd * kXcds)), dim3(512), kF6Lds, stream>>>(
         static_cast<const uint8_t*>(qx6), row_scale, static_cast<const uint8_t*>(qw6), w_scale, T, I, O, Y, ldy,
-        acc_debug, tiles_m, tiles_n, y_stays_cached(T, O) ? 1 : 0);
+        acc_debug, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

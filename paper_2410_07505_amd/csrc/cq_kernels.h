@@ -142,7 +142,9 @@ hipError_t launch_quantize_fp6(const uint16_t* X, int T, int I, int64_t ldx, con
                                float* a, float* b, void* packed, uint16_t* xhat, unsigned long long* zero_count,
                                hipStream_t stream);
 int64_t fp6_packed_bytes(int64_t R, int64_t K);
-hipError_t launch_pack_fp6(const void* codes, int src_format, int R, int K, void* packed, hipStream_t stream);
+int64_t fp6_packed_weight_bytes(int64_t O, int64_t K);
+hipError_t launch_pack_fp6(const void* codes, int src_format, bool weights, int R, int K, void* packed,
+                           hipStream_t stream);
 hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const void* qw6, const float* w_scale, int T,
                               int I, int O, uint16_t* Y, int64_t ldy, int32_t* acc_debug, hipStream_t stream);
 

@@ -1330,6 +1330,17 @@ def fp6_fragments(codes):
     return np.concatenate([lo, hi], axis=2).reshape(-1).view(np.uint8)
 
 
+def fp6_weight_fragments(codes):
+    """The weight operand: the same fragments over the rows in interleaved order -- inside every group of 64 output
+    channels, stored row 16 n + f holds channel 4 f + n (channels past O are zero rows)."""
+    O, K = codes.shape
+    padded = np.zeros(((O + 63) // 64 * 64, K), codes.dtype)
+    padded[:O] = codes
+    stored = np.arange(padded.shape[0])
+    source = (stored // 64) * 64 + 4 * (stored % 16) + (stored % 64) // 16
+    return fp6_fragments(padded[source])
+
+
 def int4_codes(R, K, seed):
     return np.random.default_rng(seed).integers(-7, 8, (R, K)).astype(np.int8)
 
@@ -1350,6 +1361,11 @@ def test_fp6_packing(cq, R, K):
     # codes outside the INT4 range saturate
     wide = (codes.astype(np.int16) * 3).clip(-128, 127).astype(np.int8)
     assert np.array_equal(host(cq.crossquant_pack_fp6(gpu(wide))), fp6_fragments(wide))
+    # the weight operand's row order
+    want_w = fp6_weight_fragments(codes)
+    got_w8 = host(cq.crossquant_pack_fp6_weights(gpu(codes)))
+    assert got_w8.shape == want_w.shape and np.array_equal(got_w8, want_w)
+    assert np.array_equal(host(cq.crossquant_pack_fp6(gpu(nibbles(codes)), weights=True)), want_w)
 
 
 @pytest.mark.parametrize("T,I,O", [(1, 128, 8), (32, 128, 32), (256, 256, 256), (300, 256, 520), (257, 384, 264),
@@ -1361,7 +1377,7 @@ def test_w4a4_linear_fp6(cq, T, I, O):
     a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
     s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
     Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
-    px, pw = cq.crossquant_pack_fp6(gpu(nibbles(qx))), cq.crossquant_pack_fp6(gpu(qw))
+    px, pw = cq.crossquant_pack_fp6(gpu(nibbles(qx))), cq.crossquant_pack_fp6_weights(gpu(qw))
     Y, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, want_acc=True)
     assert np.array_equal(host(acc), acc_ref)
     assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
@@ -1383,7 +1399,7 @@ def test_w4a4_linear_fp6_extreme_accumulators_and_guarded_output(cq):
     Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
     assert np.abs(acc_ref).max() == 49 * I
     buf = torch.full((T + 5, 96), 7.0, dtype=torch.float16, device="cuda")
-    px, pw = cq.crossquant_pack_fp6(gpu(qx)), cq.crossquant_pack_fp6(gpu(qw))
+    px, pw = cq.crossquant_pack_fp6(gpu(qx)), cq.crossquant_pack_fp6_weights(gpu(qw))
     _, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, Y=buf[:T, :O], want_acc=True)
     out = host(buf)
     assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(out[:T, :O]), bits16(Y_ref))
@@ -1403,7 +1419,7 @@ def test_w4a4_linear_fp6_longest_contraction(cq):
     s = np.full(O, 1e-3, np.float32)
     Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
     assert np.abs(acc_ref).max() == 49 * I
-    px, pw = cq.crossquant_pack_fp6(gpu(qx)), cq.crossquant_pack_fp6(gpu(qw))
+    px, pw = cq.crossquant_pack_fp6(gpu(qx)), cq.crossquant_pack_fp6_weights(gpu(qw))
     Y, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, want_acc=True)
     assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(host(Y)), bits16(Y_ref))
 
@@ -1441,7 +1457,7 @@ def test_end_to_end_a4w4_fp6_config(cq):
     t, c = cq.crossquant_absmax(Xg)
     packed, _, a, b, _ = cq.crossquant_quantize(Xg, t, c, 0.15, 4, want_xhat=False)
     qw, s = cq.crossquant_weight_quantize(Wg, b, 4)
-    px, pw = cq.crossquant_pack_fp6(packed), cq.crossquant_pack_fp6(qw)
+    px, pw = cq.crossquant_pack_fp6(packed), cq.crossquant_pack_fp6_weights(qw)
     px_direct, _, a_d, _, _ = cq.crossquant_quantize_fp6(Xg, t, c, 0.15)
     assert torch.equal(px, px_direct) and torch.equal(a, a_d)
     Y, acc = cq.crossquant_w4a4_linear(px, a, pw, s, cfg.T, cfg.I, cfg.O, want_acc=True)
@@ -1466,7 +1482,7 @@ def test_random_shapes_w4a4_fp6(cq):
         a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
         s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
         Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
-        px, pw = cq.crossquant_pack_fp6(gpu(nibbles(qx))), cq.crossquant_pack_fp6(gpu(qw))
+        px, pw = cq.crossquant_pack_fp6(gpu(nibbles(qx))), cq.crossquant_pack_fp6_weights(gpu(qw))
         Y, acc = cq.crossquant_w4a4_linear(px, gpu(a), pw, gpu(s), T, I, O, want_acc=True)
         assert np.array_equal(host(acc), acc_ref)
         assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
