@@ -34,6 +34,7 @@
 // run two to three steps ahead (described at the kernel).  Per K step a wave issues 32 matrix
 // instructions (half the cycles of the INT8 kernel for the same K) against 18 KiB of LDS reads,
 // so this kernel is bound by operand movement rather than by the matrix pipe.
+#include <algorithm>
 #include <type_traits>
 
 #include "cq_gemm_common.h"
@@ -45,8 +46,8 @@ constexpr int kFragBytes = 1536;                     // 32 rows x 64 elements x 
 constexpr int kFragLo = 1024;                        // first plane: 64 lanes x 16 bytes
 constexpr int kF6Slot = 8 * 2 * kFragBytes;          // 24 KiB: 256 rows x 128 elements
 constexpr int kF6Slots = 6;
-constexpr int kF6Ring = kF6Slots * kF6Slot;         // 144 KiB; the epilogue's row factors reuse its first 4 KiB
-constexpr int kF6Lds = kF6Ring;
+constexpr int kF6Ring = kF6Slots * kF6Slot;         // 144 KiB
+constexpr int kF6Lds = kF6Ring + 8 * 512;           // ... and the epilogue's row factors behind it
 static_assert(kF6Lds <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 // ---- packing ---------------------------------------------------------------------------------
@@ -191,20 +192,41 @@ __device__ __forceinline__ v4f mfma6(const frag6& a, const frag6& b, v4f acc) {
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(a), as_operand(b), acc, 2, 2, 0, 0, 0, 0);
 }
 
+// s_waitcnt vmcnt(n + 32), lgkmcnt(0) for a wave-uniform n in [0, 12]: the same with the 32 stores of the block's
+// previous tile still allowed in flight
+__device__ __forceinline__ void wait_vmcnt_upto_after_stores(int n) {
+    static_assert(kEpilogue16Stores == 32, "the store count of the shared epilogue");
+    switch (n) {
+        case 0: __builtin_amdgcn_s_waitcnt(waitcnt_imm(32, 0)); break;
+        case 1: __builtin_amdgcn_s_waitcnt(waitcnt_imm(33, 0)); break;
+        case 2: __builtin_amdgcn_s_waitcnt(waitcnt_imm(34, 0)); break;
+        case 3: __builtin_amdgcn_s_waitcnt(waitcnt_imm(35, 0)); break;
+        case 4: __builtin_amdgcn_s_waitcnt(waitcnt_imm(36, 0)); break;
+        case 5: __builtin_amdgcn_s_waitcnt(waitcnt_imm(37, 0)); break;
+        case 6: __builtin_amdgcn_s_waitcnt(waitcnt_imm(38, 0)); break;
+        case 7: __builtin_amdgcn_s_waitcnt(waitcnt_imm(39, 0)); break;
+        case 8: __builtin_amdgcn_s_waitcnt(waitcnt_imm(40, 0)); break;
+        case 9: __builtin_amdgcn_s_waitcnt(waitcnt_imm(41, 0)); break;
+        case 10: __builtin_amdgcn_s_waitcnt(waitcnt_imm(42, 0)); break;
+        case 11: __builtin_amdgcn_s_waitcnt(waitcnt_imm(43, 0)); break;
+        default: __builtin_amdgcn_s_waitcnt(waitcnt_imm(44, 0)); break;
+    }
+}
+
+// One output tile of 256 tokens x 256 channels starting at (m0, n0).  `prefetched`: the block's previous tile has
+// requested this tile's first half tiles already; (next_m0, next_n0): the tile this one does that for (next_m0 < 0:
+// none).
 template <bool DEBUG, bool STREAM>
-__global__ void __launch_bounds__(512)
-gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ row_scale,
-                    const uint8_t* __restrict__ qw6, const float* __restrict__ w_scale, int T, int I, int O,
-                    uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
-                    int tiles_n) {
+__device__ __forceinline__ void f6_tile(const uint8_t* __restrict__ qx6, const float* __restrict__ row_scale,
+                                        const uint8_t* __restrict__ qw6, const float* __restrict__ w_scale, int T, int I,
+                                        int O, uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug,
+                                        int m0, int n0, int8_t* lds, bool prefetched, int next_m0, int next_n0) {
     constexpr int WN = 4, WTN = 64, G = 4;
-    extern __shared__ __align__(16) int8_t lds[];
 
-    int tile_m, tile_n;
-    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n)) return;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    const int tid = threadIdx.x;
+    // (the thread id goes through an empty asm: the lane-dependent offsets below are then worked out again for every
+    // tile of the block's walk instead of being kept, and spilled, across the whole loop over tiles)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int KB = I / 64;                        // fragments along K
@@ -230,9 +252,9 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     //                                step, the early ones would otherwise idle at the barrier).
     const int lw = wave & 3;
     constexpr int kEarlyA = 2, kLateA = 6 - kEarlyA;   // 0 / 6 measured ~4 % slower, 1..3 alike
-    auto src_of = [&](const uint8_t* base, int first_rb, int last_rb, int n) {
+    auto src_of = [&](const uint8_t* base, int first_rb, int last_rb, int n, int ln) {
         const int rb = min(first_rb + n / 3, last_rb);
-        const int pair_offset = (n % 3) * 1024 + lane * 16;                  // where the 16 bytes land, in the pair
+        const int pair_offset = (n % 3) * 1024 + ln * 16;                    // where the 16 bytes land, in the pair
         const int frag = pair_offset >= kFragBytes ? 1 : 0;
         // (lds_place is its own inverse)
         return base + (int64_t)rb * KB * kFragBytes + frag * kFragBytes + lds_place(pair_offset - frag * kFragBytes);
@@ -241,12 +263,18 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     const uint8_t* src_a[kLateA > kEarlyA ? kLateA : kEarlyA];
     const int n_a = late ? kLateA : kEarlyA;      // this wave's share of an A half tile ...
     const int a_first = late ? kLateA * lw : 4 * kLateA + kEarlyA * lw;   // ... starting at this instruction
-    // (the weight operand always has whole groups of 64 channels, i.e. an even number of row blocks)
+    auto set_sources = [&](int tile_m0, int tile_n0) {
+        // (worked out from scratch at each of the two calls rather than kept in registers in between)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        // (the weight operand always has whole groups of 64 channels, i.e. an even number of row blocks)
 #pragma unroll
-    for (int ii = 0; ii < 6; ++ii) src_b[ii] = src_of(qw6, n0 / 32, 2 * ((O + 63) / 64) - 1, 6 * lw + ii);
+        for (int ii = 0; ii < 6; ++ii) src_b[ii] = src_of(qw6, tile_n0 / 32, 2 * ((O + 63) / 64) - 1, 6 * lw + ii, ln);
 #pragma unroll
-    for (int ii = 0; ii < (kLateA > kEarlyA ? kLateA : kEarlyA); ++ii)
-        src_a[ii] = src_of(qx6, m0 / 32, (T + 31) / 32 - 1, a_first + min(ii, n_a > 0 ? n_a - 1 : 0));
+        for (int ii = 0; ii < (kLateA > kEarlyA ? kLateA : kEarlyA); ++ii)
+            src_a[ii] = src_of(qx6, tile_m0 / 32, (T + 31) / 32 - 1, a_first + min(ii, n_a > 0 ? n_a - 1 : 0), ln);
+    };
+    set_sources(m0, n0);
     auto issue_b = [&](int kt, int slot) {        // early waves
         int8_t* dst = lds + slot * kF6Slot + lw * (6 * 1024);
         const int64_t koff = (int64_t)kt * (2 * kFragBytes);
@@ -280,17 +308,26 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
             for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0.0f;
 
     // prologue, oldest first: B0 A0 B1 A1 A2 (B by the early waves only); tile 0 must have landed,
-    // the rest may still be in flight
-    if (!late) issue_b(0, 1);
-    issue_a(0, 0);
-    if (nk > 1) {
-        if (!late) issue_b(1, 3);
-        issue_a(1, 2);
-    }
-    if (nk > 2) issue_a(2, 4);
+    // the rest may still be in flight -- and, when the block's previous tile made these requests before its
+    // epilogue, so may that tile's 32 stores, which are this wave's newest requests (the counter is decremented in
+    // the order of issue)
+    auto issue_prologue = [&]() {
+        if (!late) issue_b(0, 1);
+        issue_a(0, 0);
+        if (nk > 1) {
+            if (!late) issue_b(1, 3);
+            issue_a(1, 2);
+        }
+        if (nk > 2) issue_a(2, 4);
+    };
     {
         const int later = (nk > 1 ? (late ? 0 : 6) + pend_a : 0) + (nk > 2 ? pend_a : 0);
-        wait_vmcnt_upto(later);
+        if (!prefetched) {
+            issue_prologue();
+            wait_vmcnt_upto(later);
+        } else {
+            wait_vmcnt_upto_after_stores(later);
+        }
     }
     __builtin_amdgcn_s_barrier();
 
@@ -340,8 +377,13 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
         // B(kt+2)) are still in flight.  lgkmcnt(0): this wave's reads of tile kt are done (its slots
         // are handed over at the barrier).
         if (!late && AHEAD2) issue_b(kt + 2, adv(nb));          // B(kt+2) -> slot of B(kt-1)
-        if (AHEAD2) wait_vmcnt_upto(pend_a + (late ? 0 : 6));
-        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+        if (AHEAD2) {
+            // (in a prefetched tile's first step the previous tile's stores are still younger than tile 1's requests)
+            if (prefetched && kt == 0) wait_vmcnt_upto_after_stores(pend_a + (late ? 0 : 6));
+            else wait_vmcnt_upto(pend_a + (late ? 0 : 6));
+        } else {
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+        }
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         if (AHEAD3) issue_a(kt + 3, sa);                        // A(kt+3) -> slot of A(kt)
@@ -388,10 +430,43 @@ gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ r
     __builtin_amdgcn_sched_barrier(0);              // requested now, in flight during the last step
     k_step(kt, no{}, no{}, no{});
 
-    // Every wave is past the last step's barrier and all requests have landed: the ring is free, and each wave
-    // keeps its row factors in a piece of it.
-    float* a_lds = reinterpret_cast<float*>(lds + wave * 512);
+    // Every wave is past the last step's barrier and all requests have landed: the ring is free.  The prologue of the
+    // block's next tile is requested now and travels while this tile's results are scaled and stored; the row
+    // factors of the epilogue sit behind the ring.  (Not with DEBUG: the number of stores in flight is not fixed then.)
+    if (!DEBUG && next_m0 >= 0) {
+        set_sources(next_m0, next_n0);
+        issue_prologue();
+    }
+    float* a_lds = reinterpret_cast<float*>(lds + kF6Ring + wave * 512);
     epilogue16_store<WTN, G, DEBUG, STREAM>(acc, a_lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// One block per CU (a block fills a CU's LDS) walks over several tiles, as in the INT8 kernel: block b belongs to XCD
+// b % 8 and takes positions i, i + per, ... of that XCD's contiguous range of the tile walk, i = b / 8, per =
+// gridDim.x / 8.
+template <bool DEBUG, bool STREAM>
+__global__ void __launch_bounds__(512)
+gemm_f6_ring_kernel(const uint8_t* __restrict__ qx6, const float* __restrict__ row_scale,
+                    const uint8_t* __restrict__ qw6, const float* __restrict__ w_scale, int T, int I, int O,
+                    uint16_t* __restrict__ Y, int64_t ldy, int32_t* __restrict__ acc_debug, int tiles_m,
+                    int tiles_n) {
+    extern __shared__ __align__(16) int8_t lds[];
+    const int xcd = blockIdx.x % kXcds, first = blockIdx.x / kXcds, per = gridDim.x / kXcds;
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    bool prefetched = false;
+    for (int i = first; i < per_xcd; i += per) {
+        const int L = xcd * per_xcd + i;
+        if (L >= total) break;
+        int tile_m, tile_n, next_m = -1, next_n = -1;
+        tile_of_index(L, tiles_m, tiles_n, tile_m, tile_n);
+        const bool has_next = i + per < per_xcd && L + per < total;
+        if (has_next) tile_of_index(L + per, tiles_m, tiles_n, next_m, next_n);
+        f6_tile<DEBUG, STREAM>(qx6, row_scale, qw6, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN, lds,
+                               prefetched, has_next ? next_m * BM : -1, next_n * BN);
+        prefetched = has_next && !DEBUG;
+    }
 }
 
 }  // namespace
@@ -433,7 +508,14 @@ hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const voi
     const int which = (acc_debug ? 2 : 0) + (y_stays_cached(T, O) ? 0 : 1);
     const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kernels[which]), kF6Lds, lds_allowed[which]);
     if (e != hipSuccess) return e;
-    kernels[which]<<<dim3((unsigned)(per_xcd * kXcds)), dim3(512), kF6Lds, stream>>>(
+    // one block per CU (a multiple of the XCD count), fewer when there are fewer tiles than that
+    int n_cu = 0, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+        n_cu = 256;
+    const int cu_blocks = n_cu >= kXcds ? n_cu / kXcds * kXcds : kXcds;
+    const int blocks = std::min(cu_blocks, per_xcd * kXcds);
+    kernels[which]<<<dim3((unsigned)blocks), dim3(512), kF6Lds, stream>>>(
         static_cast<const uint8_t*>(qx6), row_scale, static_cast<const uint8_t*>(qw6), w_scale, T, I, O, Y, ldy,
         acc_debug, tiles_m, tiles_n);
     return hipGetLastError();

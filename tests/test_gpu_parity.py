@@ -977,6 +977,31 @@ def test_linear_with_a_partly_filled_last_round_of_tiles(cq, T, I, O):
     assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
 
 
+@pytest.mark.parametrize("T,I,O", [(5120, 128, 5120),      # 400 tiles = 1.56 rounds, taken whole: 144 blocks walk two tiles; one K step
+                                   (5120, 384, 5120),      # the same with three K steps
+                                   (4100, 256, 7688),      # 17 x 31 = 527 tiles, ragged on both edges: two whole rounds + 15 tiles as halves
+                                   (8192, 128, 6144)])     # 768 tiles = three whole rounds
+def test_linear_blocks_walk_several_tiles(cq, T, I, O):
+    """With more output tiles than CUs a block works through several of them, and (when the raw accumulators are not
+    asked for) requests the next tile's first operands before it scales and stores the current one.  Every output of
+    both forms against the oracle, twice in a row into the same buffer."""
+    say("linear, several tiles per block: T=%d I=%d O=%d" % (T, I, O))
+    qx = workloads.int8_codes(T, I, seed=T + 3)
+    qw = workloads.int8_codes(O, I, seed=O + 13)
+    rng = np.random.default_rng(T + O)
+    a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+    s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    gx, ga, gw, gs = gpu(qx), gpu(a), gpu(qw), gpu(s)
+    Y, none_acc = cq.crossquant_w8a8_linear(gx, ga, gw, gs)
+    assert none_acc is None and np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    Y.zero_()
+    cq.crossquant_w8a8_linear(gx, ga, gw, gs, Y=Y)
+    assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    Y2, acc = cq.crossquant_w8a8_linear(gx, ga, gw, gs, want_acc=True)
+    assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(host(Y2)), bits16(Y_ref))
+
+
 def test_linear_extreme_accumulators(cq):
     say("linear extremes")
     T, I, O = 256, 8192, 256
@@ -1383,6 +1408,31 @@ def test_w4a4_linear_fp6(cq, T, I, O):
     assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
     Y8, _ = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s))          # the integer path agrees
     assert np.array_equal(bits16(host(Y8)), bits16(host(Y)))
+
+
+@pytest.mark.parametrize("T,I,O", [(5120, 128, 5120),      # 400 tiles: 144 blocks walk two tiles; one K step
+                                   (5120, 256, 5120),      # two K steps
+                                   (4100, 384, 7688),      # 527 tiles, ragged on both edges; three K steps
+                                   (8192, 512, 6144)])     # 768 tiles = three whole rounds; four K steps
+def test_w4a4_linear_fp6_blocks_walk_several_tiles(cq, T, I, O):
+    """More output tiles than CUs: a block works through several of them and requests the next tile's first operands
+    before it scales and stores the current one (not when the raw accumulators are asked for).  Every output of both
+    forms against the oracle, twice in a row into the same buffer."""
+    say("w4a4 fp6, several tiles per block: T=%d I=%d O=%d" % (T, I, O))
+    qx, qw = int4_codes(T, I, seed=T + 5), int4_codes(O, I, seed=O + 17)
+    rng = np.random.default_rng(T + O)
+    a = rng.uniform(1e-3, 1e-1, T).astype(np.float32)
+    s = rng.uniform(1e-5, 1e-3, O).astype(np.float32)
+    Y_ref, acc_ref = oracle.w8a8_linear(qx, a, qw, s)
+    px, pw = cq.crossquant_pack_fp6(gpu(nibbles(qx))), cq.crossquant_pack_fp6_weights(gpu(qw))
+    ga, gs = gpu(a), gpu(s)
+    Y, none_acc = cq.crossquant_w4a4_linear(px, ga, pw, gs, T, I, O)
+    assert none_acc is None and np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    Y.zero_()
+    cq.crossquant_w4a4_linear(px, ga, pw, gs, T, I, O, Y=Y)
+    assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    Y2, acc = cq.crossquant_w4a4_linear(px, ga, pw, gs, T, I, O, want_acc=True)
+    assert np.array_equal(host(acc), acc_ref) and np.array_equal(bits16(host(Y2)), bits16(Y_ref))
 
 
 def test_w4a4_linear_fp6_extreme_accumulators_and_guarded_output(cq):
