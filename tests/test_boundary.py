@@ -194,10 +194,13 @@ def test_fp6_argument_errors(cq):
     n = cq.raw.crossquant_fp6_packed_bytes
     assert n(32, 128) == 32 * 128 * 6 // 8 and n(33, 128) == 64 * 128 * 6 // 8 and n(300, 256) == 320 * 256 * 6 // 8
     assert n(0, 128) == -1 and n(32, 64) == -1
-    f = cq.raw.crossquant_pack_fp6
-    assert f(0, 8, 32, 128, P, None) == -1 and f(P, 8, 32, 128, 0, None) == -1
-    assert f(P, 8, 0, 128, P, None) == -2 and f(P, 6, 32, 128, P, None) == -3
-    assert f(P, 8, 32, 100, P, None) == -6 and f(P + 4, 8, 32, 128, P, None) == -5
+    nw = cq.raw.crossquant_fp6_packed_weight_bytes          # whole groups of 64 output channels
+    assert nw(64, 128) == n(64, 128) and nw(8, 128) == n(64, 128) and nw(65, 256) == n(128, 256) and nw(300, 256) == n(320, 256)
+    assert nw(0, 128) == -1 and nw(64, 64) == -1
+    for f in (cq.raw.crossquant_pack_fp6, cq.raw.crossquant_pack_fp6_weights):
+        assert f(0, 8, 32, 128, P, None) == -1 and f(P, 8, 32, 128, 0, None) == -1
+        assert f(P, 8, 0, 128, P, None) == -2 and f(P, 6, 32, 128, P, None) == -3
+        assert f(P, 8, 32, 100, P, None) == -6 and f(P + 4, 8, 32, 128, P, None) == -5
     q = cq.raw.crossquant_quantize_fp6
     assert q(P, 4, 128, 128, P, P, 0.15, 0, None, P, P, None, None) == -1
     assert q(P, 4, 128, 100, P, P, 0.15, P, None, P, P, None, None) == -2
