@@ -288,7 +288,7 @@ int crossquant_quantize_linear_fused(const void *X, int64_t T, int64_t I, int64_
  *   CQ_ERR_UNSUPPORTED.  Other arguments as in crossquant_quantize.
  * crossquant_w4a4_linear: qx_fp6 are the packed activations (crossquant_pack_fp6 or crossquant_quantize_fp6,
  *   R = T, K = I), qw_fp6 the packed weights (crossquant_pack_fp6_weights, O channels, K = I).  Y, acc_debug, row_scale, w_scale as in crossquant_w8a8_linear.  Requires
- *   I % 128 == 0, O % 8 == 0, ldy % 8 == 0 and 16-byte aligned pointers, else CQ_ERR_UNSUPPORTED
+ *   I % 128 == 0, O % 8 == 0, ldy % 8 == 0, ldy < 2^22 and 16-byte aligned pointers, else CQ_ERR_UNSUPPORTED
  *   (the caller then takes the integer path); I <= 2^18.
  */
 int64_t crossquant_fp6_packed_bytes(int64_t R, int64_t K);

@@ -309,7 +309,7 @@ int crossquant_w4a4_linear(const void* qx_fp6, const float* row_scale, const voi
     if (I > (1 << 18)) return CQ_ERR_SHAPE;                 // 49 * I must stay below 2^24 (exact in binary32)
     if (!aligned(row_scale, 4) || !aligned(w_scale, 4) || !aligned(Y, 2) || !aligned(acc_debug, 4)) return CQ_ERR_ALIGN;
     if (I % 128 != 0 || O % 8 != 0 || ldy % 8 != 0 || !aligned(qx_fp6, 16) || !aligned(qw_fp6, 16) ||
-        !aligned(Y, 16) || !aligned(w_scale, 16) || !aligned(acc_debug, 16))
+        !aligned(Y, 16) || !aligned(w_scale, 16) || !aligned(acc_debug, 16) || ldy >= ((int64_t)1 << 22))
         return CQ_ERR_UNSUPPORTED;
     return from_hip(cq::launch_w4a4_linear(qx_fp6, row_scale, qw_fp6, w_scale, (int)T, (int)I, (int)O,
                                            static_cast<uint16_t*>(Y), ldy, acc_debug,

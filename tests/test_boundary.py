@@ -217,6 +217,7 @@ def test_fp6_argument_errors(cq):
     assert call(T=0) == -2 and call(ldy=4) == -2 and call(I=1 << 19) == -2
     assert call(Y=P + 1) == -5
     assert call(I=64) == -6 and call(O=12, ldy=16) == -6 and call(ldy=12) == -6 and call(qx=P + 8) == -6
+    assert call(ldy=1 << 22) == -6
 
 
 def test_calibration_argument_errors(cq):
