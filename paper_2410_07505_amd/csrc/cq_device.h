@@ -239,6 +239,41 @@ __device__ __forceinline__ uint32_t count_row8_wave(const uint4& v, float a, flo
     return nz;
 }
 
+// The same decision counted per lane: every lane returns how many of its own 8 elements have a non-zero code, and
+// the kernel adds the lanes up once at its end.  A compare and an add-with-carry per element and one running
+// minimum of |d| for the closeness test, all vector instructions: the form above hands every compare mask to the
+// scalar unit (population count, add, or), which the four SIMDs of a CU share; in the streaming count-only kernel
+// that was 1.6 scalar instructions per vector instruction.
+__device__ __forceinline__ uint32_t count_row8_lane(const uint4& v, float a, float ha, float tol, const float (&b)[8],
+                                                    const float (&rb)[8], float qmax, bool tiny) {
+    float x[8];
+    x[0] = half_lo(v.x); x[1] = half_hi(v.x);
+    x[2] = half_lo(v.y); x[3] = half_hi(v.y);
+    x[4] = half_lo(v.z); x[5] = half_hi(v.z);
+    x[6] = half_lo(v.w); x[7] = half_hi(v.w);
+    uint32_t nz = 0u;
+    float nearest = __builtin_inff();
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float d = __builtin_fmaf(__builtin_fabsf(x[e]), rb[e], -ha);
+        // nz += d > 0, as a compare and an add of its carry (written out: from "nz += d > 0 ? 1 : 0" the compiler
+        // builds a bit mask of the eight compares with shifts and ors and counts its bits, three times the work)
+        asm("v_cmp_lt_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(nz) : "v"(d) : "vcc");
+        nearest = __builtin_fminf(nearest, __builtin_fabsf(d));
+    }
+    if (__any(nearest <= tol || tiny)) {                // rare: exact division for this wave's row piece
+        nz = 0u;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float D = a * b[e];
+            float rt = (D == 0.0f) ? 0.0f : x[e] / D;
+            rt = __builtin_amdgcn_fmed3f(rt, -qmax, qmax);
+            nz += (rt + kMagic != kMagic) ? 1u : 0u;
+        }
+    }
+    return nz;
+}
+
 // number of non-zero codes among the whole wave's m[0..8): one compare per element, the counting is
 // scalar (population count of the compare mask).  Only active lanes are counted.
 __device__ __forceinline__ uint32_t count_nonzero8_wave(const float (&m)[8]) {

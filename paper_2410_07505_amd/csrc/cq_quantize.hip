@@ -307,6 +307,7 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
     for (int e = 0; e < 8; ++e) b_tiny |= tiny_factor(b[e]);
 
     uint32_t nonzero = 0u;    // codes != 0 seen by this wave (uniform)
+    uint32_t nonzero_lane = 0u;   // ... and, in the count-only form, by this lane
     int rows_done = 0;
     // No branch depends on whether a row exists: rows past the last one are worked on like the others (their data
     // is the last row's, their factor is 0), but their stores go to an empty buffer, which drops them, and their
@@ -329,9 +330,9 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
             const float ra = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, ra_lane), ri));
             if (MODE == 0) {
                 // a == 0 means D = 0 and every code of the row is 0 by definition: left to the exact path
-                const uint32_t nz = count_row8_wave(v[u], a, 0.5f * a, 0.5f * a * kTieTol, b, rb, qmax,
+                const uint32_t nz = count_row8_lane(v[u], a, 0.5f * a, 0.5f * a * kTieTol, b, rb, qmax,
                                                     b_tiny || tiny_factor(a) || a == 0.0f);
-                nonzero += row_ok ? nz : 0u;
+                nonzero_lane += row_ok ? nz : 0u;
                 continue;
             }
             const int live = row_ok ? cols_here : 0;         // columns of this row that may be stored
@@ -383,6 +384,11 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
     }
 
     if (zero_count) {
+        if (MODE == 0) {                                    // the count-only form has counted per lane
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) nonzero_lane += shx(nonzero_lane, off);
+            nonzero = nonzero_lane;
+        }
         // columns past the end read as x = 0 and add nothing to `nonzero`
         const uint32_t zeros = (uint32_t)(rows_done * cols_here) - nonzero;
         if (lane == 0) lds_cnt[wave] = zeros;
