@@ -283,6 +283,16 @@ __device__ __forceinline__ uint32_t count_nonzero8_wave(const float (&m)[8]) {
     return nz;
 }
 
+// The same per lane, for the streaming kernel, which adds the lanes up once at its end: a compare and an add of
+// its carry per element and nothing for the scalar unit, which the four SIMDs of a CU share.
+__device__ __forceinline__ uint32_t count_nonzero8_lane(const float (&m)[8]) {
+    uint32_t nz = 0u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        asm("v_cmp_neq_f32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(nz) : "v"(m[e]), "v"(kMagic) : "vcc");
+    return nz;
+}
+
 // number of non-zero codes among m[0..8) (as a float: exact far below 2^24)
 __device__ __forceinline__ float count_nonzero8(const float (&m)[8]) {
     float nz = 0.0f;

@@ -306,8 +306,7 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
 #pragma unroll
     for (int e = 0; e < 8; ++e) b_tiny |= tiny_factor(b[e]);
 
-    uint32_t nonzero = 0u;    // codes != 0 seen by this wave (uniform)
-    uint32_t nonzero_lane = 0u;   // ... and, in the count-only form, by this lane
+    uint32_t nonzero_lane = 0u;   // codes != 0 seen by this lane
     int rows_done = 0;
     // No branch depends on whether a row exists: rows past the last one are worked on like the others (their data
     // is the last row's, their factor is 0), but their stores go to an empty buffer, which drops them, and their
@@ -336,9 +335,9 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
                 continue;
             }
             const int live = row_ok ? cols_here : 0;         // columns of this row that may be stored
-            // count, pack and store one row piece; returns the wave's number of non-zero codes in it
+            // count, pack and store one row piece; returns the lane's number of non-zero codes in it
             auto emit = [&](const float (&m)[8], const float (&q)[8]) -> uint32_t {
-                const uint32_t nz = count_nonzero8_wave(m);
+                const uint32_t nz = count_nonzero8_lane(m);
                 if (MODE == 1)
                     __builtin_amdgcn_raw_buffer_store_b64(pack_codes_i8(m), row_buffer(codes + (int64_t)rr * I + col0, live),
                                                           lane * 8, 0, kWriteThrough);
@@ -364,7 +363,7 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
             } else {
                 nz = emit(m, q);
             }
-            nonzero += row_ok ? nz : 0u;
+            nonzero_lane += row_ok ? nz : 0u;
             __builtin_amdgcn_sched_barrier(0);               // rows one after the other: keeps scalar register pressure down
         }
         if (MODE == 3) {
@@ -384,11 +383,9 @@ quantize_stream_kernel(const uint16_t* __restrict__ X, int T, int I, int64_t ldx
     }
 
     if (zero_count) {
-        if (MODE == 0) {                                    // the count-only form has counted per lane
+        uint32_t nonzero = nonzero_lane;                    // ... and by the wave
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) nonzero_lane += shx(nonzero_lane, off);
-            nonzero = nonzero_lane;
-        }
+        for (int off = 32; off >= 1; off >>= 1) nonzero += shx(nonzero, off);
         // columns past the end read as x = 0 and add nothing to `nonzero`
         const uint32_t zeros = (uint32_t)(rows_done * cols_here) - nonzero;
         if (lane == 0) lds_cnt[wave] = zeros;
