@@ -435,6 +435,17 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
+    def median_ms(fn, reps):
+        """Median of the calls' own event intervals (each call bracketed by timing-only events), as for the stages."""
+        import statistics
+        ev = [make_events(torch, 2) for _ in range(reps)]
+        for e0, e1 in ev:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        return statistics.median(e0.elapsed_time(e1) for e0, e1 in ev)
+
     # ---- the same step with no event in it (host clock around the loop), with and without the two
     # quantizer calls: their difference is what absmax + quantize cost inside the step when nothing
     # but kernels is on the stream; `value` keeps the event-bracketed definition.
@@ -518,10 +529,14 @@ def main():
             ops_ = cq.crossquant_calib_mfma_i8(it_, mode)
             ms_ = event_ms(lambda: cq.crossquant_calib_mfma_i8(it_, mode), 5)
             mf[name] = ops_ / (ms_ * 1e-3) / 1e12
+        f6_it = 1000
+        f6_ops = cq.crossquant_calib_mfma_f6(f6_it)
+        f6_loop = f6_ops / (event_ms(lambda: cq.crossquant_calib_mfma_f6(f6_it), 5) * 1e-3) / 1e12
         achievable = {
             "hbm_read_GBs": (1 << 30) / (read_ms * 1e-3) / 1e9,
             "hbm_copy_GBs_read_plus_write": 2 * half / (copy_ms * 1e-3) / 1e9,
             "mfma_i8_TOPs": mf,
+            "mfma_fp6_TOPs_int4_like_operands_fed_from_lds": f6_loop,
             "quantizer_frac_of_copy": (quant_gbs / (2 * half / (copy_ms * 1e-3) / 1e9)) if quant_gbs else None,
             "w8a8_linear_frac_of_mfma_loop": (tops / mf["code_like_operands_16x16x64"]) if (tops and bits == 8) else None,
             "w8a8_linear_frac_of_lds_fed_mfma_loop": (tops / mf["code_like_operands_fed_from_lds"]) if (tops and bits == 8) else None,
@@ -539,7 +554,7 @@ def main():
             qwt = wl.qw.t()
             vend = lambda: torch._int_mm(wl.codes, qwt, out=acc32)
             event_ms(vend, 3)
-            v_ms = event_ms(vend, reps)
+            v_ms = median_ms(vend, reps)
             vendor = {"what": "torch._int_mm on the same int8 codes (int32 output, no scale epilogue)", "ms": v_ms,
                       "TOPs": ops_linear / (v_ms * 1e-3) / 1e12, "this_kernel_ms": f["ms"]["linear"]}
             del acc32
@@ -552,14 +567,16 @@ def main():
         px, pw = cq.crossquant_pack_fp6(nib), cq.crossquant_pack_fp6_weights(qw4)
         q8 = cq.crossquant_unpack_int4(nib)
         event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=wl.Y), 10)
-        fp6_ms = event_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=wl.Y), reps)
+        fp6_ms = median_ms(lambda: cq.crossquant_w4a4_linear(px, a4, pw, ws4, T, I, O, Y=wl.Y), reps)
         y6 = wl.Y.clone()
         event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=wl.Y), 10)
-        i8_ms = event_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=wl.Y), reps)
+        i8_ms = median_ms(lambda: cq.crossquant_w8a8_linear(q8, a4, qw4, ws4, Y=wl.Y), reps)
         pack_ms = event_ms(lambda: cq.crossquant_pack_fp6(nib, packed=px), 10)
         a4w4 = {"fp6_ms": fp6_ms, "fp6_TOPs": ops_linear / (fp6_ms * 1e-3) / 1e12, "int8_path_ms": i8_ms,
                 "int8_path_TOPs": ops_linear / (i8_ms * 1e-3) / 1e12, "pack_activations_ms": pack_ms,
                 "identical_outputs": bool(torch.equal(y6.view(torch.int16), wl.Y.view(torch.int16)))}
+        if achievable:
+            a4w4["fp6_frac_of_lds_fed_mfma_loop"] = a4w4["fp6_TOPs"] / achievable["mfma_fp6_TOPs_int4_like_operands_fed_from_lds"]
         del px, pw, q8, nib, qw4, y6
         cq.crossquant_w8a8_linear(wl.codes, wl.a, wl.qw, wl.ws, Y=wl.Y)      # leave Y as the W8A8 result
 

@@ -27,10 +27,14 @@ extern "C" {
  *   instructions = 0.75 KiB per 32 x 32 x 32 worth of multiply-adds; iters * 32 instructions per wave): the ceiling
  *   of a kernel with that wave tile, which no global load, barrier or epilogue burdens.
  *   *ops (HOST pointer, nullable) receives the number of integer operations of the launch.
+ * crossquant_calib_mfma_f6: the loop fed from LDS for the A4W4 kernel: v_mfma_f32_16x16x128_f8f6f4 on FP6 operands
+ *   holding bell-shaped INT4-like codes, 8 + 4 tiles (a 16-byte and an 8-byte read per lane each) per 32 instructions,
+ *   two waves per SIMD, iters * 32 instructions per wave.  *ops as above (2 per multiply-add).
  */
 int crossquant_calib_read(const void *src, int64_t bytes, unsigned long long *sink, void *stream);
 int crossquant_calib_copy(const void *src, void *dst, int64_t bytes, void *stream);
 int crossquant_calib_mfma_i8(int iters, int data_mode, int *sink, double *ops, void *stream);
+int crossquant_calib_mfma_f6(int iters, int *sink, double *ops, void *stream);
 
 /*
  * Test hook for crossquant_absmax_quantize_single_read: the number of polls a block makes at the grid

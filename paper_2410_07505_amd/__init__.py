@@ -9,7 +9,7 @@ missing or stale (the binding is imported on first use so that ``python -m
 paper_2410_07505_amd.build`` can run before the library exists).
 """
 _EXPORTS = (
-    "LIB_PATH", "CrossQuantError", "crossquant_absmax", "crossquant_absmax_batched", "crossquant_calib_copy", "crossquant_calib_mfma_i8", "crossquant_calib_read", "crossquant_absmax_quantize", "crossquant_absmax_quantize_single_read",
+    "LIB_PATH", "CrossQuantError", "crossquant_absmax", "crossquant_absmax_batched", "crossquant_calib_copy", "crossquant_calib_mfma_i8", "crossquant_calib_mfma_f6", "crossquant_calib_read", "crossquant_absmax_quantize", "crossquant_absmax_quantize_single_read",
     "crossquant_kernel_analysis", "crossquant_kernel_analysis_static", "crossquant_kernel_count", "crossquant_pack_fp6", "crossquant_pack_fp6_weights", "crossquant_w4a4_linear",
     "crossquant_quantize", "crossquant_quantize_batched", "crossquant_quantize_fp6", "crossquant_quantize_linear_fused", "crossquant_status_string", "crossquant_unpack_int4", "crossquant_version", "crossquant_w8a8_linear",
     "crossquant_weight_quantize", "crossquant_weight_quantize_grouped", "lib", "raw",

@@ -35,6 +35,8 @@ lib.crossquant_quantize_batched.argtypes = [_vp, _i64, _i64, _i64, _i64, _i64, _
 lib.crossquant_calib_read.argtypes = [_vp, _i64, _vp, _vp]
 lib.crossquant_calib_copy.argtypes = [_vp, _vp, _i64, _vp]
 lib.crossquant_calib_mfma_i8.argtypes = [_int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
+lib.crossquant_calib_mfma_f6.argtypes = [_int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
+lib.crossquant_calib_mfma_f6.restype = _int
 lib.crossquant_fp6_packed_bytes.argtypes = [_i64, _i64]
 lib.crossquant_fp6_packed_bytes.restype = ctypes.c_int64
 lib.crossquant_fp6_packed_weight_bytes.argtypes = [_i64, _i64]
@@ -416,6 +418,13 @@ def crossquant_calib_mfma_i8(iters: int, data_mode: int) -> float:
     ops = ctypes.c_double(0.0)
     _check(lib.crossquant_calib_mfma_i8(int(iters), int(data_mode), 0, ctypes.byref(ops),
                                         torch.cuda.current_stream().cuda_stream))
+    return float(ops.value)
+
+
+def crossquant_calib_mfma_f6(iters: int) -> float:
+    """FP6 MFMA loop fed from LDS on the current device and stream; returns the operations launched."""
+    ops = ctypes.c_double(0.0)
+    _check(lib.crossquant_calib_mfma_f6(int(iters), 0, ctypes.byref(ops), torch.cuda.current_stream().cuda_stream))
     return float(ops.value)
 
 

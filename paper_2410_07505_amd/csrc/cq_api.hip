@@ -337,6 +337,12 @@ int crossquant_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops, v
     return from_hip(cq::launch_calib_mfma_i8(iters, data_mode, sink, ops, static_cast<hipStream_t>(stream)));
 }
 
+int crossquant_calib_mfma_f6(int iters, int* sink, double* ops, void* stream) {
+    if (iters < 1 || iters > (1 << 20)) return CQ_ERR_SHAPE;
+    if (!aligned(sink, 4)) return CQ_ERR_ALIGN;
+    return from_hip(cq::launch_calib_mfma_f6(iters, sink, ops, static_cast<hipStream_t>(stream)));
+}
+
 const char* crossquant_status_string(int status) {
     switch (status) {
         case CQ_OK: return "ok";

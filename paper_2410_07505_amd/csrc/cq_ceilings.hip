@@ -188,6 +188,75 @@ calib_mfma_lds_kernel(int iters, int* __restrict__ sink) {
     if (s == 0x7fffffff && sink) sink[0] = s;
 }
 
+// The same for the A4W4 kernel: v_mfma_f32_16x16x128_f8f6f4 on FP6 operands that hold INT4-like codes (bell-shaped in
+// [-7, 7], encoded as E2M3), 8 waves per CU, every step reads the 8 + 4 tiles of a 128 x 64 wave tile from LDS -- one
+// 16-byte and one 8-byte read per lane and tile, 18 KiB per wave and step -- and issues its 32 matrix instructions
+// over 128 elements of the contraction.  No global loads, no barriers, no epilogue.
+typedef int calib_v8i __attribute__((ext_vector_type(8)));
+typedef float calib_v4f __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(512)
+calib_mfma_f6_lds_kernel(int iters, int* __restrict__ sink) {
+    constexpr int kRecords = 2048;                                  // lane slots: 16 bytes + 8 bytes each
+    __shared__ __align__(16) uint8_t lds[kRecords * 24];
+    uint8_t* lo = lds;                                              // [kRecords][16]
+    uint8_t* hi = lds + kRecords * 16;                              // [kRecords][8]
+    for (int rec = threadIdx.x; rec < kRecords; rec += 512) {
+        uint64_t w[3] = {0ull, 0ull, 0ull};                         // the slot's 32 fields of 6 bits
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const uint32_t r = calib_hash((uint32_t)rec * 32u + j + blockIdx.x * 7919u);
+            const int q = ((int)((r & 63) + ((r >> 6) & 63) + ((r >> 12) & 63) + ((r >> 18) & 63)) - 126) / 18;
+            const int mag = q < 0 ? -q : q;
+            const uint64_t e = ((0x1E1C1A1814100800ull >> (8 * mag)) & 0xFFull) | (q < 0 ? 32ull : 0ull);
+            const int bit = 6 * j;
+            w[bit >> 6] |= e << (bit & 63);
+            if ((bit & 63) > 58) w[(bit >> 6) + 1] |= e >> (64 - (bit & 63));
+        }
+        reinterpret_cast<uint64_t*>(lo)[rec * 2] = w[0];
+        reinterpret_cast<uint64_t*>(lo)[rec * 2 + 1] = w[1];
+        reinterpret_cast<uint64_t*>(hi)[rec] = w[2];
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    calib_v4f acc[8][4];
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0.0f;
+    auto tile = [&](int first_record) {
+        const int rec = (first_record + lane) & (kRecords - 1);
+        const uint4 l = *reinterpret_cast<const uint4*>(lo + rec * 16);
+        const uint2 h = *reinterpret_cast<const uint2*>(hi + rec * 8);
+        calib_v8i v;
+        v[0] = (int)l.x; v[1] = (int)l.y; v[2] = (int)l.z; v[3] = (int)l.w;
+        v[4] = (int)h.x; v[5] = (int)h.y; v[6] = 0; v[7] = 0;
+        return v;
+    };
+    for (int it = 0; it < iters; ++it) {
+        const int base = ((it * 5 + wave * 3) & 31) * 64;
+        calib_v8i a[8], b[4];
+#pragma unroll
+        for (int mi = 0; mi < 8; ++mi) a[mi] = tile(base + mi * 64);
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) b[ni] = tile(base + 1024 + ni * 64);
+#pragma unroll
+        for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[mi], b[ni], acc[mi][ni], 2, 2, 0, 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s += acc[mi][ni][r];
+    if (s == 12345.678f && sink) sink[0] = 1;
+}
+
 int calib_blocks() {
     int dev = 0, n_cu = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
@@ -223,6 +292,14 @@ hipError_t launch_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops
     }
     calib_mfma_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(iters, data_mode, sink);
     if (ops) *ops = (double)blocks * 4.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 32);
+    return hipGetLastError();
+}
+
+// returns the number of operations (2 per multiply-add) the launch performs through *ops
+hipError_t launch_calib_mfma_f6(int iters, int* sink, double* ops, hipStream_t stream) {
+    const int blocks = calib_blocks();
+    calib_mfma_f6_lds_kernel<<<dim3((unsigned)blocks), dim3(512), 0, stream>>>(iters, sink);
+    if (ops) *ops = (double)blocks * 8.0 * (double)iters * 32.0 * (2.0 * 16 * 16 * 128);
     return hipGetLastError();
 }
 

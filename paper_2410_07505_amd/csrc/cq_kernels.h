@@ -152,5 +152,6 @@ hipError_t launch_w4a4_linear(const void* qx6, const float* row_scale, const voi
 hipError_t launch_calib_read(const void* src, int64_t bytes, unsigned long long* sink, hipStream_t stream);
 hipError_t launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream);
 hipError_t launch_calib_mfma_i8(int iters, int data_mode, int* sink, double* ops, hipStream_t stream);
+hipError_t launch_calib_mfma_f6(int iters, int* sink, double* ops, hipStream_t stream);
 
 }  // namespace cq

@@ -226,6 +226,8 @@ def test_calibration_argument_errors(cq):
     assert r(P + 8, 1024, None, None) == -5
     assert c(P, 0, 1024, None) == -1 and c(P, P + 4096, 24, None) == -2 and c(P, P + 4, 1024, None) == -5
     assert m(0, 0, None, None, None) == -2 and m(10, 4, None, None, None) == -6
+    m6 = cq.raw.crossquant_calib_mfma_f6
+    assert m6(0, None, None, None) == -2 and m6(10, 2, None, None) == -5
 
 
 def test_linear_argument_errors(cq):

@@ -1286,6 +1286,9 @@ def test_calibration_kernels_run_and_copy_is_exact(cq):
     ops_16 = cq.crossquant_calib_mfma_i8(10, 3)             # the same instruction on operands in registers: 8 waves
     torch.cuda.synchronize()
     assert ops_lds == n_cu * 8 * 10 * 32 * 32768.0 and ops_16 == n_cu * 8 * 10 * 32 * 32768.0
+    ops_f6 = cq.crossquant_calib_mfma_f6(10)                # the FP6 loop fed from LDS: 8 waves x 32 instructions (16 x 16 x 128)
+    torch.cuda.synchronize()
+    assert ops_f6 == n_cu * 8 * 10 * 32 * 65536.0
 
 
 # ----------------------------------------------------------------------------- seeded random shapes
