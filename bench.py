@@ -350,8 +350,18 @@ class Workload:
         return {"one_call_ms": fused_ms, "two_calls_ms": two_ms, "column_tiles": (cfg.O + 255) // 256,
                 "slowdown": fused_ms / two_ms, "identical_outputs": same}
 
+    def settle(self, seconds=0.05):
+        """Untimed steps for `seconds` of wall time: a loop that starts on an idle part runs slower for its first
+        ~35 ms, which is longer than the whole loop of a small configuration."""
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(10):
+                self.step()
+            self.torch.cuda.synchronize()
+
     def summary(self, steps, warmup):
         """The per-configuration object of the `configs` section."""
+        self.settle()
         med, _, wall_ms = self.timed_steps(steps, warmup)
         f = self.figures(med)
         n = self.cfg.T * self.cfg.I
