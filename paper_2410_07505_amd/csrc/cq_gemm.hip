@@ -249,6 +249,9 @@ constexpr int kRingLds = kRingSlots * kSlotBytes; // 160 KiB: the whole LDS of a
 // One output tile of 256 tokens x (128 NI) channels starting at (m0, n0).  NI = 2 is the full 256 x 256 tile;
 // NI = 1 the half tile of the last, partly filled round (see launch_w8a8_linear): the same schedule with
 // 128 x 32 wave tiles, half the weight requests and half the matrix instructions per step.
+// A block calls this for one tile after the other.  `prefetched`: the block's previous tile has already requested
+// this tile's first two half tiles; (next_m0, next_n0): the tile this one does that for (next_m0 < 0: none).
+// DEBUG: the raw accumulators are stored too (no prefetch then); STREAM: Y is written through to memory.
 template <int NI, bool DEBUG, bool STREAM>
 __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const float* __restrict__ row_scale,
                                           const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I,
