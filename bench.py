@@ -42,10 +42,10 @@ STAGES = ("absmax", "quantize", "count", "linear")
 # workload with the commands given in that profile ("linear": the matrix kernel of the workload's linear
 # layer; "quantize": its quantize kernel); null for workloads that have not been profiled (C1).
 MEASURED_TRAFFIC_BYTES = {
-    "C2": {"quantize": (16.4 + 24.0) * 2 ** 20, "linear": (160.4 + 43.0) * 2 ** 20},
+    "C2": {"quantize": (16.4 + 24.0) * 2 ** 20, "linear": (160.5 + 43.0) * 2 ** 20},
     "C3": {"quantize": (40.5 + 60.0) * 2 ** 20, "linear": (600.6 + 160.0) * 2 ** 20},
     "C4": {"quantize": (32.5 + 44.0) * 2 ** 20, "linear": (72.3 + 32.0) * 2 ** 20},
-    "C5": {"quantize": (64.5 + 96.1) * 2 ** 20, "linear": (1344.9 + 224.0) * 2 ** 20},
+    "C5": {"quantize": (64.5 + 96.1) * 2 ** 20, "linear": (1344.8 + 224.0) * 2 ** 20},
 }
 
 
