@@ -257,7 +257,7 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
                                           const int8_t* __restrict__ qw, const float* __restrict__ w_scale, int T, int I,
                                           int O, uint16_t* __restrict__ Y, int64_t ldy,
                                           int32_t* __restrict__ acc_debug, int m0, int n0, int8_t* lds,
-                                          bool prefetched, int next_m0, int next_n0) {
+                                          bool prefetched, int next_m0, int next_n0, int next_ni) {
     constexpr int WN = 4, WTN = 32 * NI;
     constexpr int G = 2 * NI, LOG2G = NI;         // weight tiles of 16 channels per wave (4 or 2)
     constexpr int NLB = 4 * NI;                   // requests a weight-loading wave makes per half tile (8 or 4)
@@ -278,9 +278,13 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     // Tiles on the bottom / right edge of a ragged problem read a clamped (valid) row instead of
     // the rows past the end; what lands in those LDS rows only feeds outputs the epilogue drops.
     // (a weight-loading wave of a half tile fills 32 rows with 4 requests)
-    const int rows_per_loader = b_loader ? 8 * NLB : 64;
+    // The loader is written for a tile of either kind (ni_c: 2 = full tile, 1 = half tile): besides this tile's own
+    // operands a block requests the first operands of its next tile, which may be of the other kind.
     const int8_t* gsrc[8];
-    auto set_sources = [&](int tile_m0, int tile_n0) {
+    auto set_sources = [&](auto ni_c, int tile_m0, int tile_n0) {
+        constexpr int NIx = decltype(ni_c)::value;
+        constexpr int LOG2Gx = NIx, NLBx = 4 * NIx;
+        const int rows_per_loader = b_loader ? 8 * NLBx : 64;
         // (worked out from scratch at each of the two calls rather than kept in registers in between)
         int l = lane;
         asm volatile("" : "+v"(l));
@@ -293,24 +297,27 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         // b_off), which for one ni all have the same parity; so LDS row R holds tile row R ^ ((R / G) & 1) (the
         // rows of a pair change places in every other group of G) and the swizzle term comes from R / (2 G): a lane
         // then reads LDS row G fr + (ni ^ (fr & 1)), parity and group exactly as for the activation fragment.
-        const int sw_shift = b_loader ? LOG2G + 1 : 1;
+        const int sw_shift = b_loader ? LOG2Gx + 1 : 1;
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
             const int R = rows_per_loader * lw + 8 * ii + ld_r;
             const int c = ld_p ^ ((R >> sw_shift) & 7);
-            const int tile_row = b_loader ? (R ^ ((R >> LOG2G) & 1)) : R;
+            const int tile_row = b_loader ? (R ^ ((R >> LOG2Gx) & 1)) : R;
             gsrc[ii] = base + (int64_t)min(first + tile_row, last) * I + c * 16;
         }
     };
-    set_sources(m0, n0);
-    auto issue_half = [&](int kt, int slot) {
+    using this_kind = std::integral_constant<int, NI>;
+    set_sources(this_kind{}, m0, n0);
+    auto issue_half = [&](auto ni_c, int kt, int slot) {
+        constexpr int NLBx = 4 * decltype(ni_c)::value;
+        const int rows_per_loader = b_loader ? 8 * NLBx : 64;
         int8_t* dst = lds + slot * kSlotBytes + lw * (rows_per_loader * BK);
         const int64_t koff = (int64_t)kt * BK;
 #pragma unroll
         // cache policy sc0: the data goes straight to LDS and is never looked up in the vector L1 again, so the
         // requests bypass it (no measurable difference on the 70B-shaped layer; non-temporal requests are 6 % slower)
         for (int ii = 0; ii < 8; ++ii)
-            if (ii < NLB || !b_loader)
+            if (ii < NLBx || !b_loader)
                 __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[ii] + koff), (lptr_t)(dst + ii * 1024), 16, 0, 1);
     };
     // "all but the requests of the last half tile have landed", for this wave's kind of half tile
@@ -341,12 +348,15 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     // this wave, after A1 / B1, and "A0 / B0 has landed" is "at most 8 + 32 requests in flight" (the counter is
     // decremented in the order of issue).
     if (!prefetched) {
-        issue_half(0, b_loader ? 1 : 0);
-        if (nk > 1) issue_half(1, b_loader ? 3 : 2);
+        issue_half(this_kind{}, 0, b_loader ? 1 : 0);
+        if (nk > 1) issue_half(this_kind{}, 1, b_loader ? 3 : 2);
         if (nk > 1) wait_for_previous_half();
         else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
-    } else {
+    } else if (NLB == 8 || !b_loader) {
         if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(8 + kEpilogue16Stores, 15));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(kEpilogue16Stores, 15));
+    } else {
+        if (nk > 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(NLB + kEpilogue16Stores, 15));
         else __builtin_amdgcn_s_waitcnt(waitcnt_imm(kEpilogue16Stores, 15));
     }
     // (a bare barrier, as in the loop below: the second half tile's requests stay in flight across it)
@@ -401,7 +411,7 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         // must have landed: at most the 8 requests just made may still be in flight.
         if (!b_loader) {
             if (ISSUE) {
-                issue_half(kt + 2, adv(na));
+                issue_half(this_kind{}, kt + 2, adv(na));
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 0));
             } else {
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
@@ -417,7 +427,7 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
         __builtin_amdgcn_sched_barrier(0);
         // B loaders: B(kt+2) = half tile 2kt+5 -> slot (2kt+5) % 5 = sa, tile kt's A slot, which
         // nobody reads any more (the last phase's fragments are in registers)
-        if (b_loader && ISSUE) issue_half(kt + 2, sa);
+        if (b_loader && ISSUE) issue_half(this_kind{}, kt + 2, sa);
         __builtin_amdgcn_sched_barrier(0);
         if (PREFETCH) {
             load_a4(a_lo, lds + na * kSlotBytes, a_off, 0, 0);
@@ -445,11 +455,16 @@ __device__ __forceinline__ void ring_tile(const int8_t* __restrict__ qx, const f
     // Every wave is past the last step's barrier: nothing in the ring is read any more.  The first two half tiles
     // of the block's next tile are requested now, into their slots 0-3, and travel while this tile's results are
     // scaled and stored; the epilogue keeps its row factors in slot 4, which the next tile's loop does not write
-    // before its first barrier.  (Not with DEBUG: the number of stores in flight is not fixed then.)
-    if (!DEBUG && NI == 2 && next_m0 >= 0) {
-        set_sources(next_m0, next_n0);
-        issue_half(0, b_loader ? 1 : 0);
-        if (nk > 1) issue_half(1, b_loader ? 3 : 2);
+    // before its first barrier.  The next tile may be of the other kind (next_ni).  (Not with DEBUG: the number of
+    // stores in flight is not fixed then.)
+    if (!DEBUG && next_m0 >= 0) {
+        auto request_next = [&](auto ni_c) {
+            set_sources(ni_c, next_m0, next_n0);
+            issue_half(ni_c, 0, b_loader ? 1 : 0);
+            if (nk > 1) issue_half(ni_c, 1, b_loader ? 3 : 2);
+        };
+        if (next_ni == 2) request_next(std::integral_constant<int, 2>{});
+        else request_next(std::integral_constant<int, 1>{});
     }
     float* a_lds = reinterpret_cast<float*>(lds + 4 * kSlotBytes + wave * 512);
     epilogue16_store<WTN, G, DEBUG, STREAM>(acc, a_lds, scales, Y, ldy, acc_debug, T, O, m0 + wm * 128, n0 + wn * WTN, lane);
@@ -475,28 +490,55 @@ gemm_i8_ring_kernel(const int8_t* __restrict__ qx, const float* __restrict__ row
     const int xcd = blockIdx.x % kXcds, first = blockIdx.x / kXcds, per = gridDim.x / kXcds;
     int tile_m, tile_n;
     const int main_per_xcd = (n_main + kXcds - 1) / kXcds;
+    const int n_half = 2 * (tiles_m * tiles_n - n_main);
+    const int half_per_xcd = (n_half + kXcds - 1) / kXcds;
+    // position i of this XCD's half tiles -> its origin; false if there is none (past the end, or the empty second
+    // half of a tile on the ragged edge)
+    auto half_tile_at = [&](int i, int& m0, int& n0) {
+        if (i >= half_per_xcd) return false;
+        const int h = xcd * half_per_xcd + i;
+        if (h >= n_half) return false;
+        int tm, tn;
+        tile_of_index(n_main + h / 2, tiles_m, tiles_n, tm, tn);
+        m0 = tm * BM;
+        n0 = tn * BN + (h & 1) * (BN / 2);
+        return n0 < O;
+    };
     bool prefetched = false;
     for (int i = first; i < main_per_xcd; i += per) {
         const int L = xcd * main_per_xcd + i;
         if (L >= n_main) break;
         tile_of_index(L, tiles_m, tiles_n, tile_m, tile_n);
-        // the tile after this one, whose first operands this one requests before its epilogue
-        int next_m = -1, next_n = -1;
-        const bool has_next = i + per < main_per_xcd && L + per < n_main;
-        if (has_next) tile_of_index(L + per, tiles_m, tiles_n, next_m, next_n);
+        // the tile after this one, whose first operands this one requests before its epilogue: the next whole tile
+        // of the walk or, after the last one, the block's first half tile
+        int next_m0 = -1, next_n0 = -1, next_ni = 2;
+        if (i + per < main_per_xcd && L + per < n_main) {
+            int next_m, next_n;
+            tile_of_index(L + per, tiles_m, tiles_n, next_m, next_n);
+            next_m0 = next_m * BM;
+            next_n0 = next_n * BN;
+        } else if (half_tile_at(first, next_m0, next_n0)) {
+            next_ni = 1;
+        } else {
+            next_m0 = -1;
+        }
         ring_tile<2, DEBUG, STREAM>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM, tile_n * BN, lds,
-                                    prefetched, has_next ? next_m * BM : -1, next_n * BN);
-        prefetched = has_next && !DEBUG;
+                                    prefetched, next_m0, next_n0, next_ni);
+        prefetched = next_m0 >= 0 && !DEBUG;
     }
-    const int n_half = 2 * (tiles_m * tiles_n - n_main);
-    const int half_per_xcd = (n_half + kXcds - 1) / kXcds;
+    // (a half tile that does not exist -- the empty second half of a tile on the ragged edge -- is neither run nor
+    // requested for by the tile before it)
     for (int i = first; i < half_per_xcd; i += per) {
-        const int h = xcd * half_per_xcd + i;
-        if (h >= n_half) break;
-        tile_of_index(n_main + h / 2, tiles_m, tiles_n, tile_m, tile_n);
-        if (tile_n * BN + (h & 1) * (BN / 2) >= O) continue;      // the second half of a tile on the ragged edge may be empty
-        ring_tile<1, DEBUG, STREAM>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, tile_m * BM,
-                                    tile_n * BN + (h & 1) * (BN / 2), lds, false, -1, -1);
+        int m0, n0;
+        if (!half_tile_at(i, m0, n0)) {
+            prefetched = false;
+            continue;
+        }
+        int next_m0 = -1, next_n0 = -1;
+        if (!half_tile_at(i + per, next_m0, next_n0)) next_m0 = -1;
+        ring_tile<1, DEBUG, STREAM>(qx, row_scale, qw, w_scale, T, I, O, Y, ldy, acc_debug, m0, n0, lds, prefetched, next_m0,
+                                    next_n0, 1);
+        prefetched = next_m0 >= 0 && !DEBUG;
     }
 }
 

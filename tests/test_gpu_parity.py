@@ -975,6 +975,10 @@ def test_linear_with_a_partly_filled_last_round_of_tiles(cq, T, I, O):
     Y, acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s), want_acc=True)
     assert np.array_equal(host(acc), acc_ref)
     assert np.array_equal(bits16(host(Y)), bits16(Y_ref))
+    # without the raw accumulators a block requests its next (half) tile's first operands before its epilogue
+    for _ in range(2):
+        Y2, none_acc = cq.crossquant_w8a8_linear(gpu(qx), gpu(a), gpu(qw), gpu(s))
+        assert none_acc is None and np.array_equal(bits16(host(Y2)), bits16(Y_ref))
 
 
 @pytest.mark.parametrize("T,I,O", [(5120, 128, 5120),      # 400 tiles = 1.56 rounds, taken whole: 144 blocks walk two tiles; one K step
