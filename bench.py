@@ -90,9 +90,12 @@ class _TimingEvent:
         return ms.value
 
     def __del__(self):
-        if getattr(self, "_e", None) is not None and self._e.value:
-            self._h.hipEventDestroy(self._e)
-            self._e = None
+        try:
+            if getattr(self, "_e", None) is not None and self._e.value:
+                self._h.hipEventDestroy(self._e)
+                self._e = None
+        except Exception:                                   # interpreter shutdown: the runtime may be gone already
+            pass
 
 
 EVENT_KINDS = set()     # what make_events handed out in this run, for the JSON line
