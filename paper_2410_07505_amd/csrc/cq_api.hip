@@ -358,6 +358,6 @@ const char* crossquant_status_string(int status) {
     }
 }
 
-int crossquant_version(void) { return 100; }
+int crossquant_version(void) { return 200; }      // 0.2.0: the A4W4 weight operand has its own row order
 
 }  // extern "C"
